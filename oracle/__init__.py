@@ -1,0 +1,224 @@
+"""CPU oracle for the ScaleBITS bitwidth-allocation search (test infrastructure).
+
+numpy-facing ctypes wrappers around ``sbits_oracle.c``.  Only tests, the smoke
+check and the benchmark's ``cpu_baseline`` leg may import this package; the GPU
+library and its binding never do, and this package never imports them.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sbits_oracle.c")
+_HDR = os.path.join(_HERE, "sbits_oracle.h")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+CFLAGS = ["-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math",
+          "-D_DEFAULT_SOURCE", "-shared", "-fPIC", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no contraction)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
+    if force or stale:
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class Params(C.Structure):
+    _fields_ = [("gamma0", C.c_double), ("gammaT", C.c_double),
+                ("init_mode", C.c_int32), ("max_iters", C.c_int32)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("iters", C.c_int32), ("expansions", C.c_int32),
+                ("swaps_ok", C.c_int32), ("swaps_rej", C.c_int32),
+                ("k_final", C.c_int64), ("bits_used", C.c_int64),
+                ("bits_budget", C.c_int64), ("cost_fixed", C.c_int64),
+                ("cost_shift", C.c_int32), ("pad_", C.c_int32)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_ if f != "pad_"}
+
+
+class Trace(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("pad_", C.c_int32), ("k", C.c_int64),
+                ("n_up", C.c_int64), ("n_dn", C.c_int64),
+                ("p_up", C.c_int64), ("p_dn", C.c_int64),
+                ("bits_before", C.c_int64), ("bits_after", C.c_int64),
+                ("delta_fixed", C.c_int64)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_ if f != "pad_"}
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_canon8.restype = C.c_float
+        _lib.orc_brute_force.restype = C.c_double
+        _lib.orc_fx.restype = C.c_int64
+        _lib.orc_fx.argtypes = [C.c_float, C.c_int32]
+        _lib.orc_cost_shift.restype = C.c_int32
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, "bf16 data travels as raw uint16"
+    return a
+
+
+def f32_to_bf16(x) -> np.ndarray:
+    """Round float32 to bfloat16 (nearest even), returned as raw uint16."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return r.astype(np.uint16)
+
+
+def bf16_to_f32(h) -> np.ndarray:
+    return (np.ascontiguousarray(h, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def canon8(x) -> float:
+    x = _f32(x)
+    return float(lib().orc_canon8(_p(x), C.c_int64(x.size), C.c_int64(1)))
+
+
+def channel_scores(S):
+    S = _f32(S)
+    R, Cc = S.shape
+    rs = np.empty(R, np.float32)
+    cs = np.empty(Cc, np.float32)
+    lib().orc_channel_scores(_p(S), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), _p(rs), _p(cs))
+    return rs, cs
+
+
+def argsort_desc(score):
+    score = _f32(score)
+    perm = np.empty(score.size, np.int32)
+    lib().orc_argsort_desc(_p(score), C.c_int64(score.size), _p(perm))
+    return perm
+
+
+def gather(W_u16, S, rp, cp):
+    W_u16 = _u16(W_u16)
+    S = _f32(S)
+    rp, cp = _i32(rp), _i32(cp)
+    R, Cc = W_u16.shape
+    Wo = np.empty_like(W_u16)
+    So = np.empty_like(S)
+    lib().orc_gather_bf16(_p(W_u16), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), _p(rp), _p(cp), _p(Wo))
+    lib().orc_gather_f32(_p(S), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), _p(rp), _p(cp), _p(So))
+    return Wo, So
+
+
+def quant_group(w, bits):
+    w = _f32(w)
+    q = np.empty(w.size, np.int32)
+    sc = C.c_float()
+    ze = C.c_float()
+    lib().orc_quant_group(_p(w), C.c_int(w.size), C.c_int(bits), _p(q), C.byref(sc), C.byref(ze))
+    return q, np.float32(sc.value), np.float32(ze.value)
+
+
+def cost_table(Wp_u16, Sp, m, n, bits):
+    Wp_u16 = _u16(Wp_u16)
+    Sp = _f32(Sp)
+    bits = _i32(bits)
+    R, Cc = Wp_u16.shape
+    assert R % m == 0 and Cc % n == 0
+    cost = np.empty(((R // m) * (Cc // n), bits.size), np.float32)
+    lib().orc_cost_table(_p(Wp_u16), _p(Sp), C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n),
+                         _p(bits), C.c_int(bits.size), _p(cost))
+    return cost
+
+
+def allocate(cost, bits, avg_bits, gamma0=0.05, gammaT=0.02, init_mode=0,
+             max_iters=100000, want_trace=False):
+    cost = _f32(cost)
+    bits = _i32(bits)
+    N, K = cost.shape
+    assert K == bits.size
+    level = np.zeros(N, np.uint8)
+    prm = Params(gamma0, gammaT, init_mode, max_iters)
+    st = Stats()
+    cap = max_iters if want_trace else 0
+    tr = (Trace * max(cap, 1))()
+    ntr = C.c_int64(0)
+    rc = lib().orc_allocate(_p(cost), C.c_int64(N), _p(bits), C.c_int(K), C.c_double(avg_bits),
+                            C.byref(prm), _p(level), C.byref(st),
+                            tr if want_trace else None, C.c_int64(cap), C.byref(ntr))
+    trace = [tr[i].as_dict() for i in range(min(ntr.value, cap))] if want_trace else None
+    return rc, level, st.as_dict(), trace
+
+
+def cost_shift(cost) -> int:
+    cost = _f32(cost)
+    N, K = cost.shape
+    return int(lib().orc_cost_shift(_p(cost), C.c_int64(N), C.c_int(K)))
+
+
+def fx(v, shift) -> int:
+    return int(lib().orc_fx(C.c_float(float(v)), C.c_int32(shift)))
+
+
+def classic_greedy(cost, bits, avg_bits):
+    cost = _f32(cost)
+    bits = _i32(bits)
+    N, K = cost.shape
+    level = np.zeros(N, np.uint8)
+    lib().orc_classic_greedy(_p(cost), C.c_int64(N), _p(bits), C.c_int(K), C.c_double(avg_bits), _p(level))
+    return level
+
+
+def brute_force(cost, bits, avg_bits):
+    cost = _f32(cost)
+    bits = _i32(bits)
+    N, K = cost.shape
+    level = np.zeros(N, np.uint8)
+    best = lib().orc_brute_force(_p(cost), C.c_int(N), _p(bits), C.c_int(K), C.c_double(avg_bits), _p(level))
+    return float(best), level
+
+
+def offsets(level, m, n, bits):
+    level = np.ascontiguousarray(level, dtype=np.uint8)
+    bits = _i32(bits)
+    off = np.empty(level.size + 1, np.int64)
+    lib().orc_offsets(_p(level), C.c_int64(level.size), C.c_int(m), C.c_int(n), _p(bits), _p(off))
+    return off
+
+
+def pack(Wp_u16, m, n, bits, level, byte_off, block_base, codes, scale, zero):
+    """Packs one matrix into the global codes/scale/zero arrays (in place)."""
+    Wp_u16 = _u16(Wp_u16)
+    bits = _i32(bits)
+    R, Cc = Wp_u16.shape
+    assert level.dtype == np.uint8 and byte_off.dtype == np.int64
+    assert codes.dtype == np.uint8 and scale.dtype == np.float32 and zero.dtype == np.float32
+    lib().orc_pack(_p(Wp_u16), C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n), _p(bits),
+                   C.c_int(bits.size), _p(level), _p(byte_off), C.c_int64(block_base),
+                   _p(codes), _p(scale), _p(zero))

@@ -1,0 +1,118 @@
+"""Pins for the oracle's channel scores, permutations and reorder-gather.
+
+Each check compares the oracle with something fixed by mathematics or by a
+library routine, never with the oracle itself: exact integer sums, numpy's
+stable argsort and fancy indexing, and the invariance of a linear layer's
+output under consistent row/column permutation (paper Sec. 4.1: reordering must
+preserve functional equivalence).
+"""
+import numpy as np
+import pytest
+
+
+def test_canon8_exact_on_integers(orc):
+    # integer-valued floats below 2^24 add exactly in any order
+    rng = np.random.default_rng(0)
+    for L in (1, 7, 8, 9, 63, 64, 65, 1000, 1792 * 8):
+        x = rng.integers(0, 100, size=L).astype(np.float32)
+        assert orc.canon8(x) == float(x.astype(np.int64).sum())
+
+
+def test_canon8_order_is_chunk_sequential_then_pair_tree(orc):
+    big = np.float32(2.0 ** 24)
+    # chunk 0 runs left to right from +0: 2^24 absorbs each following 1 (ties to even)
+    x = np.array([big] + [1] * 7 + [1] * 8, np.float32)
+    assert orc.canon8(x) == 2.0 ** 24 + 8.0
+    # a pairwise tree inside the chunk would give 2^24 + 6 + 8; a fully sequential
+    # sum would give 2^24: both differ from the canonical value
+    x = np.zeros(32, np.float32)
+    x[0], x[8], x[16], x[24] = big, 1, 1, 1
+    # ((2^24 + 1) + (1 + 1)) = 2^24 + 2, whereas left-to-right over chunk sums gives 2^24
+    assert orc.canon8(x) == 2.0 ** 24 + 2.0
+
+
+def test_canon8_padding_to_power_of_two(orc):
+    # 3 chunks -> padded to 4: ((c0 + c1) + (c2 + 0))
+    big = np.float32(2.0 ** 24)
+    x = np.zeros(24, np.float32)
+    x[0], x[8], x[16] = 1, big, 1
+    assert orc.canon8(x) == 2.0 ** 24                 # (1 + 2^24) -> 2^24, then + (1 + 0) -> 2^24 (ties to even)
+    x[0], x[8], x[16] = 1, 1, big
+    assert orc.canon8(x) == 2.0 ** 24 + 2.0          # (1 + 1) + (2^24 + 0)
+
+
+def test_channel_scores_rows_vs_columns(orc):
+    rng = np.random.default_rng(1)
+    S = rng.integers(0, 50, size=(24, 40)).astype(np.float32)
+    S[3, 5] = -7.0                                    # l1 norm: sign must not cancel
+    rs, cs = orc.channel_scores(S)
+    assert rs.shape == (24,) and cs.shape == (40,)
+    np.testing.assert_array_equal(rs, np.abs(S).sum(axis=1))
+    np.testing.assert_array_equal(cs, np.abs(S).sum(axis=0))
+
+
+def test_channel_scores_close_to_float64(orc):
+    rng = np.random.default_rng(2)
+    S = np.exp(rng.normal(size=(136, 264))).astype(np.float32)
+    rs, cs = orc.channel_scores(S)
+    np.testing.assert_allclose(rs, S.astype(np.float64).sum(1), rtol=2e-6)
+    np.testing.assert_allclose(cs, S.astype(np.float64).sum(0), rtol=2e-6)
+
+
+def test_argsort_matches_numpy_stable_descending(orc):
+    rng = np.random.default_rng(3)
+    s = rng.integers(0, 20, size=500).astype(np.float32)   # many ties
+    perm = orc.argsort_desc(s)
+    ref = np.argsort(-s, kind="stable").astype(np.int32)
+    np.testing.assert_array_equal(perm, ref)
+    assert sorted(perm.tolist()) == list(range(500))        # a bijection
+    assert np.all(np.diff(s[perm]) <= 0)                     # scores non-increasing
+    s = rng.normal(size=1000).astype(np.float32)
+    np.testing.assert_array_equal(orc.argsort_desc(s), np.argsort(-s, kind="stable"))
+
+
+def test_argsort_zero_signs_tie(orc):
+    s = np.array([0.0, -0.0, 0.0, 1.0, -0.0], np.float32)
+    np.testing.assert_array_equal(orc.argsort_desc(s), [3, 0, 1, 2, 4])
+
+
+def test_gather_is_fancy_indexing(orc):
+    rng = np.random.default_rng(4)
+    W = rng.integers(0, 65535, size=(16, 24)).astype(np.uint16)
+    S = rng.random((16, 24)).astype(np.float32)
+    rp = rng.permutation(16).astype(np.int32)
+    cp = rng.permutation(24).astype(np.int32)
+    Wo, So = orc.gather(W, S, rp, cp)
+    np.testing.assert_array_equal(Wo, W[rp][:, cp])
+    np.testing.assert_array_equal(So, S[rp][:, cp])
+
+
+def test_reordered_layer_output_is_a_permutation_of_the_original(orc):
+    # W' (P_c x) = P_r (W x), exact with small integers (bf16 holds them exactly)
+    rng = np.random.default_rng(5)
+    R, C = 32, 48
+    Wf = rng.integers(-8, 9, size=(R, C)).astype(np.float32)
+    S = np.exp(rng.normal(size=(R, 1)) + rng.normal(size=(1, C))).astype(np.float32)
+    W = orc.f32_to_bf16(Wf)
+    np.testing.assert_array_equal(orc.bf16_to_f32(W), Wf)
+    rs, cs = orc.channel_scores(S)
+    rp, cp = orc.argsort_desc(rs), orc.argsort_desc(cs)
+    Wp, Sp = orc.gather(W, S, rp, cp)
+    x = rng.integers(-5, 6, size=C).astype(np.float32)
+    y = Wf @ x
+    yp = orc.bf16_to_f32(Wp) @ x[cp]
+    np.testing.assert_array_equal(yp, y[rp])
+    # sensitive channels first: scores of the reordered matrix are non-increasing
+    assert np.all(np.diff(rs[rp]) <= 0)
+    assert np.all(np.diff(cs[cp]) <= 0)
+    # the same channels, summed in the new element order: equal up to rounding
+    rs2, cs2 = orc.channel_scores(Sp)
+    np.testing.assert_allclose(rs2, rs[rp], rtol=1e-5)
+    np.testing.assert_allclose(cs2, cs[cp], rtol=1e-5)
+
+
+def test_bf16_helpers_round_to_nearest_even(orc):
+    # 1 + 2^-8 is halfway between bf16 neighbours 1 and 1 + 2^-7: ties to even -> 1
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5, 0.0], np.float32)
+    h = orc.f32_to_bf16(x)
+    np.testing.assert_array_equal(orc.bf16_to_f32(h), np.array([1.0, 1.0 + 2.0 ** -6, -2.5, 0.0], np.float32))
