@@ -1,0 +1,193 @@
+/*
+ * libscalebits -- the data-parallel hot path of ScaleBITS' global bitwidth
+ * allocation search (arXiv 2602.17698), hand-written HIP for gfx950 (MI355X).
+ *
+ * The calls follow the paper's statement of the problem (Sec. 2.1, Eq. 1): a
+ * partition of the weights into components, a candidate precision set, a
+ * budget B in bits per weight and a quantizer.  Weights, per-weight
+ * sensitivity, block shape, candidate bitwidths and budget go in;
+ * permutations, per-block bitwidths and packed codes with scales come out.
+ *
+ * General conventions
+ *   - Every tensor argument is DEVICE memory owned by the caller unless the
+ *     comment says HOST.  The library allocates no device memory; scratch is
+ *     the caller's workspace `ws` of sbits_workspace_bytes() bytes, 256-byte
+ *     aligned.  Calls that share a workspace must not overlap in time.
+ *   - All work is enqueued on the stream given to sbits_create() and the call
+ *     returns without waiting, except where stated (sbits_allocate and
+ *     sbits_search wait for the stream because they return host results).
+ *   - A weight matrix is rows x cols, row-major, rows = output channels,
+ *     cols = input channels (paper App. D); weights are bfloat16, sensitivities
+ *     are float32, non-negative and finite (NaN/Inf: results undefined).
+ *   - A block is block_rows x block_cols (m x n) of the REORDERED matrix and is
+ *     the unit of precision (paper Sec. 4.1).  The quantization group is one
+ *     block row: group size = block width (paper App. E, block size).  m and n
+ *     are powers of two, 8 <= m <= 1024, 8 <= n <= 512; rows % m == 0 and
+ *     cols % n == 0.
+ *   - Blocks are numbered globally: matrix after matrix in plan order, inside a
+ *     matrix row-major over the block grid: id = base(mat) + I*(cols/n) + J.
+ *   - Candidate bitwidths are strictly increasing integers in 1..8, at most 8
+ *     of them.  A "level" is an index into that list.
+ *   - Permutations are in gather form: reordered[i] = original[perm[i]].
+ *   - Return value: 0 (SBITS_OK) or a negative sbits_status; nothing throws or
+ *     aborts; outputs are undefined after an error.
+ */
+#ifndef SCALEBITS_H
+#define SCALEBITS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SBITS_OK                   =  0,
+    SBITS_ERR_INVALID_ARG      = -1,  /* null pointer, index out of range, misaligned workspace */
+    SBITS_ERR_BAD_SHAPE        = -2,  /* block shape not a supported power of two, or not dividing the matrix */
+    SBITS_ERR_BAD_BITWIDTHS    = -3,  /* empty, more than 8, not strictly increasing, outside 1..8 */
+    SBITS_ERR_INFEASIBLE_BUDGET= -4,  /* avg_bits below the smallest candidate */
+    SBITS_ERR_WORKSPACE        = -5,  /* reserved: workspace too small */
+    SBITS_ERR_MAX_ITERS        = -6,  /* search stopped by max_iters; levels are valid and within budget */
+    SBITS_ERR_HIP              = -7,  /* a HIP call failed; sbits_last_hip_error() has its code */
+    SBITS_ERR_UNIMPLEMENTED    = -8,
+    SBITS_ERR_CAPACITY         = -9   /* an output buffer (codes) is too small */
+} sbits_status;
+
+typedef struct sbits_ctx  sbits_ctx;    /* device + stream; small host state only           */
+typedef struct sbits_plan sbits_plan;   /* shapes, block numbering, candidate list (host)   */
+
+/* One weight matrix and its sensitivity. ld_* are row pitches in elements.  */
+typedef struct {
+    const void  *w_bf16;   /* DEVICE, rows x cols bfloat16                                   */
+    const float *sens;     /* DEVICE, rows x cols float32, element sensitivity (paper Eq. 3
+                              evaluated by the caller; static input here)                    */
+    int64_t rows, cols, ld_w, ld_s;
+} sbits_matrix;
+
+/* Hyper-parameters of the scalable greedy search (paper Algorithm 2, Sec. 5). */
+typedef struct {
+    double  gamma0;     /* initial update ratio, k = floor(gamma0*N); paper: 0.05            */
+    double  gammaT;     /* stop when k < floor(gammaT*N); paper: 0.02                         */
+    int32_t init_mode;  /* 0: warm start, every block at the largest candidate <= floor(B)
+                              (Alg. 2 line 2);  1: every block at the smallest candidate
+                              (Alg. 1 line 2)                                                 */
+    int32_t max_iters;  /* hard cap on loop iterations (>= 1)                                 */
+} sbits_params;
+
+typedef struct {
+    int32_t iters, expansions, swaps_ok, swaps_rej;
+    int64_t k_final;       /* batch size when the loop ended                                 */
+    int64_t bits_used;     /* sum over blocks of the chosen bitwidth                         */
+    int64_t bits_budget;   /* floor(avg_bits * N)  (Eq. 1, all blocks have equal size)       */
+    int64_t cost_fixed;    /* sum_i FX(cost[i][level_i]), FX(v) = rint(v * 2^cost_shift)     */
+    int32_t cost_shift;
+    int32_t pad_;
+} sbits_stats;
+
+/* One record per loop iteration of sbits_allocate (optional, for inspection). */
+typedef struct {
+    int32_t kind;          /* 0 expansion, 1 swap accepted, 2 swap rejected                  */
+    int32_t pad_;
+    int64_t k;
+    int64_t n_up, n_dn;    /* blocks raised / lowered (0 when rejected)                      */
+    int64_t p_up, p_dn;    /* sizes of the proposal                                          */
+    int64_t bits_before, bits_after;
+    int64_t delta_fixed;   /* swap: fixed-point cost change of the proposal                  */
+} sbits_trace;
+
+/* ---- context ---------------------------------------------------------------
+ * device >= 0: HIP device ordinal; hip_stream: a hipStream_t (NULL = the null
+ * stream).  device == -1 creates a host-only context: plans, sizes and argument
+ * validation work, every call that would touch the GPU returns SBITS_ERR_HIP.  */
+int  sbits_create (sbits_ctx **out, int device, void *hip_stream);
+int  sbits_destroy(sbits_ctx *ctx);
+int  sbits_last_hip_error(const sbits_ctx *ctx);
+const char *sbits_strerror(int status);
+
+/* ---- plan: the partition Pi_w (paper Sec. 2, Sec. 4.1) -----------------------
+ * rows/cols: HOST arrays of n_mats entries; bitwidths: HOST array of n_bits.    */
+int  sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, int n_mats,
+                       int block_rows, int block_cols, const int32_t *bitwidths, int n_bits,
+                       sbits_plan **out);
+int  sbits_plan_destroy(sbits_plan *plan);
+int64_t sbits_num_blocks(const sbits_plan *plan, int mat /* -1: all matrices */);
+int64_t sbits_block_base(const sbits_plan *plan, int mat);
+size_t  sbits_workspace_bytes(const sbits_plan *plan);
+/* upper bound on the packed size in bytes for a budget: floor(avg_bits*N)*m*n/8 */
+int64_t sbits_codes_bytes_bound(const sbits_plan *plan, double avg_bits);
+
+/* ---- bi-directional channel reordering (paper Sec. 4.1; per matrix) ----------
+ * Channel score = l1 norm of the channel's element sensitivities, summed in the
+ * canonical order (runs of 8 left to right, then an adjacent-pair tree, zero
+ * padded to a power of two); permutation = channels by score, descending, ties
+ * to the lower index.  row_perm[rows], col_perm[cols] out.  Uses ws.            */
+int  sbits_reorder(sbits_plan *plan, int mat, const sbits_matrix *M,
+                   int32_t *row_perm, int32_t *col_perm, void *ws);
+/* the scores alone: row_score[rows], col_score[cols] (float32).  Uses ws.       */
+int  sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M,
+                          float *row_score, float *col_score, void *ws);
+/* w_out[i][j] = W[row_perm[i]][col_perm[j]], s_out likewise; outputs are dense
+ * (pitch = cols) and must not alias the inputs.                                 */
+int  sbits_gather(sbits_plan *plan, int mat, const sbits_matrix *M,
+                  const int32_t *row_perm, const int32_t *col_perm,
+                  void *w_out_bf16, float *s_out);
+
+/* ---- block x bitwidth cost table (paper Sec. 5: RTN quantizer, group = block
+ * row; App. E: the exact re-quantized change that the surrogates approximate) --
+ * For every block of matrix `mat` and every candidate c_l:
+ *   cost[(base+b)*K + l] = sum over the block of s * (w - what_l)^2
+ * with what_l the asymmetric min-max round-to-nearest-even grid of 2^c_l levels
+ * on each block row (scale = range/qmax, origin = row minimum).  w_re, s_re are
+ * the dense reordered matrix (pitch = cols).  `cost` is the GLOBAL table [N][K];
+ * the call writes this matrix's rows only.  One HBM pass over w_re and s_re.    */
+int  sbits_cost_table(sbits_plan *plan, int mat, const void *w_re_bf16, const float *s_re,
+                      float *cost);
+
+/* ---- scalable greedy search (paper Algorithm 2 with the relaxed step Eq. 5) ---
+ * Runs on the device over the cost table: marginal change per bit from the
+ * table, radix selection of the top-k / bottom-k sets on (value, index) keys,
+ * budget prefix, fixed-point acceptance test.  level[N] out (uint8 candidate
+ * index).  host_stats (HOST, may be NULL) and trace (HOST, may be NULL, at most
+ * trace_cap records) are filled after the stream has been waited for.
+ * Returns SBITS_ERR_INFEASIBLE_BUDGET if avg_bits < smallest candidate,
+ * SBITS_ERR_MAX_ITERS if the cap ended the loop.  Uses ws.                      */
+int  sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits,
+                    const sbits_params *params, uint8_t *level,
+                    sbits_stats *host_stats, sbits_trace *host_trace, int64_t trace_cap,
+                    void *ws);
+
+/* ---- storage (paper Sec. 5.3: one bitwidth per tile) --------------------------
+ * byte_off[i] = sum_{i'<i} m*n*c[level[i']]/8, byte_off[N] = total.  Uses ws.   */
+int  sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws);
+/* Re-quantizes matrix `mat` at the chosen bitwidths and writes, for each of its
+ * blocks b (global id), the codes at codes[byte_off[b]...]: element e (row-major
+ * in the block) occupies bits [e*c, (e+1)*c) of the block's little-endian bit
+ * stream; scale[b*m + r], zero[b*m + r] for block row r (dequantized value =
+ * code*scale + zero).  level, byte_off, codes, scale, zero are the GLOBAL arrays.*/
+int  sbits_pack(sbits_plan *plan, int mat, const void *w_re_bf16, const uint8_t *level,
+                const int64_t *byte_off, uint8_t *codes, float *scale, float *zero);
+
+/* ---- the whole path in one call -------------------------------------------- */
+typedef struct {
+    int32_t *row_perm;     /* concatenated over matrices: sum(rows) entries                  */
+    int32_t *col_perm;     /* concatenated: sum(cols) entries                                */
+    void    *w_re_bf16;    /* reordered weights, matrices concatenated, each dense           */
+    float   *s_re;         /* reordered sensitivities, same layout                           */
+    float   *cost;         /* [N][K]                                                         */
+    uint8_t *level;        /* [N]                                                            */
+    int64_t *byte_off;     /* [N+1]                                                          */
+    uint8_t *codes;        /* codes_capacity bytes (>= sbits_codes_bytes_bound)              */
+    int64_t  codes_capacity;
+    float   *scale, *zero; /* [N*m] each                                                     */
+} sbits_outputs;
+/* mats: HOST array of the plan's n_mats matrices.  Waits for the stream.        */
+int  sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits,
+                  const sbits_params *params, const sbits_outputs *out,
+                  sbits_stats *host_stats, void *ws);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCALEBITS_H */

@@ -1,0 +1,511 @@
+// Scalable greedy bitwidth search (paper Algorithm 2, relaxed step Eq. 5) on the
+// block x bitwidth cost table, run on the device.
+//
+// Per iteration:
+//   gains   : marginal cost change per bit of raising / lowering every block,
+//             read off the table at the current levels (Alg. 2 line 5), encoded
+//             as 64-bit keys  [ordered value : 32][N-1-index : IB][step bits : 8]
+//             so that "larger key" = "earlier in (value, lower index first)".
+//   select  : radix descent, 8 bits per pass, over the keys: the longest prefix
+//             of the descending order that keeps count <= cnt_max and
+//             cumulative step bits <= w_max.  Each pass builds a count/weight
+//             histogram of the digits under the decided prefix; the workgroup
+//             that finishes last scans the 256 bins and fixes the next digit.
+//   expansion (Alg. 2 lines 6-7)  : top-k raised, capped by the remaining
+//             budget and by gain > 0.
+//   swap (Alg. 2 lines 9-12)      : top-k/2 raised, bottom-k/2 (outside the
+//             raised set) lowered; accepted iff the summed cost change, held in
+//             order-independent int64 fixed point, is strictly negative; on
+//             rejection k is halved.
+// All sums that decide anything are integers, so results do not depend on the
+// order in which atomics land.
+#include <math.h>
+#include <string.h>
+
+#include "sbits_internal.hpp"
+
+namespace sbits {
+
+constexpr int AL_THREADS = 256;
+constexpr int64_t TRACE_CAP = 16384;
+
+struct SelJob {
+    unsigned long long prefix;     // decided high digits, right aligned
+    long long cnt_above, w_above;  // totals of the keys above the current bucket
+    long long cnt_max, w_max;
+    unsigned long long key_min;    // keys below are never selected (0 = ineligible)
+    unsigned long long tau;        // result: selected <=> key >= tau
+    long long n_sel, w_sel;
+    int resolved;
+    unsigned int ticket;
+    unsigned int hist_cnt[256];
+    unsigned int hist_w[256];
+};
+
+enum { JOB_E = 0, JOB_U = 1, JOB_D = 2, JOB_U2 = 3, N_JOBS = 4 };
+enum { MODE_NONE = 0, MODE_EXPAND = 1, MODE_ACCEPT = 2, MODE_REJECT = 3 };
+
+struct AllocState {
+    long long N, T, k, kmin, used;
+    long long lossD, gainU;        // fixed-point sums of the current proposal
+    long long cost_fixed, bits_check;
+    int K, IB, P, shift;
+    int iters, max_iters, expansions, swaps_ok, swaps_rej;
+    int done, status, mode;
+    unsigned int maxc_bits;
+    int bits[8];
+    SelJob job[N_JOBS];
+};
+
+__device__ __forceinline__ unsigned int ord_f32(float f)
+{
+    const unsigned int u = __float_as_uint(f + 0.0f);          // -0 -> +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ long long fx(float v, int shift)
+{
+    const double p2 = __longlong_as_double((long long)(1023 + shift) << 52);
+    return __double2ll_rn((double)v * p2);
+}
+
+// ---- initialisation -------------------------------------------------------------
+__global__ void max_cost_kernel(const float *__restrict__ cost, long long n, AllocState *st)
+{
+    unsigned int mx = 0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x) {
+        const float v = cost[i];
+        if (v > 0.0f) mx = max(mx, __float_as_uint(v));
+    }
+    for (int off = 32; off; off >>= 1) mx = max(mx, (unsigned int)__shfl_xor((int)mx, off));
+    if ((threadIdx.x & 63) == 0 && mx) atomicMax(&st->maxc_bits, mx);
+}
+
+__global__ void init_state_kernel(AllocState *st, int ceil_log2_n)
+{
+    const unsigned int b = st->maxc_bits;
+    int shift = 0;
+    if (b) {
+        const int e = (int)(b >> 23);
+        const int ilog = e ? e - 127 : (31 - __clz((int)(b & 0x7fffffu))) - 149;
+        shift = 61 - ceil_log2_n - (ilog + 1);
+    }
+    st->shift = shift;
+}
+
+__global__ void fill_level_kernel(uint8_t *level, long long n, uint8_t v)
+{
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x)
+        level[i] = v;
+}
+
+// ---- gains ------------------------------------------------------------------------
+__device__ void job_reset(SelJob *j, long long cnt_max, long long w_max, unsigned long long key_min)
+{
+    j->prefix = 0; j->cnt_above = 0; j->w_above = 0;
+    j->cnt_max = cnt_max; j->w_max = w_max; j->key_min = key_min;
+    j->tau = ~0ull; j->n_sel = 0; j->w_sel = 0; j->resolved = 0;
+}
+
+__global__ __launch_bounds__(AL_THREADS)
+void gains_kernel(AllocState *st, const float *__restrict__ cost, const uint8_t *__restrict__ level,
+                  unsigned long long *__restrict__ keyU, unsigned long long *__restrict__ keyD)
+{
+    const long long N = st->N;
+    const int K = st->K, IB = st->IB;
+    int bits[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) bits[c] = st->bits[c];
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x) {
+        const int l = level[i];
+        const float *c = cost + i * K;
+        const float cl = c[l];
+        const unsigned long long low = (unsigned long long)(N - 1 - i) << 8;
+        unsigned long long ku = 0, kd = 0;
+        if (l < K - 1) {
+            const int step = bits[l + 1] - bits[l];
+            const float g = (cl - c[l + 1]) / (float)step;
+            ku = ((unsigned long long)ord_f32(g) << (IB + 8)) | low | (unsigned)step;
+        }
+        if (l > 0) {
+            const int step = bits[l] - bits[l - 1];
+            const float g = (c[l - 1] - cl) / (float)step;
+            kd = ((unsigned long long)(~ord_f32(g)) << (IB + 8)) | low | (unsigned)step;
+        }
+        keyU[i] = ku;
+        keyD[i] = kd;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const long long slack = st->T - st->used;
+        long long h = st->k / 2;
+        if (h < 1) h = 1;
+        const unsigned long long key_pos = (unsigned long long)0x80000001u << (IB + 8);  // value > +0
+        job_reset(&st->job[JOB_E], st->k, slack, key_pos);
+        job_reset(&st->job[JOB_U], h, 0x7fffffffffffffffll, 1);
+        job_reset(&st->job[JOB_D], h, 0x7fffffffffffffffll, 1);
+        st->mode = MODE_NONE;
+        st->lossD = 0;
+        st->gainU = 0;
+    }
+}
+
+// ---- one radix-descent pass ---------------------------------------------------------
+// excl != null: keys whose partner key excl[i] >= st->job[excl_job].tau are skipped.
+__global__ __launch_bounds__(AL_THREADS)
+void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__restrict__ keys,
+                        const unsigned long long *__restrict__ excl, int excl_job, int pass)
+{
+    SelJob *job = &st->job[job_id];
+    if (job->resolved) return;                                   // uniform over the grid
+    __shared__ unsigned int hc[256], hw[256];
+    __shared__ bool is_last;
+    hc[threadIdx.x] = 0;
+    hw[threadIdx.x] = 0;
+    __syncthreads();
+    const long long N = st->N;
+    const int P = st->P;
+    const unsigned long long prefix = job->prefix, key_min = job->key_min;
+    const unsigned long long excl_tau = excl ? st->job[excl_job].tau : 0;
+    const int sh_digit = 8 * (P - 1 - pass), sh_prefix = 8 * (P - pass);
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x) {
+        const unsigned long long key = keys[i];
+        if (key < key_min) continue;
+        if (excl && excl[i] >= excl_tau) continue;
+        const unsigned long long s = key >> 8;
+        const unsigned long long hi = sh_prefix >= 64 ? 0ull : (s >> sh_prefix);
+        if (hi != prefix) continue;
+        const unsigned int d = (unsigned int)(s >> sh_digit) & 255u;
+        atomicAdd(&hc[d], 1u);
+        atomicAdd(&hw[d], (unsigned int)(key & 255u));
+    }
+    __syncthreads();
+    if (hc[threadIdx.x]) {
+        atomicAdd(&job->hist_cnt[threadIdx.x], hc[threadIdx.x]);
+        atomicAdd(&job->hist_w[threadIdx.x], hw[threadIdx.x]);
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int t = atomicAdd(&job->ticket, 1u);
+        is_last = (t == gridDim.x - 1);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    // the last workgroup: read the finished histogram, clear it for the next pass
+    hc[threadIdx.x] = __hip_atomic_exchange(&job->hist_cnt[threadIdx.x], 0u, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+    hw[threadIdx.x] = __hip_atomic_exchange(&job->hist_w[threadIdx.x], 0u, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        job->ticket = 0;
+        long long c = job->cnt_above, w = job->w_above;
+        int boundary = -1;
+        for (int b = 255; b >= 0; --b) {
+            const long long bc = hc[b], bw = hw[b];
+            if (!bc) continue;
+            if (c + bc <= job->cnt_max && w + bw <= job->w_max) { c += bc; w += bw; }
+            else { boundary = b; break; }
+        }
+        if (boundary < 0) {
+            // every key under the prefix fits: the selection ends at the bucket's lower edge
+            unsigned long long lo = sh_prefix >= 56 ? 0ull : ((prefix << sh_prefix) << 8);
+            job->tau = lo > key_min ? lo : key_min;
+            job->n_sel = c; job->w_sel = w; job->resolved = 1;
+        } else {
+            const unsigned long long np = (prefix << 8) | (unsigned long long)boundary;
+            job->cnt_above = c; job->w_above = w;
+            if (pass == P - 1) {
+                // a single key that does not fit: select the keys strictly above it
+                job->tau = (np + 1) << 8;
+                job->n_sel = c; job->w_sel = w; job->resolved = 1;
+            } else {
+                job->prefix = np;
+            }
+        }
+    }
+}
+
+// ---- expansion ----------------------------------------------------------------------
+__device__ void trace_write(sbits_trace *tr, int it, int kind, long long k, long long n_up, long long n_dn,
+                            long long p_up, long long p_dn, long long before, long long after, long long delta)
+{
+    if (it >= TRACE_CAP) return;
+    sbits_trace &t = tr[it];
+    t.kind = kind; t.pad_ = 0; t.k = k; t.n_up = n_up; t.n_dn = n_dn; t.p_up = p_up; t.p_dn = p_dn;
+    t.bits_before = before; t.bits_after = after; t.delta_fixed = delta;
+}
+
+__device__ void finish_iteration(AllocState *st)
+{
+    st->iters++;
+    if (st->k < st->kmin) { st->done = 1; }
+    else if (st->iters >= st->max_iters) { st->done = 1; st->status = SBITS_ERR_MAX_ITERS; }
+}
+
+__global__ void decide_expand_kernel(AllocState *st, sbits_trace *tr)
+{
+    const SelJob &e = st->job[JOB_E];
+    if (st->T - st->used > 0 && e.n_sel > 0) {
+        st->mode = MODE_EXPAND;
+        trace_write(tr, st->iters, 0, st->k, e.n_sel, 0, e.n_sel, 0, st->used, st->used + e.w_sel, 0);
+        st->used += e.w_sel;
+        st->expansions++;
+        finish_iteration(st);
+    }
+}
+
+__global__ __launch_bounds__(AL_THREADS)
+void apply_expand_kernel(const AllocState *st, const unsigned long long *__restrict__ keyU,
+                         uint8_t *__restrict__ level)
+{
+    if (st->mode != MODE_EXPAND) return;
+    const unsigned long long tau = st->job[JOB_E].tau;
+    const long long N = st->N;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x)
+        if (keyU[i] >= tau) level[i] = level[i] + 1;
+}
+
+// ---- swap -----------------------------------------------------------------------------
+// after U and D are known: the raised set is the prefix of U that fits slack + freed bits
+__global__ void prep_u2_kernel(AllocState *st)
+{
+    const SelJob &u = st->job[JOB_U];
+    const SelJob &d = st->job[JOB_D];
+    long long h = st->k / 2;
+    if (h < 1) h = 1;
+    const long long w_max = (st->T - st->used) + d.w_sel;
+    SelJob *j = &st->job[JOB_U2];
+    job_reset(j, h, w_max, 1);
+    if (u.w_sel <= w_max) {           // all of U fits
+        j->tau = u.tau; j->n_sel = u.n_sel; j->w_sel = u.w_sel; j->resolved = 1;
+    }
+}
+
+__global__ __launch_bounds__(AL_THREADS)
+void eval_swap_kernel(AllocState *st, const float *__restrict__ cost, const uint8_t *__restrict__ level,
+                      const unsigned long long *__restrict__ keyU, const unsigned long long *__restrict__ keyD)
+{
+    __shared__ long long sl[AL_THREADS / 64], sg[AL_THREADS / 64];
+    const long long N = st->N;
+    const int K = st->K, shift = st->shift;
+    const unsigned long long tauU = st->job[JOB_U].tau, tauD = st->job[JOB_D].tau, tauU2 = st->job[JOB_U2].tau;
+    long long loss = 0, gain = 0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x) {
+        const unsigned long long ku = keyU[i], kd = keyD[i];
+        const bool up = ku >= tauU2;
+        const bool dn = kd >= tauD && !(ku >= tauU);
+        if (up || dn) {
+            const int l = level[i];
+            const float *c = cost + i * K;
+            if (up) gain += fx(c[l] - c[l + 1], shift);
+            if (dn) loss += fx(c[l - 1] - c[l], shift);
+        }
+    }
+    for (int off = 32; off; off >>= 1) {
+        loss += __shfl_xor(loss, off);
+        gain += __shfl_xor(gain, off);
+    }
+    const int wv = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { sl[wv] = loss; sg[wv] = gain; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long a = 0, b = 0;
+        for (int w = 0; w < AL_THREADS / 64; ++w) { a += sl[w]; b += sg[w]; }
+        if (a) atomicAdd((unsigned long long *)&st->lossD, (unsigned long long)a);
+        if (b) atomicAdd((unsigned long long *)&st->gainU, (unsigned long long)b);
+    }
+}
+
+__global__ void decide_swap_kernel(AllocState *st, sbits_trace *tr)
+{
+    const SelJob &u2 = st->job[JOB_U2];
+    const SelJob &d = st->job[JOB_D];
+    const long long delta = st->lossD - st->gainU;
+    if (u2.n_sel > 0 && d.n_sel > 0 && delta < 0) {
+        st->mode = MODE_ACCEPT;
+        trace_write(tr, st->iters, 1, st->k, u2.n_sel, d.n_sel, u2.n_sel, d.n_sel, st->used,
+                    st->used + u2.w_sel - d.w_sel, delta);
+        st->used += u2.w_sel - d.w_sel;
+        st->swaps_ok++;
+    } else {
+        st->mode = MODE_REJECT;
+        trace_write(tr, st->iters, 2, st->k, 0, 0, u2.n_sel, d.n_sel, st->used, st->used, delta);
+        st->k = st->k / 2;
+        st->swaps_rej++;
+    }
+    finish_iteration(st);
+}
+
+__global__ __launch_bounds__(AL_THREADS)
+void apply_swap_kernel(const AllocState *st, const unsigned long long *__restrict__ keyU,
+                       const unsigned long long *__restrict__ keyD, uint8_t *__restrict__ level)
+{
+    if (st->mode != MODE_ACCEPT) return;
+    const unsigned long long tauU = st->job[JOB_U].tau, tauD = st->job[JOB_D].tau, tauU2 = st->job[JOB_U2].tau;
+    const long long N = st->N;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x) {
+        const unsigned long long ku = keyU[i], kd = keyD[i];
+        if (ku >= tauU2) level[i] = level[i] + 1;
+        else if (kd >= tauD && !(ku >= tauU)) level[i] = level[i] - 1;
+    }
+}
+
+// ---- final statistics ---------------------------------------------------------------------
+__global__ __launch_bounds__(AL_THREADS)
+void final_stats_kernel(AllocState *st, const float *__restrict__ cost, const uint8_t *__restrict__ level)
+{
+    __shared__ long long sa[AL_THREADS / 64], sb[AL_THREADS / 64];
+    const long long N = st->N;
+    const int K = st->K, shift = st->shift;
+    long long cf = 0, bu = 0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x) {
+        const int l = level[i];
+        cf += fx(cost[i * K + l], shift);
+        bu += st->bits[l];
+    }
+    for (int off = 32; off; off >>= 1) { cf += __shfl_xor(cf, off); bu += __shfl_xor(bu, off); }
+    const int wv = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { sa[wv] = cf; sb[wv] = bu; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long a = 0, b = 0;
+        for (int w = 0; w < AL_THREADS / 64; ++w) { a += sa[w]; b += sb[w]; }
+        atomicAdd((unsigned long long *)&st->cost_fixed, (unsigned long long)a);
+        atomicAdd((unsigned long long *)&st->bits_check, (unsigned long long)b);
+    }
+}
+
+static int ceil_log2_ll(long long v) { int p = 0; while ((1ll << p) < v) ++p; return p; }
+
+}  // namespace sbits
+
+using namespace sbits;
+
+// workspace: AllocState | keyU [N] | keyD [N] | trace [TRACE_CAP]
+size_t sbits_alloc_ws_bytes(int64_t N)
+{
+    size_t b = sbits_align_up(sizeof(AllocState), 256);
+    b += 2 * sbits_align_up((size_t)N * 8, 256);
+    b += sbits_align_up((size_t)TRACE_CAP * sizeof(sbits_trace), 256);
+    return b;
+}
+
+int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
+                       const sbits_params *prm, uint8_t *level, sbits_stats *host_stats,
+                       sbits_trace *host_trace, int64_t trace_cap, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    hipStream_t sm = ctx->stream;
+    const int64_t N = plan->N;
+    const int K = plan->K;
+    if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
+
+    char *p = static_cast<char *>(ws);
+    AllocState *st = reinterpret_cast<AllocState *>(p);
+    p += sbits_align_up(sizeof(AllocState), 256);
+    unsigned long long *keyU = reinterpret_cast<unsigned long long *>(p);
+    p += sbits_align_up((size_t)N * 8, 256);
+    unsigned long long *keyD = reinterpret_cast<unsigned long long *>(p);
+    p += sbits_align_up((size_t)N * 8, 256);
+    sbits_trace *tr = reinterpret_cast<sbits_trace *>(p);
+
+    static AllocState h;                       // host image
+    memset(&h, 0, sizeof h);
+    h.N = N;
+    h.T = (long long)floor(avg_bits * (double)N);
+    h.k = (long long)floor(prm->gamma0 * (double)N);
+    h.kmin = (long long)floor(prm->gammaT * (double)N);
+    if (h.k < 1) h.k = 1;
+    if (h.kmin < 1) h.kmin = 1;
+    h.K = K;
+    h.IB = ceil_log2_ll(N) > 0 ? ceil_log2_ll(N) : 1;
+    h.P = (32 + h.IB + 7) / 8;
+    h.max_iters = prm->max_iters;
+    for (int c = 0; c < 8; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
+
+    const bool all_max = avg_bits >= (double)plan->bits[K - 1];
+    int l0 = 0;
+    if (all_max) l0 = K - 1;
+    else if (prm->init_mode == 0) {
+        const double fb = floor(avg_bits);
+        for (int l = 0; l < K; ++l) if ((double)plan->bits[l] <= fb) l0 = l;
+    }
+    h.used = N * (long long)plan->bits[l0];
+    if (all_max) h.done = 1;
+
+    const unsigned grid = (unsigned)((N + AL_THREADS - 1) / AL_THREADS < 1024 ? (N + AL_THREADS - 1) / AL_THREADS : 1024);
+    SBITS_HIP(ctx, hipMemcpyAsync(st, &h, sizeof h, hipMemcpyHostToDevice, sm));
+    SBITS_HIP(ctx, hipStreamSynchronize(sm));  // h is reused below
+    hipLaunchKernelGGL(max_cost_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, cost, (long long)(N * K), st);
+    hipLaunchKernelGGL(init_state_kernel, dim3(1), dim3(1), 0, sm, st, ceil_log2_ll(N));
+    hipLaunchKernelGGL(fill_level_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, level, (long long)N, (uint8_t)l0);
+    SBITS_HIP(ctx, hipGetLastError());
+
+    long long used = h.used;
+    bool done = all_max;
+    const int P = h.P;
+    while (!done) {
+        hipLaunchKernelGGL(gains_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level, keyU, keyD);
+        bool expanded = false;
+        if (h.T - used > 0) {
+            for (int ps = 0; ps < P; ++ps)
+                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_E, keyU,
+                                   (const unsigned long long *)nullptr, 0, ps);
+            hipLaunchKernelGGL(decide_expand_kernel, dim3(1), dim3(1), 0, sm, st, tr);
+            hipLaunchKernelGGL(apply_expand_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, level);
+            SBITS_HIP(ctx, hipGetLastError());
+            SBITS_HIP(ctx, hipMemcpyAsync(&h, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+            SBITS_HIP(ctx, hipStreamSynchronize(sm));
+            expanded = h.mode == MODE_EXPAND;
+        }
+        if (!expanded) {
+            for (int ps = 0; ps < P; ++ps)
+                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U, keyU,
+                                   (const unsigned long long *)nullptr, 0, ps);
+            for (int ps = 0; ps < P; ++ps)
+                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_D, keyD,
+                                   (const unsigned long long *)keyU, (int)JOB_U, ps);
+            hipLaunchKernelGGL(prep_u2_kernel, dim3(1), dim3(1), 0, sm, st);
+            for (int ps = 0; ps < P; ++ps)
+                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U2, keyU,
+                                   (const unsigned long long *)nullptr, 0, ps);
+            hipLaunchKernelGGL(eval_swap_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level, keyU, keyD);
+            hipLaunchKernelGGL(decide_swap_kernel, dim3(1), dim3(1), 0, sm, st, tr);
+            hipLaunchKernelGGL(apply_swap_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, keyD, level);
+            SBITS_HIP(ctx, hipGetLastError());
+            SBITS_HIP(ctx, hipMemcpyAsync(&h, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+            SBITS_HIP(ctx, hipStreamSynchronize(sm));
+        }
+        used = h.used;
+        done = h.done != 0;
+    }
+
+    hipLaunchKernelGGL(final_stats_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level);
+    SBITS_HIP(ctx, hipGetLastError());
+    SBITS_HIP(ctx, hipMemcpyAsync(&h, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+    SBITS_HIP(ctx, hipStreamSynchronize(sm));
+    if (host_stats) {
+        host_stats->iters = h.iters; host_stats->expansions = h.expansions;
+        host_stats->swaps_ok = h.swaps_ok; host_stats->swaps_rej = h.swaps_rej;
+        host_stats->k_final = h.k; host_stats->bits_used = h.bits_check; host_stats->bits_budget = h.T;
+        host_stats->cost_fixed = h.cost_fixed; host_stats->cost_shift = h.shift; host_stats->pad_ = 0;
+    }
+    if (host_trace && trace_cap > 0 && h.iters > 0) {
+        int64_t nrec = h.iters < trace_cap ? h.iters : trace_cap;
+        if (nrec > TRACE_CAP) nrec = TRACE_CAP;
+        SBITS_HIP(ctx, hipMemcpyAsync(host_trace, tr, (size_t)nrec * sizeof(sbits_trace), hipMemcpyDeviceToHost, sm));
+        SBITS_HIP(ctx, hipStreamSynchronize(sm));
+    }
+    if (h.bits_check != h.used) return SBITS_ERR_INVALID_ARG;   // internal accounting must agree
+    return h.status;
+}

@@ -1,0 +1,288 @@
+// C-ABI entry points of libscalebits: argument validation, plan bookkeeping and
+// the sequencing of the kernel stages.  No arithmetic of the method lives here.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+
+#include "sbits_internal.hpp"
+
+static bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+extern "C" {
+
+const char *sbits_strerror(int status)
+{
+    switch (status) {
+    case SBITS_OK: return "ok";
+    case SBITS_ERR_INVALID_ARG: return "invalid argument";
+    case SBITS_ERR_BAD_SHAPE: return "unsupported or non-dividing block shape";
+    case SBITS_ERR_BAD_BITWIDTHS: return "bad candidate bitwidth list";
+    case SBITS_ERR_INFEASIBLE_BUDGET: return "budget below the smallest candidate bitwidth";
+    case SBITS_ERR_WORKSPACE: return "workspace too small";
+    case SBITS_ERR_MAX_ITERS: return "search stopped by max_iters";
+    case SBITS_ERR_HIP: return "HIP runtime error";
+    case SBITS_ERR_UNIMPLEMENTED: return "not implemented";
+    case SBITS_ERR_CAPACITY: return "output buffer too small";
+    }
+    return "unknown status";
+}
+
+int sbits_create(sbits_ctx **out, int device, void *hip_stream)
+{
+    if (!out || device < -1) return SBITS_ERR_INVALID_ARG;
+    sbits_ctx *c = new (std::nothrow) sbits_ctx;
+    if (!c) return SBITS_ERR_INVALID_ARG;
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->last_hip = 0;
+    if (device >= 0) {
+        hipError_t e = hipSetDevice(device);
+        if (e != hipSuccess) { c->last_hip = (int)e; delete c; return SBITS_ERR_HIP; }
+    }
+    *out = c;
+    return SBITS_OK;
+}
+
+int sbits_destroy(sbits_ctx *ctx)
+{
+    if (!ctx) return SBITS_ERR_INVALID_ARG;
+    delete ctx;
+    return SBITS_OK;
+}
+
+int sbits_last_hip_error(const sbits_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, int n_mats,
+                      int block_rows, int block_cols, const int32_t *bitwidths, int n_bits,
+                      sbits_plan **out)
+{
+    if (!ctx || !rows || !cols || n_mats <= 0 || !out || !bitwidths) return SBITS_ERR_INVALID_ARG;
+    if (n_bits <= 0 || n_bits > 8) return SBITS_ERR_BAD_BITWIDTHS;
+    for (int l = 0; l < n_bits; ++l) {
+        if (bitwidths[l] < 1 || bitwidths[l] > 8) return SBITS_ERR_BAD_BITWIDTHS;
+        if (l && bitwidths[l] <= bitwidths[l - 1]) return SBITS_ERR_BAD_BITWIDTHS;
+    }
+    if (!is_pow2(block_rows) || !is_pow2(block_cols) || block_rows < 8 || block_rows > 1024 ||
+        block_cols < 8 || block_cols > 512)
+        return SBITS_ERR_BAD_SHAPE;
+    sbits_plan *p = new (std::nothrow) sbits_plan;
+    if (!p) return SBITS_ERR_INVALID_ARG;
+    p->ctx = ctx;
+    p->n_mats = n_mats;
+    p->m = block_rows;
+    p->n = block_cols;
+    p->K = n_bits;
+    for (int l = 0; l < 8; ++l) p->bits[l] = l < n_bits ? bitwidths[l] : 0;
+    p->N = 0;
+    p->max_rows = p->max_cols = 0;
+    for (int i = 0; i < n_mats; ++i) {
+        if (rows[i] <= 0 || cols[i] <= 0 || rows[i] % block_rows || cols[i] % block_cols ||
+            rows[i] > 0x7fffffff || cols[i] > 32768 || rows[i] > 2097120) {
+            delete p;
+            return SBITS_ERR_BAD_SHAPE;
+        }
+        p->rows.push_back(rows[i]);
+        p->cols.push_back(cols[i]);
+        p->base.push_back(p->N);
+        p->N += (rows[i] / block_rows) * (cols[i] / block_cols);
+        if (rows[i] > p->max_rows) p->max_rows = rows[i];
+        if (cols[i] > p->max_cols) p->max_cols = cols[i];
+    }
+    if (p->N > (1ll << 24)) { delete p; return SBITS_ERR_BAD_SHAPE; }   // index field of the selection keys
+    size_t ws = sbits_score_ws_bytes(p->max_rows, p->max_cols);
+    const size_t a = sbits_alloc_ws_bytes(p->N), o = sbits_offsets_ws_bytes(p->N);
+    if (a > ws) ws = a;
+    if (o > ws) ws = o;
+    p->ws_bytes = ws;
+    *out = p;
+    return SBITS_OK;
+}
+
+int sbits_plan_destroy(sbits_plan *plan)
+{
+    if (!plan) return SBITS_ERR_INVALID_ARG;
+    delete plan;
+    return SBITS_OK;
+}
+
+int64_t sbits_num_blocks(const sbits_plan *plan, int mat)
+{
+    if (!plan || mat < -1 || mat >= plan->n_mats) return SBITS_ERR_INVALID_ARG;
+    if (mat < 0) return plan->N;
+    return (plan->rows[mat] / plan->m) * (plan->cols[mat] / plan->n);
+}
+
+int64_t sbits_block_base(const sbits_plan *plan, int mat)
+{
+    if (!plan || mat < 0 || mat >= plan->n_mats) return SBITS_ERR_INVALID_ARG;
+    return plan->base[mat];
+}
+
+size_t sbits_workspace_bytes(const sbits_plan *plan) { return plan ? plan->ws_bytes : 0; }
+
+int64_t sbits_codes_bytes_bound(const sbits_plan *plan, double avg_bits)
+{
+    if (!plan || !(avg_bits >= 0)) return SBITS_ERR_INVALID_ARG;
+    double b = avg_bits;
+    if (b > plan->bits[plan->K - 1]) b = plan->bits[plan->K - 1];
+    const int64_t T = (int64_t)floor(b * (double)plan->N);
+    return T * ((int64_t)plan->m * plan->n / 8);
+}
+
+static int check_matrix(const sbits_plan *plan, int mat, const sbits_matrix *M, bool need_w, bool need_s)
+{
+    if (!plan || !M || mat < 0 || mat >= plan->n_mats) return SBITS_ERR_INVALID_ARG;
+    if (M->rows != plan->rows[mat] || M->cols != plan->cols[mat]) return SBITS_ERR_BAD_SHAPE;
+    if (need_w && (!M->w_bf16 || M->ld_w < M->cols || (M->ld_w % 8) || !aligned16(M->w_bf16)))
+        return SBITS_ERR_INVALID_ARG;
+    if (need_s && (!M->sens || M->ld_s < M->cols || (M->ld_s % 4) || !aligned16(M->sens)))
+        return SBITS_ERR_INVALID_ARG;
+    return SBITS_OK;
+}
+
+static int need_device(const sbits_plan *plan)
+{
+    if (plan->ctx->device < 0) return SBITS_ERR_HIP;
+    return SBITS_OK;
+}
+
+static bool ws_ok(const void *ws) { return ws && (reinterpret_cast<uintptr_t>(ws) & 255) == 0; }
+
+// workspace slices used by reorder: [score partials ...][rank][rs][cs] (see reorder.hip)
+static void reorder_slices(const sbits_plan *plan, int64_t R, int64_t C, void *ws, int **rank,
+                           float **rs, float **cs)
+{
+    const int64_t nseg = (C + 511) / 512, nband = (R + 31) / 32;
+    char *p = static_cast<char *>(ws);
+    p += sbits_align_up((size_t)(R * nseg) * 4, 256);
+    p += sbits_align_up((size_t)(nband * C) * 4, 256);
+    *rank = reinterpret_cast<int *>(p);
+    p += sbits_align_up((size_t)(R > C ? R : C) * 4, 256);
+    *rs = reinterpret_cast<float *>(p);
+    p += sbits_align_up((size_t)R * 4, 256);
+    *cs = reinterpret_cast<float *>(p);
+    (void)plan;
+}
+
+int sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M, float *row_score,
+                         float *col_score, void *ws)
+{
+    int rc = check_matrix(plan, mat, M, false, true);
+    if (rc) return rc;
+    if (!row_score || !col_score || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if ((rc = need_device(plan))) return rc;
+    return sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, row_score, col_score, ws);
+}
+
+int sbits_reorder(sbits_plan *plan, int mat, const sbits_matrix *M, int32_t *row_perm,
+                  int32_t *col_perm, void *ws)
+{
+    int rc = check_matrix(plan, mat, M, false, true);
+    if (rc) return rc;
+    if (!row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if ((rc = need_device(plan))) return rc;
+    int *rank;
+    float *rs, *cs;
+    reorder_slices(plan, M->rows, M->cols, ws, &rank, &rs, &cs);
+    if ((rc = sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, rs, cs, ws))) return rc;
+    if ((rc = sbits_launch_argsort(plan->ctx, rs, M->rows, row_perm, rank))) return rc;
+    return sbits_launch_argsort(plan->ctx, cs, M->cols, col_perm, rank);
+}
+
+int sbits_gather(sbits_plan *plan, int mat, const sbits_matrix *M, const int32_t *row_perm,
+                 const int32_t *col_perm, void *w_out_bf16, float *s_out)
+{
+    int rc = check_matrix(plan, mat, M, w_out_bf16 != nullptr, s_out != nullptr);
+    if (rc) return rc;
+    if (!row_perm || !col_perm || (!w_out_bf16 && !s_out) || !aligned16(col_perm) ||
+        !aligned16(w_out_bf16) || !aligned16(s_out))
+        return SBITS_ERR_INVALID_ARG;
+    if (w_out_bf16 == M->w_bf16 || (const void *)s_out == (const void *)M->sens) return SBITS_ERR_INVALID_ARG;
+    if ((rc = need_device(plan))) return rc;
+    return sbits_launch_gather(plan->ctx, M->w_bf16, M->sens, M->rows, M->cols, M->ld_w, M->ld_s,
+                               row_perm, col_perm, w_out_bf16, s_out);
+}
+
+int sbits_cost_table(sbits_plan *plan, int mat, const void *w_re_bf16, const float *s_re, float *cost)
+{
+    if (!plan || mat < 0 || mat >= plan->n_mats || !w_re_bf16 || !s_re || !cost) return SBITS_ERR_INVALID_ARG;
+    if (!aligned16(w_re_bf16) || !aligned16(s_re)) return SBITS_ERR_INVALID_ARG;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_launch_cost(plan->ctx, w_re_bf16, s_re, plan->rows[mat], plan->cols[mat], plan->m, plan->n,
+                             plan->bits, plan->K, cost + plan->base[mat] * plan->K);
+}
+
+int sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits, const sbits_params *params,
+                   uint8_t *level, sbits_stats *host_stats, sbits_trace *host_trace, int64_t trace_cap,
+                   void *ws)
+{
+    if (!plan || !cost || !params || !level || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!(params->gamma0 >= 0) || !(params->gammaT >= 0) || params->max_iters < 1 ||
+        (params->init_mode != 0 && params->init_mode != 1) || !(avg_bits == avg_bits))
+        return SBITS_ERR_INVALID_ARG;
+    if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_run_allocate(plan, cost, avg_bits, params, level, host_stats, host_trace, trace_cap, ws);
+}
+
+int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws)
+{
+    if (!plan || !level || !byte_off || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_launch_offsets(plan->ctx, level, plan->N, plan->m, plan->n, plan->bits, plan->K, byte_off, ws);
+}
+
+int sbits_pack(sbits_plan *plan, int mat, const void *w_re_bf16, const uint8_t *level,
+               const int64_t *byte_off, uint8_t *codes, float *scale, float *zero)
+{
+    if (!plan || mat < 0 || mat >= plan->n_mats || !w_re_bf16 || !level || !byte_off || !codes || !scale || !zero)
+        return SBITS_ERR_INVALID_ARG;
+    if (!aligned16(w_re_bf16) || !aligned16(codes)) return SBITS_ERR_INVALID_ARG;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_launch_pack(plan->ctx, w_re_bf16, plan->rows[mat], plan->cols[mat], plan->m, plan->n,
+                             plan->bits, plan->K, level, byte_off, plan->base[mat], codes, scale, zero);
+}
+
+int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, const sbits_params *params,
+                 const sbits_outputs *out, sbits_stats *host_stats, void *ws)
+{
+    if (!plan || !mats || !params || !out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!out->row_perm || !out->col_perm || !out->w_re_bf16 || !out->s_re || !out->cost || !out->level ||
+        !out->byte_off || !out->codes || !out->scale || !out->zero)
+        return SBITS_ERR_INVALID_ARG;
+    if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
+    if (out->codes_capacity < sbits_codes_bytes_bound(plan, avg_bits)) return SBITS_ERR_CAPACITY;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    int64_t roff = 0, coff = 0, eoff = 0;
+    for (int i = 0; i < plan->n_mats; ++i) {
+        const sbits_matrix *M = &mats[i];
+        int32_t *rp = out->row_perm + roff, *cp = out->col_perm + coff;
+        uint16_t *w_re = static_cast<uint16_t *>(out->w_re_bf16) + eoff;
+        float *s_re = out->s_re + eoff;
+        if ((rc = sbits_reorder(plan, i, M, rp, cp, ws))) return rc;
+        if ((rc = sbits_gather(plan, i, M, rp, cp, w_re, s_re))) return rc;
+        if ((rc = sbits_cost_table(plan, i, w_re, s_re, out->cost))) return rc;
+        roff += M->rows; coff += M->cols; eoff += M->rows * M->cols;
+    }
+    rc = sbits_allocate(plan, out->cost, avg_bits, params, out->level, host_stats, nullptr, 0, ws);
+    const int alloc_rc = rc;
+    if (rc && rc != SBITS_ERR_MAX_ITERS) return rc;
+    if ((rc = sbits_offsets(plan, out->level, out->byte_off, ws))) return rc;
+    eoff = 0;
+    for (int i = 0; i < plan->n_mats; ++i) {
+        const uint16_t *w_re = static_cast<const uint16_t *>(out->w_re_bf16) + eoff;
+        if ((rc = sbits_pack(plan, i, w_re, out->level, out->byte_off, out->codes, out->scale, out->zero))) return rc;
+        eoff += mats[i].rows * mats[i].cols;
+    }
+    SBITS_HIP(plan->ctx, hipStreamSynchronize(plan->ctx->stream));
+    return alloc_rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Device helpers for gfx950: cross-lane exchange inside a lane group, the
+// quantization-grid constants and the bf16 unpack.  A "lane group" is LPG
+// adjacent lanes (LPG a power of two, 1..64) that together own one
+// quantization group of LPG*8 consecutive weights.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sbits {
+
+// ---- DPP within a row of 16 lanes ------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+
+constexpr int DPP_XOR1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i <-> 7-i inside each 8 lanes
+constexpr int DPP_MIRROR = 0x140;       // lane i <-> 15-i inside each 16 lanes
+constexpr int DPP_BCAST0 = 0x150;       // row_newbcast:0 (+n for lane n of the row)
+
+// Butterfly all-reduce over the LPG lanes of a group.  The exchange pattern is
+// an adjacent-pair tree (lanes 2j,2j+1, then pairs of pairs, ...): after the
+// quad steps all lanes of a quad agree, so the mirror steps pair quads and
+// halves exactly as xor 4 / xor 8 would.  Every lane ends with the same bits.
+template <int LPG, class Op>
+__device__ __forceinline__ float group_allreduce(float v, Op op)
+{
+    if (LPG >= 2)  v = op(v, dpp_mov<DPP_XOR1>(v));
+    if (LPG >= 4)  v = op(v, dpp_mov<DPP_XOR2>(v));
+    if (LPG >= 8)  v = op(v, dpp_mov<DPP_HALF_MIRROR>(v));
+    if (LPG >= 16) v = op(v, dpp_mov<DPP_MIRROR>(v));
+    if (LPG >= 32) v = op(v, __shfl_xor(v, 16));
+    if (LPG >= 64) v = op(v, __shfl_xor(v, 32));
+    return v;
+}
+
+struct OpAdd { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+struct OpMin { __device__ __forceinline__ float operator()(float a, float b) const { return fminf(a, b); } };
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
+
+// value held by lane J of the caller's lane group
+template <int LPG, int J>
+__device__ __forceinline__ float group_bcast(float v)
+{
+    if (LPG == 1) return v;
+    if (LPG == 16) return dpp_mov<DPP_BCAST0 + (J & 15)>(v);
+    const int lane = (int)(threadIdx.x & 63);
+    return __shfl(v, (lane & ~(LPG - 1)) + J);
+}
+
+// ---- quantization grid constants, one set per candidate ---------------------
+struct GridConsts {
+    float qmaxf[8];   // 2^c - 1
+    float thr[8];     // smallest range R for which qmax / R is finite
+    int   bits[8];
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// 8 consecutive bf16 (one 128-bit load) -> 8 floats, element order preserved
+__device__ __forceinline__ void unpack8(const uint4 &p, float (&w)[8])
+{
+    w[0] = bf16_lo(p.x); w[1] = bf16_hi(p.x);
+    w[2] = bf16_lo(p.y); w[3] = bf16_hi(p.y);
+    w[4] = bf16_lo(p.z); w[5] = bf16_hi(p.z);
+    w[6] = bf16_lo(p.w); w[7] = bf16_hi(p.w);
+}
+
+}  // namespace sbits

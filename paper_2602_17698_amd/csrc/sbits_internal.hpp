@@ -1,0 +1,60 @@
+// Internal declarations shared by the translation units of libscalebits.
+// Host-side plan/context state and the launch entry of every kernel stage.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include <vector>
+
+#include "scalebits.h"
+
+struct sbits_ctx {
+    int device;            // -1: host-only context
+    hipStream_t stream;
+    int last_hip;
+};
+
+struct sbits_plan {
+    sbits_ctx *ctx;
+    int n_mats;
+    std::vector<int64_t> rows, cols, base;   // base[mat] = first global block id
+    int m, n, K;
+    int32_t bits[8];
+    int64_t N;                               // total blocks
+    int64_t max_rows, max_cols;
+    size_t ws_bytes;
+};
+
+#define SBITS_HIP(ctx, expr)                                                   \
+    do {                                                                       \
+        hipError_t e_ = (expr);                                                \
+        if (e_ != hipSuccess) { (ctx)->last_hip = (int)e_; return SBITS_ERR_HIP; } \
+    } while (0)
+
+static inline size_t sbits_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- stage launchers (each returns an sbits_status) ------------------------
+
+// workspace sizes in bytes
+size_t sbits_score_ws_bytes(int64_t max_rows, int64_t max_cols);
+size_t sbits_alloc_ws_bytes(int64_t N);
+size_t sbits_offsets_ws_bytes(int64_t N);
+
+int sbits_launch_scores(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, int64_t ld,
+                        float *row_score, float *col_score, void *ws);
+int sbits_launch_argsort(sbits_ctx *ctx, const float *score, int64_t n, int32_t *perm, void *ws_rank);
+int sbits_launch_gather(sbits_ctx *ctx, const void *W, const float *S, int64_t R, int64_t C,
+                        int64_t ld_w, int64_t ld_s, const int32_t *rp, const int32_t *cp,
+                        void *w_out, float *s_out);
+int sbits_launch_cost(sbits_ctx *ctx, const void *Wp, const float *Sp, int64_t R, int64_t C,
+                      int m, int n, const int32_t *bits, int K, float *cost_rows);
+int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
+                       const sbits_params *prm, uint8_t *level, sbits_stats *host_stats,
+                       sbits_trace *host_trace, int64_t trace_cap, void *ws);
+int sbits_launch_offsets(sbits_ctx *ctx, const uint8_t *level, int64_t N, int m, int n,
+                         const int32_t *bits, int K, int64_t *byte_off, void *ws);
+int sbits_launch_pack(sbits_ctx *ctx, const void *Wp, int64_t R, int64_t C, int m, int n,
+                      const int32_t *bits, int K, const uint8_t *level, const int64_t *byte_off,
+                      int64_t block_base, uint8_t *codes, float *scale, float *zero);

@@ -1,0 +1,101 @@
+"""Host-only checks of the C-ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching a device (device = -1 context)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2602_17698_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sb.LIB_PATH):
+        from paper_2602_17698_amd import build
+        build.build()
+    return sb.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "scalebits.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sbits_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(sb.EXPORTS)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_covers_all_codes(lib):
+    for code in range(0, -10, -1):
+        assert sb.strerror(code) != "unknown status"
+    assert sb.strerror(-99) == "unknown status"
+
+
+@pytest.fixture()
+def ctx(lib):
+    c = sb.Context(device=-1)
+    yield c
+    c.close()
+
+
+def test_plan_numbers_blocks_matrix_after_matrix(ctx):
+    p = sb.Plan(ctx, [(4096, 4096), (1024, 4096), (4096, 14336)], 128, 128, [2, 3, 4])
+    assert p.num_blocks(0) == 1024 and p.num_blocks(1) == 256 and p.num_blocks(2) == 32 * 112
+    assert p.num_blocks() == 1024 + 256 + 3584
+    assert [p.block_base(i) for i in range(3)] == [0, 1024, 1280]
+    assert p.workspace_bytes() > 0 and p.workspace_bytes() % 256 == 0
+    assert p.codes_bytes_bound(3.0) == int(3.0 * p.num_blocks()) * 128 * 128 // 8
+    assert p.codes_bytes_bound(9.0) == 4 * p.num_blocks() * 128 * 128 // 8
+    p.close()
+
+
+@pytest.mark.parametrize("shape,m,n,bits,err", [
+    ((1024, 1024), 128, 100, [2, 3, 4], sb.ERR_BAD_SHAPE),       # not a power of two
+    ((1024, 1024), 4, 128, [2, 3, 4], sb.ERR_BAD_SHAPE),         # block rows < 8
+    ((1024, 1024), 128, 1024, [2, 3, 4], sb.ERR_BAD_SHAPE),      # block cols > 512
+    ((1000, 1024), 128, 128, [2, 3, 4], sb.ERR_BAD_SHAPE),       # rows not divisible
+    ((1024, 1024), 128, 128, [], sb.ERR_BAD_BITWIDTHS),
+    ((1024, 1024), 128, 128, [2, 2, 4], sb.ERR_BAD_BITWIDTHS),   # not strictly increasing
+    ((1024, 1024), 128, 128, [4, 3, 2], sb.ERR_BAD_BITWIDTHS),
+    ((1024, 1024), 128, 128, [0, 1, 2], sb.ERR_BAD_BITWIDTHS),   # 0 bits (pruning) unsupported
+    ((1024, 1024), 128, 128, [2, 3, 9], sb.ERR_BAD_BITWIDTHS),
+    ((1024, 1024), 128, 128, list(range(1, 9)) + [8], sb.ERR_BAD_BITWIDTHS),
+])
+def test_plan_rejects_bad_partitions(ctx, shape, m, n, bits, err):
+    with pytest.raises(sb.SbitsError) as e:
+        sb.Plan(ctx, [shape], m, n, bits)
+    assert e.value.status == err
+
+
+def test_calls_validate_before_touching_the_device(ctx, lib):
+    p = sb.Plan(ctx, [(256, 256)], 128, 128, [2, 3, 4])
+    ws = 256 * 1024                                    # fake, aligned, never dereferenced
+    cost = np.zeros((4, 3), np.float32)
+    level = np.zeros(4, np.uint8)
+    prm = sb.Params(0.05, 0.02, 0, 100)
+    call = lambda *a: lib.sbits_allocate(p.h, *a)
+    args = lambda avg, prm_, ws_: (sb._ptr(cost), C.c_double(avg), C.byref(prm_), sb._ptr(level), None, None,
+                                   C.c_int64(0), C.c_void_p(ws_))
+    assert call(*args(1.5, prm, ws)) == sb.ERR_INFEASIBLE_BUDGET
+    assert call(*args(3.0, prm, ws + 8)) == sb.ERR_INVALID_ARG          # misaligned workspace
+    assert call(*args(3.0, sb.Params(0.05, 0.02, 0, 0), ws)) == sb.ERR_INVALID_ARG
+    assert call(*args(3.0, sb.Params(0.05, 0.02, 7, 10), ws)) == sb.ERR_INVALID_ARG
+    assert call(*args(float("nan"), prm, ws)) == sb.ERR_INVALID_ARG
+    assert call(*args(3.0, prm, ws)) == sb.ERR_HIP                       # host-only context: no device
+    # null pointers and wrong matrix index
+    assert lib.sbits_cost_table(p.h, C.c_int(0), None, None, None) == sb.ERR_INVALID_ARG
+    assert lib.sbits_cost_table(p.h, C.c_int(3), C.c_void_p(256), C.c_void_p(256), C.c_void_p(256)) == sb.ERR_INVALID_ARG
+    M = sb.Matrix(256, 256, 128, 256, 256, 256)                          # shape differs from the plan
+    assert lib.sbits_reorder(p.h, C.c_int(0), C.byref(M), C.c_void_p(256), C.c_void_p(256), C.c_void_p(ws)) == sb.ERR_BAD_SHAPE
+    M = sb.Matrix(256, 256, 256, 256, 256, 250)                          # pitch not a multiple of 4
+    assert lib.sbits_reorder(p.h, C.c_int(0), C.byref(M), C.c_void_p(256), C.c_void_p(256), C.c_void_p(ws)) == sb.ERR_INVALID_ARG
+    assert lib.sbits_num_blocks(p.h, C.c_int(5)) == sb.ERR_INVALID_ARG
+    p.close()

@@ -1,0 +1,429 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle, element by element,
+on the same seeded inputs, through the C-ABI (binding -> libscalebits.so).
+
+Bar: permutations, levels, statistics, offsets, packed bytes, scales and zeros bit-exact;
+cost entries bit-exact as well (the summation order is part of the definition), which is
+inside the 1e-5 relative bound the search is specified to.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2602_17698_amd import binding as sb
+from paper_2602_17698_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    sb.load()                                            # fails loudly if the library is not built
+    return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def ctx(dev):
+    c = sb.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    yield c
+    c.close()
+
+
+def make_plan(ctx, shapes, m, n, bits, dev):
+    plan = sb.Plan(ctx, shapes, m, n, bits)
+    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device=dev)
+    assert ws.data_ptr() % 256 == 0
+    return plan, ws
+
+
+def to_np_bf16(w):
+    return synth.bf16_bits(w)
+
+
+# ------------------------------------------------------------------ scores + permutations
+
+@pytest.mark.parametrize("R,C,m,n", [(8, 8, 8, 8), (40, 520, 8, 8), (264, 1032, 8, 8), (1024, 1024, 128, 128),
+                                      (96, 4096, 32, 128), (2048, 64, 64, 64)])
+def test_scores_and_permutations(orc, ctx, dev, R, C, m, n):
+    say("scores/perm", R, C)
+    g = torch.Generator().manual_seed(R * 7 + C)
+    S = torch.exp(torch.randn(R, 1, generator=g) + torch.randn(1, C, generator=g) + 0.5 * torch.randn(R, C, generator=g))
+    plan, ws = make_plan(ctx, [(R, C)], m, n, [2, 3, 4], dev)
+    Sd = S.to(dev)
+    M = sb.matrix(None, Sd)
+    rs = torch.empty(R, dtype=torch.float32, device=dev)
+    cs = torch.empty(C, dtype=torch.float32, device=dev)
+    plan.channel_scores(0, M, rs, cs, ws)
+    rp = torch.empty(R, dtype=torch.int32, device=dev)
+    cp = torch.empty(C, dtype=torch.int32, device=dev)
+    plan.reorder(0, M, rp, cp, ws)
+    torch.cuda.synchronize()
+    rs_o, cs_o = orc.channel_scores(S.numpy())
+    np.testing.assert_array_equal(rs.cpu().numpy(), rs_o)
+    np.testing.assert_array_equal(cs.cpu().numpy(), cs_o)
+    np.testing.assert_array_equal(rp.cpu().numpy(), orc.argsort_desc(rs_o))
+    np.testing.assert_array_equal(cp.cpu().numpy(), orc.argsort_desc(cs_o))
+    plan.close()
+
+
+def test_permutation_ties_go_to_the_lower_index(orc, ctx, dev):
+    say("perm ties")
+    R, C = 64, 128
+    S = torch.ones(R, C)
+    S[10] = 2.0
+    S[:, 5] = 3.0
+    S[40] = 0.0                                           # a dead channel: score 0 (+0 / -0 immaterial)
+    plan, ws = make_plan(ctx, [(R, C)], 8, 8, [2, 3], dev)
+    Sd = S.to(dev)
+    rp = torch.empty(R, dtype=torch.int32, device=dev)
+    cp = torch.empty(C, dtype=torch.int32, device=dev)
+    plan.reorder(0, sb.matrix(None, Sd), rp, cp, ws)
+    torch.cuda.synchronize()
+    rs_o, cs_o = orc.channel_scores(S.numpy())
+    np.testing.assert_array_equal(rp.cpu().numpy(), orc.argsort_desc(rs_o))
+    np.testing.assert_array_equal(cp.cpu().numpy(), orc.argsort_desc(cs_o))
+    assert rp[0].item() == 10 and rp[-1].item() == 40 and cp[0].item() == 5
+    plan.close()
+
+
+# ------------------------------------------------------------------------------- gather
+
+@pytest.mark.parametrize("R,C", [(8, 8), (40, 520), (256, 4096), (64, 14336)])
+def test_gather(orc, ctx, dev, R, C):
+    say("gather", R, C)
+    W, S = synth.make_matrix("student_t", R, C, seed=1, tid=R + C)
+    g = torch.Generator().manual_seed(3)
+    rp = torch.randperm(R, generator=g).to(torch.int32)
+    cp = torch.randperm(C, generator=g).to(torch.int32)
+    plan, ws = make_plan(ctx, [(R, C)], 8, 8, [2, 3, 4], dev)
+    Wd, Sd = W.to(dev), S.to(dev)
+    Wo = torch.empty_like(Wd)
+    So = torch.empty_like(Sd)
+    plan.gather(0, sb.matrix(Wd, Sd), rp.to(dev), cp.to(dev), Wo, So)
+    torch.cuda.synchronize()
+    Wr, Sr = orc.gather(to_np_bf16(W), S.numpy(), rp.numpy(), cp.numpy())
+    np.testing.assert_array_equal(to_np_bf16(Wo), Wr)
+    np.testing.assert_array_equal(So.cpu().numpy(), Sr)
+    plan.close()
+
+
+def test_gather_with_row_pitch(orc, ctx, dev):
+    say("gather pitch")
+    R, C, ld = 32, 256, 384
+    W, S = synth.make_matrix("student_t", R, ld, seed=2)
+    Wd, Sd = W.to(dev), S.to(dev)
+    g = torch.Generator().manual_seed(4)
+    rp = torch.randperm(R, generator=g).to(torch.int32)
+    cp = torch.randperm(C, generator=g).to(torch.int32)
+    plan, ws = make_plan(ctx, [(R, C)], 8, 8, [2], dev)
+    M = sb.Matrix(Wd.data_ptr(), Sd.data_ptr(), R, C, ld, ld)
+    Wo = torch.empty(R, C, dtype=torch.bfloat16, device=dev)
+    So = torch.empty(R, C, dtype=torch.float32, device=dev)
+    plan.gather(0, M, rp.to(dev), cp.to(dev), Wo, So)
+    rs = torch.empty(R, dtype=torch.float32, device=dev)
+    cs = torch.empty(C, dtype=torch.float32, device=dev)
+    plan.channel_scores(0, M, rs, cs, ws)
+    torch.cuda.synchronize()
+    Wr, Sr = orc.gather(to_np_bf16(W)[:, :C].copy(), S.numpy()[:, :C].copy(), rp.numpy(), cp.numpy())
+    np.testing.assert_array_equal(to_np_bf16(Wo), Wr)
+    np.testing.assert_array_equal(So.cpu().numpy(), Sr)
+    rs_o, cs_o = orc.channel_scores(S.numpy()[:, :C].copy())
+    np.testing.assert_array_equal(rs.cpu().numpy(), rs_o)
+    np.testing.assert_array_equal(cs.cpu().numpy(), cs_o)
+    plan.close()
+
+
+# --------------------------------------------------------------------------- cost table
+
+COST_CASES = [
+    # R, C, m, n, bits
+    (256, 384, 128, 128, [2, 3, 4]),
+    (256, 384, 128, 128, [1, 2, 3, 4]),
+    (192, 320, 64, 64, [1, 2, 3, 4, 8]),
+    (24, 40, 8, 8, [1, 2, 3, 4, 5, 6, 7, 8]),
+    (64, 96, 16, 32, [2, 4]),
+    (32, 48, 8, 16, [3]),
+    (2048, 256, 1024, 256, [2, 3, 4]),
+    (128, 1024, 64, 512, [1, 2, 3, 4, 8]),
+    (520, 128, 8, 128, [2, 3, 4]),                        # 65 row blocks: ragged last workgroup
+]
+
+
+@pytest.mark.parametrize("R,C,m,n,bits", COST_CASES)
+def test_cost_table(orc, ctx, dev, R, C, m, n, bits):
+    say("cost", R, C, m, n, bits)
+    W, S = synth.make_matrix("student_t", R, C, seed=5, tid=m * n + len(bits))
+    plan, ws = make_plan(ctx, [(m, n), (R, C)], m, n, bits, dev)
+    N, K = plan.num_blocks(), len(bits)
+    cost = torch.full((N, K), -1.0, dtype=torch.float32, device=dev)
+    Wd, Sd = W.to(dev), S.to(dev)
+    plan.cost_table(1, Wd, Sd, cost)                      # second matrix: rows start at its block base
+    torch.cuda.synchronize()
+    got = cost.cpu().numpy()
+    ref = orc.cost_table(to_np_bf16(W), S.numpy(), m, n, bits)
+    base = plan.block_base(1)
+    assert base == 1 and np.all(got[:base] == -1.0)       # other matrices' rows untouched
+    np.testing.assert_array_equal(got[base:], ref)
+    np.testing.assert_allclose(got[base:], ref, rtol=1e-5)
+    plan.close()
+
+
+def test_cost_table_degenerate_groups(orc, ctx, dev):
+    say("cost degenerate")
+    m = n = 64
+    R, C = 128, 128
+    W, S = synth.make_matrix("gauss_outlier", R, C, seed=6)
+    Wn = to_np_bf16(W).copy()
+    Wn[0, :64] = Wn[0, 0]                                 # constant group: range 0
+    Wn[1, :64] = 0
+    Wn[1, 7] = 0x0001                                     # range = smallest subnormal: qmax / R overflows
+    Wn[2, :64] = 0x8000                                   # all -0
+    Wn[2, 3] = 0x0000                                     # +0 among -0: range 0
+    Wn[3, :64] = 0
+    Wn[3, 9] = 0x0040                                     # subnormal range whose reciprocal is finite for small qmax
+    Wn[4, 64:] = 0x7F7F                                   # largest finite bf16, constant
+    Wd = torch.from_numpy(Wn.view(np.int16)).view(torch.bfloat16).to(dev)
+    bits = [1, 2, 3, 4, 8]
+    plan, ws = make_plan(ctx, [(R, C)], m, n, bits, dev)
+    cost = torch.empty(plan.num_blocks(), len(bits), dtype=torch.float32, device=dev)
+    plan.cost_table(0, Wd, S.to(dev), cost)
+    torch.cuda.synchronize()
+    ref = orc.cost_table(Wn, S.numpy(), m, n, bits)
+    np.testing.assert_array_equal(cost.cpu().numpy(), ref)
+    plan.close()
+
+
+# --------------------------------------------------------------------------- allocation
+
+def synthetic_cost(N, bits, seed, noise=0.2):
+    rng = np.random.default_rng(seed)
+    sens = np.exp(2.0 * rng.normal(size=(N, 1)))
+    c = sens * 4.0 ** -np.asarray(bits, np.float64)[None, :] * np.exp(noise * rng.normal(size=(N, len(bits))))
+    return c.astype(np.float32)
+
+
+ALLOC_CASES = [
+    ([2, 3, 4], 3.0, 64, 0.05, 0.02, 0),
+    ([2, 3, 4], 3.0, 4000, 0.05, 0.02, 0),
+    ([1, 2, 3, 4], 2.5, 5000, 0.05, 0.02, 0),
+    ([1, 2, 3, 4], 3.0, 5000, 0.05, 0.02, 0),
+    ([1, 2, 3, 4, 8], 2.25, 3000, 0.05, 0.02, 0),
+    ([2, 3, 4], 2.75, 2048, 0.05, 0.02, 0),
+    ([2, 3, 4], 2.6, 1000, 0.3, 0.0, 1),                  # cold start, runs down to k = 0
+    ([1, 2, 4, 8], 3.5, 777, 0.1, 0.01, 0),               # floor(B) is no candidate
+    ([2, 3, 4], 3.999, 300, 0.05, 0.02, 0),
+    ([2, 3, 4], 2.0, 300, 0.05, 0.02, 0),                 # no slack at the lowest level
+    ([3], 3.0, 100, 0.05, 0.02, 0),                       # a single candidate
+    ([2, 3, 4], 5.0, 100, 0.05, 0.02, 0),                 # budget above the largest candidate
+    ([2, 3, 4], 3.0, 70000, 0.05, 0.02, 0),               # several workgroups and histogram flushes
+]
+
+
+@pytest.mark.parametrize("bits,avg,N,g0,gT,init", ALLOC_CASES)
+def test_allocate_matches_oracle_step_by_step(orc, ctx, dev, bits, avg, N, g0, gT, init):
+    say("alloc", bits, avg, N, g0, gT, init)
+    cost = synthetic_cost(N, bits, seed=N + len(bits))
+    plan, ws = make_plan(ctx, [(8 * N, 8)], 8, 8, bits, dev)
+    assert plan.num_blocks() == N
+    level = torch.full((N,), 255, dtype=torch.uint8, device=dev)
+    rc, st, tr = plan.allocate(torch.from_numpy(cost).to(dev), avg, level, ws, gamma0=g0, gammaT=gT,
+                               init_mode=init, max_iters=5000, trace_cap=5000)
+    rc_o, level_o, st_o, tr_o = orc.allocate(cost, bits, avg, gamma0=g0, gammaT=gT, init_mode=init,
+                                             max_iters=5000, want_trace=True)
+    assert rc == 0 and rc_o == 0
+    assert st == st_o
+    assert tr == tr_o
+    np.testing.assert_array_equal(level.cpu().numpy(), level_o)
+    plan.close()
+
+
+def test_allocate_ties_and_flat_tables(orc, ctx, dev):
+    say("alloc ties")
+    for cost, bits, avg in [
+        (np.tile(np.array([[5, 2, 1]], np.float32), (600, 1)), [2, 3, 4], 2.5),      # all blocks identical
+        (np.ones((300, 3), np.float32), [2, 3, 4], 2.5),                              # no gain anywhere
+        (np.zeros((300, 3), np.float32), [2, 3, 4], 3.0),                             # all-zero table: shift 0
+        (np.tile(np.array([[1, 2, 3]], np.float32), (128, 1)), [2, 3, 4], 2.5),      # cost grows with bits
+    ]:
+        N = cost.shape[0]
+        plan, ws = make_plan(ctx, [(8 * N, 8)], 8, 8, bits, dev)
+        level = torch.empty(N, dtype=torch.uint8, device=dev)
+        rc, st, tr = plan.allocate(torch.from_numpy(cost).to(dev), avg, level, ws, trace_cap=1000)
+        rc_o, level_o, st_o, tr_o = orc.allocate(cost, bits, avg, want_trace=True)
+        assert (rc, st, tr) == (rc_o, st_o, tr_o)
+        np.testing.assert_array_equal(level.cpu().numpy(), level_o)
+        plan.close()
+
+
+def test_allocate_max_iters_status(orc, ctx, dev):
+    say("alloc max_iters")
+    N, bits = 2000, [2, 3, 4]
+    cost = synthetic_cost(N, bits, seed=9)
+    plan, ws = make_plan(ctx, [(8 * N, 8)], 8, 8, bits, dev)
+    level = torch.empty(N, dtype=torch.uint8, device=dev)
+    rc, st, _ = plan.allocate(torch.from_numpy(cost).to(dev), 2.5, level, ws, max_iters=3)
+    rc_o, level_o, st_o, _ = orc.allocate(cost, bits, 2.5, max_iters=3)
+    assert rc == sb.ERR_MAX_ITERS and rc_o == -2 and st == st_o
+    np.testing.assert_array_equal(level.cpu().numpy(), level_o)
+    plan.close()
+
+
+# ---------------------------------------------------------------------- offsets and pack
+
+@pytest.mark.parametrize("R,C,m,n,bits", [(256, 384, 128, 128, [2, 3, 4]), (192, 320, 64, 64, [1, 2, 3, 4, 8]),
+                                           (24, 40, 8, 8, [1, 2, 3, 4, 5, 6, 7, 8]), (64, 96, 16, 32, [1, 3, 5]),
+                                           (64, 1024, 32, 512, [1, 2, 3, 4, 8]), (4096, 16, 8, 16, [3, 4])])
+def test_offsets_and_pack(orc, ctx, dev, R, C, m, n, bits):
+    say("pack", R, C, m, n, bits)
+    W, _ = synth.make_matrix("student_t", R, C, seed=7, tid=m + n)
+    plan, ws = make_plan(ctx, [(m, n), (R, C), (m, 2 * n)], m, n, bits, dev)
+    N, base = plan.num_blocks(), plan.block_base(1)
+    rng = np.random.default_rng(R + C)
+    level = rng.integers(0, len(bits), size=N).astype(np.uint8)
+    level_d = torch.from_numpy(level).to(dev)
+    off_d = torch.empty(N + 1, dtype=torch.int64, device=dev)
+    plan.offsets(level_d, off_d, ws)
+    off = orc.offsets(level, m, n, bits)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(off_d.cpu().numpy(), off)
+    total = int(off[-1])
+    codes_d = torch.full((total,), 0x55, dtype=torch.uint8, device=dev)
+    scale_d = torch.full((N * m,), -1.0, dtype=torch.float32, device=dev)
+    zero_d = torch.full((N * m,), -1.0, dtype=torch.float32, device=dev)
+    plan.pack(1, W.to(dev), level_d, off_d, codes_d, scale_d, zero_d)
+    torch.cuda.synchronize()
+    codes = np.full(total, 0x55, np.uint8)
+    scale = np.full(N * m, -1.0, np.float32)
+    zero = np.full(N * m, -1.0, np.float32)
+    orc.pack(to_np_bf16(W), m, n, bits, level, off, base, codes, scale, zero)
+    np.testing.assert_array_equal(codes_d.cpu().numpy(), codes)
+    np.testing.assert_array_equal(scale_d.cpu().numpy(), scale)
+    np.testing.assert_array_equal(zero_d.cpu().numpy().view(np.uint32), zero.view(np.uint32))
+    plan.close()
+
+
+def test_offsets_many_tiles(orc, ctx, dev):
+    say("offsets large")
+    N, bits = 601000, [1, 2, 3, 4, 8]
+    plan, ws = make_plan(ctx, [(8000, 4808)], 8, 8, bits, dev)
+    assert plan.num_blocks() == N
+    level = np.random.default_rng(1).integers(0, 5, size=N).astype(np.uint8)
+    off_d = torch.empty(N + 1, dtype=torch.int64, device=dev)
+    plan.offsets(torch.from_numpy(level).to(dev), off_d, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(off_d.cpu().numpy(), orc.offsets(level, 8, 8, bits))
+    plan.close()
+
+
+# --------------------------------------------------------------------------- end to end
+
+def oracle_search(orc, mats, m, n, bits, avg, **kw):
+    """The whole path on the CPU oracle: returns every output the library produces."""
+    perms, W2, S2, costs = [], [], [], []
+    for W, S in mats:
+        Wn, Sn = to_np_bf16(W), S.numpy()
+        rs, cs = orc.channel_scores(Sn)
+        rp, cp = orc.argsort_desc(rs), orc.argsort_desc(cs)
+        Wp, Sp = orc.gather(Wn, Sn, rp, cp)
+        perms.append((rp, cp)); W2.append(Wp); S2.append(Sp)
+        costs.append(orc.cost_table(Wp, Sp, m, n, bits))
+    cost = np.concatenate(costs, 0)
+    rc, level, st, _ = orc.allocate(cost, bits, avg, **kw)
+    off = orc.offsets(level, m, n, bits)
+    N = cost.shape[0]
+    codes = np.zeros(int(off[-1]), np.uint8)
+    scale = np.zeros(N * m, np.float32)
+    zero = np.zeros(N * m, np.float32)
+    base = 0
+    for Wp in W2:
+        orc.pack(Wp, m, n, bits, level, off, base, codes, scale, zero)
+        base += (Wp.shape[0] // m) * (Wp.shape[1] // n)
+    return dict(perms=perms, W2=W2, S2=S2, cost=cost, level=level, stats=st, off=off, codes=codes,
+                scale=scale, zero=zero, rc=rc)
+
+
+def gpu_search(ctx, dev, mats, m, n, bits, avg, **kw):
+    shapes = [tuple(W.shape) for W, _ in mats]
+    plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
+    N, K = plan.num_blocks(), len(bits)
+    dW = [W.to(dev) for W, _ in mats]
+    dS = [S.to(dev) for _, S in mats]
+    nel = sum(r * c for r, c in shapes)
+    o = dict(
+        row_perm=torch.empty(sum(r for r, _ in shapes), dtype=torch.int32, device=dev),
+        col_perm=torch.empty(sum(c for _, c in shapes), dtype=torch.int32, device=dev),
+        w_re=torch.empty(nel, dtype=torch.bfloat16, device=dev),
+        s_re=torch.empty(nel, dtype=torch.float32, device=dev),
+        cost=torch.empty(N, K, dtype=torch.float32, device=dev),
+        level=torch.empty(N, dtype=torch.uint8, device=dev),
+        byte_off=torch.empty(N + 1, dtype=torch.int64, device=dev),
+        codes=torch.zeros(plan.codes_bytes_bound(avg), dtype=torch.uint8, device=dev),
+        scale=torch.empty(N * m, dtype=torch.float32, device=dev),
+        zero=torch.empty(N * m, dtype=torch.float32, device=dev),
+    )
+    out = sb.Outputs(o["row_perm"].data_ptr(), o["col_perm"].data_ptr(), o["w_re"].data_ptr(), o["s_re"].data_ptr(),
+                     o["cost"].data_ptr(), o["level"].data_ptr(), o["byte_off"].data_ptr(), o["codes"].data_ptr(),
+                     o["codes"].numel(), o["scale"].data_ptr(), o["zero"].data_ptr())
+    rc, st = plan.search([sb.matrix(w, s) for w, s in zip(dW, dS)], avg, out, ws, **kw)
+    torch.cuda.synchronize()
+    plan.close()
+    return rc, st, o, shapes
+
+
+def compare_search(orc, ref, rc, st, o, shapes, m):
+    assert rc == ref["rc"] and st == ref["stats"]
+    ro = co = eo = 0
+    for (R, C), (rp, cp), Wp, Sp in zip(shapes, ref["perms"], ref["W2"], ref["S2"]):
+        np.testing.assert_array_equal(o["row_perm"][ro:ro + R].cpu().numpy(), rp)
+        np.testing.assert_array_equal(o["col_perm"][co:co + C].cpu().numpy(), cp)
+        np.testing.assert_array_equal(to_np_bf16(o["w_re"][eo:eo + R * C]).reshape(R, C), Wp)
+        np.testing.assert_array_equal(o["s_re"][eo:eo + R * C].cpu().numpy().reshape(R, C), Sp)
+        ro, co, eo = ro + R, co + C, eo + R * C
+    np.testing.assert_array_equal(o["cost"].cpu().numpy(), ref["cost"])
+    np.testing.assert_array_equal(o["level"].cpu().numpy(), ref["level"])
+    np.testing.assert_array_equal(o["byte_off"].cpu().numpy(), ref["off"])
+    total = int(ref["off"][-1])
+    np.testing.assert_array_equal(o["codes"][:total].cpu().numpy(), ref["codes"])
+    np.testing.assert_array_equal(o["scale"].cpu().numpy(), ref["scale"])
+    np.testing.assert_array_equal(o["zero"].cpu().numpy().view(np.uint32), ref["zero"].view(np.uint32))
+
+
+def test_search_single_matrix_config(orc, ctx, dev):
+    """One 1024 x 1024 matrix, N(0, 0.02) weights with 0.1 % outliers x50, squared-normal
+    sensitivity, 128 x 128 blocks, {2,3,4} bits, budget 3.0, seed 0."""
+    say("search config 1")
+    mats = [synth.make_matrix("gauss_outlier", 1024, 1024, seed=0, tid=0)]
+    ref = oracle_search(orc, mats, 128, 128, [2, 3, 4], 3.0)
+    rc, st, o, shapes = gpu_search(ctx, dev, mats, 128, 128, [2, 3, 4], 3.0)
+    compare_search(orc, ref, rc, st, o, shapes, 128)
+    assert st["bits_used"] <= st["bits_budget"] == 192
+
+
+@pytest.mark.parametrize("m,n,bits,avg,recipe", [(64, 64, [1, 2, 3, 4, 8], 2.25, "outlier_chan"),
+                                                  (128, 128, [1, 2, 3, 4], 2.5, "student_t"),
+                                                  (32, 256, [2, 3, 4], 2.75, "student_t")])
+def test_search_several_matrices(orc, ctx, dev, m, n, bits, avg, recipe):
+    say("search multi", m, n, bits, avg, recipe)
+    shapes = [(512, 512), (256, 1024), (1024, 256), (256, 512)]
+    mats = [synth.make_matrix(recipe, r, c, seed=3, tid=i) for i, (r, c) in enumerate(shapes)]
+    ref = oracle_search(orc, mats, m, n, bits, avg)
+    rc, st, o, shp = gpu_search(ctx, dev, mats, m, n, bits, avg)
+    compare_search(orc, ref, rc, st, o, shp, m)
+
+
+def test_search_is_deterministic(ctx, dev):
+    say("determinism")
+    mats = [synth.make_matrix("student_t", 512, 1024, seed=11, tid=i) for i in range(3)]
+    a = gpu_search(ctx, dev, mats, 64, 64, [1, 2, 3, 4], 2.5)
+    b = gpu_search(ctx, dev, mats, 64, 64, [1, 2, 3, 4], 2.5)
+    assert a[1] == b[1]
+    for key in a[2]:
+        assert torch.equal(a[2][key].view(torch.uint8), b[2][key].view(torch.uint8)), key
