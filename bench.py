@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the bitwidth-allocation search on one MI355X.
+
+One "step" = one pass of the whole hot path over the full 32-layer Llama-3-8B-shaped
+synthetic model (224 matrices, 6.98 G weights, bf16 weights + fp32 sensitivities resident
+in HBM): channel scores + argsort, reorder-gather, block x bitwidth cost table, scalable
+greedy allocation to the budget, offsets + bit-packing.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--budget B]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--layers", type=int, default=32, help="decoder layers (32 = the full 8B-shaped model)")
+    ap.add_argument("--budget", type=float, default=2.5, help="average bits per weight")
+    ap.add_argument("--block", type=int, default=128)
+    ap.add_argument("--bits", type=str, default="1,2,3,4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def cpu_baseline(torch, synth, shapes_sample, m, n, bits, avg, seed):
+    """The oracle as it stands, single-threaded, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    oracle.lib()
+    mats = []
+    for i, (name, r, c) in enumerate(shapes_sample):
+        W, S = synth.make_matrix("student_t", r, c, seed=seed, tid=synth.tensor_id(0, name))
+        mats.append((synth.bf16_bits(W), S.numpy()))
+    nw = sum(w.size for w, _ in mats)
+    t0 = time.perf_counter()
+    costs, packed = [], []
+    for Wn, Sn in mats:
+        rs, cs = oracle.channel_scores(Sn)
+        rp, cp = oracle.argsort_desc(rs), oracle.argsort_desc(cs)
+        Wp, Sp = oracle.gather(Wn, Sn, rp, cp)
+        costs.append(oracle.cost_table(Wp, Sp, m, n, bits))
+        packed.append(Wp)
+    cost = np.concatenate(costs, 0)
+    rc, level, st, _ = oracle.allocate(cost, bits, avg)
+    off = oracle.offsets(level, m, n, bits)
+    N = cost.shape[0]
+    codes = np.zeros(int(off[-1]), np.uint8)
+    scale = np.zeros(N * m, np.float32)
+    zero = np.zeros(N * m, np.float32)
+    base = 0
+    for Wp in packed:
+        oracle.pack(Wp, m, n, bits, level, off, base, codes, scale, zero)
+        base += (Wp.shape[0] // m) * (Wp.shape[1] // n)
+    dt = time.perf_counter() - t0
+    return {"value": nw / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
+            "sample": "layer-0 %s (%d weights), whole path incl. allocation on the sample's own table, %.1f s"
+                      % ("+".join(nm for nm, _, _ in shapes_sample), nw, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
+              "in this library; see DESIGN.md for how the path would shard)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_17698_amd import binding as sb
+    from paper_2602_17698_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    sb.load()
+    bits = [int(b) for b in args.bits.split(",")]
+    m = n = args.block
+    K = len(bits)
+    model = dict(synth.LLAMA3_8B)
+    shapes = []
+    for layer in range(args.layers):
+        for name, r, c in synth.layer_shapes(model):
+            shapes.append((layer, name, r, c))
+
+    # ---- synthetic inputs, generated on the device, resident before any timing ----
+    t_gen = time.perf_counter()
+    Ws, Ss = [], []
+    for layer, name, r, c in shapes:
+        W, S = synth.make_matrix("student_t", r, c, seed=args.seed, tid=synth.tensor_id(layer, name), device=dev)
+        Ws.append(W)
+        Ss.append(S)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    ctx = sb.Context(0, torch.cuda.current_stream().cuda_stream)
+    plan = sb.Plan(ctx, [(r, c) for _, _, r, c in shapes], m, n, bits)
+    N = plan.num_blocks()
+    nw = sum(r * c for _, _, r, c in shapes)
+    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device=dev)
+    mats = [sb.matrix(w, s) for w, s in zip(Ws, Ss)]
+    row_perm = [torch.empty(r, dtype=torch.int32, device=dev) for _, _, r, _ in shapes]
+    col_perm = [torch.empty(c, dtype=torch.int32, device=dev) for _, _, _, c in shapes]
+    w_re = [torch.empty_like(w) for w in Ws]
+    s_re = [torch.empty_like(s) for s in Ss]
+    cost = torch.empty(N, K, dtype=torch.float32, device=dev)
+    level = torch.empty(N, dtype=torch.uint8, device=dev)
+    byte_off = torch.empty(N + 1, dtype=torch.int64, device=dev)
+    codes = torch.empty(plan.codes_bytes_bound(args.budget), dtype=torch.uint8, device=dev)
+    scale = torch.empty(N * m, dtype=torch.float32, device=dev)
+    zero = torch.empty(N * m, dtype=torch.float32, device=dev)
+    nm = len(shapes)
+
+    stage_names = ["reorder", "gather", "cost", "allocate", "offsets_pack"]
+
+    def step(ev):
+        ev[0].record()
+        for i in range(nm):
+            plan.reorder(i, mats[i], row_perm[i], col_perm[i], ws)
+        ev[1].record()
+        for i in range(nm):
+            plan.gather(i, mats[i], row_perm[i], col_perm[i], w_re[i], s_re[i])
+        ev[2].record()
+        for i in range(nm):
+            plan.cost_table(i, w_re[i], s_re[i], cost)
+        ev[3].record()
+        rc, st, _ = plan.allocate(cost, args.budget, level, ws)
+        ev[4].record()
+        plan.offsets(level, byte_off, ws)
+        for i in range(nm):
+            plan.pack(i, w_re[i], level, byte_off, codes, scale, zero)
+        ev[5].record()
+        return rc, st
+
+    def new_events():
+        return [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+
+    for _ in range(args.warmup):
+        step(new_events())
+    torch.cuda.synchronize()
+
+    evs = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev = new_events()
+        rc, st = step(ev)
+        evs.append(ev)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    stage_ms = {nm_: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, nm_ in enumerate(stage_names)}
+    cost_ms = stage_ms["cost"]
+    # cost-table pass: each weight is read once as bf16 (2 B) with its fp32 sensitivity (4 B);
+    # the table written is K*4 bytes per m*n weights
+    cost_bytes = nw * 6 + N * K * 4
+    launches = nm
+    achieved = cost_bytes / (cost_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "weights scored/s through the whole search path (8B-shaped, all bitwidths)",
+        "value": nw / (ms_per_step * 1e-3),
+        "unit": "weights/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "Llama-3-8B-shaped, %d layers, %d matrices, %d weights (bf16) + fp32 sensitivity, "
+                               "%dx%d blocks (%d), bitwidths %s, budget %.2f"
+                               % (args.layers, nm, nw, m, n, N, bits, args.budget)},
+        "full_search_ms": ms_per_step,
+        "stage_ms": stage_ms,
+        "cost_pass_weights_per_s": nw / (cost_ms * 1e-3),
+        "search_stats": st, "search_status": rc,
+        "gen_s": t_gen,
+        "roofline": {"kernel": "cost_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "launches_per_step": launches, "avg_launch_ms": cost_ms / launches,
+                     "algorithmic_bytes_per_launch": cost_bytes / launches},
+    }
+    if not args.no_cpu_baseline:
+        sample = synth.layer_shapes(model)          # one full decoder layer: 218 M weights, ~15-20 s
+        out["cpu_baseline"] = cpu_baseline(torch, synth, sample, m, n, bits, args.budget, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
