@@ -145,6 +145,12 @@ int  sbits_gather(sbits_plan *plan, int mat, const sbits_matrix *M,
 int  sbits_cost_table(sbits_plan *plan, int mat, const void *w_re_bf16, const float *s_re,
                       float *cost);
 
+/* The same for every matrix of the plan in ONE launch.  w_re, s_re: the reordered
+ * matrices concatenated in plan order, each dense (matrix i starts at element
+ * sum_{j<i} rows_j*cols_j).  Uses ws.                                            */
+int  sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *s_re,
+                          float *cost, void *ws);
+
 /* ---- scalable greedy search (paper Algorithm 2 with the relaxed step Eq. 5) ---
  * Runs on the device over the cost table: marginal change per bit from the
  * table, radix selection of the top-k / bottom-k sets on (value, index) keys,

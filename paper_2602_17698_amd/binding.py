@@ -10,7 +10,7 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libscalebits.so")
+LIB_PATH = os.environ.get("SBITS_LIB") or os.path.join(_HERE, "libscalebits.so")
 
 OK = 0
 ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_BAD_BITWIDTHS, ERR_INFEASIBLE_BUDGET = -1, -2, -3, -4
@@ -20,7 +20,7 @@ EXPORTS = [
     "sbits_create", "sbits_destroy", "sbits_last_hip_error", "sbits_strerror",
     "sbits_plan_create", "sbits_plan_destroy", "sbits_num_blocks", "sbits_block_base",
     "sbits_workspace_bytes", "sbits_codes_bytes_bound",
-    "sbits_reorder", "sbits_channel_scores", "sbits_gather", "sbits_cost_table",
+    "sbits_reorder", "sbits_channel_scores", "sbits_gather", "sbits_cost_table", "sbits_cost_table_all",
     "sbits_allocate", "sbits_offsets", "sbits_pack", "sbits_search",
 ]
 
@@ -183,6 +183,10 @@ class Plan:
     def cost_table(self, mat, w_re, s_re, cost):
         return _check(load().sbits_cost_table(self.h, C.c_int(mat), _ptr(w_re), _ptr(s_re), _ptr(cost)),
                       "sbits_cost_table")
+
+    def cost_table_all(self, w_re, s_re, cost, ws):
+        return _check(load().sbits_cost_table_all(self.h, _ptr(w_re), _ptr(s_re), _ptr(cost), _ptr(ws)),
+                      "sbits_cost_table_all")
 
     def allocate(self, cost, avg_bits, level, ws, gamma0=0.05, gammaT=0.02, init_mode=0,
                  max_iters=100000, trace_cap=0):

@@ -77,6 +77,7 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
     for (int l = 0; l < 8; ++l) p->bits[l] = l < n_bits ? bitwidths[l] : 0;
     p->N = 0;
     p->max_rows = p->max_cols = 0;
+    p->sum_rows = p->sum_cols = p->sum_elems = 0;
     for (int i = 0; i < n_mats; ++i) {
         if (rows[i] <= 0 || cols[i] <= 0 || rows[i] % block_rows || cols[i] % block_cols ||
             rows[i] > 0x7fffffff || cols[i] > 32768 || rows[i] > 2097120) {
@@ -86,6 +87,14 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
         p->rows.push_back(rows[i]);
         p->cols.push_back(cols[i]);
         p->base.push_back(p->N);
+        sbits::MatDesc d;
+        memset(&d, 0, sizeof d);
+        d.rows = rows[i]; d.cols = cols[i]; d.ld_w = d.ld_s = cols[i];
+        d.elem_off = p->sum_elems; d.block_base = p->N;
+        d.row_off = p->sum_rows; d.col_off = p->sum_cols;
+        d.nbr = (int)(rows[i] / block_rows); d.nbc = (int)(cols[i] / block_cols);
+        p->descs.push_back(d);
+        p->sum_rows += rows[i]; p->sum_cols += cols[i]; p->sum_elems += rows[i] * cols[i];
         p->N += (rows[i] / block_rows) * (cols[i] / block_cols);
         if (rows[i] > p->max_rows) p->max_rows = rows[i];
         if (cols[i] > p->max_cols) p->max_cols = cols[i];
@@ -95,7 +104,8 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
     const size_t a = sbits_alloc_ws_bytes(p->N), o = sbits_offsets_ws_bytes(p->N);
     if (a > ws) ws = a;
     if (o > ws) ws = o;
-    p->ws_bytes = ws;
+    p->head_bytes = sbits_desc_bytes(n_mats) + SBITS_N_PREFIX * sbits_prefix_bytes(n_mats);
+    p->ws_bytes = p->head_bytes + ws;
     *out = p;
     return SBITS_OK;
 }
@@ -148,6 +158,29 @@ static int need_device(const sbits_plan *plan)
     return SBITS_OK;
 }
 
+}  // extern "C"
+
+// Copies the descriptor table into the workspace head.  mats == nullptr: shapes only.
+int sbits_upload_descs(sbits_plan *plan, const sbits_matrix *mats, void *ws)
+{
+    for (int i = 0; i < plan->n_mats; ++i) {
+        sbits::MatDesc &d = plan->descs[i];
+        if (mats) {
+            d.w = static_cast<const uint16_t *>(mats[i].w_bf16);
+            d.s = mats[i].sens;
+            d.ld_w = mats[i].ld_w;
+            d.ld_s = mats[i].ld_s;
+        } else {
+            d.w = nullptr; d.s = nullptr;
+        }
+    }
+    SBITS_HIP(plan->ctx, hipMemcpyAsync(ws, plan->descs.data(), plan->n_mats * sizeof(sbits::MatDesc),
+                                        hipMemcpyHostToDevice, plan->ctx->stream));
+    return SBITS_OK;
+}
+
+extern "C" {
+
 static bool ws_ok(const void *ws) { return ws && (reinterpret_cast<uintptr_t>(ws) & 255) == 0; }
 
 // workspace slices used by reorder: [score partials ...][rank][rs][cs] (see reorder.hip)
@@ -173,7 +206,8 @@ int sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M, float
     if (rc) return rc;
     if (!row_score || !col_score || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
     if ((rc = need_device(plan))) return rc;
-    return sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, row_score, col_score, ws);
+    return sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, row_score, col_score,
+                               sbits_scratch(plan, ws));
 }
 
 int sbits_reorder(sbits_plan *plan, int mat, const sbits_matrix *M, int32_t *row_perm,
@@ -185,8 +219,9 @@ int sbits_reorder(sbits_plan *plan, int mat, const sbits_matrix *M, int32_t *row
     if ((rc = need_device(plan))) return rc;
     int *rank;
     float *rs, *cs;
-    reorder_slices(plan, M->rows, M->cols, ws, &rank, &rs, &cs);
-    if ((rc = sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, rs, cs, ws))) return rc;
+    void *scr = sbits_scratch(plan, ws);
+    reorder_slices(plan, M->rows, M->cols, scr, &rank, &rs, &cs);
+    if ((rc = sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, rs, cs, scr))) return rc;
     if ((rc = sbits_launch_argsort(plan->ctx, rs, M->rows, row_perm, rank))) return rc;
     return sbits_launch_argsort(plan->ctx, cs, M->cols, col_perm, rank);
 }
@@ -215,6 +250,16 @@ int sbits_cost_table(sbits_plan *plan, int mat, const void *w_re_bf16, const flo
                              plan->bits, plan->K, cost + plan->base[mat] * plan->K);
 }
 
+int sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *s_re, float *cost, void *ws)
+{
+    if (!plan || !w_re_bf16 || !s_re || !cost || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!aligned16(w_re_bf16) || !aligned16(s_re)) return SBITS_ERR_INVALID_ARG;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    if ((rc = sbits_upload_descs(plan, nullptr, ws))) return rc;
+    return sbits_launch_cost_all(plan, w_re_bf16, s_re, cost, ws);
+}
+
 int sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits, const sbits_params *params,
                    uint8_t *level, sbits_stats *host_stats, sbits_trace *host_trace, int64_t trace_cap,
                    void *ws)
@@ -226,7 +271,8 @@ int sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits, const s
     if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
     int rc = need_device(plan);
     if (rc) return rc;
-    return sbits_run_allocate(plan, cost, avg_bits, params, level, host_stats, host_trace, trace_cap, ws);
+    return sbits_run_allocate(plan, cost, avg_bits, params, level, host_stats, host_trace, trace_cap,
+                              sbits_scratch(plan, ws));
 }
 
 int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws)
@@ -234,7 +280,8 @@ int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, voi
     if (!plan || !level || !byte_off || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
     int rc = need_device(plan);
     if (rc) return rc;
-    return sbits_launch_offsets(plan->ctx, level, plan->N, plan->m, plan->n, plan->bits, plan->K, byte_off, ws);
+    return sbits_launch_offsets(plan->ctx, level, plan->N, plan->m, plan->n, plan->bits, plan->K, byte_off,
+                                sbits_scratch(plan, ws));
 }
 
 int sbits_pack(sbits_plan *plan, int mat, const void *w_re_bf16, const uint8_t *level,

@@ -17,12 +17,21 @@
 //   octet  : adjacent-pair tree over the 8 rows, per lane (per 8-column chunk)
 //   lanes  : adjacent-pair butterfly over the LPG lanes of the group
 //   block  : adjacent-pair tree over the m/8 octets (through LDS)
+//
+// Launch shape.  The kernel is persistent: a fixed grid of workgroups strides
+// over "units" (whole blocks), and every lane keeps the next half octet's loads
+// in flight while it computes on the current one, so HBM latency is hidden by
+// the kernel's own arithmetic rather than by occupancy (the kernel needs ~190
+// VGPRs, i.e. two waves per SIMD).
 #include <string.h>
 
 #include <type_traits>
+#include <vector>
 
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
+
+void sbits_fill_grid_consts(const int32_t *bits, int K, sbits::GridConsts *gc);
 
 namespace sbits {
 
@@ -35,97 +44,176 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-constexpr int COST_THREADS = 256;
-
-template <int LPG, int K>
-__global__ __launch_bounds__(COST_THREADS)
-void cost_kernel(const uint16_t *__restrict__ W, const float *__restrict__ S, int64_t C,
-                 int m, int nbc, int64_t nblocks, float *__restrict__ cost, GridConsts gc)
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uni64(int64_t v)
 {
-    constexpr int GPW = COST_THREADS / LPG;          // lane groups per workgroup
-    constexpr int NS = (2 * K + LPG - 1) / LPG;      // grid divisions per lane per row
-    __shared__ float osum[256 * K];
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
 
-    const int tid = threadIdx.x;
-    const int g = tid / LPG;
-    const int lig = tid % LPG;
-    const int opb = m >> 3;                          // octets per block
-    const int bpw = opb >= GPW ? 1 : GPW / opb;      // blocks per workgroup
-    const int passes = opb >= GPW ? opb / GPW : 1;
+constexpr int COST_THREADS = 256;
+constexpr int HALF = 4;                               // rows per pipeline stage
+#ifndef SBITS_COST_STRIDED
+#define SBITS_COST_STRIDED true
+#endif
 
-    // Each lane computes NS of the 2K quotients of a row (slot 2c: qmax_c / R,
-    // slot 2c+1: R / qmax_c); they are then broadcast inside the group.
-    float my_qf[NS], my_thr[NS];
-    bool my_is_scale[NS];
+// value held by lane j*SP + SLOT of the caller's lane group, j in [0, LPG/SP)
+template <int LPG, int SP, int SLOT>
+__device__ __forceinline__ float bcast_row(float v, int j)
+{
+    constexpr int RPG = LPG / SP;
+    if (RPG <= 1 || j == 0) return group_bcast<LPG, SLOT>(v);
+    if (RPG >= 2 && j == 1) return group_bcast<LPG, (1 * SP + SLOT) % LPG>(v);
+    if (RPG >= 4 && j == 2) return group_bcast<LPG, (2 * SP + SLOT) % LPG>(v);
+    return group_bcast<LPG, (3 * SP + SLOT) % LPG>(v);
+}
+
+// the raw loads of HALF consecutive rows of one lane
+struct HalfBuf {
+    uint4 w[HALF];
+    float4 s0[HALF], s1[HALF];
+};
+
+// Uniform 64-bit bases plus per-lane 32-bit byte offsets (a matrix is below 4 GiB), so the
+// loads use the scalar-base + vector-offset addressing form and need one add per row.
+__device__ __forceinline__ void load_half(HalfBuf &h, const char *__restrict__ Wb, const char *__restrict__ Sb,
+                                          uint32_t woff, uint32_t wstride)
+{
+    // S is fp32, W bf16, same element index: byte offsets differ by a factor of two
 #pragma unroll
-    for (int t = 0; t < NS; ++t) {
-        const int slot = lig + t * LPG;
-        int c = slot >> 1;
-        c = c < K ? c : K - 1;
-        float qf = gc.qmaxf[0], th = gc.thr[0];
-#pragma unroll
-        for (int cc = 1; cc < K; ++cc)
-            if (c == cc) { qf = gc.qmaxf[cc]; th = gc.thr[cc]; }
-        my_qf[t] = qf;
-        my_thr[t] = th;
-        my_is_scale[t] = (slot & 1) != 0;
+    for (int j = 0; j < HALF; ++j) {
+        const uint32_t wo = woff + (uint32_t)j * wstride;
+        const uint32_t so = 2u * wo;
+#ifdef SBITS_COST_NT
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 tw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Wb + wo));
+        const f32x4 ta = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(Sb + so));
+        const f32x4 tb = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(Sb + so + 16u));
+        h.w[j] = make_uint4(tw.x, tw.y, tw.z, tw.w);
+        h.s0[j] = make_float4(ta.x, ta.y, ta.z, ta.w);
+        h.s1[j] = make_float4(tb.x, tb.y, tb.z, tb.w);
+#else
+        h.w[j] = *reinterpret_cast<const uint4 *>(Wb + wo);
+        h.s0[j] = *reinterpret_cast<const float4 *>(Sb + so);
+        h.s1[j] = *reinterpret_cast<const float4 *>(Sb + so + 16u);
+#endif
     }
+}
 
-    for (int pass = 0; pass < passes; ++pass) {
-        const int oct_in_wg = g + pass * GPW;
-        const int blk_local = oct_in_wg / opb;
-        const int o = oct_in_wg - blk_local * opb;
-        int64_t blk = (int64_t)blockIdx.x * bpw + blk_local;
-        if (blk >= nblocks) blk = nblocks - 1;       // keep every lane in bounds; result discarded
-        const int64_t I = blk / nbc, J = blk - I * nbc;
-        const int64_t off0 = (I * m + (int64_t)o * 8) * C + J * (LPG * 8) + lig * 8;
+// Per-lane constants of the distributed grid divisions.  The 2K quotients of a
+// row (slot 2c: qmax_c / R, slot 2c+1: R / qmax_c) are spread over the lanes of
+// the group, one division per lane, and broadcast afterwards.  When the group
+// has more lanes than slots, RP rows share one round of divisions.
+template <int LPG, int K>
+struct DivPlan {
+    static constexpr int SP = (2 * K <= 2) ? 2 : (2 * K <= 4) ? 4 : (2 * K <= 8) ? 8 : 16;   // slots per row
+    static constexpr int RP0 = (LPG >= SP) ? (LPG / SP) : 1;
+    static constexpr int RP = RP0 < HALF ? RP0 : HALF;                                         // rows per round
+    static constexpr int NS = (LPG >= SP) ? 1 : (2 * K + LPG - 1) / LPG;                       // divisions per lane
+    float qf[NS], thr[NS];
+    bool is_scale[NS];
+    int my_row;
 
-        float t1[K], t2[K], t3[K], cur[K];
+    __device__ __forceinline__ void init(const GridConsts &gc, int lig)
+    {
 #pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            const int64_t off = off0 + (int64_t)rr * C;
-            const uint4 wp = *reinterpret_cast<const uint4 *>(W + off);
-            const float4 s0 = *reinterpret_cast<const float4 *>(S + off);
-            const float4 s1 = *reinterpret_cast<const float4 *>(S + off + 4);
-            float w[8];
-            unpack8(wp, w);
-            const float s[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        for (int t = 0; t < NS; ++t) {
+            const int slot = (LPG >= SP) ? (lig % SP) : (lig + t * LPG);
+            int c = slot >> 1;
+            c = c < K ? c : K - 1;
+            float q = gc.qmaxf[0], th = gc.thr[0];
+#pragma unroll
+            for (int cc = 1; cc < K; ++cc)
+                if (c == cc) { q = gc.qmaxf[cc]; th = gc.thr[cc]; }
+            qf[t] = q;
+            thr[t] = th;
+            is_scale[t] = (slot & 1) != 0;
+        }
+        my_row = (LPG >= SP) ? (lig / SP) : 0;
+    }
+};
 
+// HALF rows of one octet: rows R_BASE .. R_BASE + HALF - 1 (R_BASE is 0 or 4).  Updates the
+// pending levels of the row tree (t1, t2, t3) and leaves the running result in cur.
+template <int LPG, int K, int R_BASE>
+__device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG, K> &dp,
+                                             float (&t1)[K], float (&t2)[K], float (&t3)[K], float (&cur)[K])
+{
+    using DP = DivPlan<LPG, K>;
+    constexpr int SP = DP::SP, RP = DP::RP, NS = DP::NS;
+#ifdef SBITS_COST_LOADONLY
+    {
+        float acc = 0.0f;
+#pragma unroll
+        for (int j = 0; j < HALF; ++j)
+            acc += __uint_as_float(h.w[j].x ^ h.w[j].y ^ h.w[j].z ^ h.w[j].w) + h.s0[j].x + h.s0[j].y + h.s0[j].z +
+                   h.s0[j].w + h.s1[j].x + h.s1[j].y + h.s1[j].z + h.s1[j].w;
+#pragma unroll
+        for (int c = 0; c < K; ++c) cur[c] = (R_BASE ? cur[c] : 0.0f) + acc;
+        (void)t1; (void)t2; (void)t3; (void)dp;
+        return;
+    }
+#endif
+#pragma unroll
+    for (int r0 = 0; r0 < HALF; r0 += RP) {
+        float x[RP][8], s[RP][8], Rg[RP];
+#pragma unroll
+        for (int j = 0; j < RP; ++j) {
+            float w[8];
+            unpack8(h.w[r0 + j], w);
+            const float4 a = h.s0[r0 + j], b = h.s1[r0 + j];
+            s[j][0] = a.x; s[j][1] = a.y; s[j][2] = a.z; s[j][3] = a.w;
+            s[j][4] = b.x; s[j][5] = b.y; s[j][6] = b.z; s[j][7] = b.w;
             float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])),
                              fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
             float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])),
                              fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
             mn = group_allreduce<LPG>(mn, OpMin{});
             mx = group_allreduce<LPG>(mx, OpMax{});
-            const float R = mx - mn;
+            Rg[j] = mx - mn;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[j][e] = w[e] - mn;
+        }
 
-            float val[NS];
+        float val[NS];
+        {
+            float Rsel = Rg[0];
+#pragma unroll
+            for (int j = 1; j < RP; ++j)
+                if (dp.my_row == j) Rsel = Rg[j];
 #pragma unroll
             for (int t = 0; t < NS; ++t) {
-                const float num = my_is_scale[t] ? R : my_qf[t];
-                const float den = my_is_scale[t] ? my_qf[t] : R;
+                const float num = dp.is_scale[t] ? Rsel : dp.qf[t];
+                const float den = dp.is_scale[t] ? dp.qf[t] : Rsel;
                 const float v = num / den;           // IEEE correctly rounded
-                val[t] = (R < my_thr[t]) ? 0.0f : v;
+                val[t] = (Rsel < dp.thr[t]) ? 0.0f : v;
             }
+        }
 
-            float x[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = w[e] - mn;
-
+        for (int j = 0; j < RP; ++j) {
+            const int rr = R_BASE + r0 + j;
             static_for<0, K>([&](auto ic) {
                 constexpr int c = decltype(ic)::value;
-                const float inv = group_bcast<LPG, (2 * c) % LPG>(val[(2 * c) / LPG]);
-                const float scl = group_bcast<LPG, (2 * c + 1) % LPG>(val[(2 * c + 1) / LPG]);
-                float a = 0.0f;
+                float inv, scl;
+                if constexpr (LPG >= SP) {
+                    inv = bcast_row<LPG, SP, 2 * c>(val[0], j);
+                    scl = bcast_row<LPG, SP, 2 * c + 1>(val[0], j);
+                } else {
+                    inv = group_bcast<LPG, (2 * c) % LPG>(val[(2 * c) / LPG]);
+                    scl = group_bcast<LPG, (2 * c + 1) % LPG>(val[(2 * c + 1) / LPG]);
+                }
+                float acc = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float q = rintf(x[e] * inv);
-                    const float d = fmaf(-q, scl, x[e]);
-                    a = fmaf(s[e], d * d, a);
+                    const float q = rintf(x[j][e] * inv);
+                    const float d = fmaf(-q, scl, x[j][e]);
+                    acc = fmaf(s[j][e], d * d, acc);
                 }
-                cur[c] = a;
+                cur[c] = acc;
             });
-
             // adjacent-pair tree over the 8 rows of the octet
 #pragma unroll
             for (int c = 0; c < K; ++c) {
@@ -145,29 +233,170 @@ void cost_kernel(const uint16_t *__restrict__ W, const float *__restrict__ S, in
                 cur[c] = v;
             }
         }
-        // cur[c] now holds the octet sum of this lane's 8-column chunk
+        // keep the rounds apart: interleaving them only lengthens live ranges
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Work decomposition.  A wave holds GW = 64/LPG lane groups.  BX = min(GW, 8) of them sit side
+// by side on BX adjacent blocks of one block row and walk the same octet, so every load
+// instruction of a wave reads one contiguous run per row (1 KiB of weights, 2 KiB of
+// sensitivities for LPG >= 8).  The remaining OW = GW/BX groups of the wave and the four waves
+// of the workgroup take different octets: OS = 4*OW octets per step.
+//   opb >= OS : a unit is BX blocks, walked in opb/OS steps
+//   opb <  OS : a unit is BX*(OS/opb) blocks, one step
+// (the last unit of a block row may be ragged: surplus groups recompute the row's last block
+// and their result is dropped).  unit_start[] (n_mats + 1 entries) is the prefix of units per
+// matrix.  Unit bookkeeping is scalar; a lane's offset inside a unit is a constant of the lane
+// (times the row pitch).  STRIDED: workgroup w takes units w, w + G, ...; otherwise a
+// contiguous range.
+template <int LPG>
+struct CostGeom {
+    static constexpr int GW = 64 / LPG;
+    static constexpr int BX = GW < 8 ? GW : 8;
+    static constexpr int OW = GW / BX;
+    static constexpr int OS = 4 * OW;
+    static int blocks_per_unit(int m) { const int opb = m / 8; return opb >= OS ? BX : BX * (OS / opb); }
+};
+
+template <int LPG, int K, bool STRIDED>
+__global__ __launch_bounds__(COST_THREADS, 2)
+void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ unit_start,
+                 int n_mats, int total_units, const uint16_t *__restrict__ W, const float *__restrict__ S,
+                 int m, float *__restrict__ cost, GridConsts gc)
+{
+    using G = CostGeom<LPG>;
+    constexpr int BX = G::BX, OS = G::OS;
+    __shared__ float osum[BX * 128 * K];             // [block in unit][octet][candidate]
+
+    const int tid = threadIdx.x;
+    const int lig = tid % LPG;
+    const int gw = (tid & 63) / LPG;                 // lane group inside the wave
+    const int slot = (tid >> 6) * G::OW + gw / BX;   // octet slot of this group, 0 .. OS-1
+    const int opb = m >> 3;
+    const int bpu = opb >= OS ? BX : BX * (OS / opb);           // blocks per unit
+    const int steps = opb >= OS ? opb / OS : 1;                 // steps per unit
+    const int bl = (gw % BX) + (opb >= OS ? 0 : BX * (slot / opb));   // this group's block inside the unit
+    const int o0 = opb >= OS ? slot : slot % opb;               // this group's octet (plus p*OS in step p)
+
+    DivPlan<LPG, K> dp;
+    dp.init(gc, lig);
+
+    int u_begin, u_end, u_step;
+    if (STRIDED) {
+        u_begin = (int)blockIdx.x; u_end = total_units; u_step = (int)gridDim.x;
+    } else {
+        const int per = (total_units + (int)gridDim.x - 1) / (int)gridDim.x;
+        u_begin = (int)blockIdx.x * per; u_end = min(u_begin + per, total_units); u_step = 1;
+    }
+    if (u_begin >= u_end) return;
+    const int nsteps = ((u_end - u_begin + u_step - 1) / u_step) * steps;
+
+    // ---- scalar state of the unit being LOADED (runs ahead of the one being computed) ----
+    // Everything here is the same in all lanes; readfirstlane tells the compiler so, which keeps
+    // the bookkeeping in scalar registers and the loads in scalar-base + vector-offset form.
+    int mat = 0, mat_begin = 0, mat_end = total_units;
+    int d_cols, d_nbc, upr;
+    int64_t d_elem, d_cbase;
+    int unit = u_begin, I = 0, U = 0, p = 0;
+    auto enter_unit = [&](bool first) {              // (mat, I, U) of `unit`
+        if (descs && (first || unit >= mat_end)) {
+            if (first) mat = uni(find_matrix(unit_start, n_mats, unit));
+            else while (unit >= uni(unit_start[mat + 1])) ++mat;
+            mat_begin = uni(unit_start[mat]);
+            mat_end = uni(unit_start[mat + 1]);
+        }
+        if (first || descs) {
+            const MatDesc &d = descs ? descs[mat] : one;
+            d_cols = uni((int)d.cols);
+            d_nbc = uni(d.nbc);
+            d_elem = uni64(d.elem_off);
+            d_cbase = uni64(d.block_base * K);
+            upr = (d_nbc + bpu - 1) / bpu;
+        }
+        const int ul = unit - mat_begin;
+        I = uni(ul / upr);
+        U = ul - I * upr;
+    };
+    enter_unit(true);
+
+    struct StepAddr {
+        const char *Wb, *Sb;      // uniform
+        uint32_t voff;            // per-lane byte offset (bf16 units) inside the step
+        uint32_t wstride;
+        int J0, nbc, I;           // uniform: first block column of the unit, block columns, block row
+        float *cbase;             // uniform: cost rows of the matrix
+    };
+    auto address = [&]() {
+        StepAddr a;
+        const int J0 = U * bpu;
+        const int64_t ubase = ((int64_t)I * m + (int64_t)p * OS * 8) * d_cols + (int64_t)J0 * (LPG * 8);
+        a.Wb = reinterpret_cast<const char *>(W + d_elem + ubase);
+        a.Sb = reinterpret_cast<const char *>(S + d_elem + ubase);
+        const int lim = d_nbc - 1 - J0;              // ragged unit: clamp the block column
+        const int ble = bl < lim ? bl : lim;
+        a.voff = ((uint32_t)o0 * 8u * (uint32_t)d_cols + (uint32_t)ble * (LPG * 8) + (uint32_t)lig * 8u) * 2u;
+        a.wstride = (uint32_t)d_cols * 2u;
+        a.J0 = J0; a.nbc = d_nbc; a.I = I;
+        a.cbase = cost + d_cbase;
+        return a;
+    };
+    auto advance = [&]() {                           // to the next step, possibly the next unit / matrix
+        if (++p < steps) return;
+        if (unit + u_step >= u_end) { p = steps - 1; return; }  // stay on the last step
+        p = 0;
+        unit += u_step;
+        if (STRIDED || unit >= mat_end) {
+            enter_unit(false);
+        } else if (++U >= upr) {
+            U = 0; ++I;
+        }
+    };
+
+    HalfBuf A, B;
+    StepAddr nxt = address();
+    load_half(A, nxt.Wb, nxt.Sb, nxt.voff, nxt.wstride);
+
+    int pc = 0;                                      // step inside the unit being computed
+    for (int sidx = 0; sidx < nsteps; ++sidx) {
+        const StepAddr now = nxt;
+        load_half(B, now.Wb, now.Sb, now.voff + HALF * now.wstride, now.wstride);
+        float t1[K], t2[K], t3[K], cur[K];
+        compute_half<LPG, K, 0>(A, dp, t1, t2, t3, cur);
+
+        // the next step's first half goes in flight before this step's second half is computed
+        // (after the last step this re-reads the last step: harmless, keeps the loop branch-free)
+        advance();
+        nxt = address();
+        load_half(A, nxt.Wb, nxt.Sb, nxt.voff, nxt.wstride);
+        compute_half<LPG, K, HALF>(B, dp, t1, t2, t3, cur);
+
+        const int oct = bl * opb + o0 + pc * OS;
 #pragma unroll
         for (int c = 0; c < K; ++c) {
             const float v = group_allreduce<LPG>(cur[c], OpAdd{});
-            if (lig == 0) osum[oct_in_wg * K + c] = v;
+            if (lig == 0) osum[oct * K + c] = v;
         }
-    }
-    __syncthreads();
-
-    const int noct_wg = bpw * opb;
-    for (int s = 1; s < opb; s <<= 1) {
-        const int npairs = noct_wg / (2 * s);
-        for (int p = tid; p < npairs * K; p += COST_THREADS) {
-            const int pi = p / K, c = p - pi * K;
-            const int oo = pi * 2 * s;
-            osum[oo * K + c] = osum[oo * K + c] + osum[(oo + s) * K + c];
+        if (++pc == steps) {
+            pc = 0;
+            __syncthreads();
+            const int noct = bpu * opb;
+            for (int s = 1; s < opb; s <<= 1) {
+                const int npairs = noct / (2 * s);
+                for (int q = tid; q < npairs * K; q += COST_THREADS) {
+                    const int pi = q / K, c = q - pi * K;
+                    const int oo = pi * 2 * s;
+                    osum[oo * K + c] = osum[oo * K + c] + osum[(oo + s) * K + c];
+                }
+                __syncthreads();
+            }
+            for (int q = tid; q < bpu * K; q += COST_THREADS) {
+                const int b2 = q / K, c = q - b2 * K;
+                const int J = now.J0 + b2;
+                if (J < now.nbc) now.cbase[((int64_t)now.I * now.nbc + J) * K + c] = osum[(b2 * opb) * K + c];
+            }
+            __syncthreads();
         }
-        __syncthreads();
-    }
-    for (int p = tid; p < bpw * K; p += COST_THREADS) {
-        const int bl = p / K, c = p - bl * K;
-        const int64_t blk = (int64_t)blockIdx.x * bpw + bl;
-        if (blk < nblocks) cost[blk * K + c] = osum[(bl * opb) * K + c];
     }
 }
 
@@ -187,36 +416,85 @@ static float finite_threshold(float qf)
     return r;
 }
 
-template <int LPG, int K>
-static int launch_lk(sbits_ctx *ctx, const uint16_t *W, const float *S, int64_t C, int m, int nbc,
-                     int64_t nblocks, float *cost, const GridConsts &gc)
+static int persistent_grid(sbits_ctx *ctx, int64_t total_units)
 {
-    constexpr int GPW = COST_THREADS / LPG;
-    const int opb = m / 8;
-    const int bpw = opb >= GPW ? 1 : GPW / opb;
-    const int64_t nwg = (nblocks + bpw - 1) / bpw;
-    if (nwg > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
-    hipLaunchKernelGGL((cost_kernel<LPG, K>), dim3((unsigned)nwg), dim3(COST_THREADS), 0, ctx->stream,
-                       W, S, C, m, nbc, nblocks, cost, gc);
+    static int n_cu = 0;
+    if (!n_cu) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess) n_cu = prop.multiProcessorCount;
+        if (n_cu <= 0) n_cu = 256;
+    }
+    const int64_t g = (int64_t)n_cu * 2;             // two workgroups (8 waves) per CU
+    return (int)(total_units < g ? total_units : g);
+}
+
+struct CostLaunch {
+    const MatDesc *descs;   // device table or null
+    MatDesc one;            // used when descs == null
+    const int *unit_start;  // device prefix or null
+    int n_mats;
+    int64_t total_units;
+    const uint16_t *W;
+    const float *S;
+    int m;
+    float *cost;
+    GridConsts gc;
+};
+
+template <int LPG, int K>
+static int launch_lk(sbits_ctx *ctx, const CostLaunch &a)
+{
+    if (a.total_units > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
+    const int grid = persistent_grid(ctx, a.total_units);
+    if (grid == 0) return SBITS_OK;
+    hipLaunchKernelGGL((cost_kernel<LPG, K, SBITS_COST_STRIDED>), dim3((unsigned)grid), dim3(COST_THREADS), 0, ctx->stream,
+                       a.descs, a.one, a.unit_start, a.n_mats, (int)a.total_units, a.W, a.S, a.m, a.cost, a.gc);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
 
 template <int LPG>
-static int launch_l(int K, sbits_ctx *ctx, const uint16_t *W, const float *S, int64_t C, int m,
-                    int nbc, int64_t nblocks, float *cost, const GridConsts &gc)
+static int launch_l(int K, sbits_ctx *ctx, const CostLaunch &a)
 {
     switch (K) {
-    case 1: return launch_lk<LPG, 1>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
-    case 2: return launch_lk<LPG, 2>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
-    case 3: return launch_lk<LPG, 3>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
-    case 4: return launch_lk<LPG, 4>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
-    case 5: return launch_lk<LPG, 5>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
-    case 6: return launch_lk<LPG, 6>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
-    case 7: return launch_lk<LPG, 7>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
-    case 8: return launch_lk<LPG, 8>(ctx, W, S, C, m, nbc, nblocks, cost, gc);
+    case 1: return launch_lk<LPG, 1>(ctx, a);
+    case 2: return launch_lk<LPG, 2>(ctx, a);
+    case 3: return launch_lk<LPG, 3>(ctx, a);
+    case 4: return launch_lk<LPG, 4>(ctx, a);
+    case 5: return launch_lk<LPG, 5>(ctx, a);
+    case 6: return launch_lk<LPG, 6>(ctx, a);
+    case 7: return launch_lk<LPG, 7>(ctx, a);
+    case 8: return launch_lk<LPG, 8>(ctx, a);
     }
     return SBITS_ERR_BAD_BITWIDTHS;
+}
+
+static int launch(int n, int K, sbits_ctx *ctx, const CostLaunch &a)
+{
+    switch (n / 8) {
+    case 1:  return launch_l<1>(K, ctx, a);
+    case 2:  return launch_l<2>(K, ctx, a);
+    case 4:  return launch_l<4>(K, ctx, a);
+    case 8:  return launch_l<8>(K, ctx, a);
+    case 16: return launch_l<16>(K, ctx, a);
+    case 32: return launch_l<32>(K, ctx, a);
+    case 64: return launch_l<64>(K, ctx, a);
+    }
+    return SBITS_ERR_BAD_SHAPE;
+}
+
+static int blocks_per_unit(int m, int n)
+{
+    switch (n / 8) {
+    case 1:  return CostGeom<1>::blocks_per_unit(m);
+    case 2:  return CostGeom<2>::blocks_per_unit(m);
+    case 4:  return CostGeom<4>::blocks_per_unit(m);
+    case 8:  return CostGeom<8>::blocks_per_unit(m);
+    case 16: return CostGeom<16>::blocks_per_unit(m);
+    case 32: return CostGeom<32>::blocks_per_unit(m);
+    case 64: return CostGeom<64>::blocks_per_unit(m);
+    }
+    return 1;
 }
 
 }  // namespace sbits
@@ -231,23 +509,51 @@ void sbits_fill_grid_consts(const int32_t *bits, int K, sbits::GridConsts *gc)
     }
 }
 
+// one matrix: the descriptor travels as a kernel argument, nothing is read from a table
 int sbits_launch_cost(sbits_ctx *ctx, const void *Wp, const float *Sp, int64_t R, int64_t C,
                       int m, int n, const int32_t *bits, int K, float *cost_rows)
 {
     using namespace sbits;
-    GridConsts gc;
-    sbits_fill_grid_consts(bits, K, &gc);
-    const int nbc = (int)(C / n);
-    const int64_t nblocks = (R / m) * (C / n);
-    const uint16_t *W = static_cast<const uint16_t *>(Wp);
-    switch (n / 8) {
-    case 1:  return launch_l<1>(K, ctx, W, Sp, C, m, nbc, nblocks, cost_rows, gc);
-    case 2:  return launch_l<2>(K, ctx, W, Sp, C, m, nbc, nblocks, cost_rows, gc);
-    case 4:  return launch_l<4>(K, ctx, W, Sp, C, m, nbc, nblocks, cost_rows, gc);
-    case 8:  return launch_l<8>(K, ctx, W, Sp, C, m, nbc, nblocks, cost_rows, gc);
-    case 16: return launch_l<16>(K, ctx, W, Sp, C, m, nbc, nblocks, cost_rows, gc);
-    case 32: return launch_l<32>(K, ctx, W, Sp, C, m, nbc, nblocks, cost_rows, gc);
-    case 64: return launch_l<64>(K, ctx, W, Sp, C, m, nbc, nblocks, cost_rows, gc);
+    CostLaunch a;
+    memset(&a, 0, sizeof a);
+    sbits_fill_grid_consts(bits, K, &a.gc);
+    a.one.rows = R; a.one.cols = C; a.one.nbr = (int)(R / m); a.one.nbc = (int)(C / n);
+    const int bpu = blocks_per_unit(m, n);
+    a.n_mats = 1;
+    a.total_units = (R / m) * ((C / n + bpu - 1) / bpu);
+    a.W = static_cast<const uint16_t *>(Wp);
+    a.S = Sp;
+    a.m = m;
+    a.cost = cost_rows;
+    return launch(n, K, ctx, a);
+}
+
+// all matrices of the plan in one launch; the descriptor table is already in the workspace head
+int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re, float *cost, void *ws)
+{
+    using namespace sbits;
+    sbits_ctx *ctx = plan->ctx;
+    CostLaunch a;
+    memset(&a, 0, sizeof a);
+    sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
+    const int bpu = blocks_per_unit(plan->m, plan->n);
+    std::vector<int> pre(plan->n_mats + 1);
+    int64_t tot = 0;
+    for (int i = 0; i < plan->n_mats; ++i) {
+        pre[i] = (int)tot;
+        tot += (int64_t)plan->descs[i].nbr * ((plan->descs[i].nbc + bpu - 1) / bpu);
+        if (tot > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
     }
-    return SBITS_ERR_BAD_SHAPE;
+    pre[plan->n_mats] = (int)tot;
+    int *d_pre = sbits_prefix_ptr(plan, ws, 0);
+    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, pre.data(), pre.size() * 4, hipMemcpyHostToDevice, ctx->stream));
+    a.descs = sbits_desc_ptr(ws);
+    a.unit_start = d_pre;
+    a.n_mats = plan->n_mats;
+    a.total_units = tot;
+    a.W = static_cast<const uint16_t *>(w_re);
+    a.S = s_re;
+    a.m = plan->m;
+    a.cost = cost;
+    return launch(plan->n, plan->K, ctx, a);
 }

@@ -13,8 +13,11 @@ namespace sbits {
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v)
 {
+    // every control used here reads a valid lane, so neither "old" nor bound_ctrl matters;
+    // bound_ctrl = 1 spares the initialisation of the destination and lets the compiler
+    // fold the move into the instruction that consumes it
     return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
 
 constexpr int DPP_XOR1 = 0xB1;          // quad_perm [1,0,3,2]
@@ -51,6 +54,28 @@ __device__ __forceinline__ float group_bcast(float v)
     if (LPG == 16) return dpp_mov<DPP_BCAST0 + (J & 15)>(v);
     const int lane = (int)(threadIdx.x & 63);
     return __shfl(v, (lane & ~(LPG - 1)) + J);
+}
+
+// ---- batched launches: one descriptor per matrix of the plan -------------------
+struct MatDesc {
+    const uint16_t *w;        // original weights (bf16) and sensitivities, caller's pointers
+    const float *s;
+    int64_t rows, cols, ld_w, ld_s;
+    int64_t elem_off;         // element offset of the dense reordered copy in the concatenated arrays
+    int64_t block_base;       // first global block id
+    int64_t row_off, col_off; // offsets into the concatenated row / column permutations
+    int nbr, nbc;             // block grid
+};
+
+// largest i with wg_start[i] <= wg  (wg_start has n + 1 ascending entries, wg_start[0] = 0)
+__device__ __forceinline__ int find_matrix(const int *__restrict__ wg_start, int n, int wg)
+{
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (wg_start[mid] <= wg) lo = mid; else hi = mid;
+    }
+    return lo;
 }
 
 // ---- quantization grid constants, one set per candidate ---------------------

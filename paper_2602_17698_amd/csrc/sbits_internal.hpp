@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "scalebits.h"
+#include "sbits_device.hpp"
 
 struct sbits_ctx {
     int device;            // -1: host-only context
@@ -24,8 +25,24 @@ struct sbits_plan {
     int32_t bits[8];
     int64_t N;                               // total blocks
     int64_t max_rows, max_cols;
+    int64_t sum_rows, sum_cols, sum_elems;
+    std::vector<sbits::MatDesc> descs;       // shape part filled at creation; pointers per call
+    size_t head_bytes;                       // workspace head: descriptor table + workgroup prefixes
     size_t ws_bytes;
 };
+
+// The workspace head holds the per-matrix descriptor table and up to four workgroup-prefix
+// arrays of the batched launches; stage scratch starts at sbits_scratch(plan, ws).
+constexpr int SBITS_N_PREFIX = 4;
+static inline size_t sbits_desc_bytes(int n_mats) { return (size_t)((n_mats * sizeof(sbits::MatDesc) + 255) / 256 * 256); }
+static inline size_t sbits_prefix_bytes(int n_mats) { return (size_t)(((n_mats + 1) * 4 + 255) / 256 * 256); }
+static inline sbits::MatDesc *sbits_desc_ptr(void *ws) { return static_cast<sbits::MatDesc *>(ws); }
+static inline int *sbits_prefix_ptr(const sbits_plan *p, void *ws, int slot)
+{
+    return reinterpret_cast<int *>(static_cast<char *>(ws) + sbits_desc_bytes(p->n_mats) +
+                                   (size_t)slot * sbits_prefix_bytes(p->n_mats));
+}
+static inline void *sbits_scratch(const sbits_plan *p, void *ws) { return static_cast<char *>(ws) + p->head_bytes; }
 
 #define SBITS_HIP(ctx, expr)                                                   \
     do {                                                                       \
@@ -50,6 +67,9 @@ int sbits_launch_gather(sbits_ctx *ctx, const void *W, const float *S, int64_t R
                         void *w_out, float *s_out);
 int sbits_launch_cost(sbits_ctx *ctx, const void *Wp, const float *Sp, int64_t R, int64_t C,
                       int m, int n, const int32_t *bits, int K, float *cost_rows);
+// batched over all matrices of the plan (descriptor table already in the workspace head)
+int sbits_upload_descs(sbits_plan *plan, const sbits_matrix *mats, void *ws);
+int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re, float *cost, void *ws);
 int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
                        const sbits_params *prm, uint8_t *level, sbits_stats *host_stats,
                        sbits_trace *host_trace, int64_t trace_cap, void *ws);
