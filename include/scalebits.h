@@ -23,7 +23,7 @@
  *     the unit of precision (paper Sec. 4.1).  The quantization group is one
  *     block row: group size = block width (paper App. E, block size).  m and n
  *     are powers of two, 8 <= m <= 1024, 8 <= n <= 512; rows % m == 0 and
- *     cols % n == 0.
+ *     cols % n == 0; rows, cols <= 32768 per matrix; at most 2^24 blocks in all.
  *   - Blocks are numbered globally: matrix after matrix in plan order, inside a
  *     matrix row-major over the block grid: id = base(mat) + I*(cols/n) + J.
  *   - Candidate bitwidths are strictly increasing integers in 1..8, at most 8
@@ -128,11 +128,22 @@ int  sbits_reorder(sbits_plan *plan, int mat, const sbits_matrix *M,
 /* the scores alone: row_score[rows], col_score[cols] (float32).  Uses ws.       */
 int  sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M,
                           float *row_score, float *col_score, void *ws);
+/* The same for every matrix of the plan in a few launches.  mats: HOST array of the
+ * plan's n_mats matrices; row_perm / col_perm: the permutations concatenated in
+ * plan order (sum of rows / sum of cols entries).  Uses ws.                       */
+int  sbits_reorder_all(sbits_plan *plan, const sbits_matrix *mats,
+                       int32_t *row_perm, int32_t *col_perm, void *ws);
 /* w_out[i][j] = W[row_perm[i]][col_perm[j]], s_out likewise; outputs are dense
  * (pitch = cols) and must not alias the inputs.                                 */
 int  sbits_gather(sbits_plan *plan, int mat, const sbits_matrix *M,
                   const int32_t *row_perm, const int32_t *col_perm,
                   void *w_out_bf16, float *s_out);
+
+/* All matrices: w_re / s_re receive the reordered matrices concatenated in plan
+ * order, each dense (matrix i starts at element sum_{j<i} rows_j*cols_j); either
+ * may be NULL.  Permutations concatenated as in sbits_reorder_all.  Uses ws.      */
+int  sbits_gather_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                      const int32_t *col_perm, void *w_re_bf16, float *s_re, void *ws);
 
 /* ---- block x bitwidth cost table (paper Sec. 5: RTN quantizer, group = block
  * row; App. E: the exact re-quantized change that the surrogates approximate) --
@@ -174,6 +185,10 @@ int  sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, vo
  * code*scale + zero).  level, byte_off, codes, scale, zero are the GLOBAL arrays.*/
 int  sbits_pack(sbits_plan *plan, int mat, const void *w_re_bf16, const uint8_t *level,
                 const int64_t *byte_off, uint8_t *codes, float *scale, float *zero);
+
+/* All matrices in one launch; w_re concatenated as in sbits_gather_all.  Uses ws.  */
+int  sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *level,
+                    const int64_t *byte_off, uint8_t *codes, float *scale, float *zero, void *ws);
 
 /* ---- the whole path in one call -------------------------------------------- */
 typedef struct {

@@ -20,7 +20,8 @@ EXPORTS = [
     "sbits_create", "sbits_destroy", "sbits_last_hip_error", "sbits_strerror",
     "sbits_plan_create", "sbits_plan_destroy", "sbits_num_blocks", "sbits_block_base",
     "sbits_workspace_bytes", "sbits_codes_bytes_bound",
-    "sbits_reorder", "sbits_channel_scores", "sbits_gather", "sbits_cost_table", "sbits_cost_table_all",
+    "sbits_reorder", "sbits_reorder_all", "sbits_channel_scores", "sbits_gather", "sbits_gather_all",
+    "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
     "sbits_allocate", "sbits_offsets", "sbits_pack", "sbits_search",
 ]
 
@@ -183,6 +184,20 @@ class Plan:
     def cost_table(self, mat, w_re, s_re, cost):
         return _check(load().sbits_cost_table(self.h, C.c_int(mat), _ptr(w_re), _ptr(s_re), _ptr(cost)),
                       "sbits_cost_table")
+
+    def reorder_all(self, mats, row_perm, col_perm, ws):
+        arr = (Matrix * len(mats))(*mats)
+        return _check(load().sbits_reorder_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(ws)),
+                      "sbits_reorder_all")
+
+    def gather_all(self, mats, row_perm, col_perm, w_re, s_re, ws):
+        arr = (Matrix * len(mats))(*mats)
+        return _check(load().sbits_gather_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(w_re),
+                                              _ptr(s_re), _ptr(ws)), "sbits_gather_all")
+
+    def pack_all(self, w_re, level, byte_off, codes, scale, zero, ws):
+        return _check(load().sbits_pack_all(self.h, _ptr(w_re), _ptr(level), _ptr(byte_off), _ptr(codes),
+                                            _ptr(scale), _ptr(zero), _ptr(ws)), "sbits_pack_all")
 
     def cost_table_all(self, w_re, s_re, cost, ws):
         return _check(load().sbits_cost_table_all(self.h, _ptr(w_re), _ptr(s_re), _ptr(cost), _ptr(ws)),

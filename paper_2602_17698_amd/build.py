@@ -16,7 +16,8 @@ SOURCES = ["api.hip", "reorder.hip", "cost.hip", "alloc.hip", "pack.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-ffp-contract=off",                       # no implicit FMA: only the fmaf() the method names
-         "-fno-honor-nans",                         # inputs are finite by contract; spares NaN-quieting ops
+         "-Xarch_device", "-fno-honor-nans",        # device code only: inputs are finite by contract,
+                                                    # spares the NaN-quieting ops around min/max
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + INCLUDE, "-I" + CSRC, "-Wall", "-Wno-unused-function"]
 

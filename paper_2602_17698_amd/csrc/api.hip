@@ -78,9 +78,11 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
     p->N = 0;
     p->max_rows = p->max_cols = 0;
     p->sum_rows = p->sum_cols = p->sum_elems = 0;
+    p->sum_rowpart = p->sum_colpart = 0;
+    int64_t score_wgs = 0;
     for (int i = 0; i < n_mats; ++i) {
         if (rows[i] <= 0 || cols[i] <= 0 || rows[i] % block_rows || cols[i] % block_cols ||
-            rows[i] > 0x7fffffff || cols[i] > 32768 || rows[i] > 2097120) {
+            rows[i] > 32768 || cols[i] > 32768) {
             delete p;
             return SBITS_ERR_BAD_SHAPE;
         }
@@ -93,14 +95,20 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
         d.elem_off = p->sum_elems; d.block_base = p->N;
         d.row_off = p->sum_rows; d.col_off = p->sum_cols;
         d.nbr = (int)(rows[i] / block_rows); d.nbc = (int)(cols[i] / block_cols);
+        sbits_score_geometry(rows[i], cols[i], &d.nseg, &d.nband);
+        d.rowpart_off = p->sum_rowpart; d.colpart_off = p->sum_colpart;
+        p->sum_rowpart += rows[i] * d.nseg; p->sum_colpart += (int64_t)d.nband * cols[i];
+        p->score_wg_start.push_back((int)score_wgs);
+        score_wgs += (int64_t)d.nseg * d.nband;
         p->descs.push_back(d);
         p->sum_rows += rows[i]; p->sum_cols += cols[i]; p->sum_elems += rows[i] * cols[i];
         p->N += (rows[i] / block_rows) * (cols[i] / block_cols);
         if (rows[i] > p->max_rows) p->max_rows = rows[i];
         if (cols[i] > p->max_cols) p->max_cols = cols[i];
     }
-    if (p->N > (1ll << 24)) { delete p; return SBITS_ERR_BAD_SHAPE; }   // index field of the selection keys
-    size_t ws = sbits_score_ws_bytes(p->max_rows, p->max_cols);
+    if (p->N > (1ll << 24) || score_wgs > 0x7fffffff) { delete p; return SBITS_ERR_BAD_SHAPE; }   // index field of the selection keys
+    p->score_wg_start.push_back((int)score_wgs);
+    size_t ws = sbits_reorder_ws_bytes(p->sum_rows + p->sum_cols, p->sum_rowpart, p->sum_colpart);
     const size_t a = sbits_alloc_ws_bytes(p->N), o = sbits_offsets_ws_bytes(p->N);
     if (a > ws) ws = a;
     if (o > ws) ws = o;
@@ -183,22 +191,6 @@ extern "C" {
 
 static bool ws_ok(const void *ws) { return ws && (reinterpret_cast<uintptr_t>(ws) & 255) == 0; }
 
-// workspace slices used by reorder: [score partials ...][rank][rs][cs] (see reorder.hip)
-static void reorder_slices(const sbits_plan *plan, int64_t R, int64_t C, void *ws, int **rank,
-                           float **rs, float **cs)
-{
-    const int64_t nseg = (C + 511) / 512, nband = (R + 31) / 32;
-    char *p = static_cast<char *>(ws);
-    p += sbits_align_up((size_t)(R * nseg) * 4, 256);
-    p += sbits_align_up((size_t)(nband * C) * 4, 256);
-    *rank = reinterpret_cast<int *>(p);
-    p += sbits_align_up((size_t)(R > C ? R : C) * 4, 256);
-    *rs = reinterpret_cast<float *>(p);
-    p += sbits_align_up((size_t)R * 4, 256);
-    *cs = reinterpret_cast<float *>(p);
-    (void)plan;
-}
-
 int sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M, float *row_score,
                          float *col_score, void *ws)
 {
@@ -217,13 +209,41 @@ int sbits_reorder(sbits_plan *plan, int mat, const sbits_matrix *M, int32_t *row
     if (rc) return rc;
     if (!row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
     if ((rc = need_device(plan))) return rc;
-    int *rank;
-    float *rs, *cs;
-    void *scr = sbits_scratch(plan, ws);
-    reorder_slices(plan, M->rows, M->cols, scr, &rank, &rs, &cs);
-    if ((rc = sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, rs, cs, scr))) return rc;
-    if ((rc = sbits_launch_argsort(plan->ctx, rs, M->rows, row_perm, rank))) return rc;
-    return sbits_launch_argsort(plan->ctx, cs, M->cols, col_perm, rank);
+    return sbits_launch_reorder(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, row_perm, col_perm,
+                                sbits_scratch(plan, ws));
+}
+
+static int check_all(const sbits_plan *plan, const sbits_matrix *mats, bool need_w, bool need_s)
+{
+    if (!plan || !mats) return SBITS_ERR_INVALID_ARG;
+    for (int i = 0; i < plan->n_mats; ++i) {
+        const int rc = check_matrix(plan, i, &mats[i], need_w, need_s);
+        if (rc) return rc;
+    }
+    return SBITS_OK;
+}
+
+int sbits_reorder_all(sbits_plan *plan, const sbits_matrix *mats, int32_t *row_perm, int32_t *col_perm, void *ws)
+{
+    int rc = check_all(plan, mats, false, true);
+    if (rc) return rc;
+    if (!row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if ((rc = need_device(plan))) return rc;
+    if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    return sbits_launch_reorder_all(plan, row_perm, col_perm, ws);
+}
+
+int sbits_gather_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                     const int32_t *col_perm, void *w_re_bf16, float *s_re, void *ws)
+{
+    int rc = check_all(plan, mats, w_re_bf16 != nullptr, s_re != nullptr);
+    if (rc) return rc;
+    if (!row_perm || !col_perm || (!w_re_bf16 && !s_re) || !aligned16(col_perm) || !aligned16(w_re_bf16) ||
+        !aligned16(s_re) || !ws_ok(ws))
+        return SBITS_ERR_INVALID_ARG;
+    if ((rc = need_device(plan))) return rc;
+    if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    return sbits_launch_gather_all(plan, row_perm, col_perm, w_re_bf16, s_re, ws);
 }
 
 int sbits_gather(sbits_plan *plan, int mat, const sbits_matrix *M, const int32_t *row_perm,
@@ -296,6 +316,18 @@ int sbits_pack(sbits_plan *plan, int mat, const void *w_re_bf16, const uint8_t *
                              plan->bits, plan->K, level, byte_off, plan->base[mat], codes, scale, zero);
 }
 
+int sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *level, const int64_t *byte_off,
+                   uint8_t *codes, float *scale, float *zero, void *ws)
+{
+    if (!plan || !w_re_bf16 || !level || !byte_off || !codes || !scale || !zero || !ws_ok(ws))
+        return SBITS_ERR_INVALID_ARG;
+    if (!aligned16(w_re_bf16) || !aligned16(codes)) return SBITS_ERR_INVALID_ARG;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    if ((rc = sbits_upload_descs(plan, nullptr, ws))) return rc;
+    return sbits_launch_pack_all(plan, w_re_bf16, level, byte_off, codes, scale, zero, ws);
+}
+
 int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, const sbits_params *params,
                  const sbits_outputs *out, sbits_stats *host_stats, void *ws)
 {
@@ -307,27 +339,18 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
     if (out->codes_capacity < sbits_codes_bytes_bound(plan, avg_bits)) return SBITS_ERR_CAPACITY;
     int rc = need_device(plan);
     if (rc) return rc;
-    int64_t roff = 0, coff = 0, eoff = 0;
-    for (int i = 0; i < plan->n_mats; ++i) {
-        const sbits_matrix *M = &mats[i];
-        int32_t *rp = out->row_perm + roff, *cp = out->col_perm + coff;
-        uint16_t *w_re = static_cast<uint16_t *>(out->w_re_bf16) + eoff;
-        float *s_re = out->s_re + eoff;
-        if ((rc = sbits_reorder(plan, i, M, rp, cp, ws))) return rc;
-        if ((rc = sbits_gather(plan, i, M, rp, cp, w_re, s_re))) return rc;
-        if ((rc = sbits_cost_table(plan, i, w_re, s_re, out->cost))) return rc;
-        roff += M->rows; coff += M->cols; eoff += M->rows * M->cols;
-    }
+    if ((rc = check_all(plan, mats, true, true))) return rc;
+    if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    if ((rc = sbits_launch_reorder_all(plan, out->row_perm, out->col_perm, ws))) return rc;
+    if ((rc = sbits_launch_gather_all(plan, out->row_perm, out->col_perm, out->w_re_bf16, out->s_re, ws))) return rc;
+    if ((rc = sbits_launch_cost_all(plan, out->w_re_bf16, out->s_re, out->cost, ws))) return rc;
     rc = sbits_allocate(plan, out->cost, avg_bits, params, out->level, host_stats, nullptr, 0, ws);
     const int alloc_rc = rc;
     if (rc && rc != SBITS_ERR_MAX_ITERS) return rc;
     if ((rc = sbits_offsets(plan, out->level, out->byte_off, ws))) return rc;
-    eoff = 0;
-    for (int i = 0; i < plan->n_mats; ++i) {
-        const uint16_t *w_re = static_cast<const uint16_t *>(out->w_re_bf16) + eoff;
-        if ((rc = sbits_pack(plan, i, w_re, out->level, out->byte_off, out->codes, out->scale, out->zero))) return rc;
-        eoff += mats[i].rows * mats[i].cols;
-    }
+    if ((rc = sbits_launch_pack_all(plan, out->w_re_bf16, out->level, out->byte_off, out->codes, out->scale,
+                                    out->zero, ws)))
+        return rc;
     SBITS_HIP(plan->ctx, hipStreamSynchronize(plan->ctx->stream));
     return alloc_rc;
 }

@@ -536,17 +536,20 @@ int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re,
     CostLaunch a;
     memset(&a, 0, sizeof a);
     sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
-    const int bpu = blocks_per_unit(plan->m, plan->n);
-    std::vector<int> pre(plan->n_mats + 1);
-    int64_t tot = 0;
-    for (int i = 0; i < plan->n_mats; ++i) {
-        pre[i] = (int)tot;
-        tot += (int64_t)plan->descs[i].nbr * ((plan->descs[i].nbc + bpu - 1) / bpu);
-        if (tot > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
+    if (plan->cost_unit_start.empty()) {             // depends on shapes only: computed once, kept for the copies
+        const int bpu = blocks_per_unit(plan->m, plan->n);
+        int64_t t = 0;
+        for (int i = 0; i < plan->n_mats; ++i) {
+            plan->cost_unit_start.push_back((int)t);
+            t += (int64_t)plan->descs[i].nbr * ((plan->descs[i].nbc + bpu - 1) / bpu);
+            if (t > 0x7fffffff) { plan->cost_unit_start.clear(); return SBITS_ERR_BAD_SHAPE; }
+        }
+        plan->cost_unit_start.push_back((int)t);
     }
-    pre[plan->n_mats] = (int)tot;
+    const int64_t tot = plan->cost_unit_start.back();
     int *d_pre = sbits_prefix_ptr(plan, ws, 0);
-    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, pre.data(), pre.size() * 4, hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, plan->cost_unit_start.data(), plan->cost_unit_start.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
     a.descs = sbits_desc_ptr(ws);
     a.unit_start = d_pre;
     a.n_mats = plan->n_mats;

@@ -8,6 +8,8 @@
 //           [e*c, (e+1)*c) of the block's little-endian bit stream.  A lane owns
 //           8 consecutive weights = exactly c bytes of the stream; the lanes of
 //           a row stage their bytes in LDS and the row is written out as dwords.
+#include <string.h>
+
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
 
@@ -93,88 +95,168 @@ void tile_scan_kernel(const uint8_t *__restrict__ level, long long N, long long 
 // ---- pack -------------------------------------------------------------------------
 constexpr int PK_THREADS = 256;
 
+// Geometry as in the cost kernel: the GW = 64/LPG lane groups of a wave sit on BX adjacent
+// blocks of one block row (contiguous reads), the four waves (and the remaining OW groups of a
+// wave) take different octets.  A workgroup is one step of one unit; each lane group packs one
+// octet (8 rows) of one block, staged in LDS and written out as one contiguous run.
+template <int LPG>
+struct PackGeom {
+    static constexpr int GW = 64 / LPG;
+    static constexpr int BX = GW < 8 ? GW : 8;
+    static constexpr int OW = GW / BX;
+    static constexpr int OS = 4 * OW;
+    static int blocks_per_unit(int m) { const int opb = m / 8; return opb >= OS ? BX : BX * (OS / opb); }
+    static int steps(int m) { const int opb = m / 8; return opb >= OS ? opb / OS : 1; }
+};
+
 template <int LPG>
 __global__ __launch_bounds__(PK_THREADS)
-void pack_kernel(const uint16_t *__restrict__ W, int64_t C, int m, int nbc, int64_t nrows_total,
-                 const uint8_t *__restrict__ level, const int64_t *__restrict__ byte_off,
-                 int64_t block_base, uint8_t *__restrict__ codes, float *__restrict__ scale,
+void pack_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ wg_start, int n_mats,
+                 const uint16_t *__restrict__ W, int m, const uint8_t *__restrict__ level,
+                 const int64_t *__restrict__ byte_off, uint8_t *__restrict__ codes, float *__restrict__ scale,
                  float *__restrict__ zero, GridConsts gc)
 {
-    constexpr int GPW = PK_THREADS / LPG;            // block rows per workgroup
-    __shared__ __align__(16) uint8_t stage[PK_THREADS * 8];
-    const int tid = threadIdx.x;
-    const int g = tid / LPG, lig = tid % LPG;
+    using G = PackGeom<LPG>;
+    constexpr int BX = G::BX, OS = G::OS, NG = PK_THREADS / LPG;
+    __shared__ __align__(16) uint8_t stage[NG][8 * LPG * 8];     // per group: 8 rows x LPG*c bytes (c <= 8)
 
-    // global row id over (block, row in block): rows of one block are consecutive
-    int64_t rid = (int64_t)blockIdx.x * GPW + g;
-    const bool valid = rid < nrows_total;
-    if (!valid) rid = nrows_total - 1;
-    const int64_t blk = rid / m;
-    const int r = (int)(rid - blk * m);
-    const int64_t I = blk / nbc, J = blk - I * nbc;
-    const int64_t gb = block_base + blk;
+    const int mat = descs ? find_matrix(wg_start, n_mats, (int)blockIdx.x) : 0;
+    const MatDesc d = descs ? descs[mat] : one;
+    const int lid = (int)blockIdx.x - (descs ? wg_start[mat] : 0);
+    const int opb = m >> 3;
+    const int bpu = opb >= OS ? BX : BX * (OS / opb);
+    const int steps = opb >= OS ? opb / OS : 1;
+    const int upr = (d.nbc + bpu - 1) / bpu;
+    const int I = lid / (upr * steps);
+    const int rem = lid - I * (upr * steps);
+    const int U = rem / steps, p = rem - U * steps;
+
+    const int tid = threadIdx.x;
+    const int lig = tid % LPG;
+    const int g = tid / LPG;
+    const int gw = (tid & 63) / LPG;
+    const int slot = (tid >> 6) * G::OW + gw / BX;
+    const int bl = (gw % BX) + (opb >= OS ? 0 : BX * (slot / opb));
+    const int o = (opb >= OS ? slot : slot % opb) + p * OS;
+    const int J = U * bpu + bl;
+    const bool valid = J < d.nbc;
+    const int Jc = valid ? J : d.nbc - 1;
+    const int64_t gb = d.block_base + (int64_t)I * d.nbc + Jc;   // global block id
     const int lv = level[gb];
     int c = gc.bits[0];
     float qf = gc.qmaxf[0], th = gc.thr[0];
 #pragma unroll
     for (int cc = 1; cc < 8; ++cc)
         if (lv == cc) { c = gc.bits[cc]; qf = gc.qmaxf[cc]; th = gc.thr[cc]; }
-
-    const int64_t off = (I * m + r) * C + J * (LPG * 8) + lig * 8;
-    const uint4 wp = *reinterpret_cast<const uint4 *>(W + off);
-    float w[8];
-    unpack8(wp, w);
-    float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
-    float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
-    mn = group_allreduce<LPG>(mn, OpMin{});
-    mx = group_allreduce<LPG>(mx, OpMax{});
-    const float R = mx - mn;
-    float inv = qf / R, scl = R / qf;
-    if (R < th) { inv = 0.0f; scl = 0.0f; }
-
-    unsigned long long word = 0;
     const unsigned int qmax = (unsigned int)qf;
+
+    const uint16_t *__restrict__ src = W + d.elem_off + ((int64_t)I * m + (int64_t)o * 8) * d.cols +
+                                       (int64_t)Jc * (LPG * 8) + lig * 8;
+    uint4 raw[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float t = rintf((w[e] - mn) * inv);
-        unsigned int q = (unsigned int)(int)t;
-        q = q > qmax ? qmax : q;
-        word |= (unsigned long long)q << (e * c);
+    for (int rr = 0; rr < 8; ++rr) raw[rr] = *reinterpret_cast<const uint4 *>(src + (int64_t)rr * d.cols);
+
+    const int row_bytes = LPG * c;
+    const bool odd = (lig & 1) != 0;                 // even lanes divide qmax/R, odd lanes R/qmax
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+        float w[8];
+        unpack8(raw[rr], w);
+        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
+        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+        mn = group_allreduce<LPG>(mn, OpMin{});
+        mx = group_allreduce<LPG>(mx, OpMax{});
+        const float R = mx - mn;
+        float inv, scl;
+        if (LPG >= 2) {
+            float v = (odd ? R : qf) / (odd ? qf : R);
+            if (R < th) v = 0.0f;
+            inv = group_bcast<LPG, 0>(v);
+            scl = group_bcast<LPG, 1 % LPG>(v);
+        } else {
+            inv = qf / R; scl = R / qf;
+            if (R < th) { inv = 0.0f; scl = 0.0f; }
+        }
+        unsigned long long word = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            unsigned int q = (unsigned int)(int)rintf((w[e] - mn) * inv);
+            q = q > qmax ? qmax : q;
+            word |= (unsigned long long)q << (e * c);
+        }
+        uint8_t *mine = &stage[g][rr * row_bytes + lig * c];
+        for (int t = 0; t < c; ++t) mine[t] = (uint8_t)(word >> (8 * t));
+        if (valid && lig == 0) {
+            const int64_t ri = gb * m + o * 8 + rr;
+            scale[ri] = scl;
+            zero[ri] = mn + 0.0f;
+        }
     }
-    // each group has a fixed slot of LPG*8 bytes; the row's LPG*c bytes sit at its start
-    uint8_t *mine = stage + (size_t)g * LPG * 8 + (size_t)lig * c;
-    for (int t = 0; t < c; ++t) mine[t] = (uint8_t)(word >> (8 * t));
     __syncthreads();
     if (valid) {
-        const int row_bytes = LPG * c;
-        uint8_t *dst = codes + byte_off[gb] + (int64_t)r * row_bytes;
-        const uint8_t *src = stage + (size_t)g * LPG * 8;
-        if ((row_bytes & 3) == 0) {
-            for (int d = lig; d < row_bytes / 4; d += LPG)
-                reinterpret_cast<uint32_t *>(dst)[d] = reinterpret_cast<const uint32_t *>(src)[d];
-        } else {
-            for (int d = lig; d < row_bytes; d += LPG) dst[d] = src[d];
-        }
-        if (lig == 0) {
-            scale[gb * m + r] = scl;
-            zero[gb * m + r] = mn + 0.0f;
-        }
+        // the octet's 8 rows are consecutive in the block's stream: one run of 8*row_bytes bytes
+        uint8_t *dst = codes + byte_off[gb] + (int64_t)o * 8 * row_bytes;
+        const int nbytes = 8 * row_bytes;            // a multiple of 8
+        const uint32_t *s32 = reinterpret_cast<const uint32_t *>(&stage[g][0]);
+        uint32_t *d32 = reinterpret_cast<uint32_t *>(dst);
+        for (int k = lig; k < nbytes / 4; k += LPG) d32[k] = s32[k];
     }
 }
 
+struct PackLaunch {
+    const MatDesc *descs;
+    MatDesc one;
+    const int *wg_start;
+    int n_mats;
+    int64_t total_wg;
+    const uint16_t *W;
+    int m;
+    const uint8_t *level;
+    const int64_t *byte_off;
+    uint8_t *codes;
+    float *scale, *zero;
+    GridConsts gc;
+};
+
 template <int LPG>
-static int launch_pack_l(sbits_ctx *ctx, const uint16_t *W, int64_t C, int m, int nbc, int64_t nblocks,
-                         const uint8_t *level, const int64_t *byte_off, int64_t block_base,
-                         uint8_t *codes, float *scale, float *zero, const GridConsts &gc)
+static int launch_pack_l(sbits_ctx *ctx, const PackLaunch &a)
 {
-    constexpr int GPW = PK_THREADS / LPG;
-    const int64_t nrows = nblocks * m;
-    const int64_t nwg = (nrows + GPW - 1) / GPW;
-    if (nwg > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
-    hipLaunchKernelGGL((pack_kernel<LPG>), dim3((unsigned)nwg), dim3(PK_THREADS), 0, ctx->stream,
-                       W, C, m, nbc, nrows, level, byte_off, block_base, codes, scale, zero, gc);
+    if (a.total_wg > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
+    if (a.total_wg == 0) return SBITS_OK;
+    hipLaunchKernelGGL((pack_kernel<LPG>), dim3((unsigned)a.total_wg), dim3(PK_THREADS), 0, ctx->stream,
+                       a.descs, a.one, a.wg_start, a.n_mats, a.W, a.m, a.level, a.byte_off, a.codes, a.scale,
+                       a.zero, a.gc);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
+}
+
+static int launch_pack(int n, sbits_ctx *ctx, const PackLaunch &a)
+{
+    switch (n / 8) {
+    case 1:  return launch_pack_l<1>(ctx, a);
+    case 2:  return launch_pack_l<2>(ctx, a);
+    case 4:  return launch_pack_l<4>(ctx, a);
+    case 8:  return launch_pack_l<8>(ctx, a);
+    case 16: return launch_pack_l<16>(ctx, a);
+    case 32: return launch_pack_l<32>(ctx, a);
+    case 64: return launch_pack_l<64>(ctx, a);
+    }
+    return SBITS_ERR_BAD_SHAPE;
+}
+
+static int64_t pack_wgs(int m, int n, int nbr, int nbc)
+{
+    int bpu = 1, st = 1;
+    switch (n / 8) {
+    case 1:  bpu = PackGeom<1>::blocks_per_unit(m);  st = PackGeom<1>::steps(m); break;
+    case 2:  bpu = PackGeom<2>::blocks_per_unit(m);  st = PackGeom<2>::steps(m); break;
+    case 4:  bpu = PackGeom<4>::blocks_per_unit(m);  st = PackGeom<4>::steps(m); break;
+    case 8:  bpu = PackGeom<8>::blocks_per_unit(m);  st = PackGeom<8>::steps(m); break;
+    case 16: bpu = PackGeom<16>::blocks_per_unit(m); st = PackGeom<16>::steps(m); break;
+    case 32: bpu = PackGeom<32>::blocks_per_unit(m); st = PackGeom<32>::steps(m); break;
+    case 64: bpu = PackGeom<64>::blocks_per_unit(m); st = PackGeom<64>::steps(m); break;
+    }
+    return (int64_t)nbr * ((nbc + bpu - 1) / bpu) * st;
 }
 
 }  // namespace sbits
@@ -208,19 +290,45 @@ int sbits_launch_pack(sbits_ctx *ctx, const void *Wp, int64_t R, int64_t C, int 
                       const int32_t *bits, int K, const uint8_t *level, const int64_t *byte_off,
                       int64_t block_base, uint8_t *codes, float *scale, float *zero)
 {
-    GridConsts gc;
-    sbits_fill_grid_consts(bits, K, &gc);
-    const int nbc = (int)(C / n);
-    const int64_t nblocks = (R / m) * (C / n);
-    const uint16_t *W = static_cast<const uint16_t *>(Wp);
-    switch (n / 8) {
-    case 1:  return launch_pack_l<1>(ctx, W, C, m, nbc, nblocks, level, byte_off, block_base, codes, scale, zero, gc);
-    case 2:  return launch_pack_l<2>(ctx, W, C, m, nbc, nblocks, level, byte_off, block_base, codes, scale, zero, gc);
-    case 4:  return launch_pack_l<4>(ctx, W, C, m, nbc, nblocks, level, byte_off, block_base, codes, scale, zero, gc);
-    case 8:  return launch_pack_l<8>(ctx, W, C, m, nbc, nblocks, level, byte_off, block_base, codes, scale, zero, gc);
-    case 16: return launch_pack_l<16>(ctx, W, C, m, nbc, nblocks, level, byte_off, block_base, codes, scale, zero, gc);
-    case 32: return launch_pack_l<32>(ctx, W, C, m, nbc, nblocks, level, byte_off, block_base, codes, scale, zero, gc);
-    case 64: return launch_pack_l<64>(ctx, W, C, m, nbc, nblocks, level, byte_off, block_base, codes, scale, zero, gc);
+    PackLaunch a;
+    memset(&a, 0, sizeof a);
+    sbits_fill_grid_consts(bits, K, &a.gc);
+    a.one.rows = R; a.one.cols = C; a.one.nbr = (int)(R / m); a.one.nbc = (int)(C / n);
+    a.one.block_base = block_base;
+    a.n_mats = 1;
+    a.total_wg = pack_wgs(m, n, a.one.nbr, a.one.nbc);
+    a.W = static_cast<const uint16_t *>(Wp);
+    a.m = m;
+    a.level = level; a.byte_off = byte_off; a.codes = codes; a.scale = scale; a.zero = zero;
+    return launch_pack(n, ctx, a);
+}
+
+// all matrices of the plan in one launch; the descriptor table is already in the workspace head
+int sbits_launch_pack_all(sbits_plan *plan, const void *w_re, const uint8_t *level, const int64_t *byte_off,
+                          uint8_t *codes, float *scale, float *zero, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    PackLaunch a;
+    memset(&a, 0, sizeof a);
+    sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
+    if (plan->pack_wg_start.empty()) {
+        int64_t tot = 0;
+        for (int i = 0; i < plan->n_mats; ++i) {
+            plan->pack_wg_start.push_back((int)tot);
+            tot += pack_wgs(plan->m, plan->n, plan->descs[i].nbr, plan->descs[i].nbc);
+            if (tot > 0x7fffffff) { plan->pack_wg_start.clear(); return SBITS_ERR_BAD_SHAPE; }
+        }
+        plan->pack_wg_start.push_back((int)tot);
     }
-    return SBITS_ERR_BAD_SHAPE;
+    int *d_pre = sbits_prefix_ptr(plan, ws, 2);
+    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, plan->pack_wg_start.data(), plan->pack_wg_start.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
+    a.descs = sbits_desc_ptr(ws);
+    a.wg_start = d_pre;
+    a.n_mats = plan->n_mats;
+    a.total_wg = plan->pack_wg_start.back();
+    a.W = static_cast<const uint16_t *>(w_re);
+    a.m = plan->m;
+    a.level = level; a.byte_off = byte_off; a.codes = codes; a.scale = scale; a.zero = zero;
+    return launch_pack(plan->n, ctx, a);
 }

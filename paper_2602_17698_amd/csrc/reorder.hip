@@ -1,166 +1,317 @@
 // Bi-directional channel reordering (paper Sec. 4.1): channel scores, argsort,
-// and the reorder-gather of weights and sensitivities.
+// and the reorder-gather of weights and sensitivities.  Every kernel serves all
+// matrices of a plan in one launch (descriptor table + workgroup prefix) or a
+// single matrix whose descriptor travels as a kernel argument.
 //
 // Scores.  Row score = l1 norm of the row of S, column score = l1 norm of the
 // column, each summed in the canonical order: runs of 8 consecutive elements
 // left to right from +0, then an adjacent-pair tree over the runs (zero padded
 // to a power of two).  One pass over S serves both directions: a lane owns an
 // 8 x 8 tile (8 rows, 8 consecutive columns), so it holds 8 row runs and 8
-// column runs at once.  A wave covers 8 rows x 512 columns, a workgroup of four
-// waves 32 rows x 512 columns.  Partial trees are written to the workspace and
-// finished by two small kernels.
+// column runs at once.  A wave covers 8 rows x 512 columns per octet and walks
+// 8 octets; a workgroup of four waves covers 256 rows x 512 columns.  The
+// partial trees (per row and 512-column segment; per column and 256-row band)
+// go to the workspace and a small kernel finishes them.
 //
-// Argsort.  Descending by score, ties to the lower index: rank by counting over
-// a strict total order, which is exact and needs no multi-pass machinery for
-// the at most few ten thousand channels of a matrix.
+// Argsort.  Descending by score, ties to the lower index: a stable LSD radix
+// sort (4 passes of 8 bits) of the inverted ordered-float keys, one workgroup
+// of 16 waves per channel array, all arrays of the plan side by side.
 //
 // Gather.  out[i][j] = in[rp[i]][cp[j]]: the source row is staged in LDS with
 // coalesced 128-bit loads and read out permuted, so global traffic stays
 // coalesced in both directions.
+#include <string.h>
+
+#include <vector>
+
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
 
 namespace sbits {
 
+// ================================================================ scores
 constexpr int SC_THREADS = 256;
-constexpr int SC_ROWS = 32;     // rows per workgroup (4 waves x 8)
+constexpr int SC_ROWS = 256;    // rows per workgroup (4 waves x 8 octets x 8 rows)
 constexpr int SC_COLS = 512;    // columns per workgroup (64 lanes x 8)
 
-static inline int64_t pow2_ceil(int64_t v) { int64_t p = 1; while (p < v) p <<= 1; return p; }
-
 // rowpart[r][seg]  : tree over the 64 column runs of segment seg (zero beyond C)
-// colpart[band][c] : tree over the 4 row runs of band (zero beyond R)
+// colpart[band][c] : tree over the 32 row runs of band (zero beyond R)
 __global__ __launch_bounds__(SC_THREADS)
-void score_partial_kernel(const float *__restrict__ S, int64_t R, int64_t C, int64_t ld,
-                          int nseg, float *__restrict__ rowpart, float *__restrict__ colpart)
+void score_partial_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ wg_start,
+                          int n_mats, float *__restrict__ rowpart_all, float *__restrict__ colpart_all)
 {
     __shared__ float cbuf[4][SC_COLS];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t seg = blockIdx.x, band = blockIdx.y;
-    const int64_t r0 = band * SC_ROWS + wave * 8;
-    const int64_t c0 = seg * SC_COLS + lane * 8;
+    const int mat = descs ? find_matrix(wg_start, n_mats, (int)blockIdx.x) : 0;
+    const MatDesc d = descs ? descs[mat] : one;
+    const int lid = (int)blockIdx.x - (descs ? wg_start[mat] : 0);
+    const int band = lid / d.nseg, seg = lid - band * d.nseg;
+    const int64_t R = d.rows, C = d.cols, ld = d.ld_s;
+    const float *__restrict__ S = d.s;
+    float *__restrict__ rowpart = rowpart_all + d.rowpart_off;
+    float *__restrict__ colpart = colpart_all + d.colpart_off;
 
-    float rowrun[8], colrun[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) colrun[e] = 0.0f;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t c0 = (int64_t)seg * SC_COLS + lane * 8;
     const bool col_ok = c0 < C;                      // C is a multiple of 8
+
+    float t1[8], t2[8], t3[8], col[8];
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr) {
-        float v[8];
-        if (col_ok && r0 + rr < R) {
-            const float *p = S + (r0 + rr) * ld + c0;
-            const float4 a = *reinterpret_cast<const float4 *>(p);
-            const float4 b = *reinterpret_cast<const float4 *>(p + 4);
-            v[0] = fabsf(a.x); v[1] = fabsf(a.y); v[2] = fabsf(a.z); v[3] = fabsf(a.w);
-            v[4] = fabsf(b.x); v[5] = fabsf(b.y); v[6] = fabsf(b.z); v[7] = fabsf(b.w);
-        } else {
+    for (int oc = 0; oc < 8; ++oc) {
+        const int64_t r0 = (int64_t)band * SC_ROWS + wave * 64 + oc * 8;
+        float rowrun[8], colrun[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+        for (int e = 0; e < 8; ++e) colrun[e] = 0.0f;
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            float v[8];
+            if (col_ok && r0 + rr < R) {
+                const float *p = S + (r0 + rr) * ld + c0;
+                const float4 a = *reinterpret_cast<const float4 *>(p);
+                const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+                v[0] = fabsf(a.x); v[1] = fabsf(a.y); v[2] = fabsf(a.z); v[3] = fabsf(a.w);
+                v[4] = fabsf(b.x); v[5] = fabsf(b.y); v[6] = fabsf(b.z); v[7] = fabsf(b.w);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+            }
+            float a = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                a = a + v[e];                        // row run: left to right
+                colrun[e] = colrun[e] + v[e];        // column run: top to bottom
+            }
+            rowrun[rr] = a;
         }
-        float a = 0.0f;
+        // rows: adjacent-pair tree over the 64 lanes (64 runs = 512 columns)
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const float t = group_allreduce<64>(rowrun[rr], OpAdd{});
+            if (lane == 0 && r0 + rr < R) rowpart[(r0 + rr) * d.nseg + seg] = t;
+        }
+        // columns: adjacent-pair tree over the wave's 8 octets, in registers
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            a = a + v[e];                            // row run: left to right
-            colrun[e] = colrun[e] + v[e];            // column run: top to bottom
+            float v = colrun[e];
+            if (oc & 1) {
+                v = t1[e] + v;
+                if (oc & 2) {
+                    v = t2[e] + v;
+                    if (oc & 4) v = t3[e] + v;
+                    else t3[e] = v;
+                } else {
+                    t2[e] = v;
+                }
+            } else {
+                t1[e] = v;
+            }
+            col[e] = v;
         }
-        rowrun[rr] = a;
     }
-    // rows: adjacent-pair tree over the 64 lanes (64 runs = 512 columns)
+    // columns: tree over the 4 waves
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr) {
-        const float t = group_allreduce<64>(rowrun[rr], OpAdd{});
-        if (lane == 0 && r0 + rr < R) rowpart[(r0 + rr) * nseg + seg] = t;
-    }
-    // columns: tree over the 4 waves (row runs 4*band .. 4*band+3)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) cbuf[wave][lane * 8 + e] = colrun[e];
+    for (int e = 0; e < 8; ++e) cbuf[wave][lane * 8 + e] = col[e];
     __syncthreads();
     for (int c = threadIdx.x; c < SC_COLS; c += SC_THREADS) {
-        const int64_t col = seg * SC_COLS + c;
-        if (col < C)
-            colpart[band * C + col] = (cbuf[0][c] + cbuf[1][c]) + (cbuf[2][c] + cbuf[3][c]);
+        const int64_t colx = (int64_t)seg * SC_COLS + c;
+        if (colx < C)
+            colpart[(int64_t)band * C + colx] = (cbuf[0][c] + cbuf[1][c]) + (cbuf[2][c] + cbuf[3][c]);
     }
 }
 
-// Finishes an adjacent-pair tree over n leaves x[i*stride] (zero padded to a
-// power of two; adding the zero padding is the identity, so the stack of
-// completed subtrees is folded from the lowest level up).
-__device__ __forceinline__ float finish_tree(const float *x, int64_t n, int64_t stride)
+// adjacent-pair tree over 32 leaves x[(i0 + i) * stride], i < 32, zero beyond n
+__device__ __forceinline__ float tree32(const float *__restrict__ x, int i0, int n, int64_t stride)
 {
-    float stack[24];
-    for (int64_t i = 0; i < n; ++i) {
-        float v = x[i * stride];
-        int lvl = 0;
-        for (int64_t b = i; b & 1; b >>= 1) { v = stack[lvl] + v; ++lvl; }
-        stack[lvl] = v;
-    }
-    float v = 0.0f;
-    bool have = false;
-    int lvl = 0;
-    for (int64_t b = n; b; b >>= 1, ++lvl) {
-        if (b & 1) { v = have ? stack[lvl] + v : stack[lvl]; have = true; }
-    }
-    return v;
+    float v[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) v[i] = (i0 + i < n) ? x[(int64_t)(i0 + i) * stride] : 0.0f;
+#pragma unroll
+    for (int w = 16; w >= 1; w >>= 1)
+#pragma unroll
+        for (int i = 0; i < w; ++i) v[i] = v[2 * i] + v[2 * i + 1];
+    return v[0];
 }
 
-__global__ void score_finish_kernel(const float *__restrict__ rowpart, const float *__restrict__ colpart,
-                                    int64_t R, int64_t C, int nseg, int64_t nband,
-                                    float *__restrict__ rs, float *__restrict__ cs)
+// adjacent-pair tree over n <= 128 leaves, zero padded to a power of two (adding the padding
+// is the identity, so trees of 32, 64 and 128 leaves nest)
+__device__ __forceinline__ float tree_upto128(const float *__restrict__ x, int n, int64_t stride)
+{
+    float a = tree32(x, 0, n, stride);
+    if (n > 32) a = a + tree32(x, 32, n, stride);
+    if (n > 64) {
+        float b = tree32(x, 64, n, stride);
+        if (n > 96) b = b + tree32(x, 96, n, stride);
+        a = a + b;
+    }
+    return a;
+}
+
+// one thread per channel; scores = [rows of matrix 0 | rows of matrix 1 | ... | cols of matrix 0 | ...]
+__global__ void score_finish_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_mats,
+                                    int64_t sum_rows, int64_t sum_cols,
+                                    const float *__restrict__ rowpart_all, const float *__restrict__ colpart_all,
+                                    float *__restrict__ rs_all, float *__restrict__ cs_all)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < R) rs[t] = finish_tree(rowpart + t * nseg, nseg, 1);
-    else if (t - R < C) cs[t - R] = finish_tree(colpart + (t - R), nband, C);
-}
-
-// ---- argsort: rank by counting ------------------------------------------------
-constexpr int AS_THREADS = 256;
-constexpr int AS_TILE = 2048;    // keys per j-tile
-
-__global__ __launch_bounds__(AS_THREADS)
-void rank_kernel(const float *__restrict__ score, int n, int *__restrict__ rank)
-{
-    __shared__ float tile[AS_TILE];
-    const int i = blockIdx.x * AS_THREADS + threadIdx.x;
-    const int j0 = blockIdx.y * AS_TILE;
-    const int jn = min(AS_TILE, n - j0);
-    for (int j = threadIdx.x; j < jn; j += AS_THREADS) tile[j] = score[j0 + j];
-    __syncthreads();
-    if (i >= n) return;
-    const float si = score[i];
-    int cnt = 0;
-    for (int j = 0; j < jn; ++j) {
-        const float sj = tile[j];
-        cnt += (sj > si) || (sj == si && (j0 + j) < i);   // j precedes i
+    if (t >= sum_rows + sum_cols) return;
+    const bool is_row = t < sum_rows;
+    const int64_t ch = is_row ? t : t - sum_rows;
+    int mat = 0;
+    if (descs) {                                     // largest mat with offset <= ch
+        int lo = 0, hi = n_mats;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            const int64_t o = is_row ? descs[mid].row_off : descs[mid].col_off;
+            if (o <= ch) lo = mid; else hi = mid;
+        }
+        mat = lo;
     }
-    if (cnt) atomicAdd(&rank[i], cnt);
+    const MatDesc &d = descs ? descs[mat] : one;
+    if (is_row) {
+        const int64_t r = ch - d.row_off;
+        rs_all[ch] = tree_upto128(rowpart_all + d.rowpart_off + r * d.nseg, d.nseg, 1);
+    } else {
+        const int64_t c = ch - d.col_off;
+        cs_all[ch] = tree_upto128(colpart_all + d.colpart_off + c, d.nband, d.cols);
+    }
 }
 
-__global__ void scatter_perm_kernel(const int *__restrict__ rank, int n, int32_t *__restrict__ perm)
+// ================================================================ argsort
+constexpr int RS_THREADS = 1024;
+constexpr int RS_WAVES = RS_THREADS / 64;
+
+__device__ __forceinline__ unsigned int sort_key(float f)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) perm[rank[i]] = i;
+    const unsigned int u = __float_as_uint(f + 0.0f);                 // -0 -> +0
+    const unsigned int ord = (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // ascending in f
+    return ~ord;                                                      // ascending key = descending score
 }
 
-__global__ void zero_i32_kernel(int *p, int64_t n)
+// Array a of the launch: a < n_mats -> the rows of matrix a, else the columns of matrix a - n_mats.
+// k0/k1/i0/i1 are ping-pong buffers with the same indexing as the score array.
+__global__ __launch_bounds__(RS_THREADS)
+void radix_argsort_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_mats, int64_t sum_rows,
+                          const float *__restrict__ scores, unsigned int *__restrict__ k0,
+                          unsigned int *__restrict__ k1, unsigned int *__restrict__ i0,
+                          unsigned int *__restrict__ i1, int32_t *__restrict__ row_perm,
+                          int32_t *__restrict__ col_perm)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
+    __shared__ unsigned int hist[RS_WAVES][256];     // per-wave digit counts, then running offsets
+    __shared__ unsigned int total[256];
+    const int a = blockIdx.x;
+    const bool is_row = a < n_mats;
+    const MatDesc &d = descs ? descs[is_row ? a : a - n_mats] : one;
+    const int n = (int)(is_row ? d.rows : d.cols);
+    const int64_t off = is_row ? d.row_off : sum_rows + d.col_off;
+    int32_t *__restrict__ perm = is_row ? row_perm + d.row_off : col_perm + d.col_off;
+    const float *__restrict__ sc = scores + off;
+    unsigned int *kb[2] = {k0 + off, k1 + off};
+    unsigned int *ib[2] = {i0 + off, i1 + off};
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // each wave owns a contiguous segment (a multiple of 64 long) of the current order
+    const int seg = ((n + RS_WAVES - 1) / RS_WAVES + 63) / 64 * 64;
+    const int beg = wave * seg, end = min(beg + seg, n);
+
+    for (int i = tid; i < n; i += RS_THREADS) {
+        kb[0][i] = sort_key(sc[i]);
+        ib[0][i] = (unsigned int)i;
+    }
+    __syncthreads();
+
+    for (int pass = 0; pass < 4; ++pass) {
+        const unsigned int *__restrict__ kin = kb[pass & 1];
+        const unsigned int *__restrict__ iin = ib[pass & 1];
+        unsigned int *__restrict__ kout = kb[(pass + 1) & 1];
+        unsigned int *__restrict__ iout = ib[(pass + 1) & 1];
+        const int shift = 8 * pass;
+
+        for (int b = lane; b < 256; b += 64) hist[wave][b] = 0;
+        __syncthreads();
+        for (int i = beg + lane; i < end; i += 64) atomicAdd(&hist[wave][(kin[i] >> shift) & 255u], 1u);
+        __syncthreads();
+        // offsets in (digit, wave) order: first the per-digit totals and the per-wave prefix inside a digit
+        if (tid < 256) {
+            unsigned int run = 0;
+            for (int w = 0; w < RS_WAVES; ++w) {
+                const unsigned int c = hist[w][tid];
+                hist[w][tid] = run;
+                run += c;
+            }
+            total[tid] = run;
+        }
+        __syncthreads();
+        if (wave == 0) {                             // exclusive scan of the 256 totals by one wave
+            unsigned int v[4], s = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { v[j] = total[lane * 4 + j]; s += v[j]; }
+            unsigned int inc = s;
+            for (int o = 1; o < 64; o <<= 1) {
+                const unsigned int t = __shfl_up(inc, o);
+                if (lane >= o) inc += t;
+            }
+            unsigned int ex = inc - s;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { total[lane * 4 + j] = ex; ex += v[j]; }
+        }
+        __syncthreads();
+        for (int b = lane; b < 256; b += 64) hist[wave][b] += total[b];
+        __syncthreads();
+        // stable scatter: the wave walks its segment in order, 64 elements at a time
+        for (int i = beg + lane; i - lane < end; i += 64) {
+            const bool valid = i < end;
+            const unsigned int key = valid ? kin[i] : 0u;
+            const unsigned int idx = valid ? iin[i] : 0u;
+            const unsigned int dg = (key >> shift) & 255u;
+            unsigned long long same = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const unsigned long long bal = __ballot((dg >> b) & 1u);
+                same &= ((dg >> b) & 1u) ? bal : ~bal;
+            }
+            const unsigned long long lt = (1ull << lane) - 1ull;
+            const unsigned int rank = __popcll(same & lt);
+            if (valid) {
+                const unsigned int base = hist[wave][dg];
+                const unsigned int dst = base + rank;
+                if (pass == 3) perm[dst] = (int32_t)idx;
+                else { kout[dst] = key; iout[dst] = idx; }
+                if (rank == 0) hist[wave][dg] = base + __popcll(same);
+            }
+        }
+        __syncthreads();
+    }
 }
 
-// ---- gather -------------------------------------------------------------------
+// ================================================================ gather
 constexpr int GA_THREADS = 256;
 
-// T = uint16_t (bf16) or float.  One workgroup per output row.
+// T = uint16_t (bf16) or float.  One workgroup per output row; rows of all matrices side by side.
 template <class T>
 __global__ __launch_bounds__(GA_THREADS)
-void gather_kernel(const T *__restrict__ in, int64_t R, int64_t C, int64_t ld, const int32_t *__restrict__ rp,
-                   const int32_t *__restrict__ cp, T *__restrict__ out)
+void gather_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_mats,
+                   const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm,
+                   T *__restrict__ out_all)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     T *row = reinterpret_cast<T *>(smem);
     constexpr int V = 16 / sizeof(T);               // elements per 128-bit access
-    const int64_t i = blockIdx.x;
-    int64_t sr = rp[i];
+    const int64_t g = blockIdx.x;                    // global row index
+    int mat = 0;
+    if (descs) {
+        int lo = 0, hi = n_mats;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (descs[mid].row_off <= g) lo = mid; else hi = mid;
+        }
+        mat = lo;
+    }
+    const MatDesc &d = descs ? descs[mat] : one;
+    const int64_t R = d.rows, C = d.cols;
+    const int64_t i = g - d.row_off;
+    const T *in = sizeof(T) == 2 ? reinterpret_cast<const T *>(d.w) : reinterpret_cast<const T *>(d.s);
+    const int64_t ld = sizeof(T) == 2 ? d.ld_w : d.ld_s;
+    const int32_t *__restrict__ cp = col_perm + d.col_off;
+    int64_t sr = row_perm[g];
     sr = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);       // a permutation never trips this; keeps a bad one in bounds
     const T *src = in + sr * ld;
     const bool aligned = ((reinterpret_cast<uintptr_t>(src) & 15) == 0);
@@ -171,7 +322,7 @@ void gather_kernel(const T *__restrict__ in, int64_t R, int64_t C, int64_t ld, c
         for (int64_t j = threadIdx.x; j < C; j += GA_THREADS) row[j] = src[j];
     }
     __syncthreads();
-    T *dst = out + i * C;                            // dense output, C % 8 == 0: 16-byte aligned rows
+    T *dst = out_all + d.elem_off + i * C;           // dense output, C % 8 == 0: 16-byte aligned rows
     for (int64_t j = (int64_t)threadIdx.x * V; j < C; j += (int64_t)GA_THREADS * V) {
         T tmp[V];
         const int4 c0 = *reinterpret_cast<const int4 *>(cp + j);
@@ -188,49 +339,108 @@ void gather_kernel(const T *__restrict__ in, int64_t R, int64_t C, int64_t ld, c
 
 using namespace sbits;
 
-// workspace: rowpart [R][nseg] | colpart [nband][C] | rank [max(R,C)] | rs [R] | cs [C]
-size_t sbits_score_ws_bytes(int64_t R, int64_t C)
+// ---- workspace of the reorder stage (after the head) ---------------------------------
+//   scores [L] | rowpart [RP] | colpart [CP] | k0 [L] | k1 [L] | i0 [L] | i1 [L]
+// with L = channels (rows + cols), RP = sum rows*nseg, CP = sum nband*cols.
+struct ReorderWs {
+    float *scores, *rowpart, *colpart;
+    unsigned int *k0, *k1, *i0, *i1;
+};
+
+static size_t reorder_ws_layout(void *base, int64_t L, int64_t RP, int64_t CP, ReorderWs *out)
 {
-    const int64_t nseg = (C + SC_COLS - 1) / SC_COLS, nband = (R + SC_ROWS - 1) / SC_ROWS;
+    char *p = static_cast<char *>(base);
     size_t b = 0;
-    b += sbits_align_up((size_t)(R * nseg) * 4, 256);
-    b += sbits_align_up((size_t)(nband * C) * 4, 256);
-    b += sbits_align_up((size_t)(R > C ? R : C) * 4, 256);
-    b += sbits_align_up((size_t)R * 4, 256);
-    b += sbits_align_up((size_t)C * 4, 256);
+    auto take = [&](size_t bytes) { char *q = p ? p + b : nullptr; b += sbits_align_up(bytes, 256); return q; };
+    float *scores = reinterpret_cast<float *>(take((size_t)L * 4));
+    float *rowpart = reinterpret_cast<float *>(take((size_t)RP * 4));
+    float *colpart = reinterpret_cast<float *>(take((size_t)CP * 4));
+    unsigned int *k0 = reinterpret_cast<unsigned int *>(take((size_t)L * 4));
+    unsigned int *k1 = reinterpret_cast<unsigned int *>(take((size_t)L * 4));
+    unsigned int *i0 = reinterpret_cast<unsigned int *>(take((size_t)L * 4));
+    unsigned int *i1 = reinterpret_cast<unsigned int *>(take((size_t)L * 4));
+    if (out) { out->scores = scores; out->rowpart = rowpart; out->colpart = colpart;
+               out->k0 = k0; out->k1 = k1; out->i0 = i0; out->i1 = i1; }
     return b;
 }
 
-int sbits_launch_scores(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, int64_t ld,
-                        float *row_score, float *col_score, void *ws)
+void sbits_score_geometry(int64_t R, int64_t C, int *nseg, int *nband)
 {
-    const int64_t nseg = (C + SC_COLS - 1) / SC_COLS, nband = (R + SC_ROWS - 1) / SC_ROWS;
-    if (nband > 65535) return SBITS_ERR_BAD_SHAPE;
-    char *p = static_cast<char *>(ws);
-    float *rowpart = reinterpret_cast<float *>(p);
-    p += sbits_align_up((size_t)(R * nseg) * 4, 256);
-    float *colpart = reinterpret_cast<float *>(p);
-    hipLaunchKernelGGL(score_partial_kernel, dim3((unsigned)nseg, (unsigned)nband), dim3(SC_THREADS), 0,
-                       ctx->stream, S, R, C, ld, (int)nseg, rowpart, colpart);
+    *nseg = (int)((C + SC_COLS - 1) / SC_COLS);
+    *nband = (int)((R + SC_ROWS - 1) / SC_ROWS);
+}
+
+size_t sbits_reorder_ws_bytes(int64_t L, int64_t RP, int64_t CP)
+{
+    return reorder_ws_layout(nullptr, L, RP, CP, nullptr);
+}
+
+// descriptor of a single matrix with its own (offset-free) layout
+static MatDesc single_desc(const void *W, const float *S, int64_t R, int64_t C, int64_t ld_w, int64_t ld_s)
+{
+    MatDesc d;
+    memset(&d, 0, sizeof d);
+    d.w = static_cast<const uint16_t *>(W);
+    d.s = S;
+    d.rows = R; d.cols = C; d.ld_w = ld_w; d.ld_s = ld_s;
+    sbits_score_geometry(R, C, &d.nseg, &d.nband);
+    return d;
+}
+
+static int run_scores(sbits_ctx *ctx, const MatDesc *descs, const MatDesc &one, const int *d_wg_start,
+                      int n_mats, int total_wg, int64_t sum_rows, int64_t sum_cols, const ReorderWs &w)
+{
+    hipLaunchKernelGGL(score_partial_kernel, dim3((unsigned)total_wg), dim3(SC_THREADS), 0, ctx->stream,
+                       descs, one, d_wg_start, n_mats, w.rowpart, w.colpart);
     SBITS_HIP(ctx, hipGetLastError());
-    const int64_t tot = R + C;
-    hipLaunchKernelGGL(score_finish_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
-                       rowpart, colpart, R, C, (int)nseg, nband, row_score, col_score);
+    const int64_t L = sum_rows + sum_cols;
+    hipLaunchKernelGGL(score_finish_kernel, dim3((unsigned)((L + 255) / 256)), dim3(256), 0, ctx->stream,
+                       descs, one, n_mats, sum_rows, sum_cols, w.rowpart, w.colpart, w.scores,
+                       w.scores + sum_rows);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
 
-int sbits_launch_argsort(sbits_ctx *ctx, const float *score, int64_t n, int32_t *perm, void *ws_rank)
+// ---- single matrix ----------------------------------------------------------------------
+int sbits_launch_scores(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, int64_t ld,
+                        float *row_score, float *col_score, void *scratch)
 {
-    int *rank = static_cast<int *>(ws_rank);
-    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, rank, n);
+    MatDesc one = single_desc(nullptr, S, R, C, C, ld);
+    ReorderWs w;
+    reorder_ws_layout(scratch, R + C, R * one.nseg, (int64_t)one.nband * C, &w);
+    int rc = run_scores(ctx, nullptr, one, nullptr, 1, one.nseg * one.nband, R, C, w);
+    if (rc) return rc;
+    if (row_score)
+        SBITS_HIP(ctx, hipMemcpyAsync(row_score, w.scores, (size_t)R * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    if (col_score)
+        SBITS_HIP(ctx, hipMemcpyAsync(col_score, w.scores + R, (size_t)C * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    return SBITS_OK;
+}
+
+int sbits_launch_reorder(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, int64_t ld,
+                         int32_t *row_perm, int32_t *col_perm, void *scratch)
+{
+    MatDesc one = single_desc(nullptr, S, R, C, C, ld);
+    ReorderWs w;
+    reorder_ws_layout(scratch, R + C, R * one.nseg, (int64_t)one.nband * C, &w);
+    int rc = run_scores(ctx, nullptr, one, nullptr, 1, one.nseg * one.nband, R, C, w);
+    if (rc) return rc;
+    hipLaunchKernelGGL(radix_argsort_kernel, dim3(2), dim3(RS_THREADS), 0, ctx->stream,
+                       (const MatDesc *)nullptr, one, 1, R, w.scores, w.k0, w.k1, w.i0, w.i1, row_perm, col_perm);
     SBITS_HIP(ctx, hipGetLastError());
-    dim3 grid((unsigned)((n + AS_THREADS - 1) / AS_THREADS), (unsigned)((n + AS_TILE - 1) / AS_TILE));
-    hipLaunchKernelGGL(rank_kernel, grid, dim3(AS_THREADS), 0, ctx->stream, score, (int)n, rank);
-    SBITS_HIP(ctx, hipGetLastError());
-    hipLaunchKernelGGL(scatter_perm_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream,
-                       rank, (int)n, perm);
-    SBITS_HIP(ctx, hipGetLastError());
+    return SBITS_OK;
+}
+
+static int gather_attr(sbits_ctx *ctx)
+{
+    static bool done = false;
+    if (!done) {
+        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<float>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<uint16_t>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        done = true;
+    }
     return SBITS_OK;
 }
 
@@ -238,24 +448,65 @@ int sbits_launch_gather(sbits_ctx *ctx, const void *W, const float *S, int64_t R
                         int64_t ld_w, int64_t ld_s, const int32_t *rp, const int32_t *cp,
                         void *w_out, float *s_out)
 {
-    const size_t lds_w = (size_t)C * 2, lds_s = (size_t)C * 4;
-    if (lds_s > 160 * 1024) return SBITS_ERR_BAD_SHAPE;
-    static bool attr_done = false;
-    if (!attr_done) {
-        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<float>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<uint16_t>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_done = true;
-    }
+    if ((size_t)C * 4 > 160 * 1024) return SBITS_ERR_BAD_SHAPE;
+    int rc = gather_attr(ctx);
+    if (rc) return rc;
+    MatDesc one = single_desc(W, S, R, C, ld_w, ld_s);
     if (w_out) {
-        hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3((unsigned)R), dim3(GA_THREADS), lds_w, ctx->stream,
-                           static_cast<const uint16_t *>(W), R, C, ld_w, rp, cp, static_cast<uint16_t *>(w_out));
+        hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3((unsigned)R), dim3(GA_THREADS), (size_t)C * 2, ctx->stream,
+                           (const MatDesc *)nullptr, one, 1, rp, cp, static_cast<uint16_t *>(w_out));
         SBITS_HIP(ctx, hipGetLastError());
     }
     if (s_out) {
-        hipLaunchKernelGGL(gather_kernel<float>, dim3((unsigned)R), dim3(GA_THREADS), lds_s, ctx->stream,
-                           S, R, C, ld_s, rp, cp, s_out);
+        hipLaunchKernelGGL(gather_kernel<float>, dim3((unsigned)R), dim3(GA_THREADS), (size_t)C * 4, ctx->stream,
+                           (const MatDesc *)nullptr, one, 1, rp, cp, s_out);
+        SBITS_HIP(ctx, hipGetLastError());
+    }
+    return SBITS_OK;
+}
+
+// ---- all matrices of the plan (descriptor table already in the workspace head) ------------
+int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_perm, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    ReorderWs w;
+    reorder_ws_layout(sbits_scratch(plan, ws), plan->sum_rows + plan->sum_cols, plan->sum_rowpart,
+                      plan->sum_colpart, &w);
+    int *d_pre = sbits_prefix_ptr(plan, ws, 1);
+    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, plan->score_wg_start.data(), plan->score_wg_start.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
+    MatDesc none;
+    memset(&none, 0, sizeof none);
+    int rc = run_scores(ctx, sbits_desc_ptr(ws), none, d_pre, plan->n_mats, plan->score_wg_start.back(),
+                        plan->sum_rows, plan->sum_cols, w);
+    if (rc) return rc;
+    hipLaunchKernelGGL(radix_argsort_kernel, dim3((unsigned)(2 * plan->n_mats)), dim3(RS_THREADS), 0, ctx->stream,
+                       (const MatDesc *)sbits_desc_ptr(ws), none, plan->n_mats, plan->sum_rows, w.scores,
+                       w.k0, w.k1, w.i0, w.i1, row_perm, col_perm);
+    SBITS_HIP(ctx, hipGetLastError());
+    return SBITS_OK;
+}
+
+int sbits_launch_gather_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                            void *w_re, float *s_re, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    if ((size_t)plan->max_cols * 4 > 160 * 1024) return SBITS_ERR_BAD_SHAPE;
+    int rc = gather_attr(ctx);
+    if (rc) return rc;
+    MatDesc none;
+    memset(&none, 0, sizeof none);
+    if (plan->sum_rows > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
+    if (w_re) {
+        hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3((unsigned)plan->sum_rows), dim3(GA_THREADS),
+                           (size_t)plan->max_cols * 2, ctx->stream, (const MatDesc *)sbits_desc_ptr(ws), none,
+                           plan->n_mats, row_perm, col_perm, static_cast<uint16_t *>(w_re));
+        SBITS_HIP(ctx, hipGetLastError());
+    }
+    if (s_re) {
+        hipLaunchKernelGGL(gather_kernel<float>, dim3((unsigned)plan->sum_rows), dim3(GA_THREADS),
+                           (size_t)plan->max_cols * 4, ctx->stream, (const MatDesc *)sbits_desc_ptr(ws), none,
+                           plan->n_mats, row_perm, col_perm, s_re);
         SBITS_HIP(ctx, hipGetLastError());
     }
     return SBITS_OK;

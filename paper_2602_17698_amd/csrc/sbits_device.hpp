@@ -65,6 +65,8 @@ struct MatDesc {
     int64_t block_base;       // first global block id
     int64_t row_off, col_off; // offsets into the concatenated row / column permutations
     int nbr, nbc;             // block grid
+    int nseg, nband;          // score partials: 512-column segments, 256-row bands
+    int64_t rowpart_off, colpart_off;   // offsets of this matrix's score partials
 };
 
 // largest i with wg_start[i] <= wg  (wg_start has n + 1 ascending entries, wg_start[0] = 0)

@@ -26,6 +26,10 @@ struct sbits_plan {
     int64_t N;                               // total blocks
     int64_t max_rows, max_cols;
     int64_t sum_rows, sum_cols, sum_elems;
+    int64_t sum_rowpart, sum_colpart;        // score partials over all matrices
+    std::vector<int> score_wg_start;         // workgroup prefixes of the batched launches
+    std::vector<int> cost_unit_start;
+    std::vector<int> pack_wg_start;
     std::vector<sbits::MatDesc> descs;       // shape part filled at creation; pointers per call
     size_t head_bytes;                       // workspace head: descriptor table + workgroup prefixes
     size_t ws_bytes;
@@ -55,13 +59,20 @@ static inline size_t sbits_align_up(size_t v, size_t a) { return (v + a - 1) / a
 // ---- stage launchers (each returns an sbits_status) ------------------------
 
 // workspace sizes in bytes
-size_t sbits_score_ws_bytes(int64_t max_rows, int64_t max_cols);
+void sbits_score_geometry(int64_t R, int64_t C, int *nseg, int *nband);
+size_t sbits_reorder_ws_bytes(int64_t channels, int64_t rowpart, int64_t colpart);
 size_t sbits_alloc_ws_bytes(int64_t N);
 size_t sbits_offsets_ws_bytes(int64_t N);
 
 int sbits_launch_scores(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, int64_t ld,
                         float *row_score, float *col_score, void *ws);
-int sbits_launch_argsort(sbits_ctx *ctx, const float *score, int64_t n, int32_t *perm, void *ws_rank);
+int sbits_launch_reorder(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, int64_t ld,
+                         int32_t *row_perm, int32_t *col_perm, void *scratch);
+int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_perm, void *ws);
+int sbits_launch_gather_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                            void *w_re, float *s_re, void *ws);
+int sbits_launch_pack_all(sbits_plan *plan, const void *w_re, const uint8_t *level, const int64_t *byte_off,
+                          uint8_t *codes, float *scale, float *zero, void *ws);
 int sbits_launch_gather(sbits_ctx *ctx, const void *W, const float *S, int64_t R, int64_t C,
                         int64_t ld_w, int64_t ld_s, const int32_t *rp, const int32_t *cp,
                         void *w_out, float *s_out);

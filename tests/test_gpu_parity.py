@@ -48,6 +48,14 @@ def to_np_bf16(w):
     return synth.bf16_bits(w)
 
 
+def shape_with_blocks(N):
+    """A matrix shape with exactly N blocks of 8 x 8 inside the library's per-matrix limits."""
+    b = 1
+    while N % b or N // b > 4096:
+        b += 1
+    return (8 * (N // b), 8 * b)
+
+
 # ------------------------------------------------------------------ scores + permutations
 
 @pytest.mark.parametrize("R,C,m,n", [(8, 8, 8, 8), (40, 520, 8, 8), (264, 1032, 8, 8), (1024, 1024, 128, 128),
@@ -231,7 +239,7 @@ ALLOC_CASES = [
 def test_allocate_matches_oracle_step_by_step(orc, ctx, dev, bits, avg, N, g0, gT, init):
     say("alloc", bits, avg, N, g0, gT, init)
     cost = synthetic_cost(N, bits, seed=N + len(bits))
-    plan, ws = make_plan(ctx, [(8 * N, 8)], 8, 8, bits, dev)
+    plan, ws = make_plan(ctx, [shape_with_blocks(N)], 8, 8, bits, dev)
     assert plan.num_blocks() == N
     level = torch.full((N,), 255, dtype=torch.uint8, device=dev)
     rc, st, tr = plan.allocate(torch.from_numpy(cost).to(dev), avg, level, ws, gamma0=g0, gammaT=gT,
@@ -254,7 +262,7 @@ def test_allocate_ties_and_flat_tables(orc, ctx, dev):
         (np.tile(np.array([[1, 2, 3]], np.float32), (128, 1)), [2, 3, 4], 2.5),      # cost grows with bits
     ]:
         N = cost.shape[0]
-        plan, ws = make_plan(ctx, [(8 * N, 8)], 8, 8, bits, dev)
+        plan, ws = make_plan(ctx, [shape_with_blocks(N)], 8, 8, bits, dev)
         level = torch.empty(N, dtype=torch.uint8, device=dev)
         rc, st, tr = plan.allocate(torch.from_numpy(cost).to(dev), avg, level, ws, trace_cap=1000)
         rc_o, level_o, st_o, tr_o = orc.allocate(cost, bits, avg, want_trace=True)
@@ -267,7 +275,7 @@ def test_allocate_max_iters_status(orc, ctx, dev):
     say("alloc max_iters")
     N, bits = 2000, [2, 3, 4]
     cost = synthetic_cost(N, bits, seed=9)
-    plan, ws = make_plan(ctx, [(8 * N, 8)], 8, 8, bits, dev)
+    plan, ws = make_plan(ctx, [shape_with_blocks(N)], 8, 8, bits, dev)
     level = torch.empty(N, dtype=torch.uint8, device=dev)
     rc, st, _ = plan.allocate(torch.from_numpy(cost).to(dev), 2.5, level, ws, max_iters=3)
     rc_o, level_o, st_o, _ = orc.allocate(cost, bits, 2.5, max_iters=3)
