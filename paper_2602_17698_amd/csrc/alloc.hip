@@ -454,12 +454,14 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     long long used = h.used;
     bool done = all_max;
     const int P = h.P;
+    // the selection passes end in one global atomic per non-empty bin and workgroup: few, fat workgroups
+    const unsigned sgrid = (unsigned)((N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) < 128 ? (N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) : 128);
     while (!done) {
         hipLaunchKernelGGL(gains_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level, keyU, keyD);
         bool expanded = false;
         if (h.T - used > 0) {
             for (int ps = 0; ps < P; ++ps)
-                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_E, keyU,
+                hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_E, keyU,
                                    (const unsigned long long *)nullptr, 0, ps);
             hipLaunchKernelGGL(decide_expand_kernel, dim3(1), dim3(1), 0, sm, st, tr);
             hipLaunchKernelGGL(apply_expand_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, level);
@@ -470,14 +472,14 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
         }
         if (!expanded) {
             for (int ps = 0; ps < P; ++ps)
-                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U, keyU,
+                hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U, keyU,
                                    (const unsigned long long *)nullptr, 0, ps);
             for (int ps = 0; ps < P; ++ps)
-                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_D, keyD,
+                hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_D, keyD,
                                    (const unsigned long long *)keyU, (int)JOB_U, ps);
             hipLaunchKernelGGL(prep_u2_kernel, dim3(1), dim3(1), 0, sm, st);
             for (int ps = 0; ps < P; ++ps)
-                hipLaunchKernelGGL(select_pass_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U2, keyU,
+                hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U2, keyU,
                                    (const unsigned long long *)nullptr, 0, ps);
             hipLaunchKernelGGL(eval_swap_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level, keyU, keyD);
             hipLaunchKernelGGL(decide_swap_kernel, dim3(1), dim3(1), 0, sm, st, tr);

@@ -36,7 +36,7 @@ constexpr int SC_COLS = 512;    // columns per workgroup (64 lanes x 8)
 
 // rowpart[r][seg]  : tree over the 64 column runs of segment seg (zero beyond C)
 // colpart[band][c] : tree over the 32 row runs of band (zero beyond R)
-__global__ __launch_bounds__(SC_THREADS)
+__global__ __launch_bounds__(SC_THREADS, 3)
 void score_partial_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ wg_start,
                           int n_mats, float *__restrict__ rowpart_all, float *__restrict__ colpart_all)
 {
@@ -45,67 +45,96 @@ void score_partial_kernel(const MatDesc *__restrict__ descs, MatDesc one, const 
     const MatDesc d = descs ? descs[mat] : one;
     const int lid = (int)blockIdx.x - (descs ? wg_start[mat] : 0);
     const int band = lid / d.nseg, seg = lid - band * d.nseg;
-    const int64_t R = d.rows, C = d.cols, ld = d.ld_s;
-    const float *__restrict__ S = d.s;
+    const int R = (int)d.rows, C = (int)d.cols;
+    const int64_t ld = d.ld_s;
+    // the descriptor's pointer is a generic one for the compiler: say that it is global memory
+    typedef const char __attribute__((address_space(1))) *gcharp;
+    gcharp Sg = (gcharp)(reinterpret_cast<const char *>(d.s));
     float *__restrict__ rowpart = rowpart_all + d.rowpart_off;
     float *__restrict__ colpart = colpart_all + d.colpart_off;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t c0 = (int64_t)seg * SC_COLS + lane * 8;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int c0 = seg * SC_COLS + lane * 8;
     const bool col_ok = c0 < C;                      // C is a multiple of 8
+    const int c0c = col_ok ? c0 : C - 8;             // clamped: loads stay in bounds, values are dropped
+    const int rbase = band * SC_ROWS + wave * 64;
 
-    float t1[8], t2[8], t3[8], col[8];
+    // loads of half an octet (4 rows x 8 columns per lane); rows beyond R are clamped and dropped
+    // (row addresses are the same in all lanes of a wave: scalar base + per-lane 32-bit offset)
+    struct Half { float4 a[4], b[4]; };
+    const uint32_t voff = (uint32_t)c0c * 4u;
+    auto load_half = [&](Half &o, int h) {           // h = 2*octet + half
 #pragma unroll
-    for (int oc = 0; oc < 8; ++oc) {
-        const int64_t r0 = (int64_t)band * SC_ROWS + wave * 64 + oc * 8;
-        float rowrun[8], colrun[8];
+        for (int rr = 0; rr < 4; ++rr) {
+            int r = rbase + h * 4 + rr;
+            r = r < R ? r : R - 1;
+            gcharp p = Sg + (int64_t)r * ld * 4;
+            o.a[rr] = gload_f4((const char *)p + voff);
+            o.b[rr] = gload_f4((const char *)p + voff + 16u);
+        }
+    };
+
+    float t1[8], t2[8], t3[8], col[8], colrun[8];
+    auto process = [&](const Half &cur, int h) {
+        const int r0 = rbase + h * 4;
+        float rowrun[4];
+        if ((h & 1) == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) colrun[e] = 0.0f;
+            for (int e = 0; e < 8; ++e) colrun[e] = 0.0f;
+        }
 #pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            float v[8];
-            if (col_ok && r0 + rr < R) {
-                const float *p = S + (r0 + rr) * ld + c0;
-                const float4 a = *reinterpret_cast<const float4 *>(p);
-                const float4 b = *reinterpret_cast<const float4 *>(p + 4);
-                v[0] = fabsf(a.x); v[1] = fabsf(a.y); v[2] = fabsf(a.z); v[3] = fabsf(a.w);
-                v[4] = fabsf(b.x); v[5] = fabsf(b.y); v[6] = fabsf(b.z); v[7] = fabsf(b.w);
-            } else {
+        for (int rr = 0; rr < 4; ++rr) {
+            const bool ok = col_ok && (r0 + rr < R);
+            float v[8] = {cur.a[rr].x, cur.a[rr].y, cur.a[rr].z, cur.a[rr].w,
+                          cur.b[rr].x, cur.b[rr].y, cur.b[rr].z, cur.b[rr].w};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = 0.0f;
-            }
+            for (int e = 0; e < 8; ++e) v[e] = ok ? fabsf(v[e]) : 0.0f;
             float a = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 a = a + v[e];                        // row run: left to right
-                colrun[e] = colrun[e] + v[e];        // column run: top to bottom
+                colrun[e] = colrun[e] + v[e];        // column run: top to bottom, 8 rows
             }
             rowrun[rr] = a;
         }
         // rows: adjacent-pair tree over the 64 lanes (64 runs = 512 columns)
 #pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
+        for (int rr = 0; rr < 4; ++rr) {
             const float t = group_allreduce<64>(rowrun[rr], OpAdd{});
-            if (lane == 0 && r0 + rr < R) rowpart[(r0 + rr) * d.nseg + seg] = t;
+            if (lane == 0 && r0 + rr < R) rowpart[(int64_t)(r0 + rr) * d.nseg + seg] = t;
         }
-        // columns: adjacent-pair tree over the wave's 8 octets, in registers
+        if (h & 1) {
+            // columns: adjacent-pair tree over the wave's 8 octets, in registers
+            const int oc = h >> 1;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float v = colrun[e];
-            if (oc & 1) {
-                v = t1[e] + v;
-                if (oc & 2) {
-                    v = t2[e] + v;
-                    if (oc & 4) v = t3[e] + v;
-                    else t3[e] = v;
+            for (int e = 0; e < 8; ++e) {
+                float v = colrun[e];
+                if (oc & 1) {
+                    v = t1[e] + v;
+                    if (oc & 2) {
+                        v = t2[e] + v;
+                        if (oc & 4) v = t3[e] + v;
+                        else t3[e] = v;
+                    } else {
+                        t2[e] = v;
+                    }
                 } else {
-                    t2[e] = v;
+                    t1[e] = v;
                 }
-            } else {
-                t1[e] = v;
+                col[e] = v;
             }
-            col[e] = v;
         }
+    };
+    // two buffers in ping-pong: the next half octet is in flight while the current one is summed
+    Half A, B;
+    load_half(A, 0);
+#pragma unroll 1
+    for (int h = 0; h < 16; h += 2) {
+        load_half(B, h + 1);
+        process(A, h);
+        load_half(A, h + 2 < 16 ? h + 2 : 15);       // the last reload is redundant and harmless
+        process(B, h + 1);
     }
     // columns: tree over the 4 waves
 #pragma unroll
@@ -283,56 +312,72 @@ void radix_argsort_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_
 }
 
 // ================================================================ gather
-constexpr int GA_THREADS = 256;
+constexpr int GA_THREADS = 512;
+constexpr int GA_LDS_TARGET = 48 * 1024;            // rows per workgroup are chosen to fill about this much
 
-// T = uint16_t (bf16) or float.  One workgroup per output row; rows of all matrices side by side.
+// T = uint16_t (bf16) or float.  A workgroup stages rpw consecutive output rows of one matrix
+// (their source rows) in LDS and emits them permuted; the column indices are read once per
+// column chunk and serve all rpw rows.  A launch covers the matrices of one "class" (equal
+// column count, hence equal LDS need): members[] lists them, wg_start[] is their workgroup prefix.
 template <class T>
 __global__ __launch_bounds__(GA_THREADS)
-void gather_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_mats,
+void gather_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ members,
+                   const int *__restrict__ wg_start, int n_members, int rpw,
                    const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm,
                    T *__restrict__ out_all)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    T *row = reinterpret_cast<T *>(smem);
+    T *rows = reinterpret_cast<T *>(smem);
     constexpr int V = 16 / sizeof(T);               // elements per 128-bit access
-    const int64_t g = blockIdx.x;                    // global row index
-    int mat = 0;
-    if (descs) {
-        int lo = 0, hi = n_mats;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (descs[mid].row_off <= g) lo = mid; else hi = mid;
-        }
-        mat = lo;
-    }
-    const MatDesc &d = descs ? descs[mat] : one;
-    const int64_t R = d.rows, C = d.cols;
-    const int64_t i = g - d.row_off;
+    typedef const T __attribute__((address_space(1))) *gtp;
+
+    int mem = 0;
+    if (descs) mem = find_matrix(wg_start, n_members, (int)blockIdx.x);
+    const MatDesc &d = descs ? descs[members[mem]] : one;
+    const int R = (int)d.rows, C = (int)d.cols;
+    const int i0 = ((int)blockIdx.x - (descs ? wg_start[mem] : 0)) * rpw;     // first output row
+    const int nr = min(rpw, R - i0);
     const T *in = sizeof(T) == 2 ? reinterpret_cast<const T *>(d.w) : reinterpret_cast<const T *>(d.s);
     const int64_t ld = sizeof(T) == 2 ? d.ld_w : d.ld_s;
+    const int32_t *__restrict__ rp = row_perm + d.row_off;
     const int32_t *__restrict__ cp = col_perm + d.col_off;
-    int64_t sr = row_perm[g];
-    sr = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);       // a permutation never trips this; keeps a bad one in bounds
-    const T *src = in + sr * ld;
-    const bool aligned = ((reinterpret_cast<uintptr_t>(src) & 15) == 0);
-    if (aligned) {
-        for (int64_t j = (int64_t)threadIdx.x * V; j < C; j += (int64_t)GA_THREADS * V)
-            *reinterpret_cast<uint4 *>(row + j) = *reinterpret_cast<const uint4 *>(src + j);
-    } else {
-        for (int64_t j = threadIdx.x; j < C; j += GA_THREADS) row[j] = src[j];
+
+    for (int r = 0; r < nr; ++r) {
+        int sr = rp[i0 + r];
+        sr = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);   // a permutation never trips this; keeps a bad one in bounds
+        const T *src = in + (int64_t)sr * ld;
+        T *dstl = rows + (size_t)r * C;
+        if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+            for (int j = threadIdx.x * V; j < C; j += GA_THREADS * V)
+                *reinterpret_cast<uint4 *>(dstl + j) = gload_u4(src + j);
+        } else {
+            for (int j = threadIdx.x; j < C; j += GA_THREADS) dstl[j] = *(gtp)(src + j);
+        }
     }
     __syncthreads();
-    T *dst = out_all + d.elem_off + i * C;           // dense output, C % 8 == 0: 16-byte aligned rows
-    for (int64_t j = (int64_t)threadIdx.x * V; j < C; j += (int64_t)GA_THREADS * V) {
-        T tmp[V];
+    T *dst = out_all + d.elem_off + (int64_t)i0 * C;      // dense output, C % 8 == 0: 16-byte aligned rows
+    for (int j = threadIdx.x * V; j < C; j += GA_THREADS * V) {
+        int ci[V];
         const int4 c0 = *reinterpret_cast<const int4 *>(cp + j);
-        tmp[0] = row[c0.x]; tmp[1] = row[c0.y]; tmp[2] = row[c0.z]; tmp[3] = row[c0.w];
+        ci[0] = c0.x; ci[1] = c0.y; ci[2] = c0.z; ci[3] = c0.w;
         if constexpr (V == 8) {
             const int4 c1 = *reinterpret_cast<const int4 *>(cp + j + 4);
-            tmp[4] = row[c1.x]; tmp[5] = row[c1.y]; tmp[6] = row[c1.z]; tmp[7] = row[c1.w];
+            ci[4] = c1.x; ci[5] = c1.y; ci[6] = c1.z; ci[7] = c1.w;
         }
-        *reinterpret_cast<uint4 *>(dst + j) = *reinterpret_cast<const uint4 *>(tmp);
+        for (int r = 0; r < nr; ++r) {
+            const T *srcl = rows + (size_t)r * C;
+            T tmp[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) tmp[e] = srcl[ci[e]];
+            *reinterpret_cast<uint4 *>(dst + (int64_t)r * C + j) = *reinterpret_cast<const uint4 *>(tmp);
+        }
     }
+}
+
+static int gather_rows_per_wg(int64_t C, size_t elem)
+{
+    int64_t r = GA_LDS_TARGET / (C * (int64_t)elem);
+    return (int)(r < 1 ? 1 : (r > 8 ? 8 : r));
 }
 
 }  // namespace sbits
@@ -452,14 +497,19 @@ int sbits_launch_gather(sbits_ctx *ctx, const void *W, const float *S, int64_t R
     int rc = gather_attr(ctx);
     if (rc) return rc;
     MatDesc one = single_desc(W, S, R, C, ld_w, ld_s);
+    const int *nul = nullptr;
     if (w_out) {
-        hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3((unsigned)R), dim3(GA_THREADS), (size_t)C * 2, ctx->stream,
-                           (const MatDesc *)nullptr, one, 1, rp, cp, static_cast<uint16_t *>(w_out));
+        const int rpw = gather_rows_per_wg(C, 2);
+        hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3((unsigned)((R + rpw - 1) / rpw)), dim3(GA_THREADS),
+                           (size_t)rpw * C * 2, ctx->stream, (const MatDesc *)nullptr, one, nul, nul, 1, rpw,
+                           rp, cp, static_cast<uint16_t *>(w_out));
         SBITS_HIP(ctx, hipGetLastError());
     }
     if (s_out) {
-        hipLaunchKernelGGL(gather_kernel<float>, dim3((unsigned)R), dim3(GA_THREADS), (size_t)C * 4, ctx->stream,
-                           (const MatDesc *)nullptr, one, 1, rp, cp, s_out);
+        const int rpw = gather_rows_per_wg(C, 4);
+        hipLaunchKernelGGL(gather_kernel<float>, dim3((unsigned)((R + rpw - 1) / rpw)), dim3(GA_THREADS),
+                           (size_t)rpw * C * 4, ctx->stream, (const MatDesc *)nullptr, one, nul, nul, 1, rpw,
+                           rp, cp, s_out);
         SBITS_HIP(ctx, hipGetLastError());
     }
     return SBITS_OK;
@@ -487,6 +537,10 @@ int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_p
     return SBITS_OK;
 }
 
+// One launch per class of matrices with equal column count (equal LDS need) and element type.
+// The class tables depend on shapes only: built once, kept in the plan, copied per call.
+//   slot 3 of the workspace head: members of all classes, class after class
+//   slot 4: workgroup prefixes (W), slot 5: workgroup prefixes (S); each class has n_k + 1 entries
 int sbits_launch_gather_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                             void *w_re, float *s_re, void *ws)
 {
@@ -494,20 +548,65 @@ int sbits_launch_gather_all(sbits_plan *plan, const int32_t *row_perm, const int
     if ((size_t)plan->max_cols * 4 > 160 * 1024) return SBITS_ERR_BAD_SHAPE;
     int rc = gather_attr(ctx);
     if (rc) return rc;
+    if (plan->gather_members.empty()) {
+        std::vector<int64_t> classes;
+        for (int i = 0; i < plan->n_mats; ++i) {
+            bool seen = false;
+            for (int64_t c : classes) seen = seen || c == plan->cols[i];
+            if (!seen) classes.push_back(plan->cols[i]);
+        }
+        for (int64_t c : classes) {
+            sbits_plan::GatherClass gc;
+            gc.cols = c;
+            gc.first = (int)plan->gather_members.size();
+            gc.pre_first = (int)plan->gather_pre_w.size();
+            gc.rpw_w = gather_rows_per_wg(c, 2);
+            gc.rpw_s = gather_rows_per_wg(c, 4);
+            int64_t tw = 0, ts = 0;
+            gc.n = 0;
+            for (int i = 0; i < plan->n_mats; ++i) {
+                if (plan->cols[i] != c) continue;
+                plan->gather_members.push_back(i);
+                plan->gather_pre_w.push_back((int)tw);
+                plan->gather_pre_s.push_back((int)ts);
+                tw += (plan->rows[i] + gc.rpw_w - 1) / gc.rpw_w;
+                ts += (plan->rows[i] + gc.rpw_s - 1) / gc.rpw_s;
+                ++gc.n;
+            }
+            if (tw > 0x7fffffff || ts > 0x7fffffff) { plan->gather_members.clear(); return SBITS_ERR_BAD_SHAPE; }
+            plan->gather_pre_w.push_back((int)tw);
+            plan->gather_pre_s.push_back((int)ts);
+            plan->gather_classes.push_back(gc);
+        }
+    }
+    int *d_mem = sbits_prefix_ptr(plan, ws, 3);
+    int *d_pw = sbits_prefix_ptr(plan, ws, 4);
+    int *d_ps = sbits_prefix_ptr(plan, ws, 5);
+    SBITS_HIP(ctx, hipMemcpyAsync(d_mem, plan->gather_members.data(), plan->gather_members.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_pw, plan->gather_pre_w.data(), plan->gather_pre_w.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_ps, plan->gather_pre_s.data(), plan->gather_pre_s.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
     MatDesc none;
     memset(&none, 0, sizeof none);
-    if (plan->sum_rows > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
-    if (w_re) {
-        hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3((unsigned)plan->sum_rows), dim3(GA_THREADS),
-                           (size_t)plan->max_cols * 2, ctx->stream, (const MatDesc *)sbits_desc_ptr(ws), none,
-                           plan->n_mats, row_perm, col_perm, static_cast<uint16_t *>(w_re));
-        SBITS_HIP(ctx, hipGetLastError());
-    }
-    if (s_re) {
-        hipLaunchKernelGGL(gather_kernel<float>, dim3((unsigned)plan->sum_rows), dim3(GA_THREADS),
-                           (size_t)plan->max_cols * 4, ctx->stream, (const MatDesc *)sbits_desc_ptr(ws), none,
-                           plan->n_mats, row_perm, col_perm, s_re);
-        SBITS_HIP(ctx, hipGetLastError());
+    const MatDesc *descs = sbits_desc_ptr(ws);
+    for (const sbits_plan::GatherClass &gc : plan->gather_classes) {
+        if (w_re) {
+            const int tot = plan->gather_pre_w[gc.pre_first + gc.n];
+            hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3((unsigned)tot), dim3(GA_THREADS),
+                               (size_t)gc.rpw_w * gc.cols * 2, ctx->stream, descs, none, d_mem + gc.first,
+                               d_pw + gc.pre_first, gc.n, gc.rpw_w, row_perm, col_perm,
+                               static_cast<uint16_t *>(w_re));
+            SBITS_HIP(ctx, hipGetLastError());
+        }
+        if (s_re) {
+            const int tot = plan->gather_pre_s[gc.pre_first + gc.n];
+            hipLaunchKernelGGL(gather_kernel<float>, dim3((unsigned)tot), dim3(GA_THREADS),
+                               (size_t)gc.rpw_s * gc.cols * 4, ctx->stream, descs, none, d_mem + gc.first,
+                               d_ps + gc.pre_first, gc.n, gc.rpw_s, row_perm, col_perm, s_re);
+            SBITS_HIP(ctx, hipGetLastError());
+        }
     }
     return SBITS_OK;
 }

@@ -56,6 +56,22 @@ __device__ __forceinline__ float group_bcast(float v)
     return __shfl(v, (lane & ~(LPG - 1)) + J);
 }
 
+// ---- loads through a pointer that is known to be global memory ------------------
+// (pointers read from a descriptor are generic for the compiler; saying "global" gives
+// global_load instead of flat_load)
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 gload_f4(const void *p)
+{
+    const f32x4_t v = *(const __attribute__((address_space(1))) f32x4_t *)p;
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint4 gload_u4(const void *p)
+{
+    const u32x4_t v = *(const __attribute__((address_space(1))) u32x4_t *)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // ---- batched launches: one descriptor per matrix of the plan -------------------
 struct MatDesc {
     const uint16_t *w;        // original weights (bf16) and sensitivities, caller's pointers

@@ -30,6 +30,9 @@ struct sbits_plan {
     std::vector<int> score_wg_start;         // workgroup prefixes of the batched launches
     std::vector<int> cost_unit_start;
     std::vector<int> pack_wg_start;
+    struct GatherClass { int64_t cols; int first, pre_first, n, rpw_w, rpw_s; };
+    std::vector<GatherClass> gather_classes; // matrices grouped by column count
+    std::vector<int> gather_members, gather_pre_w, gather_pre_s;
     std::vector<sbits::MatDesc> descs;       // shape part filled at creation; pointers per call
     size_t head_bytes;                       // workspace head: descriptor table + workgroup prefixes
     size_t ws_bytes;
@@ -37,9 +40,9 @@ struct sbits_plan {
 
 // The workspace head holds the per-matrix descriptor table and up to four workgroup-prefix
 // arrays of the batched launches; stage scratch starts at sbits_scratch(plan, ws).
-constexpr int SBITS_N_PREFIX = 4;
+constexpr int SBITS_N_PREFIX = 6;
 static inline size_t sbits_desc_bytes(int n_mats) { return (size_t)((n_mats * sizeof(sbits::MatDesc) + 255) / 256 * 256); }
-static inline size_t sbits_prefix_bytes(int n_mats) { return (size_t)(((n_mats + 1) * 4 + 255) / 256 * 256); }
+static inline size_t sbits_prefix_bytes(int n_mats) { return (size_t)((2 * (n_mats + 1) * 4 + 255) / 256 * 256); }
 static inline sbits::MatDesc *sbits_desc_ptr(void *ws) { return static_cast<sbits::MatDesc *>(ws); }
 static inline int *sbits_prefix_ptr(const sbits_plan *p, void *ws, int slot)
 {
