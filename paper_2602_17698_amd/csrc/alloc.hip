@@ -6,11 +6,11 @@
 //             read off the table at the current levels (Alg. 2 line 5), encoded
 //             as 64-bit keys  [ordered value : 32][N-1-index : IB][step bits : 8]
 //             so that "larger key" = "earlier in (value, lower index first)".
-//   select  : radix descent, 8 bits per pass, over the keys: the longest prefix
+//   select  : radix descent, 11 bits per pass, over the keys: the longest prefix
 //             of the descending order that keeps count <= cnt_max and
 //             cumulative step bits <= w_max.  Each pass builds a count/weight
 //             histogram of the digits under the decided prefix; the workgroup
-//             that finishes last scans the 256 bins and fixes the next digit.
+//             that finishes last scans the 2048 bins and fixes the next digit.
 //   expansion (Alg. 2 lines 6-7)  : top-k raised, capped by the remaining
 //             budget and by gain > 0.
 //   swap (Alg. 2 lines 9-12)      : top-k/2 raised, bottom-k/2 (outside the
@@ -28,6 +28,8 @@ namespace sbits {
 
 constexpr int AL_THREADS = 256;
 constexpr int64_t TRACE_CAP = 16384;
+constexpr int SEL_DB = 11;                    // digit bits of the selection's radix descent
+constexpr int SEL_BINS = 1 << SEL_DB;
 
 struct SelJob {
     unsigned long long prefix;     // decided high digits, right aligned
@@ -38,8 +40,8 @@ struct SelJob {
     long long n_sel, w_sel;
     int resolved;
     unsigned int ticket;
-    unsigned int hist_cnt[256];
-    unsigned int hist_w[256];
+    unsigned int hist_cnt[SEL_BINS];
+    unsigned int hist_w[SEL_BINS];
 };
 
 enum { JOB_E = 0, JOB_U = 1, JOB_D = 2, JOB_U2 = 3, N_JOBS = 4 };
@@ -160,33 +162,44 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
 {
     SelJob *job = &st->job[job_id];
     if (job->resolved) return;                                   // uniform over the grid
-    __shared__ unsigned int hc[256], hw[256];
+    __shared__ unsigned int hc[SEL_BINS], hw[SEL_BINS];
+    __shared__ long long gcnt[AL_THREADS], gwgt[AL_THREADS];
     __shared__ bool is_last;
-    hc[threadIdx.x] = 0;
-    hw[threadIdx.x] = 0;
+    for (int b = threadIdx.x; b < SEL_BINS; b += AL_THREADS) { hc[b] = 0; hw[b] = 0; }
     __syncthreads();
     const long long N = st->N;
     const int P = st->P;
     const unsigned long long prefix = job->prefix, key_min = job->key_min;
     const unsigned long long excl_tau = excl ? st->job[excl_job].tau : 0;
-    const int sh_digit = 8 * (P - 1 - pass), sh_prefix = 8 * (P - pass);
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
-         i += (long long)gridDim.x * blockDim.x) {
-        const unsigned long long key = keys[i];
-        if (key < key_min) continue;
-        if (excl && excl[i] >= excl_tau) continue;
-        const unsigned long long s = key >> 8;
-        const unsigned long long hi = sh_prefix >= 64 ? 0ull : (s >> sh_prefix);
-        if (hi != prefix) continue;
-        const unsigned int d = (unsigned int)(s >> sh_digit) & 255u;
-        atomicAdd(&hc[d], 1u);
-        atomicAdd(&hw[d], (unsigned int)(key & 255u));
+    const int sh_digit = SEL_DB * (P - 1 - pass), sh_prefix = SEL_DB * (P - pass);
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    // four independent loads in flight per thread
+    for (long long i0 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i0 < N; i0 += 4 * stride) {
+        unsigned long long key[4], ex[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long long i = i0 + u * stride;
+            key[u] = i < N ? keys[i] : 0ull;
+            ex[u] = (excl && i < N) ? excl[i] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (key[u] < key_min) continue;                      // also drops the padding (key 0)
+            if (excl && ex[u] >= excl_tau) continue;
+            const unsigned long long s = key[u] >> 8;
+            const unsigned long long hi = sh_prefix >= 64 ? 0ull : (s >> sh_prefix);
+            if (hi != prefix) continue;
+            const unsigned int d = (unsigned int)(s >> sh_digit) & (SEL_BINS - 1);
+            atomicAdd(&hc[d], 1u);
+            atomicAdd(&hw[d], (unsigned int)(key[u] & 255u));
+        }
     }
     __syncthreads();
-    if (hc[threadIdx.x]) {
-        atomicAdd(&job->hist_cnt[threadIdx.x], hc[threadIdx.x]);
-        atomicAdd(&job->hist_w[threadIdx.x], hw[threadIdx.x]);
-    }
+    for (int b = threadIdx.x; b < SEL_BINS; b += AL_THREADS)
+        if (hc[b]) {
+            atomicAdd(&job->hist_cnt[b], hc[b]);
+            atomicAdd(&job->hist_w[b], hw[b]);
+        }
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -196,21 +209,34 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
     __syncthreads();
     if (!is_last) return;
     __threadfence();
-    // the last workgroup: read the finished histogram, clear it for the next pass
-    hc[threadIdx.x] = __hip_atomic_exchange(&job->hist_cnt[threadIdx.x], 0u, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT);
-    hw[threadIdx.x] = __hip_atomic_exchange(&job->hist_w[threadIdx.x], 0u, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT);
+    // the last workgroup: read the finished histogram, clear it for the next pass; thread t owns
+    // the SEL_BINS/256 consecutive bins [t*G, (t+1)*G)
+    constexpr int G = SEL_BINS / AL_THREADS;
+    long long gc = 0, gw = 0;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int b = threadIdx.x * G + j;
+        hc[b] = __hip_atomic_exchange(&job->hist_cnt[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        hw[b] = __hip_atomic_exchange(&job->hist_w[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        gc += hc[b]; gw += hw[b];
+    }
+    gcnt[threadIdx.x] = gc; gwgt[threadIdx.x] = gw;
     __syncthreads();
     if (threadIdx.x == 0) {
         job->ticket = 0;
         long long c = job->cnt_above, w = job->w_above;
+        const long long cmax = job->cnt_max, wmax = job->w_max;
         int boundary = -1;
-        for (int b = 255; b >= 0; --b) {
-            const long long bc = hc[b], bw = hw[b];
-            if (!bc) continue;
-            if (c + bc <= job->cnt_max && w + bw <= job->w_max) { c += bc; w += bw; }
-            else { boundary = b; break; }
+        // bins in descending order: whole groups while they fit, then bin by bin inside the first that does not
+        for (int g = AL_THREADS - 1; g >= 0 && boundary < 0; --g) {
+            if (!gcnt[g]) continue;
+            if (c + gcnt[g] <= cmax && w + gwgt[g] <= wmax) { c += gcnt[g]; w += gwgt[g]; continue; }
+            for (int b = g * G + G - 1; b >= g * G; --b) {
+                const long long bc = hc[b], bw = hw[b];
+                if (!bc) continue;
+                if (c + bc <= cmax && w + bw <= wmax) { c += bc; w += bw; }
+                else { boundary = b; break; }
+            }
         }
         if (boundary < 0) {
             // every key under the prefix fits: the selection ends at the bucket's lower edge
@@ -218,7 +244,7 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
             job->tau = lo > key_min ? lo : key_min;
             job->n_sel = c; job->w_sel = w; job->resolved = 1;
         } else {
-            const unsigned long long np = (prefix << 8) | (unsigned long long)boundary;
+            const unsigned long long np = (prefix << SEL_DB) | (unsigned long long)boundary;
             job->cnt_above = c; job->w_above = w;
             if (pass == P - 1) {
                 // a single key that does not fit: select the keys strictly above it
@@ -429,7 +455,7 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     if (h.kmin < 1) h.kmin = 1;
     h.K = K;
     h.IB = ceil_log2_ll(N) > 0 ? ceil_log2_ll(N) : 1;
-    h.P = (32 + h.IB + 7) / 8;
+    h.P = (32 + h.IB + SEL_DB - 1) / SEL_DB;
     h.max_iters = prm->max_iters;
     for (int c = 0; c < 8; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
 
