@@ -21,6 +21,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per weight of the cost kernel from rocprofv3 counters (FETCH_SIZE x 2.000 and WRITE_SIZE
+# x 1.000 after calibration against a plain 1 GiB copy; profiles/hbm_traffic_8_layers_pmc.md)
+COST_TRAFFIC_B_PER_WEIGHT = (5114570 * 2.0 + 1664) * 1024 / 1744830464
 
 
 def parse():
@@ -34,6 +37,8 @@ def parse():
     ap.add_argument("--bits", type=str, default="1,2,3,4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy first (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -143,6 +148,13 @@ def main():
     def new_events():
         return [torch.cuda.Event(enable_timing=True) for _ in range(6)]
 
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step(new_events())
     torch.cuda.synchronize()
@@ -182,7 +194,8 @@ def main():
         "search_stats": st, "search_status": rc,
         "gen_s": t_gen,
         "roofline": {"kernel": "cost_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": COST_TRAFFIC_B_PER_WEIGHT * nw if (m == 128 and K == 4) else None,
                      "launches_per_step": launches, "avg_launch_ms": cost_ms / launches,
                      "algorithmic_bytes_per_launch": cost_bytes / launches},
     }
