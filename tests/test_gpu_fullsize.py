@@ -149,3 +149,126 @@ def test_full_model_sampled(orc, avg):
         idx = names.index((layer, name))
         say("  sampled", layer, name, shapes[idx])
         check_matrix(orc, o, shapes, bases, idx, mats[idx][0], mats[idx][1], m, n, bits, level, off)
+
+
+def test_outlier_channel_model_small_blocks(orc):
+    """8B-shaped model, 64x64 blocks (group 64), {1,2,3,4,8} bits, Student-t(3) weights with rare x100
+    outlier channels scattered per matrix, budget 2.25: uneven candidate steps, K = 5."""
+    say("config 5: 64x64 blocks, K = 5, outlier channels")
+    dev = torch.device("cuda:0")
+    m = n = 64
+    bits, avg = [1, 2, 3, 4, 8], 2.25
+    names, mats, shapes = [], [], []
+    for layer in range(32):
+        for name, r, c in synth.layer_shapes(synth.LLAMA3_8B):
+            w, s = synth.make_matrix("outlier_chan", r, c, seed=0, tid=synth.tensor_id(layer, name), device=dev)
+            names.append((layer, name)); mats.append((w, s)); shapes.append((r, c))
+    rc, st, o, bases = run_search(dev, mats, shapes, m, n, bits, avg)
+    cost = o["cost"].cpu().numpy()
+    assert cost.shape == (1703936, 5) and np.all(np.isfinite(cost)) and np.all(cost >= 0)
+    rc_o, level, st_o, _ = orc.allocate(cost, bits, avg)
+    assert rc == rc_o == 0 and st == st_o
+    np.testing.assert_array_equal(o["level"].cpu().numpy(), level)
+    assert st["bits_used"] <= st["bits_budget"] == int(avg * 1703936)
+    off = orc.offsets(level, m, n, bits)
+    np.testing.assert_array_equal(o["byte_off"].cpu().numpy(), off)
+    # reordering moves the outlier channels to the top-left: the first block row / column of a
+    # matrix gets more bits than the rest
+    idx = names.index((3, "q"))
+    lv = level[bases[idx]:bases[idx] + 64 * 64].reshape(64, 64).astype(np.float64)
+    assert lv[0].mean() > lv[1:].mean() and lv[:, 0].mean() > lv[:, 1:].mean()
+    for layer, name in [(0, "v"), (16, "o"), (31, "k")]:
+        idx = names.index((layer, name))
+        say("  sampled", layer, name, shapes[idx])
+        check_matrix(orc, o, shapes, bases, idx, mats[idx][0], mats[idx][1], m, n, bits, level, off)
+
+
+def test_streamed_70b_shaped_model(orc):
+    """80-layer Llama-3-70B-shaped model (hidden 8192, ffn 28672, 8 KV heads of 128): 410 GB of inputs
+    do not fit, so weights and sensitivities are regenerated per layer on the device from the seed;
+    128x128 blocks, {2,3,4} bits, budget 2.75.  One per-layer plan serves the per-matrix stages of
+    every layer (pointer offsets place its outputs in the global arrays); only permutations and
+    the cost table are kept, the global allocation runs on the full table, and a second streaming
+    pass packs.  Layers 0, 40 and 79 are checked against the oracle."""
+    say("config 4: streamed 70B-shaped model")
+    dev = torch.device("cuda:0")
+    m = n = 128
+    bits, avg = [2, 3, 4], 2.75
+    K = len(bits)
+    model = synth.LLAMA3_70B
+    lshapes = [(r, c) for _, r, c in synth.layer_shapes(model)]
+    L = model["layers"]
+    ctx = sb.Context(0, torch.cuda.current_stream().cuda_stream)
+    lplan = sb.Plan(ctx, lshapes, m, n, bits)                    # one layer
+    gplan = sb.Plan(ctx, lshapes * L, m, n, bits)                # the whole model: allocation, offsets
+    NL, N = lplan.num_blocks(), gplan.num_blocks()
+    assert NL == 52224 and N == 4177920
+    lws = torch.empty(lplan.workspace_bytes(), dtype=torch.uint8, device=dev)
+    gws = torch.empty(gplan.workspace_bytes(), dtype=torch.uint8, device=dev)
+    nel = sum(r * c for r, c in lshapes)
+    sum_r, sum_c = sum(r for r, _ in lshapes), sum(c for _, c in lshapes)
+    row_perm = torch.empty(L * sum_r, dtype=torch.int32, device=dev)
+    col_perm = torch.empty(L * sum_c, dtype=torch.int32, device=dev)
+    cost = torch.empty(N, K, dtype=torch.float32, device=dev)
+    w_re = torch.empty(nel, dtype=torch.bfloat16, device=dev)
+    s_re = torch.empty(nel, dtype=torch.float32, device=dev)
+    check_layers = (0, 40, 79)
+    kept = {}
+
+    def gen(layer):
+        return [synth.make_matrix("student_t", r, c, seed=0, tid=synth.tensor_id(layer, nm), device=dev)
+                for nm, r, c in synth.layer_shapes(model)]
+
+    for layer in range(L):                                       # pass 1: permutations + cost rows
+        mats = gen(layer)
+        dm = [sb.matrix(w, s) for w, s in mats]
+        rp = row_perm[layer * sum_r:(layer + 1) * sum_r]
+        cp = col_perm[layer * sum_c:(layer + 1) * sum_c]
+        lplan.reorder_all(dm, rp, cp, lws)
+        lplan.gather_all(dm, rp, cp, w_re, s_re, lws)
+        lplan.cost_table_all(w_re, s_re, cost[layer * NL:(layer + 1) * NL], lws)
+        if layer in check_layers:
+            torch.cuda.synchronize()
+            kept[layer] = dict(w_re=w_re.clone(), s_re=s_re.clone())
+        torch.cuda.synchronize()
+        del mats, dm
+        if layer % 10 == 0:
+            say("  pass 1 layer", layer)
+    level = torch.empty(N, dtype=torch.uint8, device=dev)
+    rc, st, _ = gplan.allocate(cost, avg, level, gws)
+    byte_off = torch.empty(N + 1, dtype=torch.int64, device=dev)
+    gplan.offsets(level, byte_off, gws)
+    torch.cuda.synchronize()
+    cost_h = cost.cpu().numpy()
+    say("  oracle allocation on", N, "blocks")
+    rc_o, level_o, st_o, _ = orc.allocate(cost_h, bits, avg)
+    assert rc == rc_o == 0 and st == st_o
+    np.testing.assert_array_equal(level.cpu().numpy(), level_o)
+    off = orc.offsets(level_o, m, n, bits)
+    np.testing.assert_array_equal(byte_off.cpu().numpy(), off)
+    assert st["bits_used"] <= st["bits_budget"] == 11489280
+
+    codes = torch.zeros(int(off[-1]), dtype=torch.uint8, device=dev)
+    scale = torch.empty(N * m, dtype=torch.float32, device=dev)
+    zero = torch.empty(N * m, dtype=torch.float32, device=dev)
+    for layer in range(L):                                       # pass 2: regenerate, reorder, pack
+        mats = gen(layer)
+        dm = [sb.matrix(w, s) for w, s in mats]
+        rp = row_perm[layer * sum_r:(layer + 1) * sum_r]
+        cp = col_perm[layer * sum_c:(layer + 1) * sum_c]
+        lplan.gather_all(dm, rp, cp, w_re, None, lws)
+        b0 = layer * NL
+        lplan.pack_all(w_re, level[b0:], byte_off[b0:], codes, scale[b0 * m:], zero[b0 * m:], lws)
+        torch.cuda.synchronize()
+        if layer in check_layers:
+            say("  checking layer", layer)
+            o = dict(row_perm=rp, col_perm=cp, w_re=kept[layer]["w_re"], s_re=kept[layer]["s_re"],
+                     cost=cost[b0:b0 + NL], codes=codes, scale=scale[b0 * m:], zero=zero[b0 * m:])
+            lbases = [lplan.block_base(i) for i in range(7)]
+            # the layer's slice of the global levels / offsets, as the layer plan sees them
+            lvl = level_o[b0:b0 + NL]
+            loff = off[b0:b0 + NL + 1]
+            for idx in (1, 3, 6):                                # k (1024x8192), o (8192x8192), down (8192x28672)
+                check_matrix(orc, o, lshapes, lbases, idx, mats[idx][0], mats[idx][1], m, n, bits, lvl, loff)
+        del mats, dm
+    lplan.close(); gplan.close(); ctx.close()
