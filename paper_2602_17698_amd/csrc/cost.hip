@@ -77,29 +77,54 @@ struct HalfBuf {
 
 // Uniform 64-bit bases plus per-lane 32-bit byte offsets (a matrix is below 4 GiB), so the
 // loads use the scalar-base + vector-offset addressing form and need one add per row.
+// The weights of a lane are 16 contiguous bytes, so a wave's load covers whole cache lines.
+// The 8 sensitivities of a lane are 32 bytes: loaded directly, each instruction would touch
+// every other 16 bytes of 2 KiB.  With SWIZZLE the wave instead loads its 2 KiB run as two
+// fully contiguous 1 KiB instructions (lane l takes bytes 16 l and 1024 + 16 l of the run, byte
+// offsets soA / soB) and the lanes exchange the values through LDS before use (swizzle_s).
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <bool SWIZZLE>
 __device__ __forceinline__ void load_half(HalfBuf &h, const char *__restrict__ Wb, const char *__restrict__ Sb,
-                                          uint32_t woff, uint32_t wstride)
+                                          uint32_t woff, uint32_t wstride, uint32_t soA, uint32_t soB)
 {
     // S is fp32, W bf16, same element index: byte offsets differ by a factor of two
 #pragma unroll
     for (int j = 0; j < HALF; ++j) {
         const uint32_t wo = woff + (uint32_t)j * wstride;
-        const uint32_t so = 2u * wo;
-#ifdef SBITS_COST_NT
-        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-        typedef float f32x4 __attribute__((ext_vector_type(4)));
-        const u32x4 tw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Wb + wo));
-        const f32x4 ta = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(Sb + so));
-        const f32x4 tb = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(Sb + so + 16u));
+        const uint32_t oa = SWIZZLE ? soA + 2u * (uint32_t)j * wstride : 2u * wo;
+        const uint32_t ob = SWIZZLE ? soB + 2u * (uint32_t)j * wstride : 2u * wo + 16u;
+#ifndef SBITS_COST_NO_NT
+        const u32x4_t tw = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(Wb + wo));
+        const f32x4_t ta = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(Sb + oa));
+        const f32x4_t tb = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(Sb + ob));
         h.w[j] = make_uint4(tw.x, tw.y, tw.z, tw.w);
         h.s0[j] = make_float4(ta.x, ta.y, ta.z, ta.w);
         h.s1[j] = make_float4(tb.x, tb.y, tb.z, tb.w);
 #else
         h.w[j] = *reinterpret_cast<const uint4 *>(Wb + wo);
-        h.s0[j] = *reinterpret_cast<const float4 *>(Sb + so);
-        h.s1[j] = *reinterpret_cast<const float4 *>(Sb + so + 16u);
+        h.s0[j] = *reinterpret_cast<const float4 *>(Sb + oa);
+        h.s1[j] = *reinterpret_cast<const float4 *>(Sb + ob);
 #endif
     }
+}
+
+// Lane exchange of one row of sensitivities loaded with SWIZZLE: xrow is 2 KiB of LDS private
+// to the wave.  Lane l stores its two 16-byte pieces where they sit in the run and reads back
+// the 32 bytes at 32 l.  Only lanes of one wave touch xrow and a wave's LDS operations complete
+// in order, so no workgroup barrier is needed.
+__device__ __forceinline__ void swizzle_s(float4 *xrow, int lane, float4 &a, float4 &b)
+{
+    xrow[lane] = a;
+    xrow[64 + lane] = b;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    a = xrow[2 * lane];
+    b = xrow[2 * lane + 1];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 // Per-lane constants of the distributed grid divisions.  The 2K quotients of a
@@ -137,9 +162,10 @@ struct DivPlan {
 
 // HALF rows of one octet: rows R_BASE .. R_BASE + HALF - 1 (R_BASE is 0 or 4).  Updates the
 // pending levels of the row tree (t1, t2, t3) and leaves the running result in cur.
-template <int LPG, int K, int R_BASE>
+template <int LPG, int K, int R_BASE, bool SWIZZLE>
 __device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG, K> &dp,
-                                             float (&t1)[K], float (&t2)[K], float (&t3)[K], float (&cur)[K])
+                                             float (&t1)[K], float (&t2)[K], float (&t3)[K], float (&cur)[K],
+                                             float4 *xw, int lane)
 {
     using DP = DivPlan<LPG, K>;
     constexpr int SP = DP::SP, RP = DP::RP, NS = DP::NS;
@@ -163,7 +189,8 @@ __device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG
         for (int j = 0; j < RP; ++j) {
             float w[8];
             unpack8(h.w[r0 + j], w);
-            const float4 a = h.s0[r0 + j], b = h.s1[r0 + j];
+            float4 a = h.s0[r0 + j], b = h.s1[r0 + j];
+            if constexpr (SWIZZLE) swizzle_s(xw + (r0 + j) * 128, lane, a, b);
             s[j][0] = a.x; s[j][1] = a.y; s[j][2] = a.z; s[j][3] = a.w;
             s[j][4] = b.x; s[j][5] = b.y; s[j][6] = b.z; s[j][7] = b.w;
             float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])),
@@ -267,7 +294,13 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
 {
     using G = CostGeom<LPG>;
     constexpr int BX = G::BX, OS = G::OS;
+#ifdef SBITS_COST_NO_SWIZZLE
+    constexpr bool SWZ = false;
+#else
+    constexpr bool SWZ = G::OW == 1;                 // a wave walks ONE octet: 512 contiguous columns per row
+#endif
     __shared__ float osum[BX * 128 * K];             // [block in unit][octet][candidate]
+    __shared__ float4 xbuf[SWZ ? 4 * HALF * 128 : 1];    // per wave: HALF rows of 2 KiB for the lane exchange
 
     const int tid = threadIdx.x;
     const int lig = tid % LPG;
@@ -278,6 +311,8 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
     const int steps = opb >= OS ? opb / OS : 1;                 // steps per unit
     const int bl = (gw % BX) + (opb >= OS ? 0 : BX * (slot / opb));   // this group's block inside the unit
     const int o0 = opb >= OS ? slot : slot % opb;               // this group's octet (plus p*OS in step p)
+    const int lane = tid & 63;
+    float4 *const xw = xbuf + (SWZ ? (tid >> 6) * (HALF * 128) : 0);
 
     DivPlan<LPG, K> dp;
     dp.init(gc, lig);
@@ -324,6 +359,7 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
         const char *Wb, *Sb;      // uniform
         uint32_t voff;            // per-lane byte offset (bf16 units) inside the step
         uint32_t wstride;
+        uint32_t soA, soB;        // per-lane byte offsets of the two contiguous sensitivity loads (SWZ)
         int J0, nbc, I;           // uniform: first block column of the unit, block columns, block row
         float *cbase;             // uniform: cost rows of the matrix
     };
@@ -337,6 +373,17 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
         const int ble = bl < lim ? bl : lim;
         a.voff = ((uint32_t)o0 * 8u * (uint32_t)d_cols + (uint32_t)ble * (LPG * 8) + (uint32_t)lig * 8u) * 2u;
         a.wstride = (uint32_t)d_cols * 2u;
+        a.soA = a.soB = 0;
+        if constexpr (SWZ) {
+            // column (relative to the unit) of the 4 values a lane loads from the wave's 512-column
+            // run; a block column past the row's end is clamped like ble above
+            const int c0 = (bl - gw % BX) * (LPG * 8) + 4 * lane, c1 = c0 + 256;
+            const int b0 = c0 / (LPG * 8), b1 = c1 / (LPG * 8);
+            const int e0 = (b0 < lim ? b0 : lim) * (LPG * 8) + c0 % (LPG * 8);
+            const int e1 = (b1 < lim ? b1 : lim) * (LPG * 8) + c1 % (LPG * 8);
+            a.soA = ((uint32_t)o0 * 8u * (uint32_t)d_cols + (uint32_t)e0) * 4u;
+            a.soB = ((uint32_t)o0 * 8u * (uint32_t)d_cols + (uint32_t)e1) * 4u;
+        }
         a.J0 = J0; a.nbc = d_nbc; a.I = I;
         a.cbase = cost + d_cbase;
         return a;
@@ -355,21 +402,22 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
 
     HalfBuf A, B;
     StepAddr nxt = address();
-    load_half(A, nxt.Wb, nxt.Sb, nxt.voff, nxt.wstride);
+    load_half<SWZ>(A, nxt.Wb, nxt.Sb, nxt.voff, nxt.wstride, nxt.soA, nxt.soB);
 
     int pc = 0;                                      // step inside the unit being computed
     for (int sidx = 0; sidx < nsteps; ++sidx) {
         const StepAddr now = nxt;
-        load_half(B, now.Wb, now.Sb, now.voff + HALF * now.wstride, now.wstride);
+        load_half<SWZ>(B, now.Wb, now.Sb, now.voff + HALF * now.wstride, now.wstride,
+                       now.soA + 2u * HALF * now.wstride, now.soB + 2u * HALF * now.wstride);
         float t1[K], t2[K], t3[K], cur[K];
-        compute_half<LPG, K, 0>(A, dp, t1, t2, t3, cur);
+        compute_half<LPG, K, 0, SWZ>(A, dp, t1, t2, t3, cur, xw, lane);
 
         // the next step's first half goes in flight before this step's second half is computed
         // (after the last step this re-reads the last step: harmless, keeps the loop branch-free)
         advance();
         nxt = address();
-        load_half(A, nxt.Wb, nxt.Sb, nxt.voff, nxt.wstride);
-        compute_half<LPG, K, HALF>(B, dp, t1, t2, t3, cur);
+        load_half<SWZ>(A, nxt.Wb, nxt.Sb, nxt.voff, nxt.wstride, nxt.soA, nxt.soB);
+        compute_half<LPG, K, HALF, SWZ>(B, dp, t1, t2, t3, cur, xw, lane);
 
         const int oct = bl * opb + o0 + pc * OS;
 #pragma unroll
