@@ -24,6 +24,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per weight of the cost kernel from rocprofv3 counters (FETCH_SIZE x 2.000 and WRITE_SIZE
 # x 1.000 after calibration against a plain 1 GiB copy; profiles/hbm_traffic_8_layers_pmc.md)
 COST_TRAFFIC_B_PER_WEIGHT = (5114570 * 2.0 + 1664) * 1024 / 1744830464
+ONE_PASS_TRAFFIC_B_PER_WEIGHT = None   # not measured yet
 
 
 def parse():
@@ -36,6 +37,8 @@ def parse():
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--bits", type=str, default="1,2,3,4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-pass", action="store_true",
+                    help="separate gather and cost launches instead of the fused one-pass kernel")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy first (calibrates rocprofv3 byte counters)")
@@ -119,7 +122,8 @@ def main():
     row_perm = torch.empty(sum(r for _, _, r, _ in shapes), dtype=torch.int32, device=dev)
     col_perm = torch.empty(sum(c for _, _, _, c in shapes), dtype=torch.int32, device=dev)
     w_re = torch.empty(nw, dtype=torch.bfloat16, device=dev)      # reordered matrices, concatenated
-    s_re = torch.empty(nw, dtype=torch.float32, device=dev)
+    one_pass = plan.gather_cost_supported() and not args.two_pass
+    s_re = None if one_pass else torch.empty(nw, dtype=torch.float32, device=dev)
     cost = torch.empty(N, K, dtype=torch.float32, device=dev)
     level = torch.empty(N, dtype=torch.uint8, device=dev)
     byte_off = torch.empty(N + 1, dtype=torch.int64, device=dev)
@@ -128,15 +132,20 @@ def main():
     zero = torch.empty(N * m, dtype=torch.float32, device=dev)
     nm = len(shapes)
 
+    # one_pass: the reorder-gather is fused into the cost pass (stage "gather" is then empty)
     stage_names = ["reorder", "gather", "cost", "allocate", "offsets_pack"]
 
     def step(ev):
         ev[0].record()
         plan.reorder_all(mats, row_perm, col_perm, ws)
         ev[1].record()
-        plan.gather_all(mats, row_perm, col_perm, w_re, s_re, ws)
-        ev[2].record()
-        plan.cost_table_all(w_re, s_re, cost, ws)
+        if one_pass:
+            ev[2].record()
+            plan.gather_cost_all(mats, row_perm, col_perm, w_re, cost, ws)
+        else:
+            plan.gather_all(mats, row_perm, col_perm, w_re, s_re, ws)
+            ev[2].record()
+            plan.cost_table_all(w_re, s_re, cost, ws)
         ev[3].record()
         rc, st, _ = plan.allocate(cost, args.budget, level, ws)
         ev[4].record()
@@ -172,9 +181,17 @@ def main():
     stage_ms = {nm_: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, nm_ in enumerate(stage_names)}
     cost_ms = stage_ms["cost"]
     # cost-table pass: each weight is read once as bf16 (2 B) with its fp32 sensitivity (4 B);
-    # the table written is K*4 bytes per m*n weights
-    cost_bytes = nw * 6 + N * K * 4
-    launches = 1            # one launch covers all matrices
+    # the table written is K*4 bytes per m*n weights.  The one-pass kernel also reads both
+    # permutations and writes the reordered weights (2 B per weight).
+    if one_pass:
+        cost_bytes = nw * 8 + N * K * 4 + 4 * (row_perm.numel() + col_perm.numel())
+        kernel = "gather_cost_kernel"
+        traffic = ONE_PASS_TRAFFIC_B_PER_WEIGHT * nw if (m == 128 and K == 4 and ONE_PASS_TRAFFIC_B_PER_WEIGHT) else None
+    else:
+        cost_bytes = nw * 6 + N * K * 4
+        kernel = "cost_kernel"
+        traffic = COST_TRAFFIC_B_PER_WEIGHT * nw if (m == 128 and K == 4) else None
+    launches = 1            # the stage covers all matrices (one-pass: one launch per column-count class)
     achieved = cost_bytes / (cost_ms * 1e-3) / 1e9
 
     out = {
@@ -193,9 +210,9 @@ def main():
         "cost_pass_weights_per_s": nw / (cost_ms * 1e-3),
         "search_stats": st, "search_status": rc,
         "gen_s": t_gen,
-        "roofline": {"kernel": "cost_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"kernel": kernel, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": COST_TRAFFIC_B_PER_WEIGHT * nw if (m == 128 and K == 4) else None,
+                     "traffic": traffic,
                      "launches_per_step": launches, "avg_launch_ms": cost_ms / launches,
                      "algorithmic_bytes_per_launch": cost_bytes / launches},
     }

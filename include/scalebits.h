@@ -162,6 +162,20 @@ int  sbits_cost_table(sbits_plan *plan, int mat, const void *w_re_bf16, const fl
 int  sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *s_re,
                           float *cost, void *ws);
 
+/* Reordering and scoring in ONE pass over the ORIGINAL matrices (paper Sec. 4.2
+ * reordering followed by the Sec. 5 quantizer, as above): equivalent to
+ * sbits_gather_all followed by sbits_cost_table_all, bit for bit, without writing
+ * or re-reading the reordered sensitivities.  w_re (reordered weights, needed by
+ * sbits_pack_all) and cost[N][K] are written.  Supported for 64- and 128-column
+ * blocks, rows of at most 16384 elements, and source rows that start on 16-byte
+ * boundaries (w_bf16, sens 16-byte aligned, ld_w % 8 == 0, ld_s % 4 == 0);
+ * otherwise returns SBITS_ERR_UNIMPLEMENTED and writes nothing: use the two calls
+ * above.  sbits_gather_cost_supported: 1 if the plan's shapes qualify (the
+ * alignment of the matrices is checked by the call itself), else 0.  Uses ws.     */
+int  sbits_gather_cost_supported(const sbits_plan *plan);
+int  sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                           const int32_t *col_perm, void *w_re_bf16, float *cost, void *ws);
+
 /* ---- scalable greedy search (paper Algorithm 2 with the relaxed step Eq. 5) ---
  * Runs on the device over the cost table: marginal change per bit from the
  * table, radix selection of the top-k / bottom-k sets on (value, index) keys,
@@ -195,7 +209,10 @@ typedef struct {
     int32_t *row_perm;     /* concatenated over matrices: sum(rows) entries                  */
     int32_t *col_perm;     /* concatenated: sum(cols) entries                                */
     void    *w_re_bf16;    /* reordered weights, matrices concatenated, each dense           */
-    float   *s_re;         /* reordered sensitivities, same layout                           */
+    float   *s_re;         /* reordered sensitivities, same layout; written only when the    */
+                           /* one-pass route (sbits_gather_cost_all) does not apply, and     */
+                           /* may be NULL when sbits_gather_cost_supported(plan) and every   */
+                           /* matrix meets its alignment rule                                */
     float   *cost;         /* [N][K]                                                         */
     uint8_t *level;        /* [N]                                                            */
     int64_t *byte_off;     /* [N+1]                                                          */

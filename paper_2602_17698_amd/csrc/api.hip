@@ -112,6 +112,8 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
     const size_t a = sbits_alloc_ws_bytes(p->N), o = sbits_offsets_ws_bytes(p->N);
     if (a > ws) ws = a;
     if (o > ws) ws = o;
+    const size_t f = sbits_fused_ws_bytes(p);
+    if (f > ws) ws = f;
     p->head_bytes = sbits_desc_bytes(n_mats) + SBITS_N_PREFIX * sbits_prefix_bytes(n_mats);
     p->ws_bytes = p->head_bytes + ws;
     *out = p;
@@ -280,6 +282,22 @@ int sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *s
     return sbits_launch_cost_all(plan, w_re_bf16, s_re, cost, ws);
 }
 
+int sbits_gather_cost_supported(const sbits_plan *plan) { return plan && sbits_fused_shapes_ok(plan) ? 1 : 0; }
+
+int sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                          const int32_t *col_perm, void *w_re_bf16, float *cost, void *ws)
+{
+    int rc = check_all(plan, mats, true, true);
+    if (rc) return rc;
+    if (!row_perm || !col_perm || !w_re_bf16 || !cost || !aligned16(col_perm) || !aligned16(w_re_bf16) || !ws_ok(ws))
+        return SBITS_ERR_INVALID_ARG;
+    if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
+    if ((rc = need_device(plan))) return rc;
+    if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    if (!sbits_fused_layout_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
+    return sbits_launch_gather_cost_all(plan, row_perm, col_perm, w_re_bf16, cost, ws);
+}
+
 int sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits, const sbits_params *params,
                    uint8_t *level, sbits_stats *host_stats, sbits_trace *host_trace, int64_t trace_cap,
                    void *ws)
@@ -332,7 +350,7 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
                  const sbits_outputs *out, sbits_stats *host_stats, void *ws)
 {
     if (!plan || !mats || !params || !out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
-    if (!out->row_perm || !out->col_perm || !out->w_re_bf16 || !out->s_re || !out->cost || !out->level ||
+    if (!out->row_perm || !out->col_perm || !out->w_re_bf16 || !out->cost || !out->level ||
         !out->byte_off || !out->codes || !out->scale || !out->zero)
         return SBITS_ERR_INVALID_ARG;
     if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
@@ -342,8 +360,15 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
     if ((rc = check_all(plan, mats, true, true))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
     if ((rc = sbits_launch_reorder_all(plan, out->row_perm, out->col_perm, ws))) return rc;
-    if ((rc = sbits_launch_gather_all(plan, out->row_perm, out->col_perm, out->w_re_bf16, out->s_re, ws))) return rc;
-    if ((rc = sbits_launch_cost_all(plan, out->w_re_bf16, out->s_re, out->cost, ws))) return rc;
+    if (sbits_fused_shapes_ok(plan) && sbits_fused_layout_ok(plan)) {
+        if ((rc = sbits_launch_gather_cost_all(plan, out->row_perm, out->col_perm, out->w_re_bf16, out->cost, ws)))
+            return rc;
+    } else {
+        if (!out->s_re) return SBITS_ERR_INVALID_ARG;
+        if ((rc = sbits_launch_gather_all(plan, out->row_perm, out->col_perm, out->w_re_bf16, out->s_re, ws)))
+            return rc;
+        if ((rc = sbits_launch_cost_all(plan, out->w_re_bf16, out->s_re, out->cost, ws))) return rc;
+    }
     rc = sbits_allocate(plan, out->cost, avg_bits, params, out->level, host_stats, nullptr, 0, ws);
     const int alloc_rc = rc;
     if (rc && rc != SBITS_ERR_MAX_ITERS) return rc;

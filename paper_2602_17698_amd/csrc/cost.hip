@@ -28,21 +28,13 @@
 #include <type_traits>
 #include <vector>
 
+#include "cost_core.hpp"
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
 
 void sbits_fill_grid_consts(const int32_t *bits, int K, sbits::GridConsts *gc);
 
 namespace sbits {
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int64_t uni64(int64_t v)
@@ -57,17 +49,6 @@ constexpr int HALF = 4;                               // rows per pipeline stage
 #ifndef SBITS_COST_STRIDED
 #define SBITS_COST_STRIDED true
 #endif
-
-// value held by lane j*SP + SLOT of the caller's lane group, j in [0, LPG/SP)
-template <int LPG, int SP, int SLOT>
-__device__ __forceinline__ float bcast_row(float v, int j)
-{
-    constexpr int RPG = LPG / SP;
-    if (RPG <= 1 || j == 0) return group_bcast<LPG, SLOT>(v);
-    if (RPG >= 2 && j == 1) return group_bcast<LPG, (1 * SP + SLOT) % LPG>(v);
-    if (RPG >= 4 && j == 2) return group_bcast<LPG, (2 * SP + SLOT) % LPG>(v);
-    return group_bcast<LPG, (3 * SP + SLOT) % LPG>(v);
-}
 
 // the raw loads of HALF consecutive rows of one lane
 struct HalfBuf {
@@ -127,39 +108,6 @@ __device__ __forceinline__ void swizzle_s(float4 *xrow, int lane, float4 &a, flo
     __builtin_amdgcn_wave_barrier();
 }
 
-// Per-lane constants of the distributed grid divisions.  The 2K quotients of a
-// row (slot 2c: qmax_c / R, slot 2c+1: R / qmax_c) are spread over the lanes of
-// the group, one division per lane, and broadcast afterwards.  When the group
-// has more lanes than slots, RP rows share one round of divisions.
-template <int LPG, int K>
-struct DivPlan {
-    static constexpr int SP = (2 * K <= 2) ? 2 : (2 * K <= 4) ? 4 : (2 * K <= 8) ? 8 : 16;   // slots per row
-    static constexpr int RP0 = (LPG >= SP) ? (LPG / SP) : 1;
-    static constexpr int RP = RP0 < HALF ? RP0 : HALF;                                         // rows per round
-    static constexpr int NS = (LPG >= SP) ? 1 : (2 * K + LPG - 1) / LPG;                       // divisions per lane
-    float qf[NS], thr[NS];
-    bool is_scale[NS];
-    int my_row;
-
-    __device__ __forceinline__ void init(const GridConsts &gc, int lig)
-    {
-#pragma unroll
-        for (int t = 0; t < NS; ++t) {
-            const int slot = (LPG >= SP) ? (lig % SP) : (lig + t * LPG);
-            int c = slot >> 1;
-            c = c < K ? c : K - 1;
-            float q = gc.qmaxf[0], th = gc.thr[0];
-#pragma unroll
-            for (int cc = 1; cc < K; ++cc)
-                if (c == cc) { q = gc.qmaxf[cc]; th = gc.thr[cc]; }
-            qf[t] = q;
-            thr[t] = th;
-            is_scale[t] = (slot & 1) != 0;
-        }
-        my_row = (LPG >= SP) ? (lig / SP) : 0;
-    }
-};
-
 // HALF rows of one octet: rows R_BASE .. R_BASE + HALF - 1 (R_BASE is 0 or 4).  Updates the
 // pending levels of the row tree (t1, t2, t3) and leaves the running result in cur.
 template <int LPG, int K, int R_BASE, bool SWIZZLE>
@@ -168,7 +116,7 @@ __device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG
                                              float4 *xw, int lane)
 {
     using DP = DivPlan<LPG, K>;
-    constexpr int SP = DP::SP, RP = DP::RP, NS = DP::NS;
+    constexpr int RP = DP::RP < HALF ? DP::RP : HALF;
 #ifdef SBITS_COST_LOADONLY
     {
         float acc = 0.0f;
@@ -184,81 +132,22 @@ __device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG
 #endif
 #pragma unroll
     for (int r0 = 0; r0 < HALF; r0 += RP) {
-        float x[RP][8], s[RP][8], Rg[RP];
+        uint4 wr[RP];
+        float s[RP][8], out[RP][K];
 #pragma unroll
         for (int j = 0; j < RP; ++j) {
-            float w[8];
-            unpack8(h.w[r0 + j], w);
+            wr[j] = h.w[r0 + j];
             float4 a = h.s0[r0 + j], b = h.s1[r0 + j];
             if constexpr (SWIZZLE) swizzle_s(xw + (r0 + j) * 128, lane, a, b);
             s[j][0] = a.x; s[j][1] = a.y; s[j][2] = a.z; s[j][3] = a.w;
             s[j][4] = b.x; s[j][5] = b.y; s[j][6] = b.z; s[j][7] = b.w;
-            float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])),
-                             fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
-            float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])),
-                             fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
-            mn = group_allreduce<LPG>(mn, OpMin{});
-            mx = group_allreduce<LPG>(mx, OpMax{});
-            Rg[j] = mx - mn;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[j][e] = w[e] - mn;
         }
-
-        float val[NS];
-        {
-            float Rsel = Rg[0];
-#pragma unroll
-            for (int j = 1; j < RP; ++j)
-                if (dp.my_row == j) Rsel = Rg[j];
-#pragma unroll
-            for (int t = 0; t < NS; ++t) {
-                const float num = dp.is_scale[t] ? Rsel : dp.qf[t];
-                const float den = dp.is_scale[t] ? dp.qf[t] : Rsel;
-                const float v = num / den;           // IEEE correctly rounded
-                val[t] = (Rsel < dp.thr[t]) ? 0.0f : v;
-            }
-        }
-
+        quant_cost_round<LPG, K, RP>(wr, s, dp, out);
 #pragma unroll
         for (int j = 0; j < RP; ++j) {
             const int rr = R_BASE + r0 + j;
-            static_for<0, K>([&](auto ic) {
-                constexpr int c = decltype(ic)::value;
-                float inv, scl;
-                if constexpr (LPG >= SP) {
-                    inv = bcast_row<LPG, SP, 2 * c>(val[0], j);
-                    scl = bcast_row<LPG, SP, 2 * c + 1>(val[0], j);
-                } else {
-                    inv = group_bcast<LPG, (2 * c) % LPG>(val[(2 * c) / LPG]);
-                    scl = group_bcast<LPG, (2 * c + 1) % LPG>(val[(2 * c + 1) / LPG]);
-                }
-                float acc = 0.0f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float q = rintf(x[j][e] * inv);
-                    const float d = fmaf(-q, scl, x[j][e]);
-                    acc = fmaf(s[j][e], d * d, acc);
-                }
-                cur[c] = acc;
-            });
-            // adjacent-pair tree over the 8 rows of the octet
-#pragma unroll
-            for (int c = 0; c < K; ++c) {
-                float v = cur[c];
-                if (rr & 1) {
-                    v = t1[c] + v;
-                    if (rr & 2) {
-                        v = t2[c] + v;
-                        if (rr & 4) v = t3[c] + v;
-                        else t3[c] = v;
-                    } else {
-                        t2[c] = v;
-                    }
-                } else {
-                    t1[c] = v;
-                }
-                cur[c] = v;
-            }
+            for (int c = 0; c < K; ++c) cur[c] = octet_tree_push(out[j][c], rr, t1[c], t2[c], t3[c]);
         }
         // keep the rounds apart: interleaving them only lengthens live ranges
         __builtin_amdgcn_sched_barrier(0);

@@ -1,0 +1,154 @@
+// Arithmetic core of the block x bitwidth cost: the per-row round-to-nearest grid of
+// every candidate bitwidth and the sensitivity-weighted squared change of a lane's 8 elements
+// (paper Sec. 5 "Implementation", group = one block row).  Shared by the kernel that reads
+// reordered matrices and by the one that reorders on the fly, so both produce the same bits.
+#pragma once
+
+#include <type_traits>
+
+#include "sbits_device.hpp"
+
+namespace sbits {
+
+constexpr int COST_MAX_ROUND = 4;                     // rows that may share one round of divisions
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// value held by lane j*SP + SLOT of the caller's lane group, j in [0, LPG/SP)
+template <int LPG, int SP, int SLOT>
+__device__ __forceinline__ float bcast_row(float v, int j)
+{
+    constexpr int RPG = LPG / SP;
+    if (RPG <= 1 || j == 0) return group_bcast<LPG, SLOT>(v);
+    if (RPG >= 2 && j == 1) return group_bcast<LPG, (1 * SP + SLOT) % LPG>(v);
+    if (RPG >= 4 && j == 2) return group_bcast<LPG, (2 * SP + SLOT) % LPG>(v);
+    return group_bcast<LPG, (3 * SP + SLOT) % LPG>(v);
+}
+
+// Per-lane constants of the distributed grid divisions.  The 2K quotients of a
+// row (slot 2c: qmax_c / R, slot 2c+1: R / qmax_c) are spread over the lanes of
+// the group, one division per lane, and broadcast afterwards.  When the group
+// has more lanes than slots, RP rows share one round of divisions.
+template <int LPG, int K>
+struct DivPlan {
+    static constexpr int SP = (2 * K <= 2) ? 2 : (2 * K <= 4) ? 4 : (2 * K <= 8) ? 8 : 16;   // slots per row
+    static constexpr int RP0 = (LPG >= SP) ? (LPG / SP) : 1;
+    static constexpr int RP = RP0 < COST_MAX_ROUND ? RP0 : COST_MAX_ROUND;                                         // rows per round
+    static constexpr int NS = (LPG >= SP) ? 1 : (2 * K + LPG - 1) / LPG;                       // divisions per lane
+    float qf[NS], thr[NS];
+    bool is_scale[NS];
+    int my_row;
+
+    __device__ __forceinline__ void init(const GridConsts &gc, int lig)
+    {
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            const int slot = (LPG >= SP) ? (lig % SP) : (lig + t * LPG);
+            int c = slot >> 1;
+            c = c < K ? c : K - 1;
+            float q = gc.qmaxf[0], th = gc.thr[0];
+#pragma unroll
+            for (int cc = 1; cc < K; ++cc)
+                if (c == cc) { q = gc.qmaxf[cc]; th = gc.thr[cc]; }
+            qf[t] = q;
+            thr[t] = th;
+            is_scale[t] = (slot & 1) != 0;
+        }
+        my_row = (LPG >= SP) ? (lig / SP) : 0;
+    }
+};
+
+// One round: NI rows (NI <= DivPlan::RP), each owned by the caller's lane group, the lane holding
+// 8 consecutive elements of every row: raw bf16 weights w[j] and sensitivities s[j][0..7].
+// out[j][c] = the lane's partial cost of row j at candidate c (elements left to right,
+// a = fma(s, d*d, a)).
+template <int LPG, int K, int NI>
+__device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const float (&s)[NI][8],
+                                                 const DivPlan<LPG, K> &dp, float (&out)[NI][K])
+{
+    using DP = DivPlan<LPG, K>;
+    constexpr int SP = DP::SP, NS = DP::NS;
+    static_assert(NI >= 1 && NI <= DP::RP, "too many rows for one round of divisions");
+    float x[NI][8], Rg[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        float w[8];
+        unpack8(wraw[j], w);
+        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])),
+                         fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
+        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])),
+                         fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+        mn = group_allreduce<LPG>(mn, OpMin{});
+        mx = group_allreduce<LPG>(mx, OpMax{});
+        Rg[j] = mx - mn;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[j][e] = w[e] - mn;
+    }
+
+    float val[NS];
+    {
+        float Rsel = Rg[0];
+#pragma unroll
+        for (int j = 1; j < NI; ++j)
+            if (dp.my_row == j) Rsel = Rg[j];
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            const float num = dp.is_scale[t] ? Rsel : dp.qf[t];
+            const float den = dp.is_scale[t] ? dp.qf[t] : Rsel;
+            const float v = num / den;           // IEEE correctly rounded
+            val[t] = (Rsel < dp.thr[t]) ? 0.0f : v;
+        }
+    }
+
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        static_for<0, K>([&](auto ic) {
+            constexpr int c = decltype(ic)::value;
+            float inv, scl;
+            if constexpr (LPG >= SP) {
+                inv = bcast_row<LPG, SP, 2 * c>(val[0], j);
+                scl = bcast_row<LPG, SP, 2 * c + 1>(val[0], j);
+            } else {
+                inv = group_bcast<LPG, (2 * c) % LPG>(val[(2 * c) / LPG]);
+                scl = group_bcast<LPG, (2 * c + 1) % LPG>(val[(2 * c + 1) / LPG]);
+            }
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float q = rintf(x[j][e] * inv);
+                const float d = fmaf(-q, scl, x[j][e]);
+                acc = fmaf(s[j][e], d * d, acc);
+            }
+            out[j][c] = acc;
+        });
+    }
+}
+
+// Adjacent-pair tree over the 8 rows of an octet, fed one row at a time: rr is the row's index
+// in the octet, t1..t3 hold the pending left operands of the three levels.  Returns the value of
+// the deepest level completed by this row (the octet's sum when rr == 7).
+__device__ __forceinline__ float octet_tree_push(float v, int rr, float &t1, float &t2, float &t3)
+{
+    if (rr & 1) {
+        v = t1 + v;
+        if (rr & 2) {
+            v = t2 + v;
+            if (rr & 4) v = t3 + v;
+            else t3 = v;
+        } else {
+            t2 = v;
+        }
+    } else {
+        t1 = v;
+    }
+    return v;
+}
+
+}  // namespace sbits

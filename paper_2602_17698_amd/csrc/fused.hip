@@ -1,0 +1,429 @@
+// Reorder-gather fused with the block x bitwidth cost table: the original weights (bf16) and
+// sensitivities (fp32) are read ONCE, permuted on the fly and scored; only the reordered
+// weights (which the packing stage needs) are written back.  The reordered sensitivities
+// never reach HBM.
+//
+// Operation: the same as gather followed by the cost table (paper Sec. 4.2 "bi-directional
+// channel reordering" applied to W and S, then Sec. 5 "Implementation": per-block-row
+// round-to-nearest grids for every candidate bitwidth), with the same fixed summation order,
+// so the table equals the two-pass result bit for bit.
+//
+// Mapping.  A workgroup of 512 threads owns a run of octets (8 output rows each) of one
+// matrix, all columns.  Per step it stages RS source rows (the rows row_perm names) in LDS
+// with fully contiguous 16-byte loads, then every lane picks the 8 source columns of each of
+// its CPL output chunks (chunk = 8 consecutive output columns; LPG adjacent lanes = one
+// quantization group) out of LDS.  The next step's rows are already in flight in registers
+// while the current ones are scored.  A lane keeps the pending levels of the octet's row tree
+// per chunk; at the end of an octet the group's lanes are reduced and the octet's partial sum
+// goes to part[block][octet][candidate]; a second, tiny kernel runs the tree over the octets
+// of each block.
+#include <string.h>
+
+#include <vector>
+
+#include "cost_core.hpp"
+#include "sbits_device.hpp"
+#include "sbits_internal.hpp"
+
+void sbits_fill_grid_consts(const int32_t *bits, int K, sbits::GridConsts *gc);
+
+namespace sbits {
+
+constexpr int FU_THREADS = 512;
+constexpr int FU_OPU = 16;                          // octets per workgroup (128 output rows)
+constexpr int FU_MAX_COLS = 4 * FU_THREADS * 8;     // widest row the kernel stages (CPL = 4)
+
+__device__ __forceinline__ int funi(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <int LPG, int K, int CPL, int RS>
+__global__ __launch_bounds__(FU_THREADS, 1)
+void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
+                        const int *__restrict__ wg_start, int n_members,
+                        const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
+                        uint16_t *__restrict__ w_re_all, float *__restrict__ part, GridConsts gc)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int rowsrc[FU_OPU * 8];
+    constexpr int NIT = RS * CPL;                    // rows x chunks scored per step
+    using DP = DivPlan<LPG, K>;
+    constexpr int NI = DP::RP < NIT ? DP::RP : NIT;  // of which NI share a round of divisions
+    static_assert(NIT % NI == 0 && 8 % RS == 0, "step shape");
+
+    const int tid = (int)threadIdx.x;
+    const int lig = tid % LPG;
+    const int mem = funi(find_matrix(wg_start, n_members, (int)blockIdx.x));
+    const MatDesc &d = descs[funi(members[mem])];
+    const int R = funi((int)d.rows), C = funi((int)d.cols);
+    const int nbc = funi(d.nbc);
+    const int opb = m >> 3;
+    const int oct0 = ((int)blockIdx.x - funi(wg_start[mem])) * FU_OPU;
+    const int noct = min(FU_OPU, (R >> 3) - oct0);
+    const int32_t *__restrict__ rp = row_perm + d.row_off;
+    const int32_t *__restrict__ cp = col_perm + d.col_off;
+    const char *const Wg = reinterpret_cast<const char *>(d.w);
+    const char *const Sg = reinterpret_cast<const char *>(d.s);
+    const int64_t pitch_w = d.ld_w * 2, pitch_s = d.ld_s * 4;
+
+    uint16_t *const Wl = reinterpret_cast<uint16_t *>(smem);                    // [RS][C]
+    float *const Sl = reinterpret_cast<float *>(smem + (size_t)RS * C * 2);     // [RS][C]
+
+    DP dp;
+    dp.init(gc, lig);
+
+    // source rows of the run (a permutation never trips the clamp; it keeps a bad one in bounds)
+    for (int i = tid; i < noct * 8; i += FU_THREADS) {
+        int sr = rp[oct0 * 8 + i];
+        rowsrc[i] = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);
+    }
+
+    // source columns of this lane's chunks (fixed for the whole run)
+    const int nchunk = C >> 3;
+    int ci[CPL][8];
+    bool valid[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const int chunk = tid + FU_THREADS * c;
+        valid[c] = chunk < nchunk;
+        const int cb = valid[c] ? chunk * 8 : 0;
+        const int4 a = *reinterpret_cast<const int4 *>(cp + cb);
+        const int4 b = *reinterpret_cast<const int4 *>(cp + cb + 4);
+        const int t[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ci[c][e] = t[e] < 0 ? 0 : (t[e] >= C ? C - 1 : t[e]);
+    }
+    __syncthreads();
+
+    // ---- the rows of a step, as contiguous 16-byte pieces (piece p of a row: bytes 16p..) ----
+    uint4 pw[RS][CPL];
+    float4 ps[RS][2 * CPL];
+    auto prefetch = [&](int row) {                   // row = first row of the step inside the run
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
+            const int sr = funi(rowsrc[row + rs]);
+            const char *wrow = Wg + (int64_t)sr * pitch_w;
+            const char *srow = Sg + (int64_t)sr * pitch_s;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int p = tid + FU_THREADS * c;
+                if (p < nchunk) {
+                    const u32x4_t v = __builtin_nontemporal_load(
+                        (const __attribute__((address_space(1))) u32x4_t *)(wrow + (uint32_t)p * 16u));
+                    pw[rs][c] = make_uint4(v.x, v.y, v.z, v.w);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < 2 * CPL; ++c) {
+                const int p = tid + FU_THREADS * c;
+                if (p < 2 * nchunk) {
+                    const f32x4_t v = __builtin_nontemporal_load(
+                        (const __attribute__((address_space(1))) f32x4_t *)(srow + (uint32_t)p * 16u));
+                    ps[rs][c] = make_float4(v.x, v.y, v.z, v.w);
+                }
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int p = tid + FU_THREADS * c;
+                if (p < nchunk) *reinterpret_cast<uint4 *>(Wl + (size_t)rs * C + (size_t)p * 8) = pw[rs][c];
+            }
+#pragma unroll
+            for (int c = 0; c < 2 * CPL; ++c) {
+                const int p = tid + FU_THREADS * c;
+                if (p < 2 * nchunk) *reinterpret_cast<float4 *>(Sl + (size_t)rs * C + (size_t)p * 4) = ps[rs][c];
+            }
+        }
+    };
+
+    float t1[CPL][K], t2[CPL][K], t3[CPL][K];
+    uint16_t *const wout = w_re_all + d.elem_off;
+    const int nsteps = noct * (8 / RS);
+
+    prefetch(0);
+    for (int st = 0; st < nsteps; ++st) {
+        stage();
+        __syncthreads();
+        if (st + 1 < nsteps) prefetch((st + 1) * RS);
+
+        // pick this lane's elements out of the staged rows; item = rs * CPL + c
+        uint4 gw[NIT];
+        float gs[NIT][8];
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const uint16_t *wl = Wl + (size_t)rs * C;
+                const float *sl = Sl + (size_t)rs * C;
+                uint32_t h[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    h[e] = wl[ci[c][e]];
+                    gs[rs * CPL + c][e] = sl[ci[c][e]];
+                }
+                gw[rs * CPL + c] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
+                                              h[6] | (h[7] << 16));
+            }
+        }
+        __syncthreads();                             // the rows may be overwritten from here on
+
+        const int row = st * RS;                     // first row of the step inside the run
+        const int rr0 = row & 7;
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                if (valid[c]) {
+                    const int64_t orow = (int64_t)(oct0 * 8 + row + rs);
+                    *reinterpret_cast<uint4 *>(wout + orow * C + (int64_t)(tid + FU_THREADS * c) * 8) =
+                        gw[rs * CPL + c];
+                }
+            }
+        }
+
+        float last[CPL][K];
+#pragma unroll
+        for (int i0 = 0; i0 < NIT; i0 += NI) {
+            uint4 wr[NI];
+            float s[NI][8], out[NI][K];
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                wr[j] = gw[i0 + j];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[j][e] = gs[i0 + j][e];
+            }
+            quant_cost_round<LPG, K, NI>(wr, s, dp, out);
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int rs = (i0 + j) / CPL, c = (i0 + j) % CPL;
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    last[c][k] = octet_tree_push(out[j][k], rr0 + rs, t1[c][k], t2[c][k], t3[c][k]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        if (rr0 + RS == 8) {                         // an octet is complete: lanes of the group, then out
+            const int og = oct0 + (row >> 3);
+            const int I = og / opb, oib = og - I * opb;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                float v[K];
+#pragma unroll
+                for (int k = 0; k < K; ++k) v[k] = group_allreduce<LPG>(last[c][k], OpAdd{});
+                if (lig == 0 && valid[c]) {
+                    const int J = (tid + FU_THREADS * c) / LPG;
+                    float *dst = part + ((d.block_base + (int64_t)I * nbc + J) * opb + oib) * K;
+#pragma unroll
+                    for (int k = 0; k < K; ++k) dst[k] = v[k];
+                }
+            }
+        }
+    }
+}
+
+// adjacent-pair tree over n <= 8 values p[0], p[stride], ... (n a power of two)
+__device__ __forceinline__ float tree_upto8(const float *__restrict__ p, int stride, int n)
+{
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = i < n ? p[(int64_t)i * stride] : 0.0f;
+    if (n == 1) return v[0];
+    if (n == 2) return v[0] + v[1];
+    if (n == 4) return (v[0] + v[1]) + (v[2] + v[3]);
+    return ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+}
+
+// cost[b][c] = adjacent-pair tree over the opb octet partials of block b (opb a power of two <= 128)
+__global__ __launch_bounds__(256)
+void octet_finish_kernel(const float *__restrict__ part, int64_t NK, int K, int opb, float *__restrict__ cost)
+{
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= NK) return;
+    const int64_t b = q / K;
+    const int c = (int)(q - b * K);
+    const float *p = part + b * opb * K + c;
+    if (opb <= 8) {
+        cost[q] = tree_upto8(p, K, opb);
+        return;
+    }
+    float t1 = 0.0f, t2 = 0.0f, t3 = 0.0f, t4 = 0.0f, v = 0.0f;
+    const int ng = opb >> 3;                         // 2 .. 16 groups of 8 octets
+    for (int g = 0; g < ng; ++g) {
+        v = tree_upto8(p + (int64_t)g * 8 * K, K, 8);
+        if (g & 1) {
+            v = t1 + v;
+            if (g & 2) {
+                v = t2 + v;
+                if (g & 4) {
+                    v = t3 + v;
+                    if (g & 8) v = t4 + v;
+                    else t4 = v;
+                } else {
+                    t3 = v;
+                }
+            } else {
+                t2 = v;
+            }
+        } else {
+            t1 = v;
+        }
+    }
+    cost[q] = v;
+}
+
+struct FusedLaunch {
+    const MatDesc *descs;
+    const int *members, *wg_start;
+    int n_members, total_wg;
+    const int32_t *row_perm, *col_perm;
+    int m;
+    uint16_t *w_re;
+    float *part;
+    GridConsts gc;
+    int64_t cols;
+};
+
+template <int LPG, int K, int CPL, int RS>
+static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
+{
+    static bool attr_done = false;
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS>;
+    if (!attr_done) {
+        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
+        attr_done = true;
+    }
+    const size_t lds = (size_t)RS * a.cols * 6;
+    hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(FU_THREADS), lds, ctx->stream, a.descs, a.members,
+                       a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc);
+    SBITS_HIP(ctx, hipGetLastError());
+    return SBITS_OK;
+}
+
+template <int LPG, int K>
+static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
+{
+    const int64_t chunks = a.cols / 8;
+    if (chunks <= FU_THREADS) return launch_fused_g<LPG, K, 1, 2>(ctx, a);
+    if (chunks <= 2 * FU_THREADS) return launch_fused_g<LPG, K, 2, 1>(ctx, a);
+    if (chunks <= 4 * FU_THREADS) return launch_fused_g<LPG, K, 4, 1>(ctx, a);
+    return SBITS_ERR_BAD_SHAPE;
+}
+
+template <int LPG>
+static int launch_fused_l(int K, sbits_ctx *ctx, const FusedLaunch &a)
+{
+    switch (K) {
+    case 1: return launch_fused_k<LPG, 1>(ctx, a);
+    case 2: return launch_fused_k<LPG, 2>(ctx, a);
+    case 3: return launch_fused_k<LPG, 3>(ctx, a);
+    case 4: return launch_fused_k<LPG, 4>(ctx, a);
+    case 5: return launch_fused_k<LPG, 5>(ctx, a);
+    case 6: return launch_fused_k<LPG, 6>(ctx, a);
+    case 7: return launch_fused_k<LPG, 7>(ctx, a);
+    case 8: return launch_fused_k<LPG, 8>(ctx, a);
+    }
+    return SBITS_ERR_BAD_BITWIDTHS;
+}
+
+}  // namespace sbits
+
+using namespace sbits;
+
+// shapes the fused kernel takes: 64- or 128-column blocks, rows of at most FU_MAX_COLS elements
+bool sbits_fused_shapes_ok(const sbits_plan *plan)
+{
+    if (plan->n != 64 && plan->n != 128) return false;
+    return plan->max_cols <= FU_MAX_COLS;
+}
+
+// octet partials: one float per (block, octet of the block, candidate)
+size_t sbits_fused_ws_bytes(const sbits_plan *plan)
+{
+    if (!sbits_fused_shapes_ok(plan)) return 0;
+    return sbits_align_up((size_t)plan->N * (size_t)(plan->m / 8) * (size_t)plan->K * 4, 256);
+}
+
+// every source row must start on a 16-byte boundary (the rows are staged with 128-bit loads)
+bool sbits_fused_layout_ok(const sbits_plan *plan)
+{
+    for (int i = 0; i < plan->n_mats; ++i) {
+        const MatDesc &d = plan->descs[i];
+        if ((reinterpret_cast<uintptr_t>(d.w) & 15) || (reinterpret_cast<uintptr_t>(d.s) & 15) || (d.ld_w & 7) ||
+            (d.ld_s & 3))
+            return false;
+    }
+    return true;
+}
+
+// One launch per class of matrices with equal column count (equal LDS need, equal chunks per
+// lane); the descriptor table is already in the workspace head.
+//   slot 3 of the workspace head: members of all classes, class after class
+//   slot 4: workgroup prefixes, n_k + 1 entries per class
+int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                                 void *w_re, float *cost, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    if (!sbits_fused_shapes_ok(plan) || !sbits_fused_layout_ok(plan)) return SBITS_ERR_BAD_SHAPE;
+    if (plan->fused_members.empty()) {
+        std::vector<int64_t> classes;
+        for (int i = 0; i < plan->n_mats; ++i) {
+            bool seen = false;
+            for (int64_t c : classes) seen = seen || c == plan->cols[i];
+            if (!seen) classes.push_back(plan->cols[i]);
+        }
+        for (int64_t c : classes) {
+            sbits_plan::FusedClass fc;
+            fc.cols = c;
+            fc.first = (int)plan->fused_members.size();
+            fc.pre_first = (int)plan->fused_pre.size();
+            fc.n = 0;
+            int64_t t = 0;
+            for (int i = 0; i < plan->n_mats; ++i) {
+                if (plan->cols[i] != c) continue;
+                plan->fused_members.push_back(i);
+                plan->fused_pre.push_back((int)t);
+                t += (plan->rows[i] / 8 + FU_OPU - 1) / FU_OPU;
+                ++fc.n;
+            }
+            if (t > 0x7fffffff) { plan->fused_members.clear(); plan->fused_pre.clear(); return SBITS_ERR_BAD_SHAPE; }
+            plan->fused_pre.push_back((int)t);
+            plan->fused_classes.push_back(fc);
+        }
+    }
+    int *d_mem = sbits_prefix_ptr(plan, ws, 3);
+    int *d_pre = sbits_prefix_ptr(plan, ws, 4);
+    SBITS_HIP(ctx, hipMemcpyAsync(d_mem, plan->fused_members.data(), plan->fused_members.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, plan->fused_pre.data(), plan->fused_pre.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
+    FusedLaunch a;
+    memset(&a, 0, sizeof a);
+    sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
+    a.descs = sbits_desc_ptr(ws);
+    a.row_perm = row_perm;
+    a.col_perm = col_perm;
+    a.m = plan->m;
+    a.w_re = static_cast<uint16_t *>(w_re);
+    a.part = static_cast<float *>(sbits_scratch(plan, ws));
+    for (const sbits_plan::FusedClass &fc : plan->fused_classes) {
+        a.members = d_mem + fc.first;
+        a.wg_start = d_pre + fc.pre_first;
+        a.n_members = fc.n;
+        a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
+        a.cols = fc.cols;
+        if (a.total_wg == 0) continue;
+        const int rc = plan->n == 64 ? launch_fused_l<8>(plan->K, ctx, a) : launch_fused_l<16>(plan->K, ctx, a);
+        if (rc) return rc;
+    }
+    const int64_t NK = plan->N * plan->K;
+    if (NK > 0) {
+        hipLaunchKernelGGL(octet_finish_kernel, dim3((unsigned)((NK + 255) / 256)), dim3(256), 0, ctx->stream,
+                           a.part, NK, plan->K, plan->m / 8, cost);
+        SBITS_HIP(ctx, hipGetLastError());
+    }
+    return SBITS_OK;
+}

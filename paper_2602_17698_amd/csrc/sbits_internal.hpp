@@ -33,6 +33,9 @@ struct sbits_plan {
     struct GatherClass { int64_t cols; int first, pre_first, n, rpw_w, rpw_s; };
     std::vector<GatherClass> gather_classes; // matrices grouped by column count
     std::vector<int> gather_members, gather_pre_w, gather_pre_s;
+    struct FusedClass { int64_t cols; int first, pre_first, n; };
+    std::vector<FusedClass> fused_classes;   // the same grouping for the fused gather + cost launch
+    std::vector<int> fused_members, fused_pre;
     std::vector<sbits::MatDesc> descs;       // shape part filled at creation; pointers per call
     size_t head_bytes;                       // workspace head: descriptor table + workgroup prefixes
     size_t ws_bytes;
@@ -84,6 +87,12 @@ int sbits_launch_cost(sbits_ctx *ctx, const void *Wp, const float *Sp, int64_t R
 // batched over all matrices of the plan (descriptor table already in the workspace head)
 int sbits_upload_descs(sbits_plan *plan, const sbits_matrix *mats, void *ws);
 int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re, float *cost, void *ws);
+// gather fused with the cost table (reads the original matrices once; writes w_re and cost)
+bool sbits_fused_shapes_ok(const sbits_plan *plan);
+bool sbits_fused_layout_ok(const sbits_plan *plan);
+size_t sbits_fused_ws_bytes(const sbits_plan *plan);
+int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                                 void *w_re, float *cost, void *ws);
 int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
                        const sbits_params *prm, uint8_t *level, sbits_stats *host_stats,
                        sbits_trace *host_trace, int64_t trace_cap, void *ws);

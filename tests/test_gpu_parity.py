@@ -209,6 +209,64 @@ def test_cost_table_degenerate_groups(orc, ctx, dev):
     plan.close()
 
 
+# ------------------------------------------------- reordering and cost table in one pass
+ONE_PASS_CASES = [
+    # shapes, m, n, bits
+    ([(256, 384), (128, 1024)], 128, 128, [1, 2, 3, 4]),          # one chunk per lane, two rows per step
+    ([(192, 320), (64, 4096)], 64, 64, [1, 2, 3, 4, 8]),          # ragged run of octets (192 rows), K = 5
+    ([(128, 4224), (256, 8192)], 128, 128, [2, 3, 4]),            # two chunks per lane, ragged and full
+    ([(64, 14336), (64, 16384), (64, 8320)], 64, 128, [1, 2, 3, 4]),   # four chunks per lane
+    ([(24, 192), (2048, 128)], 8, 64, [1, 2, 3, 4, 5, 6, 7, 8]),  # one octet per block; 16 runs
+    ([(2048, 256)], 1024, 128, [3]),                              # 128 octets per block
+    ([(64, 14336)], 64, 64, [1, 2, 3, 4, 8]),                     # four chunks per lane, K = 5
+]
+
+
+@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES)
+def test_gather_cost_one_pass(orc, ctx, dev, shapes, m, n, bits):
+    say("one-pass gather+cost", shapes, m, n, bits)
+    plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
+    assert plan.gather_cost_supported()
+    N, K = plan.num_blocks(), len(bits)
+    mats = [synth.make_matrix("student_t", r, c, seed=11, tid=i) for i, (r, c) in enumerate(shapes)]
+    g = torch.Generator().manual_seed(17)
+    rps = [torch.randperm(r, generator=g).to(torch.int32) for r, _ in shapes]
+    cps = [torch.randperm(c, generator=g).to(torch.int32) for _, c in shapes]
+    dW = [W.to(dev) for W, _ in mats]
+    dS = [S.to(dev) for _, S in mats]
+    nel = sum(r * c for r, c in shapes)
+    w_re = torch.zeros(nel, dtype=torch.bfloat16, device=dev)
+    cost = torch.full((N, K), -1.0, dtype=torch.float32, device=dev)
+    plan.gather_cost_all([sb.matrix(w, s_) for w, s_ in zip(dW, dS)], torch.cat(rps).to(dev), torch.cat(cps).to(dev),
+                         w_re, cost, ws)
+    torch.cuda.synchronize()
+    eo = 0
+    refs = []
+    for (R, C), (W, S), rp, cp in zip(shapes, mats, rps, cps):
+        Wp, Sp = orc.gather(to_np_bf16(W), S.numpy(), rp.numpy(), cp.numpy())
+        np.testing.assert_array_equal(to_np_bf16(w_re[eo:eo + R * C]).reshape(R, C), Wp)
+        refs.append(orc.cost_table(Wp, Sp, m, n, bits))
+        eo += R * C
+    np.testing.assert_array_equal(cost.cpu().numpy(), np.concatenate(refs, 0))
+    plan.close()
+
+
+def test_gather_cost_one_pass_refuses_other_shapes(ctx, dev):
+    say("one-pass refuses")
+    plan, ws = make_plan(ctx, [(64, 256)], 32, 256, [2, 4], dev)     # 256-column blocks: two-pass route only
+    assert not plan.gather_cost_supported()
+    W, S = synth.make_matrix("student_t", 64, 256, seed=1)
+    Wd, Sd = W.to(dev), S.to(dev)
+    rp = torch.arange(64, dtype=torch.int32, device=dev)
+    cp = torch.arange(256, dtype=torch.int32, device=dev)
+    w_re = torch.zeros(64 * 256, dtype=torch.bfloat16, device=dev)
+    cost = torch.zeros(plan.num_blocks(), 2, dtype=torch.float32, device=dev)
+    with pytest.raises(sb.SbitsError) as e:
+        plan.gather_cost_all([sb.matrix(Wd, Sd)], rp, cp, w_re, cost, ws)
+    assert e.value.status == sb.ERR_UNIMPLEMENTED
+    plan.close()
+
+
 # --------------------------------------------------------------------------- allocation
 
 def synthetic_cost(N, bits, seed, noise=0.2):
@@ -380,6 +438,7 @@ def gpu_search(ctx, dev, mats, m, n, bits, avg, **kw):
     out = sb.Outputs(o["row_perm"].data_ptr(), o["col_perm"].data_ptr(), o["w_re"].data_ptr(), o["s_re"].data_ptr(),
                      o["cost"].data_ptr(), o["level"].data_ptr(), o["byte_off"].data_ptr(), o["codes"].data_ptr(),
                      o["codes"].numel(), o["scale"].data_ptr(), o["zero"].data_ptr())
+    o["one_pass"] = plan.gather_cost_supported()         # then the reordered sensitivities are never written
     rc, st = plan.search([sb.matrix(w, s) for w, s in zip(dW, dS)], avg, out, ws, **kw)
     torch.cuda.synchronize()
     plan.close()
@@ -393,7 +452,8 @@ def compare_search(orc, ref, rc, st, o, shapes, m):
         np.testing.assert_array_equal(o["row_perm"][ro:ro + R].cpu().numpy(), rp)
         np.testing.assert_array_equal(o["col_perm"][co:co + C].cpu().numpy(), cp)
         np.testing.assert_array_equal(to_np_bf16(o["w_re"][eo:eo + R * C]).reshape(R, C), Wp)
-        np.testing.assert_array_equal(o["s_re"][eo:eo + R * C].cpu().numpy().reshape(R, C), Sp)
+        if not o["one_pass"]:
+            np.testing.assert_array_equal(o["s_re"][eo:eo + R * C].cpu().numpy().reshape(R, C), Sp)
         ro, co, eo = ro + R, co + C, eo + R * C
     np.testing.assert_array_equal(o["cost"].cpu().numpy(), ref["cost"])
     np.testing.assert_array_equal(o["level"].cpu().numpy(), ref["level"])
@@ -434,4 +494,6 @@ def test_search_is_deterministic(ctx, dev):
     b = gpu_search(ctx, dev, mats, 64, 64, [1, 2, 3, 4], 2.5)
     assert a[1] == b[1]
     for key in a[2]:
+        if key == "one_pass" or (key == "s_re" and a[2]["one_pass"]):     # s_re: not written on the one-pass route
+            continue
         assert torch.equal(a[2][key].view(torch.uint8), b[2][key].view(torch.uint8)), key
