@@ -35,8 +35,39 @@ constexpr int FU_MAX_COLS = 4 * FU_THREADS * 8;     // widest row the kernel sta
 
 __device__ __forceinline__ int funi(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+typedef __attribute__((address_space(3))) float lds_f32;
+
+// LDS address of a sensitivity from the byte offset of its weight in the staged row.  With
+// OPAQUE the compiler cannot hoist the sum out of the row loop, which would otherwise keep a
+// second address register per element alive (32 more registers at four chunks per lane).
+template <bool OPAQUE>
+__device__ __forceinline__ uint32_t s_address(uint32_t w_off, uint32_t s_base)
+{
+    if constexpr (OPAQUE) {
+        uint32_t r;
+        asm volatile("v_lshl_add_u32 %0, %1, 1, %2" : "=v"(r) : "v"(w_off), "s"(s_base));
+        return r;
+    } else {
+        return 2u * w_off + s_base;
+    }
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load in flight, which would expose the latency of the rows being prefetched into registers.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+#ifndef FU_RS1
+#define FU_RS1 2
+#endif
+#ifndef FU_MINWG
+#define FU_MINWG 1
+#endif
 template <int LPG, int K, int CPL, int RS>
-__global__ __launch_bounds__(FU_THREADS, 1)
+__global__ __launch_bounds__(FU_THREADS, (CPL == 1 ? FU_MINWG : 1))
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
@@ -46,14 +77,15 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     __shared__ int rowsrc[FU_OPU * 8];
     constexpr int NIT = RS * CPL;                    // rows x chunks scored per step
     using DP = DivPlan<LPG, K>;
-    constexpr int NI = DP::RP < NIT ? DP::RP : NIT;  // of which NI share a round of divisions
-    static_assert(NIT % NI == 0 && 8 % RS == 0, "step shape");
+    constexpr int NG = NIT > 2 ? 2 : NIT;            // of which NG are held in registers at a time
+    constexpr int NI = DP::RP < NG ? DP::RP : NG;    // and NI share a round of divisions
+    static_assert(NIT % NG == 0 && NG % NI == 0 && 8 % RS == 0, "step shape");
 
     const int tid = (int)threadIdx.x;
     const int lig = tid % LPG;
     const int mem = funi(find_matrix(wg_start, n_members, (int)blockIdx.x));
     const MatDesc &d = descs[funi(members[mem])];
-    const int R = funi((int)d.rows), C = funi((int)d.cols);
+    const int R = funi((int)d.rows), C = funi((int)d.cols) & ~7;   // (a multiple of the block width anyway)
     const int nbc = funi(d.nbc);
     const int opb = m >> 3;
     const int oct0 = ((int)blockIdx.x - funi(wg_start[mem])) * FU_OPU;
@@ -64,8 +96,8 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     const char *const Sg = reinterpret_cast<const char *>(d.s);
     const int64_t pitch_w = d.ld_w * 2, pitch_s = d.ld_s * 4;
 
-    uint16_t *const Wl = reinterpret_cast<uint16_t *>(smem);                    // [RS][C]
-    float *const Sl = reinterpret_cast<float *>(smem + (size_t)RS * C * 2);     // [RS][C]
+    // LDS: weights [RS][C] bf16, then sensitivities [RS][C] fp32 (32-bit LDS addresses below)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
     DP dp;
     dp.init(gc, lig);
@@ -76,7 +108,8 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         rowsrc[i] = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);
     }
 
-    // source columns of this lane's chunks (fixed for the whole run)
+    // source columns of this lane's chunks (fixed for the whole run), as byte offsets into a
+    // staged row of weights; twice that is the offset into a row of sensitivities
     const int nchunk = C >> 3;
     int ci[CPL][8];
     bool valid[CPL];
@@ -89,11 +122,18 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         const int4 b = *reinterpret_cast<const int4 *>(cp + cb + 4);
         const int t[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ci[c][e] = t[e] < 0 ? 0 : (t[e] >= C ? C - 1 : t[e]);
+        for (int e = 0; e < 8; ++e) ci[c][e] = 2 * (t[e] < 0 ? 0 : (t[e] >= C ? C - 1 : t[e]));
     }
     __syncthreads();
 
     // ---- the rows of a step, as contiguous 16-byte pieces (piece p of a row: bytes 16p..) ----
+    // Lanes past the row's end repeat its last piece (same bytes to the same LDS address), so no
+    // load or store sits under a lane mask.
+    uint32_t offw[CPL], offs[2 * CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) offw[c] = (uint32_t)min(tid + FU_THREADS * c, nchunk - 1) * 16u;
+#pragma unroll
+    for (int c = 0; c < 2 * CPL; ++c) offs[c] = (uint32_t)min(tid + FU_THREADS * c, 2 * nchunk - 1) * 16u;
     uint4 pw[RS][CPL];
     float4 ps[RS][2 * CPL];
     auto prefetch = [&](int row) {                   // row = first row of the step inside the run
@@ -104,21 +144,15 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
             const char *srow = Sg + (int64_t)sr * pitch_s;
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
-                const int p = tid + FU_THREADS * c;
-                if (p < nchunk) {
-                    const u32x4_t v = __builtin_nontemporal_load(
-                        (const __attribute__((address_space(1))) u32x4_t *)(wrow + (uint32_t)p * 16u));
-                    pw[rs][c] = make_uint4(v.x, v.y, v.z, v.w);
-                }
+                const u32x4_t v = __builtin_nontemporal_load(
+                    (const __attribute__((address_space(1))) u32x4_t *)(wrow + offw[c]));
+                pw[rs][c] = make_uint4(v.x, v.y, v.z, v.w);
             }
 #pragma unroll
             for (int c = 0; c < 2 * CPL; ++c) {
-                const int p = tid + FU_THREADS * c;
-                if (p < 2 * nchunk) {
-                    const f32x4_t v = __builtin_nontemporal_load(
-                        (const __attribute__((address_space(1))) f32x4_t *)(srow + (uint32_t)p * 16u));
-                    ps[rs][c] = make_float4(v.x, v.y, v.z, v.w);
-                }
+                const f32x4_t v = __builtin_nontemporal_load(
+                    (const __attribute__((address_space(1))) f32x4_t *)(srow + offs[c]));
+                ps[rs][c] = make_float4(v.x, v.y, v.z, v.w);
             }
         }
     };
@@ -126,15 +160,11 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 #pragma unroll
         for (int rs = 0; rs < RS; ++rs) {
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                const int p = tid + FU_THREADS * c;
-                if (p < nchunk) *reinterpret_cast<uint4 *>(Wl + (size_t)rs * C + (size_t)p * 8) = pw[rs][c];
-            }
+            for (int c = 0; c < CPL; ++c)
+                *reinterpret_cast<uint4 *>(smem + (size_t)rs * C * 2 + offw[c]) = pw[rs][c];
 #pragma unroll
-            for (int c = 0; c < 2 * CPL; ++c) {
-                const int p = tid + FU_THREADS * c;
-                if (p < 2 * nchunk) *reinterpret_cast<float4 *>(Sl + (size_t)rs * C + (size_t)p * 4) = ps[rs][c];
-            }
+            for (int c = 0; c < 2 * CPL; ++c)
+                *reinterpret_cast<float4 *>(smem + (size_t)(RS * 2 + rs * 4) * C + offs[c]) = ps[rs][c];
         }
     };
 
@@ -145,64 +175,59 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     prefetch(0);
     for (int st = 0; st < nsteps; ++st) {
         stage();
-        __syncthreads();
+        lds_barrier();
         if (st + 1 < nsteps) prefetch((st + 1) * RS);
-
-        // pick this lane's elements out of the staged rows; item = rs * CPL + c
-        uint4 gw[NIT];
-        float gs[NIT][8];
-#pragma unroll
-        for (int rs = 0; rs < RS; ++rs) {
-#pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                const uint16_t *wl = Wl + (size_t)rs * C;
-                const float *sl = Sl + (size_t)rs * C;
-                uint32_t h[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    h[e] = wl[ci[c][e]];
-                    gs[rs * CPL + c][e] = sl[ci[c][e]];
-                }
-                gw[rs * CPL + c] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
-                                              h[6] | (h[7] << 16));
-            }
-        }
-        __syncthreads();                             // the rows may be overwritten from here on
 
         const int row = st * RS;                     // first row of the step inside the run
         const int rr0 = row & 7;
+        float last[CPL][K];
+        // items (item = rs * CPL + c) are picked out of the staged rows and scored NG at a time
 #pragma unroll
-        for (int rs = 0; rs < RS; ++rs) {
+        for (int g0 = 0; g0 < NIT; g0 += NG) {
+            uint4 gw[NG];
+            float gs[NG][8];
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) {
+            for (int g = 0; g < NG; ++g) {
+                const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
+                const uint32_t wbase = lds0 + (uint32_t)rs * (uint32_t)C * 2u;
+                const uint32_t sbase = lds0 + (uint32_t)(RS * 2 + rs * 4) * (uint32_t)C;
+                uint32_t h[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    h[e] = *(const lds_u16 *)(wbase + (uint32_t)ci[c][e]);
+                    gs[g][e] = *(const lds_f32 *)s_address<(CPL >= 4)>((uint32_t)ci[c][e], sbase);
+                }
+                gw[g] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            }
+            if (g0 + NG == NIT) lds_barrier();       // the rows may be overwritten from here on
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
                 if (valid[c]) {
                     const int64_t orow = (int64_t)(oct0 * 8 + row + rs);
-                    *reinterpret_cast<uint4 *>(wout + orow * C + (int64_t)(tid + FU_THREADS * c) * 8) =
-                        gw[rs * CPL + c];
+                    *reinterpret_cast<uint4 *>(wout + orow * C + (int64_t)(tid + FU_THREADS * c) * 8) = gw[g];
                 }
             }
-        }
-
-        float last[CPL][K];
 #pragma unroll
-        for (int i0 = 0; i0 < NIT; i0 += NI) {
-            uint4 wr[NI];
-            float s[NI][8], out[NI][K];
+            for (int i0 = 0; i0 < NG; i0 += NI) {
+                uint4 wr[NI];
+                float s[NI][8], out[NI][K];
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                wr[j] = gw[i0 + j];
+                for (int j = 0; j < NI; ++j) {
+                    wr[j] = gw[i0 + j];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) s[j][e] = gs[i0 + j][e];
+                    for (int e = 0; e < 8; ++e) s[j][e] = gs[i0 + j][e];
+                }
+                quant_cost_round<LPG, K, NI>(wr, s, dp, out);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int rs = (g0 + i0 + j) / CPL, c = (g0 + i0 + j) % CPL;
+#pragma unroll
+                    for (int k = 0; k < K; ++k)
+                        last[c][k] = octet_tree_push(out[j][k], rr0 + rs, t1[c][k], t2[c][k], t3[c][k]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            quant_cost_round<LPG, K, NI>(wr, s, dp, out);
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int rs = (i0 + j) / CPL, c = (i0 + j) % CPL;
-#pragma unroll
-                for (int k = 0; k < K; ++k)
-                    last[c][k] = octet_tree_push(out[j][k], rr0 + rs, t1[c][k], t2[c][k], t3[c][k]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
         }
 
         if (rr0 + RS == 8) {                         // an octet is complete: lanes of the group, then out
@@ -307,7 +332,7 @@ template <int LPG, int K>
 static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int64_t chunks = a.cols / 8;
-    if (chunks <= FU_THREADS) return launch_fused_g<LPG, K, 1, 2>(ctx, a);
+    if (chunks <= FU_THREADS) return launch_fused_g<LPG, K, 1, FU_RS1>(ctx, a);
     if (chunks <= 2 * FU_THREADS) return launch_fused_g<LPG, K, 2, 1>(ctx, a);
     if (chunks <= 4 * FU_THREADS) return launch_fused_g<LPG, K, 4, 1>(ctx, a);
     return SBITS_ERR_BAD_SHAPE;
