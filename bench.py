@@ -121,8 +121,9 @@ def main():
     mats = [sb.matrix(w, s) for w, s in zip(Ws, Ss)]
     row_perm = torch.empty(sum(r for _, _, r, _ in shapes), dtype=torch.int32, device=dev)
     col_perm = torch.empty(sum(c for _, _, _, c in shapes), dtype=torch.int32, device=dev)
-    w_re = torch.empty(nw, dtype=torch.bfloat16, device=dev)      # reordered matrices, concatenated
     one_pass = plan.gather_cost_supported() and not args.two_pass
+    # reordered matrices, concatenated: only the two-pass route materialises them
+    w_re = None if one_pass else torch.empty(nw, dtype=torch.bfloat16, device=dev)
     s_re = None if one_pass else torch.empty(nw, dtype=torch.float32, device=dev)
     cost = torch.empty(N, K, dtype=torch.float32, device=dev)
     level = torch.empty(N, dtype=torch.uint8, device=dev)
@@ -150,7 +151,10 @@ def main():
         rc, st, _ = plan.allocate(cost, args.budget, level, ws)
         ev[4].record()
         plan.offsets(level, byte_off, ws)
-        plan.pack_all(w_re, level, byte_off, codes, scale, zero, ws)
+        if one_pass:
+            plan.gather_pack_all(mats, row_perm, col_perm, level, byte_off, codes, scale, zero, ws)
+        else:
+            plan.pack_all(w_re, level, byte_off, codes, scale, zero, ws)
         ev[5].record()
         return rc, st
 
@@ -182,9 +186,9 @@ def main():
     cost_ms = stage_ms["cost"]
     # cost-table pass: each weight is read once as bf16 (2 B) with its fp32 sensitivity (4 B);
     # the table written is K*4 bytes per m*n weights.  The one-pass kernel also reads both
-    # permutations and writes the reordered weights (2 B per weight).
+    # permutations.
     if one_pass:
-        cost_bytes = nw * 8 + N * K * 4 + 4 * (row_perm.numel() + col_perm.numel())
+        cost_bytes = nw * 6 + N * K * 4 + 4 * (row_perm.numel() + col_perm.numel())
         kernel = "gather_cost_kernel"
         traffic = ONE_PASS_TRAFFIC_B_PER_WEIGHT * nw if (m == 128 and K == 4 and ONE_PASS_TRAFFIC_B_PER_WEIGHT) else None
     else:

@@ -165,8 +165,9 @@ int  sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *
 /* Reordering and scoring in ONE pass over the ORIGINAL matrices (paper Sec. 4.2
  * reordering followed by the Sec. 5 quantizer, as above): equivalent to
  * sbits_gather_all followed by sbits_cost_table_all, bit for bit, without writing
- * or re-reading the reordered sensitivities.  w_re (reordered weights, needed by
- * sbits_pack_all) and cost[N][K] are written.  Supported for 64- and 128-column
+ * or re-reading the reordered sensitivities.  cost[N][K] is written, and w_re
+ * (reordered weights, what sbits_pack_all reads) unless it is NULL:
+ * sbits_gather_pack_all does not need it.  Supported for 64- and 128-column
  * blocks, rows of at most 16384 elements, and source rows that start on 16-byte
  * boundaries (w_bf16, sens 16-byte aligned, ld_w % 8 == 0, ld_s % 4 == 0);
  * otherwise returns SBITS_ERR_UNIMPLEMENTED and writes nothing: use the two calls
@@ -204,15 +205,24 @@ int  sbits_pack(sbits_plan *plan, int mat, const void *w_re_bf16, const uint8_t 
 int  sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *level,
                     const int64_t *byte_off, uint8_t *codes, float *scale, float *zero, void *ws);
 
+/* The same from the ORIGINAL weights and the permutations (reordering on the fly,
+ * no reordered copy needed); identical output.  mats: HOST array, only w_bf16 /
+ * ld_w are read.  Same shape and alignment limits as sbits_gather_cost_all (w_bf16
+ * rows on 16-byte boundaries); otherwise SBITS_ERR_UNIMPLEMENTED.  Uses ws.        */
+int  sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                           const int32_t *col_perm, const uint8_t *level, const int64_t *byte_off,
+                           uint8_t *codes, float *scale, float *zero, void *ws);
+
 /* ---- the whole path in one call -------------------------------------------- */
 typedef struct {
     int32_t *row_perm;     /* concatenated over matrices: sum(rows) entries                  */
     int32_t *col_perm;     /* concatenated: sum(cols) entries                                */
     void    *w_re_bf16;    /* reordered weights, matrices concatenated, each dense           */
-    float   *s_re;         /* reordered sensitivities, same layout; written only when the    */
-                           /* one-pass route (sbits_gather_cost_all) does not apply, and     */
-                           /* may be NULL when sbits_gather_cost_supported(plan) and every   */
-                           /* matrix meets its alignment rule                                */
+    float   *s_re;         /* reordered sensitivities, same layout                           */
+                           /* Both are needed by the two-pass route only.  When              */
+                           /* sbits_gather_cost_supported(plan) and every matrix meets the   */
+                           /* alignment rule, s_re is never written and may be NULL, and     */
+                           /* w_re_bf16 is written if not NULL (costs one more HBM write).   */
     float   *cost;         /* [N][K]                                                         */
     uint8_t *level;        /* [N]                                                            */
     int64_t *byte_off;     /* [N+1]                                                          */

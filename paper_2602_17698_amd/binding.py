@@ -22,7 +22,7 @@ EXPORTS = [
     "sbits_workspace_bytes", "sbits_codes_bytes_bound",
     "sbits_reorder", "sbits_reorder_all", "sbits_channel_scores", "sbits_gather", "sbits_gather_all",
     "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
-    "sbits_gather_cost_supported", "sbits_gather_cost_all",
+    "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
     "sbits_allocate", "sbits_offsets", "sbits_pack", "sbits_search",
 ]
 
@@ -203,6 +203,12 @@ class Plan:
         arr = (Matrix * len(mats))(*mats)
         return _check(load().sbits_gather_cost_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(w_re),
                                                    _ptr(cost), _ptr(ws)), "sbits_gather_cost_all")
+
+    def gather_pack_all(self, mats, row_perm, col_perm, level, byte_off, codes, scale, zero, ws):
+        arr = (Matrix * len(mats))(*mats)
+        return _check(load().sbits_gather_pack_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(level),
+                                                   _ptr(byte_off), _ptr(codes), _ptr(scale), _ptr(zero), _ptr(ws)),
+                      "sbits_gather_pack_all")
 
     def pack_all(self, w_re, level, byte_off, codes, scale, zero, ws):
         return _check(load().sbits_pack_all(self.h, _ptr(w_re), _ptr(level), _ptr(byte_off), _ptr(codes),

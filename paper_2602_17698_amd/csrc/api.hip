@@ -289,13 +289,29 @@ int sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int3
 {
     int rc = check_all(plan, mats, true, true);
     if (rc) return rc;
-    if (!row_perm || !col_perm || !w_re_bf16 || !cost || !aligned16(col_perm) || !aligned16(w_re_bf16) || !ws_ok(ws))
+    if (!row_perm || !col_perm || !cost || !aligned16(col_perm) || !aligned16(w_re_bf16) || !ws_ok(ws))
         return SBITS_ERR_INVALID_ARG;
     if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
-    if (!sbits_fused_layout_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
+    if (!sbits_fused_layout_ok(plan, true)) return SBITS_ERR_UNIMPLEMENTED;
     return sbits_launch_gather_cost_all(plan, row_perm, col_perm, w_re_bf16, cost, ws);
+}
+
+int sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                          const int32_t *col_perm, const uint8_t *level, const int64_t *byte_off,
+                          uint8_t *codes, float *scale, float *zero, void *ws)
+{
+    int rc = check_all(plan, mats, true, false);
+    if (rc) return rc;
+    if (!row_perm || !col_perm || !level || !byte_off || !codes || !scale || !zero || !aligned16(col_perm) ||
+        !ws_ok(ws) || (reinterpret_cast<uintptr_t>(codes) & 7))
+        return SBITS_ERR_INVALID_ARG;
+    if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
+    if ((rc = need_device(plan))) return rc;
+    if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    if (!sbits_fused_layout_ok(plan, false)) return SBITS_ERR_UNIMPLEMENTED;
+    return sbits_launch_gather_pack_all(plan, row_perm, col_perm, level, byte_off, codes, scale, zero, ws);
 }
 
 int sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits, const sbits_params *params,
@@ -350,7 +366,7 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
                  const sbits_outputs *out, sbits_stats *host_stats, void *ws)
 {
     if (!plan || !mats || !params || !out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
-    if (!out->row_perm || !out->col_perm || !out->w_re_bf16 || !out->cost || !out->level ||
+    if (!out->row_perm || !out->col_perm || !out->cost || !out->level ||
         !out->byte_off || !out->codes || !out->scale || !out->zero)
         return SBITS_ERR_INVALID_ARG;
     if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
@@ -360,11 +376,12 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
     if ((rc = check_all(plan, mats, true, true))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
     if ((rc = sbits_launch_reorder_all(plan, out->row_perm, out->col_perm, ws))) return rc;
-    if (sbits_fused_shapes_ok(plan) && sbits_fused_layout_ok(plan)) {
+    const bool one_pass = sbits_fused_shapes_ok(plan) && sbits_fused_layout_ok(plan, true);
+    if (one_pass) {
         if ((rc = sbits_launch_gather_cost_all(plan, out->row_perm, out->col_perm, out->w_re_bf16, out->cost, ws)))
             return rc;
     } else {
-        if (!out->s_re) return SBITS_ERR_INVALID_ARG;
+        if (!out->s_re || !out->w_re_bf16) return SBITS_ERR_INVALID_ARG;
         if ((rc = sbits_launch_gather_all(plan, out->row_perm, out->col_perm, out->w_re_bf16, out->s_re, ws)))
             return rc;
         if ((rc = sbits_launch_cost_all(plan, out->w_re_bf16, out->s_re, out->cost, ws))) return rc;
@@ -373,9 +390,13 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
     const int alloc_rc = rc;
     if (rc && rc != SBITS_ERR_MAX_ITERS) return rc;
     if ((rc = sbits_offsets(plan, out->level, out->byte_off, ws))) return rc;
-    if ((rc = sbits_launch_pack_all(plan, out->w_re_bf16, out->level, out->byte_off, out->codes, out->scale,
-                                    out->zero, ws)))
-        return rc;
+    if (one_pass)
+        rc = sbits_launch_gather_pack_all(plan, out->row_perm, out->col_perm, out->level, out->byte_off, out->codes,
+                                          out->scale, out->zero, ws);
+    else
+        rc = sbits_launch_pack_all(plan, out->w_re_bf16, out->level, out->byte_off, out->codes, out->scale,
+                                   out->zero, ws);
+    if (rc) return rc;
     SBITS_HIP(plan->ctx, hipStreamSynchronize(plan->ctx->stream));
     return alloc_rc;
 }

@@ -22,6 +22,7 @@
 #include <vector>
 
 #include "cost_core.hpp"
+#include "pack_core.hpp"
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
 
@@ -203,9 +204,16 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
                 const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
-                if (valid[c]) {
+#ifdef FU_NOSTORE
+                if (valid[c] && gw[g].x == 0x12345678u) {
+#else
+                if (valid[c] && w_re_all) {
+#endif
                     const int64_t orow = (int64_t)(oct0 * 8 + row + rs);
-                    *reinterpret_cast<uint4 *>(wout + orow * C + (int64_t)(tid + FU_THREADS * c) * 8) = gw[g];
+                    u32x4_t sv;
+                    sv.x = gw[g].x; sv.y = gw[g].y; sv.z = gw[g].z; sv.w = gw[g].w;
+                    __builtin_nontemporal_store(sv, (__attribute__((address_space(1))) u32x4_t *)(
+                                                        wout + orow * C + (int64_t)(tid + FU_THREADS * c) * 8));
                 }
             }
 #pragma unroll
@@ -218,7 +226,16 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 #pragma unroll
                     for (int e = 0; e < 8; ++e) s[j][e] = gs[i0 + j][e];
                 }
+#ifdef FU_NOCOMPUTE
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int k = 0; k < K; ++k)
+                        out[j][k] = __uint_as_float(wr[j].x ^ wr[j].y ^ wr[j].z ^ wr[j].w) + s[j][0] + s[j][1] + s[j][2] +
+                                    s[j][3] + s[j][4] + s[j][5] + s[j][6] + s[j][7];
+#else
                 quant_cost_round<LPG, K, NI>(wr, s, dp, out);
+#endif
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
                     const int rs = (g0 + i0 + j) / CPL, c = (g0 + i0 + j) % CPL;
@@ -299,6 +316,168 @@ void octet_finish_kernel(const float *__restrict__ part, int64_t NK, int K, int 
     cost[q] = v;
 }
 
+// ================================================================ gather + pack
+// The packing stage on the ORIGINAL weights: a workgroup owns a run of octets of one matrix,
+// stages RS source rows per step in LDS like the kernel above (weights only), and every lane
+// re-quantizes its chunks at the bitwidth chosen for their block.  The codes of a lane group's
+// RS rows are consecutive in the block's stream: they are collected in a per-group LDS strip
+// (written and read by lanes of one wave only) and leave as 32-bit words.
+// T threads per workgroup; launch bounds ask for 4 waves per SIMD (two workgroups of 512 or one
+// of 1024 per CU), which the kernel's ~120 registers allow.
+template <int LPG, int CPL, int RS, int T>
+__global__ __launch_bounds__(T, 4)
+void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
+                        const int *__restrict__ wg_start, int n_members,
+                        const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
+                        const uint8_t *__restrict__ level, const int64_t *__restrict__ byte_off,
+                        uint8_t *__restrict__ codes, float *__restrict__ scale, float *__restrict__ zero,
+                        GridConsts gc, int cmax)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int rowsrc[FU_OPU * 8];
+    constexpr int NIT = RS * CPL;
+    static_assert(8 % RS == 0, "step shape");
+
+    const int tid = (int)threadIdx.x;
+    const int lig = tid % LPG;
+    const bool odd = (lig & 1) != 0;
+    const int mem = funi(find_matrix(wg_start, n_members, (int)blockIdx.x));
+    const MatDesc &d = descs[funi(members[mem])];
+    const int R = funi((int)d.rows), C = funi((int)d.cols) & ~7;
+    const int nbc = funi(d.nbc);
+    const int opb = m >> 3;
+    const int oct0 = ((int)blockIdx.x - funi(wg_start[mem])) * FU_OPU;
+    const int noct = min(FU_OPU, (R >> 3) - oct0);
+    const int32_t *__restrict__ rp = row_perm + d.row_off;
+    const int32_t *__restrict__ cp = col_perm + d.col_off;
+    const char *const Wg = reinterpret_cast<const char *>(d.w);
+    const int64_t pitch_w = d.ld_w * 2;
+    const int64_t block_base = d.block_base;
+
+    // LDS: weights [RS][C] bf16, then one strip of RS * LPG * cmax bytes per (lane group, chunk)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const int strip = RS * LPG * cmax;
+
+    for (int i = tid; i < noct * 8; i += T) {
+        int sr = rp[oct0 * 8 + i];
+        rowsrc[i] = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);
+    }
+    const int nchunk = C >> 3;
+    int ci[CPL][8];
+    bool valid[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const int chunk = tid + T * c;
+        valid[c] = chunk < nchunk;
+        const int cb = valid[c] ? chunk * 8 : 0;
+        const int4 a = *reinterpret_cast<const int4 *>(cp + cb);
+        const int4 b = *reinterpret_cast<const int4 *>(cp + cb + 4);
+        const int t[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ci[c][e] = 2 * (t[e] < 0 ? 0 : (t[e] >= C ? C - 1 : t[e]));
+    }
+    __syncthreads();
+
+    uint32_t offw[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) offw[c] = (uint32_t)min(tid + T * c, nchunk - 1) * 16u;
+    uint4 pw[RS][CPL];
+    auto prefetch = [&](int row) {
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
+            const int sr = funi(rowsrc[row + rs]);
+            const char *wrow = Wg + (int64_t)sr * pitch_w;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const u32x4_t v = __builtin_nontemporal_load(
+                    (const __attribute__((address_space(1))) u32x4_t *)(wrow + offw[c]));
+                pw[rs][c] = make_uint4(v.x, v.y, v.z, v.w);
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs)
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+                *reinterpret_cast<uint4 *>(smem + (size_t)rs * C * 2 + offw[c]) = pw[rs][c];
+    };
+
+    // per chunk: the block it falls in (fixed column, block row changes every opb octets)
+    int curI = -1;
+    LevelConsts lk[CPL];
+    int64_t gb[CPL];
+    uint8_t *dst[CPL];
+    const int nsteps = noct * (8 / RS);
+
+    prefetch(0);
+    for (int st = 0; st < nsteps; ++st) {
+        stage();
+        lds_barrier();
+        if (st + 1 < nsteps) prefetch((st + 1) * RS);
+
+        const int row = st * RS;
+        const int og = oct0 + (row >> 3);
+        const int I = og / opb;
+        const int rib = (og - I * opb) * 8 + (row & 7);         // first row of the step inside its block
+        if (I != curI) {
+            curI = I;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int J = min((tid + T * c) / LPG, nbc - 1);
+                gb[c] = block_base + (int64_t)I * nbc + J;
+                lk[c] = level_consts(gc, level[gb[c]]);
+                dst[c] = codes + byte_off[gb[c]];
+            }
+        }
+
+        uint4 gw[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int rs = it / CPL, c = it % CPL;
+            uint32_t wbase = lds0 + (uint32_t)rs * (uint32_t)C * 2u;
+            asm volatile("" : "+s"(wbase));          // keeps the 8 sums below out of loop-invariant registers
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = *(const lds_u16 *)(wbase + (uint32_t)ci[c][e]);
+            gw[it] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        }
+        lds_barrier();                               // the rows may be overwritten from here on
+
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const int cb = lk[c].c;
+            const int row_bytes = LPG * cb;
+            unsigned char *strip0 = smem + (size_t)RS * C * 2 + (size_t)((tid / LPG) + (T / LPG) * c) * strip;
+#pragma unroll
+            for (int rs = 0; rs < RS; ++rs) {
+                float scl, mn;
+                const unsigned long long word = quant_pack_row<LPG>(gw[rs * CPL + c], lk[c], odd, scl, mn);
+                unsigned char *mine = strip0 + rs * row_bytes + lig * cb;
+                store_code_bytes(mine, word, cb);
+                if (valid[c] && lig == 0) {
+                    const int64_t ri = gb[c] * m + rib + rs;
+                    scale[ri] = scl;
+                    zero[ri] = mn + 0.0f;
+                }
+                __builtin_amdgcn_sched_barrier(0);   // one row at a time: interleaving only costs registers
+            }
+            // the strip is private to this lane group (one wave): LDS keeps a wave's operations in order
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (valid[c]) {
+                const int nwords = RS * row_bytes / 4;           // row_bytes is a multiple of 8
+                const uint32_t *s32 = reinterpret_cast<const uint32_t *>(strip0);
+                uint32_t *d32 = reinterpret_cast<uint32_t *>(dst[c] + (int64_t)rib * row_bytes);
+                for (int k = lig; k < nwords; k += LPG) d32[k] = s32[k];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
 struct FusedLaunch {
     const MatDesc *descs;
     const int *members, *wg_start;
@@ -354,6 +533,49 @@ static int launch_fused_l(int K, sbits_ctx *ctx, const FusedLaunch &a)
     return SBITS_ERR_BAD_BITWIDTHS;
 }
 
+struct FusedPackLaunch {
+    const MatDesc *descs;
+    const int *members, *wg_start;
+    int n_members, total_wg;
+    const int32_t *row_perm, *col_perm;
+    int m;
+    const uint8_t *level;
+    const int64_t *byte_off;
+    uint8_t *codes;
+    float *scale, *zero;
+    GridConsts gc;
+    int cmax;
+    int64_t cols;
+};
+
+template <int LPG, int CPL, int RS, int T>
+static int launch_gpack_g(sbits_ctx *ctx, const FusedPackLaunch &a)
+{
+    static bool attr_done = false;
+    auto *fn = &gather_pack_kernel<LPG, CPL, RS, T>;
+    if (!attr_done) {
+        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
+        attr_done = true;
+    }
+    const size_t lds = (size_t)RS * a.cols * 2 + (size_t)RS * CPL * T * a.cmax;
+    hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
+                       a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.level, a.byte_off, a.codes, a.scale,
+                       a.zero, a.gc, a.cmax);
+    SBITS_HIP(ctx, hipGetLastError());
+    return SBITS_OK;
+}
+
+template <int LPG>
+static int launch_gpack_l(sbits_ctx *ctx, const FusedPackLaunch &a)
+{
+    const int64_t chunks = a.cols / 8;
+    if (chunks <= 512) return launch_gpack_g<LPG, 1, 4, 512>(ctx, a);
+    if (chunks <= 1024) return launch_gpack_g<LPG, 2, 2, 512>(ctx, a);
+    if (chunks <= 2048) return launch_gpack_g<LPG, 2, 2, 1024>(ctx, a);
+    return SBITS_ERR_BAD_SHAPE;
+}
+
 }  // namespace sbits
 
 using namespace sbits;
@@ -373,26 +595,21 @@ size_t sbits_fused_ws_bytes(const sbits_plan *plan)
 }
 
 // every source row must start on a 16-byte boundary (the rows are staged with 128-bit loads)
-bool sbits_fused_layout_ok(const sbits_plan *plan)
+bool sbits_fused_layout_ok(const sbits_plan *plan, bool need_s)
 {
     for (int i = 0; i < plan->n_mats; ++i) {
         const MatDesc &d = plan->descs[i];
-        if ((reinterpret_cast<uintptr_t>(d.w) & 15) || (reinterpret_cast<uintptr_t>(d.s) & 15) || (d.ld_w & 7) ||
-            (d.ld_s & 3))
-            return false;
+        if ((reinterpret_cast<uintptr_t>(d.w) & 15) || (d.ld_w & 7)) return false;
+        if (need_s && ((reinterpret_cast<uintptr_t>(d.s) & 15) || (d.ld_s & 3))) return false;
     }
     return true;
 }
 
-// One launch per class of matrices with equal column count (equal LDS need, equal chunks per
-// lane); the descriptor table is already in the workspace head.
-//   slot 3 of the workspace head: members of all classes, class after class
-//   slot 4: workgroup prefixes, n_k + 1 entries per class
-int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
-                                 void *w_re, float *cost, void *ws)
+// matrices grouped by column count; members and workgroup prefixes go to slots 3 and 4 of the
+// workspace head (the tables depend on shapes only: built once, kept in the plan)
+static int fused_classes(sbits_plan *plan, void *ws, int **d_mem, int **d_pre)
 {
     sbits_ctx *ctx = plan->ctx;
-    if (!sbits_fused_shapes_ok(plan) || !sbits_fused_layout_ok(plan)) return SBITS_ERR_BAD_SHAPE;
     if (plan->fused_members.empty()) {
         std::vector<int64_t> classes;
         for (int i = 0; i < plan->n_mats; ++i) {
@@ -414,17 +631,33 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
                 t += (plan->rows[i] / 8 + FU_OPU - 1) / FU_OPU;
                 ++fc.n;
             }
-            if (t > 0x7fffffff) { plan->fused_members.clear(); plan->fused_pre.clear(); return SBITS_ERR_BAD_SHAPE; }
+            if (t > 0x7fffffff) {
+                plan->fused_members.clear(); plan->fused_pre.clear(); plan->fused_classes.clear();
+                return SBITS_ERR_BAD_SHAPE;
+            }
             plan->fused_pre.push_back((int)t);
             plan->fused_classes.push_back(fc);
         }
     }
-    int *d_mem = sbits_prefix_ptr(plan, ws, 3);
-    int *d_pre = sbits_prefix_ptr(plan, ws, 4);
-    SBITS_HIP(ctx, hipMemcpyAsync(d_mem, plan->fused_members.data(), plan->fused_members.size() * 4,
+    *d_mem = sbits_prefix_ptr(plan, ws, 3);
+    *d_pre = sbits_prefix_ptr(plan, ws, 4);
+    SBITS_HIP(ctx, hipMemcpyAsync(*d_mem, plan->fused_members.data(), plan->fused_members.size() * 4,
                                   hipMemcpyHostToDevice, ctx->stream));
-    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, plan->fused_pre.data(), plan->fused_pre.size() * 4,
+    SBITS_HIP(ctx, hipMemcpyAsync(*d_pre, plan->fused_pre.data(), plan->fused_pre.size() * 4,
                                   hipMemcpyHostToDevice, ctx->stream));
+    return SBITS_OK;
+}
+
+// One launch per class of matrices with equal column count (equal LDS need, equal chunks per
+// lane); the descriptor table is already in the workspace head.  w_re may be null.
+int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                                 void *w_re, float *cost, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    if (!sbits_fused_shapes_ok(plan) || !sbits_fused_layout_ok(plan, true)) return SBITS_ERR_BAD_SHAPE;
+    int *d_mem, *d_pre;
+    int rc0 = fused_classes(plan, ws, &d_mem, &d_pre);
+    if (rc0) return rc0;
     FusedLaunch a;
     memset(&a, 0, sizeof a);
     sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
@@ -449,6 +682,38 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
         hipLaunchKernelGGL(octet_finish_kernel, dim3((unsigned)((NK + 255) / 256)), dim3(256), 0, ctx->stream,
                            a.part, NK, plan->K, plan->m / 8, cost);
         SBITS_HIP(ctx, hipGetLastError());
+    }
+    return SBITS_OK;
+}
+
+// the packing stage on the original weights, one launch per class
+int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                                 const uint8_t *level, const int64_t *byte_off, uint8_t *codes, float *scale,
+                                 float *zero, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    if (!sbits_fused_shapes_ok(plan) || !sbits_fused_layout_ok(plan, false)) return SBITS_ERR_BAD_SHAPE;
+    int *d_mem, *d_pre;
+    int rc0 = fused_classes(plan, ws, &d_mem, &d_pre);
+    if (rc0) return rc0;
+    FusedPackLaunch a;
+    memset(&a, 0, sizeof a);
+    sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
+    a.descs = sbits_desc_ptr(ws);
+    a.row_perm = row_perm;
+    a.col_perm = col_perm;
+    a.m = plan->m;
+    a.level = level; a.byte_off = byte_off; a.codes = codes; a.scale = scale; a.zero = zero;
+    a.cmax = plan->bits[plan->K - 1];
+    for (const sbits_plan::FusedClass &fc : plan->fused_classes) {
+        a.members = d_mem + fc.first;
+        a.wg_start = d_pre + fc.pre_first;
+        a.n_members = fc.n;
+        a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
+        a.cols = fc.cols;
+        if (a.total_wg == 0) continue;
+        const int rc = plan->n == 64 ? launch_gpack_l<8>(ctx, a) : launch_gpack_l<16>(ctx, a);
+        if (rc) return rc;
     }
     return SBITS_OK;
 }

@@ -10,6 +10,7 @@
 //           a row stage their bytes in LDS and the row is written out as dwords.
 #include <string.h>
 
+#include "pack_core.hpp"
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
 
@@ -142,13 +143,8 @@ void pack_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
     const bool valid = J < d.nbc;
     const int Jc = valid ? J : d.nbc - 1;
     const int64_t gb = d.block_base + (int64_t)I * d.nbc + Jc;   // global block id
-    const int lv = level[gb];
-    int c = gc.bits[0];
-    float qf = gc.qmaxf[0], th = gc.thr[0];
-#pragma unroll
-    for (int cc = 1; cc < 8; ++cc)
-        if (lv == cc) { c = gc.bits[cc]; qf = gc.qmaxf[cc]; th = gc.thr[cc]; }
-    const unsigned int qmax = (unsigned int)qf;
+    const LevelConsts lk = level_consts(gc, level[gb]);
+    const int c = lk.c;
 
     const uint16_t *__restrict__ src = W + d.elem_off + ((int64_t)I * m + (int64_t)o * 8) * d.cols +
                                        (int64_t)Jc * (LPG * 8) + lig * 8;
@@ -160,32 +156,10 @@ void pack_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
     const bool odd = (lig & 1) != 0;                 // even lanes divide qmax/R, odd lanes R/qmax
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr) {
-        float w[8];
-        unpack8(raw[rr], w);
-        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
-        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
-        mn = group_allreduce<LPG>(mn, OpMin{});
-        mx = group_allreduce<LPG>(mx, OpMax{});
-        const float R = mx - mn;
-        float inv, scl;
-        if (LPG >= 2) {
-            float v = (odd ? R : qf) / (odd ? qf : R);
-            if (R < th) v = 0.0f;
-            inv = group_bcast<LPG, 0>(v);
-            scl = group_bcast<LPG, 1 % LPG>(v);
-        } else {
-            inv = qf / R; scl = R / qf;
-            if (R < th) { inv = 0.0f; scl = 0.0f; }
-        }
-        unsigned long long word = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            unsigned int q = (unsigned int)(int)rintf((w[e] - mn) * inv);
-            q = q > qmax ? qmax : q;
-            word |= (unsigned long long)q << (e * c);
-        }
+        float scl, mn;
+        const unsigned long long word = quant_pack_row<LPG>(raw[rr], lk, odd, scl, mn);
         uint8_t *mine = &stage[g][rr * row_bytes + lig * c];
-        for (int t = 0; t < c; ++t) mine[t] = (uint8_t)(word >> (8 * t));
+        store_code_bytes(mine, word, c);
         if (valid && lig == 0) {
             const int64_t ri = gb * m + o * 8 + rr;
             scale[ri] = scl;

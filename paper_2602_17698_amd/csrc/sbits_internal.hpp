@@ -89,10 +89,13 @@ int sbits_upload_descs(sbits_plan *plan, const sbits_matrix *mats, void *ws);
 int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re, float *cost, void *ws);
 // gather fused with the cost table (reads the original matrices once; writes w_re and cost)
 bool sbits_fused_shapes_ok(const sbits_plan *plan);
-bool sbits_fused_layout_ok(const sbits_plan *plan);
+bool sbits_fused_layout_ok(const sbits_plan *plan, bool need_s);
 size_t sbits_fused_ws_bytes(const sbits_plan *plan);
 int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                                  void *w_re, float *cost, void *ws);
+int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                                 const uint8_t *level, const int64_t *byte_off, uint8_t *codes, float *scale,
+                                 float *zero, void *ws);
 int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
                        const sbits_params *prm, uint8_t *level, sbits_stats *host_stats,
                        sbits_trace *host_trace, int64_t trace_cap, void *ws);

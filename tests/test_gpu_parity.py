@@ -251,6 +251,41 @@ def test_gather_cost_one_pass(orc, ctx, dev, shapes, m, n, bits):
     plan.close()
 
 
+@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES)
+def test_gather_pack_one_pass(orc, ctx, dev, shapes, m, n, bits):
+    """Packing straight from the original weights and the permutations == oracle gather + pack."""
+    say("one-pass gather+pack", shapes, m, n, bits)
+    plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
+    N = plan.num_blocks()
+    mats = [synth.make_matrix("student_t", r, c, seed=12, tid=i) for i, (r, c) in enumerate(shapes)]
+    g = torch.Generator().manual_seed(19)
+    rps = [torch.randperm(r, generator=g).to(torch.int32) for r, _ in shapes]
+    cps = [torch.randperm(c, generator=g).to(torch.int32) for _, c in shapes]
+    rng = np.random.default_rng(N)
+    level = rng.integers(0, len(bits), size=N).astype(np.uint8)
+    off = orc.offsets(level, m, n, bits)
+    total = int(off[-1])
+    dW = [W.to(dev) for W, _ in mats]
+    codes_d = torch.full((total,), 0x55, dtype=torch.uint8, device=dev)
+    scale_d = torch.full((N * m,), -1.0, dtype=torch.float32, device=dev)
+    zero_d = torch.full((N * m,), -1.0, dtype=torch.float32, device=dev)
+    plan.gather_pack_all([sb.matrix(w, None) for w in dW], torch.cat(rps).to(dev), torch.cat(cps).to(dev),
+                         torch.from_numpy(level).to(dev), torch.from_numpy(off).to(dev), codes_d, scale_d, zero_d, ws)
+    torch.cuda.synchronize()
+    codes = np.full(total, 0x55, np.uint8)
+    scale = np.full(N * m, -1.0, np.float32)
+    zero = np.full(N * m, -1.0, np.float32)
+    base = 0
+    for (R, C), (W, S), rp, cp in zip(shapes, mats, rps, cps):
+        Wp, _ = orc.gather(to_np_bf16(W), S.numpy(), rp.numpy(), cp.numpy())
+        orc.pack(Wp, m, n, bits, level, off, base, codes, scale, zero)
+        base += (R // m) * (C // n)
+    np.testing.assert_array_equal(codes_d.cpu().numpy(), codes)
+    np.testing.assert_array_equal(scale_d.cpu().numpy(), scale)
+    np.testing.assert_array_equal(zero_d.cpu().numpy().view(np.uint32), zero.view(np.uint32))
+    plan.close()
+
+
 def test_gather_cost_one_pass_refuses_other_shapes(ctx, dev):
     say("one-pass refuses")
     plan, ws = make_plan(ctx, [(64, 256)], 32, 256, [2, 4], dev)     # 256-column blocks: two-pass route only
