@@ -24,7 +24,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per weight of the cost kernel from rocprofv3 counters (FETCH_SIZE x 2.000 and WRITE_SIZE
 # x 1.000 after calibration against a plain 1 GiB copy; profiles/hbm_traffic_8_layers_pmc.md)
 COST_TRAFFIC_B_PER_WEIGHT = (5114570 * 2.0 + 1664) * 1024 / 1744830464
-ONE_PASS_TRAFFIC_B_PER_WEIGHT = None   # not measured yet
+# the same for the one-pass stage: both gather_cost launches + octet_finish
+ONE_PASS_TRAFFIC_B_PER_WEIGHT = ((3739337 + 1380016 + 13334) * 2.0 + 20593 + 7839 + 1664) * 1024 / 1744830464
 
 
 def parse():

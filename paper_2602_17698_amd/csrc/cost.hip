@@ -63,9 +63,6 @@ struct HalfBuf {
 // every other 16 bytes of 2 KiB.  With SWIZZLE the wave instead loads its 2 KiB run as two
 // fully contiguous 1 KiB instructions (lane l takes bytes 16 l and 1024 + 16 l of the run, byte
 // offsets soA / soB) and the lanes exchange the values through LDS before use (swizzle_s).
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
 template <bool SWIZZLE>
 __device__ __forceinline__ void load_half(HalfBuf &h, const char *__restrict__ Wb, const char *__restrict__ Sb,
                                           uint32_t woff, uint32_t wstride, uint32_t soA, uint32_t soB)
@@ -76,18 +73,12 @@ __device__ __forceinline__ void load_half(HalfBuf &h, const char *__restrict__ W
         const uint32_t wo = woff + (uint32_t)j * wstride;
         const uint32_t oa = SWIZZLE ? soA + 2u * (uint32_t)j * wstride : 2u * wo;
         const uint32_t ob = SWIZZLE ? soB + 2u * (uint32_t)j * wstride : 2u * wo + 16u;
-#ifndef SBITS_COST_NO_NT
         const u32x4_t tw = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(Wb + wo));
         const f32x4_t ta = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(Sb + oa));
         const f32x4_t tb = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(Sb + ob));
         h.w[j] = make_uint4(tw.x, tw.y, tw.z, tw.w);
         h.s0[j] = make_float4(ta.x, ta.y, ta.z, ta.w);
         h.s1[j] = make_float4(tb.x, tb.y, tb.z, tb.w);
-#else
-        h.w[j] = *reinterpret_cast<const uint4 *>(Wb + wo);
-        h.s0[j] = *reinterpret_cast<const float4 *>(Sb + oa);
-        h.s1[j] = *reinterpret_cast<const float4 *>(Sb + ob);
-#endif
     }
 }
 
@@ -117,19 +108,6 @@ __device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG
 {
     using DP = DivPlan<LPG, K>;
     constexpr int RP = DP::RP < HALF ? DP::RP : HALF;
-#ifdef SBITS_COST_LOADONLY
-    {
-        float acc = 0.0f;
-#pragma unroll
-        for (int j = 0; j < HALF; ++j)
-            acc += __uint_as_float(h.w[j].x ^ h.w[j].y ^ h.w[j].z ^ h.w[j].w) + h.s0[j].x + h.s0[j].y + h.s0[j].z +
-                   h.s0[j].w + h.s1[j].x + h.s1[j].y + h.s1[j].z + h.s1[j].w;
-#pragma unroll
-        for (int c = 0; c < K; ++c) cur[c] = (R_BASE ? cur[c] : 0.0f) + acc;
-        (void)t1; (void)t2; (void)t3; (void)dp;
-        return;
-    }
-#endif
 #pragma unroll
     for (int r0 = 0; r0 < HALF; r0 += RP) {
         uint4 wr[RP];
@@ -183,11 +161,7 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
 {
     using G = CostGeom<LPG>;
     constexpr int BX = G::BX, OS = G::OS;
-#ifdef SBITS_COST_NO_SWIZZLE
-    constexpr bool SWZ = false;
-#else
     constexpr bool SWZ = G::OW == 1;                 // a wave walks ONE octet: 512 contiguous columns per row
-#endif
     __shared__ float osum[BX * 128 * K];             // [block in unit][octet][candidate]
     __shared__ float4 xbuf[SWZ ? 4 * HALF * 128 : 1];    // per wave: HALF rows of 2 KiB for the lane exchange
 

@@ -30,9 +30,8 @@ void sbits_fill_grid_consts(const int32_t *bits, int K, sbits::GridConsts *gc);
 
 namespace sbits {
 
-constexpr int FU_THREADS = 512;
 constexpr int FU_OPU = 16;                          // octets per workgroup (128 output rows)
-constexpr int FU_MAX_COLS = 4 * FU_THREADS * 8;     // widest row the kernel stages (CPL = 4)
+constexpr int FU_MAX_COLS = 16384;                  // widest row the kernels stage (2048 chunks)
 
 __device__ __forceinline__ int funi(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -61,14 +60,8 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-#ifndef FU_RS1
-#define FU_RS1 2
-#endif
-#ifndef FU_MINWG
-#define FU_MINWG 1
-#endif
-template <int LPG, int K, int CPL, int RS>
-__global__ __launch_bounds__(FU_THREADS, (CPL == 1 ? FU_MINWG : 1))
+template <int LPG, int K, int CPL, int RS, int T>
+__global__ __launch_bounds__(T, (T >= 1024 ? 4 : 2))
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
@@ -104,7 +97,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     dp.init(gc, lig);
 
     // source rows of the run (a permutation never trips the clamp; it keeps a bad one in bounds)
-    for (int i = tid; i < noct * 8; i += FU_THREADS) {
+    for (int i = tid; i < noct * 8; i += T) {
         int sr = rp[oct0 * 8 + i];
         rowsrc[i] = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);
     }
@@ -116,7 +109,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     bool valid[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
-        const int chunk = tid + FU_THREADS * c;
+        const int chunk = tid + T * c;
         valid[c] = chunk < nchunk;
         const int cb = valid[c] ? chunk * 8 : 0;
         const int4 a = *reinterpret_cast<const int4 *>(cp + cb);
@@ -132,9 +125,9 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     // load or store sits under a lane mask.
     uint32_t offw[CPL], offs[2 * CPL];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) offw[c] = (uint32_t)min(tid + FU_THREADS * c, nchunk - 1) * 16u;
+    for (int c = 0; c < CPL; ++c) offw[c] = (uint32_t)min(tid + T * c, nchunk - 1) * 16u;
 #pragma unroll
-    for (int c = 0; c < 2 * CPL; ++c) offs[c] = (uint32_t)min(tid + FU_THREADS * c, 2 * nchunk - 1) * 16u;
+    for (int c = 0; c < 2 * CPL; ++c) offs[c] = (uint32_t)min(tid + T * c, 2 * nchunk - 1) * 16u;
     uint4 pw[RS][CPL];
     float4 ps[RS][2 * CPL];
     auto prefetch = [&](int row) {                   // row = first row of the step inside the run
@@ -182,38 +175,45 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         const int row = st * RS;                     // first row of the step inside the run
         const int rr0 = row & 7;
         float last[CPL][K];
-        // items (item = rs * CPL + c) are picked out of the staged rows and scored NG at a time
+        // Items (item = rs * CPL + c) are picked out of the staged rows: all LDS reads are issued
+        // here; the items are scored NG at a time, so the reads of the later ones complete under
+        // the arithmetic of the earlier ones.
+        uint4 gwa[NIT];
+        float gsa[NIT][8];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int rs = it / CPL, c = it % CPL;
+            const uint32_t wbase = lds0 + (uint32_t)rs * (uint32_t)C * 2u;
+            const uint32_t sbase = lds0 + (uint32_t)(RS * 2 + rs * 4) * (uint32_t)C;
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                h[e] = *(const lds_u16 *)(wbase + (uint32_t)ci[c][e]);
+                gsa[it][e] = *(const lds_f32 *)s_address<(CPL >= 4)>((uint32_t)ci[c][e], sbase);
+            }
+            gwa[it] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        }
 #pragma unroll
         for (int g0 = 0; g0 < NIT; g0 += NG) {
+            // every read has completed before the last group: the rows may be overwritten from here on
+            if (g0 + NG == NIT) lds_barrier();
             uint4 gw[NG];
             float gs[NG][8];
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
-                const uint32_t wbase = lds0 + (uint32_t)rs * (uint32_t)C * 2u;
-                const uint32_t sbase = lds0 + (uint32_t)(RS * 2 + rs * 4) * (uint32_t)C;
-                uint32_t h[8];
+                gw[g] = gwa[g0 + g];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    h[e] = *(const lds_u16 *)(wbase + (uint32_t)ci[c][e]);
-                    gs[g][e] = *(const lds_f32 *)s_address<(CPL >= 4)>((uint32_t)ci[c][e], sbase);
-                }
-                gw[g] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+                for (int e = 0; e < 8; ++e) gs[g][e] = gsa[g0 + g][e];
             }
-            if (g0 + NG == NIT) lds_barrier();       // the rows may be overwritten from here on
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
                 const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
-#ifdef FU_NOSTORE
-                if (valid[c] && gw[g].x == 0x12345678u) {
-#else
                 if (valid[c] && w_re_all) {
-#endif
                     const int64_t orow = (int64_t)(oct0 * 8 + row + rs);
                     u32x4_t sv;
                     sv.x = gw[g].x; sv.y = gw[g].y; sv.z = gw[g].z; sv.w = gw[g].w;
                     __builtin_nontemporal_store(sv, (__attribute__((address_space(1))) u32x4_t *)(
-                                                        wout + orow * C + (int64_t)(tid + FU_THREADS * c) * 8));
+                                                        wout + orow * C + (int64_t)(tid + T * c) * 8));
                 }
             }
 #pragma unroll
@@ -226,16 +226,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 #pragma unroll
                     for (int e = 0; e < 8; ++e) s[j][e] = gs[i0 + j][e];
                 }
-#ifdef FU_NOCOMPUTE
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-#pragma unroll
-                    for (int k = 0; k < K; ++k)
-                        out[j][k] = __uint_as_float(wr[j].x ^ wr[j].y ^ wr[j].z ^ wr[j].w) + s[j][0] + s[j][1] + s[j][2] +
-                                    s[j][3] + s[j][4] + s[j][5] + s[j][6] + s[j][7];
-#else
                 quant_cost_round<LPG, K, NI>(wr, s, dp, out);
-#endif
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
                     const int rs = (g0 + i0 + j) / CPL, c = (g0 + i0 + j) % CPL;
@@ -256,7 +247,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 #pragma unroll
                 for (int k = 0; k < K; ++k) v[k] = group_allreduce<LPG>(last[c][k], OpAdd{});
                 if (lig == 0 && valid[c]) {
-                    const int J = (tid + FU_THREADS * c) / LPG;
+                    const int J = (tid + T * c) / LPG;
                     float *dst = part + ((d.block_base + (int64_t)I * nbc + J) * opb + oib) * K;
 #pragma unroll
                     for (int k = 0; k < K; ++k) dst[k] = v[k];
@@ -490,18 +481,18 @@ struct FusedLaunch {
     int64_t cols;
 };
 
-template <int LPG, int K, int CPL, int RS>
+template <int LPG, int K, int CPL, int RS, int T>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
     static bool attr_done = false;
-    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS>;
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, T>;
     if (!attr_done) {
         SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
         attr_done = true;
     }
     const size_t lds = (size_t)RS * a.cols * 6;
-    hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(FU_THREADS), lds, ctx->stream, a.descs, a.members,
+    hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
@@ -511,9 +502,9 @@ template <int LPG, int K>
 static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int64_t chunks = a.cols / 8;
-    if (chunks <= FU_THREADS) return launch_fused_g<LPG, K, 1, FU_RS1>(ctx, a);
-    if (chunks <= 2 * FU_THREADS) return launch_fused_g<LPG, K, 2, 1>(ctx, a);
-    if (chunks <= 4 * FU_THREADS) return launch_fused_g<LPG, K, 4, 1>(ctx, a);
+    if (chunks <= 512) return launch_fused_g<LPG, K, 1, 2, 512>(ctx, a);
+    if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512>(ctx, a);
+    if (chunks <= 2048) return launch_fused_g<LPG, K, 4, 1, 512>(ctx, a);
     return SBITS_ERR_BAD_SHAPE;
 }
 
