@@ -227,6 +227,7 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
         long long c = job->cnt_above, w = job->w_above;
         const long long cmax = job->cnt_max, wmax = job->w_max;
         int boundary = -1;
+        long long boundary_cnt = 0;
         // bins in descending order: whole groups while they fit, then bin by bin inside the first that does not
         for (int g = AL_THREADS - 1; g >= 0 && boundary < 0; --g) {
             if (!gcnt[g]) continue;
@@ -235,7 +236,7 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
                 const long long bc = hc[b], bw = hw[b];
                 if (!bc) continue;
                 if (c + bc <= cmax && w + bw <= wmax) { c += bc; w += bw; }
-                else { boundary = b; break; }
+                else { boundary = b; boundary_cnt = bc; break; }
             }
         }
         if (boundary < 0) {
@@ -246,9 +247,10 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
         } else {
             const unsigned long long np = (prefix << SEL_DB) | (unsigned long long)boundary;
             job->cnt_above = c; job->w_above = w;
-            if (pass == P - 1) {
-                // a single key that does not fit: select the keys strictly above it
-                job->tau = (np + 1) << 8;
+            if (pass == P - 1 || boundary_cnt == 1) {
+                // a single key that does not fit (its remaining digits do not matter): select the
+                // keys strictly above its bucket
+                job->tau = ((np + 1) << sh_digit) << 8;
                 job->n_sel = c; job->w_sel = w; job->resolved = 1;
             } else {
                 job->prefix = np;
