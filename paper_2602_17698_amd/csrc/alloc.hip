@@ -220,7 +220,25 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
         hw[b] = __hip_atomic_exchange(&job->hist_w[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         gc += hc[b]; gw += hw[b];
     }
-    gcnt[threadIdx.x] = gc; gwgt[threadIdx.x] = gw;
+    // suffix sums over the groups (descending order = from the last group down): group t fits whole,
+    // given that everything above it does, iff the sums down to t stay in bounds; the sums grow
+    // downwards, so the groups that fit are the top ones
+    __shared__ int first_fail;
+    const int t = threadIdx.x;
+    gcnt[t] = gc; gwgt[t] = gw;
+    if (t == 0) first_fail = -1;
+    __syncthreads();
+    for (int off = 1; off < AL_THREADS; off <<= 1) {
+        const long long ac = t + off < AL_THREADS ? gcnt[t + off] : 0;
+        const long long aw = t + off < AL_THREADS ? gwgt[t + off] : 0;
+        __syncthreads();
+        gcnt[t] += ac; gwgt[t] += aw;
+        __syncthreads();
+    }
+    {
+        const long long c0 = job->cnt_above, w0 = job->w_above;
+        if (gc && !(c0 + gcnt[t] <= job->cnt_max && w0 + gwgt[t] <= job->w_max)) atomicMax(&first_fail, t);
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         job->ticket = 0;
@@ -228,16 +246,18 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
         const long long cmax = job->cnt_max, wmax = job->w_max;
         int boundary = -1;
         long long boundary_cnt = 0;
-        // bins in descending order: whole groups while they fit, then bin by bin inside the first that does not
-        for (int g = AL_THREADS - 1; g >= 0 && boundary < 0; --g) {
-            if (!gcnt[g]) continue;
-            if (c + gcnt[g] <= cmax && w + gwgt[g] <= wmax) { c += gcnt[g]; w += gwgt[g]; continue; }
+        const int g = first_fail;
+        if (g >= 0) {
+            if (g + 1 < AL_THREADS) { c += gcnt[g + 1]; w += gwgt[g + 1]; }
+            // bin by bin inside the first group that does not fit whole
             for (int b = g * G + G - 1; b >= g * G; --b) {
                 const long long bc = hc[b], bw = hw[b];
                 if (!bc) continue;
                 if (c + bc <= cmax && w + bw <= wmax) { c += bc; w += bw; }
                 else { boundary = b; boundary_cnt = bc; break; }
             }
+        } else {
+            c += gcnt[0]; w += gwgt[0];
         }
         if (boundary < 0) {
             // every key under the prefix fits: the selection ends at the bucket's lower edge
@@ -447,6 +467,11 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     p += sbits_align_up((size_t)N * 8, 256);
     sbits_trace *tr = reinterpret_cast<sbits_trace *>(p);
 
+    // the per-iteration read-back lands in page-locked memory: a pageable target makes every
+    // copy a staged, blocking one
+    if (!ctx->pinned) SBITS_HIP(ctx, hipHostMalloc(&ctx->pinned, SBITS_PINNED_BYTES, hipHostMallocDefault));
+    static_assert(offsetof(AllocState, job) <= SBITS_PINNED_BYTES, "state head must fit the pinned buffer");
+    AllocState *hp = static_cast<AllocState *>(ctx->pinned);   // only the head (before job[]) is valid there
     static AllocState h;                       // host image
     memset(&h, 0, sizeof h);
     h.N = N;
@@ -494,8 +519,9 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
             hipLaunchKernelGGL(decide_expand_kernel, dim3(1), dim3(1), 0, sm, st, tr);
             hipLaunchKernelGGL(apply_expand_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, level);
             SBITS_HIP(ctx, hipGetLastError());
-            SBITS_HIP(ctx, hipMemcpyAsync(&h, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+            SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
             SBITS_HIP(ctx, hipStreamSynchronize(sm));
+            memcpy(&h, hp, offsetof(AllocState, job));
             expanded = h.mode == MODE_EXPAND;
         }
         if (!expanded) {
@@ -513,8 +539,9 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
             hipLaunchKernelGGL(decide_swap_kernel, dim3(1), dim3(1), 0, sm, st, tr);
             hipLaunchKernelGGL(apply_swap_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, keyD, level);
             SBITS_HIP(ctx, hipGetLastError());
-            SBITS_HIP(ctx, hipMemcpyAsync(&h, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+            SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
             SBITS_HIP(ctx, hipStreamSynchronize(sm));
+            memcpy(&h, hp, offsetof(AllocState, job));
         }
         used = h.used;
         done = h.done != 0;
@@ -522,8 +549,9 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
 
     hipLaunchKernelGGL(final_stats_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level);
     SBITS_HIP(ctx, hipGetLastError());
-    SBITS_HIP(ctx, hipMemcpyAsync(&h, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+    SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
     SBITS_HIP(ctx, hipStreamSynchronize(sm));
+    memcpy(&h, hp, offsetof(AllocState, job));
     if (host_stats) {
         host_stats->iters = h.iters; host_stats->expansions = h.expansions;
         host_stats->swaps_ok = h.swaps_ok; host_stats->swaps_rej = h.swaps_rej;

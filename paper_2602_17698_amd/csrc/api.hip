@@ -37,6 +37,7 @@ int sbits_create(sbits_ctx **out, int device, void *hip_stream)
     c->device = device;
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->last_hip = 0;
+    c->pinned = nullptr;
     if (device >= 0) {
         hipError_t e = hipSetDevice(device);
         if (e != hipSuccess) { c->last_hip = (int)e; delete c; return SBITS_ERR_HIP; }
@@ -48,6 +49,7 @@ int sbits_create(sbits_ctx **out, int device, void *hip_stream)
 int sbits_destroy(sbits_ctx *ctx)
 {
     if (!ctx) return SBITS_ERR_INVALID_ARG;
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
     delete ctx;
     return SBITS_OK;
 }

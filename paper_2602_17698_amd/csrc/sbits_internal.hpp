@@ -15,7 +15,9 @@ struct sbits_ctx {
     int device;            // -1: host-only context
     hipStream_t stream;
     int last_hip;
+    void *pinned;          // small page-locked host buffer for state read-backs (allocated on first use)
 };
+constexpr size_t SBITS_PINNED_BYTES = 4096;
 
 struct sbits_plan {
     sbits_ctx *ctx;
