@@ -208,7 +208,8 @@ int  sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *leve
 /* The same from the ORIGINAL weights and the permutations (reordering on the fly,
  * no reordered copy needed); identical output.  mats: HOST array, only w_bf16 /
  * ld_w are read.  Same shape and alignment limits as sbits_gather_cost_all (w_bf16
- * rows on 16-byte boundaries); otherwise SBITS_ERR_UNIMPLEMENTED.  Uses ws.        */
+ * rows on 16-byte boundaries); otherwise SBITS_ERR_UNIMPLEMENTED.  codes 8-byte,
+ * scale and zero 16-byte aligned.  Uses ws.                                      */
 int  sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                            const int32_t *col_perm, const uint8_t *level, const int64_t *byte_off,
                            uint8_t *codes, float *scale, float *zero, void *ws);

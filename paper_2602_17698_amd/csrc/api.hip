@@ -307,7 +307,7 @@ int sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int3
     int rc = check_all(plan, mats, true, false);
     if (rc) return rc;
     if (!row_perm || !col_perm || !level || !byte_off || !codes || !scale || !zero || !aligned16(col_perm) ||
-        !ws_ok(ws) || (reinterpret_cast<uintptr_t>(codes) & 7))
+        !ws_ok(ws) || (reinterpret_cast<uintptr_t>(codes) & 7) || !aligned16(scale) || !aligned16(zero))
         return SBITS_ERR_INVALID_ARG;
     if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
     if ((rc = need_device(plan))) return rc;

@@ -4,22 +4,11 @@
 // reordered matrices and by the one that reorders on the fly, so both produce the same bits.
 #pragma once
 
-#include <type_traits>
-
 #include "sbits_device.hpp"
 
 namespace sbits {
 
 constexpr int COST_MAX_ROUND = 4;                     // rows that may share one round of divisions
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
 
 // value held by lane j*SP + SLOT of the caller's lane group, j in [0, LPG/SP)
 template <int LPG, int SP, int SLOT>

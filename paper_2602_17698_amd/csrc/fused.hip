@@ -331,7 +331,6 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 
     const int tid = (int)threadIdx.x;
     const int lig = tid % LPG;
-    const bool odd = (lig & 1) != 0;
     const int mem = funi(find_matrix(wg_start, n_members, (int)blockIdx.x));
     const MatDesc &d = descs[funi(members[mem])];
     const int R = funi((int)d.rows), C = funi((int)d.cols) & ~7;
@@ -347,7 +346,13 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 
     // LDS: weights [RS][C] bf16, then one strip of RS * LPG * cmax bytes per (lane group, chunk)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    const int strip = RS * LPG * cmax;
+    // (+8: a lane's third word may lie past its row; it is zero there, but has to be addressable)
+    const int strip = RS * LPG * cmax + 8;
+    const uint32_t strips = lds0 + (uint32_t)RS * (uint32_t)C * 2u;
+    for (int c = 0; c < CPL; ++c) {                  // every group zeroes its own strips
+        const uint32_t s0 = strips + (uint32_t)((tid / LPG) + (T / LPG) * c) * (uint32_t)strip;
+        for (int k = lig; k < strip / 4; k += LPG) *(lds_u32 *)(s0 + 4u * (uint32_t)k) = 0u;
+    }
 
     for (int i = tid; i < noct * 8; i += T) {
         int sr = rp[oct0 * 8 + i];
@@ -439,19 +444,32 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         for (int c = 0; c < CPL; ++c) {
             const int cb = lk[c].c;
             const int row_bytes = LPG * cb;
-            unsigned char *strip0 = smem + (size_t)RS * C * 2 + (size_t)((tid / LPG) + (T / LPG) * c) * strip;
+            const uint32_t strip0 = strips + (uint32_t)((tid / LPG) + (T / LPG) * c) * (uint32_t)strip;
+            uint4 raw[RS];
 #pragma unroll
-            for (int rs = 0; rs < RS; ++rs) {
-                float scl, mn;
-                const unsigned long long word = quant_pack_row<LPG>(gw[rs * CPL + c], lk[c], odd, scl, mn);
-                unsigned char *mine = strip0 + rs * row_bytes + lig * cb;
-                store_code_bytes(mine, word, cb);
-                if (valid[c] && lig == 0) {
-                    const int64_t ri = gb[c] * m + rib + rs;
-                    scale[ri] = scl;
-                    zero[ri] = mn + 0.0f;
+            for (int rs = 0; rs < RS; ++rs) raw[rs] = gw[rs * CPL + c];
+            unsigned long long word[RS];
+            float scl[RS], mn[RS];
+            quant_pack_rows<LPG, RS>(raw, lk[c], lig, word, scl, mn);
+#pragma unroll
+            for (int rs = 0; rs < RS; ++rs)
+                or_code_bytes(strip0 + (uint32_t)(rs * row_bytes), lig * cb, word[rs], cmax > 4);
+            if (valid[c] && lig == 0) {
+                // RS consecutive rows of one block: one vector store each (rib is a multiple of RS)
+                const int64_t ri = gb[c] * m + rib;
+                float zr[RS];
+#pragma unroll
+                for (int rs = 0; rs < RS; ++rs) zr[rs] = mn[rs] + 0.0f;
+                if constexpr (RS == 4) {
+                    *reinterpret_cast<float4 *>(scale + ri) = make_float4(scl[0], scl[1], scl[2], scl[3]);
+                    *reinterpret_cast<float4 *>(zero + ri) = make_float4(zr[0], zr[1], zr[2], zr[3]);
+                } else if constexpr (RS == 2) {
+                    *reinterpret_cast<float2 *>(scale + ri) = make_float2(scl[0], scl[1]);
+                    *reinterpret_cast<float2 *>(zero + ri) = make_float2(zr[0], zr[1]);
+                } else {
+#pragma unroll
+                    for (int rs = 0; rs < RS; ++rs) { scale[ri + rs] = scl[rs]; zero[ri + rs] = zr[rs]; }
                 }
-                __builtin_amdgcn_sched_barrier(0);   // one row at a time: interleaving only costs registers
             }
             // the strip is private to this lane group (one wave): LDS keeps a wave's operations in order
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -459,9 +477,14 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             if (valid[c]) {
                 const int nwords = RS * row_bytes / 4;           // row_bytes is a multiple of 8
-                const uint32_t *s32 = reinterpret_cast<const uint32_t *>(strip0);
                 uint32_t *d32 = reinterpret_cast<uint32_t *>(dst[c] + (int64_t)rib * row_bytes);
-                for (int k = lig; k < nwords; k += LPG) d32[k] = s32[k];
+                for (int k = lig; k < nwords; k += LPG) {
+                    lds_u32 *sp = (lds_u32 *)(strip0 + 4u * (uint32_t)k);
+                    d32[k] = *sp;
+                    *sp = 0u;                                    // zero again for the next step's ORs
+                }
+            } else {
+                for (int k = lig; k < RS * row_bytes / 4; k += LPG) *(lds_u32 *)(strip0 + 4u * (uint32_t)k) = 0u;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -549,7 +572,7 @@ static int launch_gpack_g(sbits_ctx *ctx, const FusedPackLaunch &a)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
         attr_done = true;
     }
-    const size_t lds = (size_t)RS * a.cols * 2 + (size_t)RS * CPL * T * a.cmax;
+    const size_t lds = (size_t)RS * a.cols * 2 + (size_t)(CPL * T / LPG) * ((size_t)RS * LPG * a.cmax + 8);
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.level, a.byte_off, a.codes, a.scale,
                        a.zero, a.gc, a.cmax);

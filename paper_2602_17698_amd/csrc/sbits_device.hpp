@@ -7,7 +7,20 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace sbits {
+
+// compile-time loop: f(std::integral_constant<int, I>) for I = I0 .. N-1
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 
 // ---- DPP within a row of 16 lanes ------------------------------------------
 template <int CTRL>
