@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--bits", type=str, default="1,2,3,4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-route-check", action="store_true",
+                    help="skip the untimed comparison run of the two-pass route (needs 56 GB more HBM)")
     ap.add_argument("--two-pass", action="store_true",
                     help="separate gather and cost launches instead of the fused one-pass kernel")
     ap.add_argument("--seed", type=int, default=0)
@@ -221,6 +223,30 @@ def main():
                      "launches_per_step": launches, "avg_launch_ms": cost_ms / launches,
                      "algorithmic_bytes_per_launch": cost_bytes / launches},
     }
+    if one_pass and not args.no_route_check:
+        # the two-pass route beside it, outside the timed region: its cost kernel alone (a5 as a
+        # separate pass over reordered copies) and the bit-equality of the two tables
+        w2 = torch.empty(nw, dtype=torch.bfloat16, device=dev)
+        s2 = torch.empty(nw, dtype=torch.float32, device=dev)
+        cost2 = torch.empty_like(cost)
+        plan.reorder_all(mats, row_perm, col_perm, ws)
+        plan.gather_cost_all(mats, row_perm, col_perm, None, cost, ws)
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        e[0].record()
+        plan.gather_all(mats, row_perm, col_perm, w2, s2, ws)
+        e[1].record()
+        for i in range(3):
+            plan.cost_table_all(w2, s2, cost2, ws)
+            e[2 + i].record()
+        torch.cuda.synchronize()
+        t_cost = sorted(e[1 + i].elapsed_time(e[2 + i]) for i in range(3))[1]
+        b2 = nw * 6 + N * K * 4
+        out["two_pass_route"] = {"gather_ms": e[0].elapsed_time(e[1]), "cost_kernel_ms": t_cost,
+                                 "cost_kernel_GBs": b2 / (t_cost * 1e-3) / 1e9,
+                                 "cost_kernel_frac_of_hbm_peak": b2 / (t_cost * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 "cost_kernel_weights_per_s": nw / (t_cost * 1e-3),
+                                 "tables_bit_equal": bool(torch.equal(cost.view(torch.int32), cost2.view(torch.int32)))}
+        del w2, s2, cost2
     if not args.no_cpu_baseline:
         # two full decoder layers: 436 M weights, 10-20 s of single-threaded oracle time
         sample = [(l, nm_, r, c) for l in (0, 1) for nm_, r, c in synth.layer_shapes(model)]
