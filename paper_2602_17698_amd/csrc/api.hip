@@ -101,7 +101,7 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
         d.rowpart_off = p->sum_rowpart; d.colpart_off = p->sum_colpart;
         p->sum_rowpart += rows[i] * d.nseg; p->sum_colpart += (int64_t)d.nband * cols[i];
         p->score_wg_start.push_back((int)score_wgs);
-        score_wgs += (int64_t)d.nseg * d.nband;
+        score_wgs += sbits_score_wgs(d.nseg, d.nband);
         p->descs.push_back(d);
         p->sum_rows += rows[i]; p->sum_cols += cols[i]; p->sum_elems += rows[i] * cols[i];
         p->N += (rows[i] / block_rows) * (cols[i] / block_cols);

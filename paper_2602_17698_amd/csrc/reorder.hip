@@ -6,12 +6,13 @@
 // Scores.  Row score = l1 norm of the row of S, column score = l1 norm of the
 // column, each summed in the canonical order: runs of 8 consecutive elements
 // left to right from +0, then an adjacent-pair tree over the runs (zero padded
-// to a power of two).  One pass over S serves both directions: a lane owns an
-// 8 x 8 tile (8 rows, 8 consecutive columns), so it holds 8 row runs and 8
-// column runs at once.  A wave covers 8 rows x 512 columns per octet and walks
-// 8 octets; a workgroup of four waves covers 256 rows x 512 columns.  The
-// partial trees (per row and 512-column segment; per column and 256-row band)
-// go to the workspace and a small kernel finishes them.
+// to a power of two).  One pass over S serves both directions.  A workgroup of
+// four waves walks a band of 256 rows over a panel of 4096 columns, row by row
+// (16 KiB of consecutive bytes per row); a wave owns two 512-column segments of
+// the panel and reads each with two 1 KiB loads, so a run of 8 columns sits in a
+// lane pair and the 16 columns of a lane keep their sums in registers for the
+// whole band.  The partial trees (per row and 512-column segment; per column
+// and 256-row band) go to the workspace and a small kernel finishes them.
 //
 // Argsort.  Descending by score, ties to the lower index: a stable LSD radix
 // sort (4 passes of 8 bits) of the inverted ordered-float keys, one workgroup
@@ -31,120 +32,169 @@ namespace sbits {
 
 // ================================================================ scores
 constexpr int SC_THREADS = 256;
-constexpr int SC_ROWS = 256;    // rows per workgroup (4 waves x 8 octets x 8 rows)
-constexpr int SC_COLS = 512;    // columns per workgroup (64 lanes x 8)
+constexpr int SC_ROWS = 256;    // rows per band (32 octets): one workgroup walks a whole band
+constexpr int SC_COLS = 512;    // columns per segment: one wave, two 1 KiB loads per row
+constexpr int SC_PANEL = 8;     // segments per workgroup: 4 waves x 2 segments = 4096 columns = 16 KiB per row
 
 // rowpart[r][seg]  : tree over the 64 column runs of segment seg (zero beyond C)
 // colpart[band][c] : tree over the 32 row runs of band (zero beyond R)
-__global__ __launch_bounds__(SC_THREADS, 3)
+//
+// A workgroup reads rows of 16 KiB (its panel of 8 segments) top to bottom, so HBM sees long
+// consecutive runs, and every load instruction of a wave covers 1 KiB of consecutive bytes (whole
+// cache lines), which is what non-temporal loads need to run at full rate.  Wave w owns segments
+// w and w + 4 of the panel.  Inside a segment lane l owns columns 4l..4l+3 and 256+4l..256+4l+3:
+// a run of 8 consecutive columns sits in the lane pair (2k, 2k+1).  Column sums stay in registers
+// for the whole band (16 columns per lane, a 5-level adjacent-pair tree over the 32 octets).
+__global__ __launch_bounds__(SC_THREADS, 2)
 void score_partial_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ wg_start,
                           int n_mats, float *__restrict__ rowpart_all, float *__restrict__ colpart_all)
 {
-    __shared__ float cbuf[4][SC_COLS];
     const int mat = descs ? find_matrix(wg_start, n_mats, (int)blockIdx.x) : 0;
     const MatDesc d = descs ? descs[mat] : one;
     const int lid = (int)blockIdx.x - (descs ? wg_start[mat] : 0);
-    const int band = lid / d.nseg, seg = lid - band * d.nseg;
+    const int npanel = (d.nseg + SC_PANEL - 1) / SC_PANEL;
+    const int band = lid / npanel, panel = lid - band * npanel;
     const int R = (int)d.rows, C = (int)d.cols;
     const int64_t ld = d.ld_s;
     // the descriptor's pointer is a generic one for the compiler: say that it is global memory
     typedef const char __attribute__((address_space(1))) *gcharp;
+    typedef const __attribute__((address_space(1))) f32x4_t *gf4p;
     gcharp Sg = (gcharp)(reinterpret_cast<const char *>(d.s));
     float *__restrict__ rowpart = rowpart_all + d.rowpart_off;
     float *__restrict__ colpart = colpart_all + d.colpart_off;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int c0 = seg * SC_COLS + lane * 8;
-    const bool col_ok = c0 < C;                      // C is a multiple of 8
-    const int c0c = col_ok ? c0 : C - 8;             // clamped: loads stay in bounds, values are dropped
-    const int rbase = band * SC_ROWS + wave * 64;
-
-    // loads of half an octet (4 rows x 8 columns per lane); rows beyond R are clamped and dropped
-    // (row addresses are the same in all lanes of a wave: scalar base + per-lane 32-bit offset)
-    struct Half { float4 a[4], b[4]; };
-    const uint32_t voff = (uint32_t)c0c * 4u;
-    auto load_half = [&](Half &o, int h) {           // h = 2*octet + half
+    int seg[2], col0[2][2];
+    bool ok[2][2];
+    uint32_t voff[2][2];
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            int r = rbase + h * 4 + rr;
-            r = r < R ? r : R - 1;
+    for (int j = 0; j < 2; ++j) {
+        seg[j] = panel * SC_PANEL + wave + 4 * j;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            col0[j][h] = seg[j] * SC_COLS + h * (SC_COLS / 2) + lane * 4;
+            ok[j][h] = col0[j][h] < C;                   // C is a multiple of 8 (4 columns: all in or all out)
+            voff[j][h] = (uint32_t)(ok[j][h] ? col0[j][h] : C - 4) * 4u;   // clamped: in bounds, value dropped
+        }
+    }
+    const int rbase = band * SC_ROWS;
+
+    // two rows of the panel per pipeline stage: 8 loads of 16 bytes per lane
+    struct Stage { float4 v[2][2][2]; };             // [row][segment][half of the segment]
+    auto load_stage = [&](Stage &o, int r0) {
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+            int r = rbase + r0 + rr;
+            r = r < R ? r : R - 1;                   // rows beyond R are clamped and dropped
             gcharp p = Sg + (int64_t)r * ld * 4;
-            o.a[rr] = gload_f4((const char *)p + voff);
-            o.b[rr] = gload_f4((const char *)p + voff + 16u);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const f32x4_t t = __builtin_nontemporal_load((gf4p)(p + voff[j][h]));
+                    o.v[rr][j][h] = make_float4(t.x, t.y, t.z, t.w);
+                }
         }
     };
 
-    float t1[8], t2[8], t3[8], col[8], colrun[8];
-    auto process = [&](const Half &cur, int h) {
-        const int r0 = rbase + h * 4;
-        float rowrun[4];
-        if ((h & 1) == 0) {
+    // sum of one run of 8 columns held by a lane pair, left to right; both lanes end with it
+    auto run_sum = [&](const float (&x)[4]) {
+        const float p = ((x[0] + x[1]) + x[2]) + x[3];               // the run's first four (even lane)
+        const float start = dpp_mov<0xA0>(p);                         // quad_perm [0,0,2,2]: odd lane <- even lane
+        const float q = (((start + x[0]) + x[1]) + x[2]) + x[3];      // odd lane: the whole run
+        return dpp_mov<0xF5>(q);                                      // quad_perm [1,1,3,3]: both lanes <- odd lane
+    };
+    // adjacent-pair tree over the 32 runs held by 64 lanes (lane pairs agree on entry)
+    auto tree_runs = [&](float v) {
+        v = v + dpp_mov<DPP_XOR2>(v);
+        v = v + dpp_mov<DPP_HALF_MIRROR>(v);
+        v = v + dpp_mov<DPP_MIRROR>(v);
+        v = v + __shfl_xor(v, 16);
+        v = v + __shfl_xor(v, 32);
+        return v;
+    };
+
+    float colrun[16], t1[16], t2[16], t3[16], t4[16], t5[16], col[16];
+    auto process = [&](const Stage &cur, int r0) {   // rows r0, r0 + 1 of the band
 #pragma unroll
-            for (int e = 0; e < 8; ++e) colrun[e] = 0.0f;
-        }
+        for (int rr = 0; rr < 2; ++rr) {
+            const int rb = r0 + rr;                  // row inside the band
+            const bool rok = rbase + rb < R;
+            if ((rb & 7) == 0) {
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const bool ok = col_ok && (r0 + rr < R);
-            float v[8] = {cur.a[rr].x, cur.a[rr].y, cur.a[rr].z, cur.a[rr].w,
-                          cur.b[rr].x, cur.b[rr].y, cur.b[rr].z, cur.b[rr].w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = ok ? fabsf(v[e]) : 0.0f;
-            float a = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                a = a + v[e];                        // row run: left to right
-                colrun[e] = colrun[e] + v[e];        // column run: top to bottom, 8 rows
+                for (int e = 0; e < 16; ++e) colrun[e] = 0.0f;
             }
-            rowrun[rr] = a;
-        }
-        // rows: adjacent-pair tree over the 64 lanes (64 runs = 512 columns)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const float t = group_allreduce<64>(rowrun[rr], OpAdd{});
-            if (lane == 0 && r0 + rr < R) rowpart[(int64_t)(r0 + rr) * d.nseg + seg] = t;
-        }
-        if (h & 1) {
-            // columns: adjacent-pair tree over the wave's 8 octets, in registers
-            const int oc = h >> 1;
+            for (int j = 0; j < 2; ++j) {
+                float x[2][4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float v = colrun[e];
-                if (oc & 1) {
-                    v = t1[e] + v;
-                    if (oc & 2) {
-                        v = t2[e] + v;
-                        if (oc & 4) v = t3[e] + v;
-                        else t3[e] = v;
-                    } else {
-                        t2[e] = v;
+                for (int h = 0; h < 2; ++h) {
+                    const float4 t = cur.v[rr][j][h];
+                    const float raw[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        x[h][e] = (ok[j][h] && rok) ? fabsf(raw[e]) : 0.0f;
+                        colrun[j * 8 + h * 4 + e] = colrun[j * 8 + h * 4 + e] + x[h][e];   // top to bottom, 8 rows
                     }
-                } else {
-                    t1[e] = v;
                 }
-                col[e] = v;
+                // runs of 8 left to right, then the adjacent-pair tree over the segment's 64 runs
+                // (32 in its first 256 columns, 32 in the second)
+                const float rs = tree_runs(run_sum(x[0])) + tree_runs(run_sum(x[1]));
+                if (lane == 0 && rok && seg[j] < d.nseg) rowpart[(int64_t)(rbase + rb) * d.nseg + seg[j]] = rs;
+            }
+            if ((rb & 7) == 7) {
+                // columns: adjacent-pair tree over the band's 32 octets, fed one octet at a time
+                const int oc = rb >> 3;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float v = colrun[e];
+                    if (oc & 1) {
+                        v = t1[e] + v;
+                        if (oc & 2) {
+                            v = t2[e] + v;
+                            if (oc & 4) {
+                                v = t3[e] + v;
+                                if (oc & 8) {
+                                    v = t4[e] + v;
+                                    if (oc & 16) v = t5[e] + v;
+                                    else t5[e] = v;
+                                } else {
+                                    t4[e] = v;
+                                }
+                            } else {
+                                t3[e] = v;
+                            }
+                        } else {
+                            t2[e] = v;
+                        }
+                    } else {
+                        t1[e] = v;
+                    }
+                    col[e] = v;
+                }
             }
         }
     };
-    // two buffers in ping-pong: the next half octet is in flight while the current one is summed
-    Half A, B;
-    load_half(A, 0);
+    // two buffers in ping-pong: the next two rows are in flight while the current two are summed
+    Stage A, B;
+    load_stage(A, 0);
 #pragma unroll 1
-    for (int h = 0; h < 16; h += 2) {
-        load_half(B, h + 1);
-        process(A, h);
-        load_half(A, h + 2 < 16 ? h + 2 : 15);       // the last reload is redundant and harmless
-        process(B, h + 1);
+    for (int r0 = 0; r0 < SC_ROWS; r0 += 4) {
+        load_stage(B, r0 + 2);
+        process(A, r0);
+        load_stage(A, r0 + 4 < SC_ROWS ? r0 + 4 : SC_ROWS - 2);   // the last reload is redundant and harmless
+        process(B, r0 + 2);
     }
-    // columns: tree over the 4 waves
 #pragma unroll
-    for (int e = 0; e < 8; ++e) cbuf[wave][lane * 8 + e] = col[e];
-    __syncthreads();
-    for (int c = threadIdx.x; c < SC_COLS; c += SC_THREADS) {
-        const int64_t colx = (int64_t)seg * SC_COLS + c;
-        if (colx < C)
-            colpart[(int64_t)band * C + colx] = (cbuf[0][c] + cbuf[1][c]) + (cbuf[2][c] + cbuf[3][c]);
-    }
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            if (ok[j][h]) {
+                float *dst = colpart + (int64_t)band * C + col0[j][h];
+                *reinterpret_cast<float4 *>(dst) = make_float4(col[j * 8 + h * 4], col[j * 8 + h * 4 + 1],
+                                                               col[j * 8 + h * 4 + 2], col[j * 8 + h * 4 + 3]);
+            }
 }
 
 // adjacent-pair tree over 32 leaves x[(i0 + i) * stride], i < 32, zero beyond n
@@ -409,6 +459,9 @@ static size_t reorder_ws_layout(void *base, int64_t L, int64_t RP, int64_t CP, R
     return b;
 }
 
+// workgroups of score_partial_kernel for a matrix with nseg segments and nband bands
+int sbits_score_wgs(int nseg, int nband) { return nband * ((nseg + SC_PANEL - 1) / SC_PANEL); }
+
 void sbits_score_geometry(int64_t R, int64_t C, int *nseg, int *nband)
 {
     *nseg = (int)((C + SC_COLS - 1) / SC_COLS);
@@ -453,7 +506,7 @@ int sbits_launch_scores(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, in
     MatDesc one = single_desc(nullptr, S, R, C, C, ld);
     ReorderWs w;
     reorder_ws_layout(scratch, R + C, R * one.nseg, (int64_t)one.nband * C, &w);
-    int rc = run_scores(ctx, nullptr, one, nullptr, 1, one.nseg * one.nband, R, C, w);
+    int rc = run_scores(ctx, nullptr, one, nullptr, 1, sbits_score_wgs(one.nseg, one.nband), R, C, w);
     if (rc) return rc;
     if (row_score)
         SBITS_HIP(ctx, hipMemcpyAsync(row_score, w.scores, (size_t)R * 4, hipMemcpyDeviceToDevice, ctx->stream));
@@ -468,7 +521,7 @@ int sbits_launch_reorder(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, i
     MatDesc one = single_desc(nullptr, S, R, C, C, ld);
     ReorderWs w;
     reorder_ws_layout(scratch, R + C, R * one.nseg, (int64_t)one.nband * C, &w);
-    int rc = run_scores(ctx, nullptr, one, nullptr, 1, one.nseg * one.nband, R, C, w);
+    int rc = run_scores(ctx, nullptr, one, nullptr, 1, sbits_score_wgs(one.nseg, one.nband), R, C, w);
     if (rc) return rc;
     hipLaunchKernelGGL(radix_argsort_kernel, dim3(2), dim3(RS_THREADS), 0, ctx->stream,
                        (const MatDesc *)nullptr, one, 1, R, w.scores, w.k0, w.k1, w.i0, w.i1, row_perm, col_perm);

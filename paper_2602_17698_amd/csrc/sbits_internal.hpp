@@ -68,6 +68,7 @@ static inline size_t sbits_align_up(size_t v, size_t a) { return (v + a - 1) / a
 
 // workspace sizes in bytes
 void sbits_score_geometry(int64_t R, int64_t C, int *nseg, int *nband);
+int sbits_score_wgs(int nseg, int nband);
 size_t sbits_reorder_ws_bytes(int64_t channels, int64_t rowpart, int64_t colpart);
 size_t sbits_alloc_ws_bytes(int64_t N);
 size_t sbits_offsets_ws_bytes(int64_t N);
