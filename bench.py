@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-route-check", action="store_true",
                     help="skip the untimed comparison run of the two-pass route (needs 56 GB more HBM)")
+    ap.add_argument("--coupled", action="store_true",
+                    help="coupled reordering (residual stream and MLP groups share permutations) instead of "
+                         "per-matrix reordering")
     ap.add_argument("--two-pass", action="store_true",
                     help="separate gather and cost launches instead of the fused one-pass kernel")
     ap.add_argument("--seed", type=int, default=0)
@@ -139,9 +142,14 @@ def main():
     # one_pass: the reorder-gather is fused into the cost pass (stage "gather" is then empty)
     stage_names = ["reorder", "gather", "cost", "allocate", "offsets_pack"]
 
+    coupling = synth.llama_coupling(model, args.layers) if args.coupled else None
+
     def step(ev):
         ev[0].record()
-        plan.reorder_all(mats, row_perm, col_perm, ws)
+        if coupling:
+            plan.reorder_coupled_all(mats, coupling[0], coupling[1], coupling[2], coupling[3], row_perm, col_perm, ws)
+        else:
+            plan.reorder_all(mats, row_perm, col_perm, ws)
         ev[1].record()
         if one_pass:
             ev[2].record()
@@ -210,8 +218,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "Llama-3-8B-shaped, %d layers, %d matrices, %d weights (bf16) + fp32 sensitivity, "
-                               "%dx%d blocks (%d), bitwidths %s, budget %.2f"
-                               % (args.layers, nm, nw, m, n, N, bits, args.budget)},
+                               "%dx%d blocks (%d), bitwidths %s, budget %.2f%s"
+                               % (args.layers, nm, nw, m, n, N, bits, args.budget,
+                                  ", coupled reordering" if args.coupled else "")},
         "full_search_ms": ms_per_step,
         "stage_ms": stage_ms,
         "cost_pass_weights_per_s": nw / (cost_ms * 1e-3),

@@ -133,6 +133,27 @@ int  sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M,
  * plan order (sum of rows / sum of cols entries).  Uses ws.                       */
 int  sbits_reorder_all(sbits_plan *plan, const sbits_matrix *mats,
                        int32_t *row_perm, int32_t *col_perm, void *ws);
+/* Coupled reordering (paper Sec. 4.1 last paragraph and App. "Channel Reordering"):
+ * matrix dimensions that carry the same activation (the residual stream; the
+ * up / gate rows and down columns of one MLP; the value rows and output columns
+ * of one attention block) must share ONE permutation, computed from the sum of
+ * their channel scores.  row_group[i] / col_group[i] (HOST arrays, n_mats each)
+ * give, for the rows / columns of matrix i, SBITS_DIM_INDEPENDENT (own scores, as
+ * sbits_reorder_all), SBITS_DIM_FIXED (identity: e.g. query / key rows under rotary
+ * embeddings) or a group id in [0, n_groups).  All members of a group must have
+ * the same length (else SBITS_ERR_BAD_SHAPE).  The group's score of channel j is
+ * the fp32 sum of the members' scores of channel j, added member after member in
+ * the order: rows of matrix 0, 1, ..., then columns of matrix 0, 1, ...
+ * group_segment[g] (HOST, may be NULL = all 0): 0, or a piece length dividing the
+ * group's length: channels are then only permuted inside consecutive pieces of
+ * that length (attention heads).  Order inside a piece: score descending, ties to
+ * the lower index.  Every member receives the same permutation.  Uses ws.       */
+#define SBITS_DIM_INDEPENDENT (-1)
+#define SBITS_DIM_FIXED       (-2)
+int  sbits_reorder_coupled_all(sbits_plan *plan, const sbits_matrix *mats,
+                               const int32_t *row_group, const int32_t *col_group,
+                               int n_groups, const int32_t *group_segment,
+                               int32_t *row_perm, int32_t *col_perm, void *ws);
 /* w_out[i][j] = W[row_perm[i]][col_perm[j]], s_out likewise; outputs are dense
  * (pitch = cols) and must not alias the inputs.                                 */
 int  sbits_gather(sbits_plan *plan, int mat, const sbits_matrix *M,

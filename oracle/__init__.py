@@ -124,6 +124,29 @@ def argsort_desc(score):
     return perm
 
 
+def group_scores(member_scores):
+    """Summed channel scores of coupled dimensions, member after member (fp32)."""
+    ms = [_f32(m) for m in member_scores]
+    n = ms[0].size
+    assert all(m.size == n for m in ms)
+    ptrs = (C.c_void_p * len(ms))(*[m.ctypes.data for m in ms])
+    out = np.empty(n, np.float32)
+    lib().orc_group_scores(ptrs, C.c_int(len(ms)), C.c_int64(n), _p(out))
+    return out
+
+
+def argsort_desc_pieces(score, piece=0):
+    score = _f32(score)
+    perm = np.empty(score.size, np.int32)
+    lib().orc_argsort_desc_pieces(_p(score), C.c_int64(score.size), C.c_int64(piece), _p(perm))
+    return perm
+
+
+def coupled_perm(member_scores, piece=0):
+    """The one permutation shared by coupled dimensions (App. "Channel Reordering")."""
+    return argsort_desc_pieces(group_scores(member_scores), piece)
+
+
 def gather(W_u16, S, rp, cp):
     W_u16 = _u16(W_u16)
     S = _f32(S)

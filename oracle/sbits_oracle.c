@@ -102,6 +102,30 @@ void orc_argsort_desc(const float *score, int64_t n, int32_t *perm)
     }
 }
 
+/* Coupled reordering (App. "Channel Reordering", Sec. 4.1 last paragraph): dimensions that carry
+ * the same activation share one permutation, computed from the scores aggregated over the
+ * coupled matrices.  Aggregation = plain fp32 sum, member after member in the given order. */
+void orc_group_scores(const float *const *member_scores, int n_members, int64_t n, float *out)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float acc = member_scores[0][j];
+        for (int k = 1; k < n_members; ++k) acc = acc + member_scores[k][j];
+        out[j] = acc;
+    }
+}
+
+/* The same order as orc_argsort_desc, applied inside consecutive pieces of `piece` channels
+ * (attention heads keep their channels); piece = 0 or n: the whole array. */
+void orc_argsort_desc_pieces(const float *score, int64_t n, int64_t piece, int32_t *perm)
+{
+    if (piece <= 0 || piece > n) piece = n;
+    for (int64_t p0 = 0; p0 < n; p0 += piece) {
+        const int64_t len = (n - p0 < piece) ? n - p0 : piece;
+        orc_argsort_desc(score + p0, len, perm + p0);
+        for (int64_t i = 0; i < len; ++i) perm[p0 + i] += (int32_t)p0;
+    }
+}
+
 /* ------------------------------------------------------------- a3: gather */
 
 void orc_gather_bf16(const uint16_t *W, int64_t R, int64_t C, int64_t ld,

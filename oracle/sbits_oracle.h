@@ -55,6 +55,11 @@ void orc_channel_scores(const float *S, int64_t R, int64_t C, int64_t ld,
  * Gather form: new[i] = old[perm[i]].                                        */
 void orc_argsort_desc(const float *score, int64_t n, int32_t *perm);
 
+/* coupled reordering (App. "Channel Reordering"): summed scores of the coupled dimensions, and the
+ * descending order inside consecutive pieces (heads) */
+void orc_group_scores(const float *const *member_scores, int n_members, int64_t n, float *out);
+void orc_argsort_desc_pieces(const float *score, int64_t n, int64_t piece, int32_t *perm);
+
 /* ---- a3: reorder both directions: out[i][j] = in[rp[i]][cp[j]].           */
 void orc_gather_bf16(const uint16_t *W, int64_t R, int64_t C, int64_t ld,
                      const int32_t *rp, const int32_t *cp, uint16_t *out);

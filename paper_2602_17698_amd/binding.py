@@ -14,6 +14,7 @@ LIB_PATH = os.environ.get("SBITS_LIB") or os.path.join(_HERE, "libscalebits.so")
 
 OK = 0
 ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_BAD_BITWIDTHS, ERR_INFEASIBLE_BUDGET = -1, -2, -3, -4
+DIM_INDEPENDENT, DIM_FIXED = -1, -2
 ERR_WORKSPACE, ERR_MAX_ITERS, ERR_HIP, ERR_UNIMPLEMENTED, ERR_CAPACITY = -5, -6, -7, -8, -9
 
 EXPORTS = [
@@ -23,6 +24,7 @@ EXPORTS = [
     "sbits_reorder", "sbits_reorder_all", "sbits_channel_scores", "sbits_gather", "sbits_gather_all",
     "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
+    "sbits_reorder_coupled_all",
     "sbits_allocate", "sbits_offsets", "sbits_pack", "sbits_search",
 ]
 
@@ -190,6 +192,15 @@ class Plan:
         arr = (Matrix * len(mats))(*mats)
         return _check(load().sbits_reorder_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(ws)),
                       "sbits_reorder_all")
+
+    def reorder_coupled_all(self, mats, row_group, col_group, n_groups, group_segment, row_perm, col_perm, ws):
+        """row_group / col_group / group_segment: host sequences of ints (see scalebits.h)."""
+        arr = (Matrix * len(mats))(*mats)
+        rg = (C.c_int32 * len(row_group))(*row_group)
+        cg = (C.c_int32 * len(col_group))(*col_group)
+        gs = (C.c_int32 * max(len(group_segment), 1))(*group_segment) if group_segment is not None else None
+        return _check(load().sbits_reorder_coupled_all(self.h, arr, rg, cg, C.c_int(n_groups), gs, _ptr(row_perm),
+                                                       _ptr(col_perm), _ptr(ws)), "sbits_reorder_coupled_all")
 
     def gather_all(self, mats, row_perm, col_perm, w_re, s_re, ws):
         arr = (Matrix * len(mats))(*mats)

@@ -237,6 +237,19 @@ int sbits_reorder_all(sbits_plan *plan, const sbits_matrix *mats, int32_t *row_p
     return sbits_launch_reorder_all(plan, row_perm, col_perm, ws);
 }
 
+int sbits_reorder_coupled_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_group,
+                              const int32_t *col_group, int n_groups, const int32_t *group_segment,
+                              int32_t *row_perm, int32_t *col_perm, void *ws)
+{
+    int rc = check_all(plan, mats, false, true);
+    if (rc) return rc;
+    if (!row_group || !col_group || n_groups < 0 || !row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if ((rc = need_device(plan))) return rc;
+    if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    return sbits_launch_reorder_coupled_all(plan, row_group, col_group, n_groups, group_segment, row_perm, col_perm,
+                                            ws);
+}
+
 int sbits_gather_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                      const int32_t *col_perm, void *w_re_bf16, float *s_re, void *ws)
 {

@@ -267,21 +267,36 @@ __device__ __forceinline__ unsigned int sort_key(float f)
 
 // Array a of the launch: a < n_mats -> the rows of matrix a, else the columns of matrix a - n_mats.
 // k0/k1/i0/i1 are ping-pong buffers with the same indexing as the score array.
+// arr_mode (may be null = all SORT): what to do with array a; arr_segment (with arr_mode): 0 or the
+// length of the pieces that are sorted one by one (a permutation that stays inside attention heads).
+enum { ARR_SORT = 0, ARR_IDENTITY = 1, ARR_SKIP = 2 };
 __global__ __launch_bounds__(RS_THREADS)
 void radix_argsort_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_mats, int64_t sum_rows,
                           const float *__restrict__ scores, unsigned int *__restrict__ k0,
                           unsigned int *__restrict__ k1, unsigned int *__restrict__ i0,
                           unsigned int *__restrict__ i1, int32_t *__restrict__ row_perm,
-                          int32_t *__restrict__ col_perm)
+                          int32_t *__restrict__ col_perm, const int *__restrict__ arr_mode,
+                          const int *__restrict__ arr_segment)
 {
     __shared__ unsigned int hist[RS_WAVES][256];     // per-wave digit counts, then running offsets
     __shared__ unsigned int total[256];
     const int a = blockIdx.x;
     const bool is_row = a < n_mats;
     const MatDesc &d = descs ? descs[is_row ? a : a - n_mats] : one;
-    const int n = (int)(is_row ? d.rows : d.cols);
-    const int64_t off = is_row ? d.row_off : sum_rows + d.col_off;
-    int32_t *__restrict__ perm = is_row ? row_perm + d.row_off : col_perm + d.col_off;
+    const int n_all = (int)(is_row ? d.rows : d.cols);
+    const int64_t off_all = is_row ? d.row_off : sum_rows + d.col_off;
+    int32_t *__restrict__ perm_all = is_row ? row_perm + d.row_off : col_perm + d.col_off;
+    const int mode = arr_mode ? arr_mode[a] : ARR_SORT;
+    if (mode == ARR_SKIP) return;
+    if (mode == ARR_IDENTITY) {
+        for (int i = threadIdx.x; i < n_all; i += RS_THREADS) perm_all[i] = i;
+        return;
+    }
+    const int piece = (arr_mode && arr_segment[a] > 0) ? arr_segment[a] : n_all;
+    for (int p0 = 0; p0 < n_all; p0 += piece) {      // (uniform over the workgroup)
+    const int n = min(piece, n_all - p0);
+    const int64_t off = off_all + p0;
+    int32_t *__restrict__ perm = perm_all + p0;
     const float *__restrict__ sc = scores + off;
     unsigned int *kb[2] = {k0 + off, k1 + off};
     unsigned int *ib[2] = {i0 + off, i1 + off};
@@ -352,13 +367,59 @@ void radix_argsort_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_
             if (valid) {
                 const unsigned int base = hist[wave][dg];
                 const unsigned int dst = base + rank;
-                if (pass == 3) perm[dst] = (int32_t)idx;
+                if (pass == 3) perm[dst] = (int32_t)idx + p0;
                 else { kout[dst] = key; iout[dst] = idx; }
                 if (rank == 0) hist[wave][dg] = base + __popcll(same);
             }
         }
         __syncthreads();
     }
+    }
+}
+
+// ---- coupled reordering (paper App. "Channel Reordering": one permutation for all the matrix
+// dimensions that carry the same activation; the scores of the coupled dimensions are summed) ----
+// Arrays are numbered as in the sort kernel.  arr_next[a]: the next member of a's group, or -1.
+// The leader (first member) of a group accumulates, member after member in array order:
+//   s[leader][j] = (..(s[leader][j] + s[m1][j]) + s[m2][j]) + ...
+__global__ __launch_bounds__(256)
+void group_sum_kernel(const MatDesc *__restrict__ descs, int n_mats, int64_t sum_rows, float *__restrict__ scores,
+                      const int *__restrict__ arr_mode, const int *__restrict__ arr_next)
+{
+    const int a = blockIdx.y;
+    if (arr_mode[a] != ARR_SORT || arr_next[a] < 0) return;      // only leaders with other members
+    const bool is_row = a < n_mats;
+    const MatDesc &d = descs[is_row ? a : a - n_mats];
+    const int n = (int)(is_row ? d.rows : d.cols);
+    const int64_t off = is_row ? d.row_off : sum_rows + d.col_off;
+    for (int j = (int)(blockIdx.x * blockDim.x + threadIdx.x); j < n; j += (int)(gridDim.x * blockDim.x)) {
+        float acc = scores[off + j];
+        for (int b = arr_next[a]; b >= 0; b = arr_next[b]) {
+            const bool br = b < n_mats;
+            const MatDesc &e = descs[br ? b : b - n_mats];
+            acc = acc + scores[(br ? e.row_off : sum_rows + e.col_off) + j];
+        }
+        scores[off + j] = acc;
+    }
+}
+
+// the members of a group take their leader's permutation
+__global__ __launch_bounds__(256)
+void replicate_perm_kernel(const MatDesc *__restrict__ descs, int n_mats, int32_t *__restrict__ row_perm,
+                           int32_t *__restrict__ col_perm, const int *__restrict__ arr_mode,
+                           const int *__restrict__ arr_leader)
+{
+    const int a = blockIdx.y;
+    if (arr_mode[a] != ARR_SKIP) return;
+    const int l = arr_leader[a];
+    const bool ar = a < n_mats, lr = l < n_mats;
+    const MatDesc &d = descs[ar ? a : a - n_mats];
+    const MatDesc &e = descs[lr ? l : l - n_mats];
+    const int n = (int)(ar ? d.rows : d.cols);
+    int32_t *dst = ar ? row_perm + d.row_off : col_perm + d.col_off;
+    const int32_t *src = lr ? row_perm + e.row_off : col_perm + e.col_off;
+    for (int j = (int)(blockIdx.x * blockDim.x + threadIdx.x); j < n; j += (int)(gridDim.x * blockDim.x))
+        dst[j] = src[j];
 }
 
 // ================================================================ gather
@@ -524,7 +585,8 @@ int sbits_launch_reorder(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, i
     int rc = run_scores(ctx, nullptr, one, nullptr, 1, sbits_score_wgs(one.nseg, one.nband), R, C, w);
     if (rc) return rc;
     hipLaunchKernelGGL(radix_argsort_kernel, dim3(2), dim3(RS_THREADS), 0, ctx->stream,
-                       (const MatDesc *)nullptr, one, 1, R, w.scores, w.k0, w.k1, w.i0, w.i1, row_perm, col_perm);
+                       (const MatDesc *)nullptr, one, 1, R, w.scores, w.k0, w.k1, w.i0, w.i1, row_perm, col_perm,
+                       (const int *)nullptr, (const int *)nullptr);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
@@ -585,7 +647,70 @@ int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_p
     if (rc) return rc;
     hipLaunchKernelGGL(radix_argsort_kernel, dim3((unsigned)(2 * plan->n_mats)), dim3(RS_THREADS), 0, ctx->stream,
                        (const MatDesc *)sbits_desc_ptr(ws), none, plan->n_mats, plan->sum_rows, w.scores,
-                       w.k0, w.k1, w.i0, w.i1, row_perm, col_perm);
+                       w.k0, w.k1, w.i0, w.i1, row_perm, col_perm, (const int *)nullptr, (const int *)nullptr);
+    SBITS_HIP(ctx, hipGetLastError());
+    return SBITS_OK;
+}
+
+// Coupled reordering of all matrices.  group[a] for every array a (rows of matrix a, or columns of
+// matrix a - n_mats): SBITS_DIM_INDEPENDENT, SBITS_DIM_FIXED or a group id; segment[g]: 0 or the
+// piece length for group g.  Tables go to slots 6..9 of the workspace head.
+int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group, const int32_t *col_group,
+                                     int n_groups, const int32_t *group_segment, int32_t *row_perm,
+                                     int32_t *col_perm, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    const int nm = plan->n_mats, na = 2 * nm;
+    std::vector<int> mode(na), seg(na, 0), next(na, -1), leader(na, -1), last(n_groups > 0 ? n_groups : 0, -1);
+    std::vector<int> first(last);
+    auto len = [&](int a) { return a < nm ? plan->rows[a] : plan->cols[a - nm]; };
+    for (int a = 0; a < na; ++a) {
+        const int g = a < nm ? row_group[a] : col_group[a - nm];
+        if (g == SBITS_DIM_INDEPENDENT) { mode[a] = ARR_SORT; continue; }
+        if (g == SBITS_DIM_FIXED) { mode[a] = ARR_IDENTITY; continue; }
+        if (g < 0 || g >= n_groups) return SBITS_ERR_INVALID_ARG;
+        const int sg = group_segment ? group_segment[g] : 0;
+        if (sg < 0 || (sg > 0 && len(a) % sg)) return SBITS_ERR_BAD_SHAPE;
+        if (first[g] < 0) {
+            first[g] = last[g] = a;
+            mode[a] = ARR_SORT;
+            seg[a] = sg;
+        } else {
+            if (len(a) != len(first[g])) return SBITS_ERR_BAD_SHAPE;   // coupled dimensions are the same activation
+            mode[a] = ARR_SKIP;
+            leader[a] = first[g];
+            next[last[g]] = a;
+            last[g] = a;
+        }
+    }
+    int *d_mode = sbits_prefix_ptr(plan, ws, 6), *d_seg = sbits_prefix_ptr(plan, ws, 7);
+    int *d_next = sbits_prefix_ptr(plan, ws, 8), *d_leader = sbits_prefix_ptr(plan, ws, 9);
+    SBITS_HIP(ctx, hipMemcpyAsync(d_mode, mode.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_seg, seg.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_next, next.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_leader, leader.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipStreamSynchronize(ctx->stream));           // the host vectors go away on return
+
+    ReorderWs w;
+    reorder_ws_layout(sbits_scratch(plan, ws), plan->sum_rows + plan->sum_cols, plan->sum_rowpart,
+                      plan->sum_colpart, &w);
+    int *d_pre = sbits_prefix_ptr(plan, ws, 1);
+    SBITS_HIP(ctx, hipMemcpyAsync(d_pre, plan->score_wg_start.data(), plan->score_wg_start.size() * 4,
+                                  hipMemcpyHostToDevice, ctx->stream));
+    MatDesc none;
+    memset(&none, 0, sizeof none);
+    const MatDesc *descs = sbits_desc_ptr(ws);
+    int rc = run_scores(ctx, descs, none, d_pre, nm, plan->score_wg_start.back(), plan->sum_rows, plan->sum_cols, w);
+    if (rc) return rc;
+    const int64_t maxlen = plan->max_rows > plan->max_cols ? plan->max_rows : plan->max_cols;
+    const dim3 g2((unsigned)((maxlen + 255) / 256), (unsigned)na);
+    hipLaunchKernelGGL(group_sum_kernel, g2, dim3(256), 0, ctx->stream, descs, nm, plan->sum_rows, w.scores,
+                       (const int *)d_mode, (const int *)d_next);
+    hipLaunchKernelGGL(radix_argsort_kernel, dim3((unsigned)na), dim3(RS_THREADS), 0, ctx->stream, descs, none, nm,
+                       plan->sum_rows, w.scores, w.k0, w.k1, w.i0, w.i1, row_perm, col_perm, (const int *)d_mode,
+                       (const int *)d_seg);
+    hipLaunchKernelGGL(replicate_perm_kernel, g2, dim3(256), 0, ctx->stream, descs, nm, row_perm, col_perm,
+                       (const int *)d_mode, (const int *)d_leader);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }

@@ -33,6 +33,24 @@ def layer_shapes(model: dict):
             ("gate", f, h), ("up", f, h), ("down", h, f)]
 
 
+def llama_coupling(model: dict, layers: int):
+    """Permutation groups of a Llama-shaped decoder stack, matrices in layer_shapes() order per layer
+    (paper App. "Channel Reordering"): group 0 = the residual stream (columns of q, k, v, gate, up and
+    rows of o, down of every layer); one group per layer for the MLP activation (rows of gate, up,
+    columns of down).  Rows of q and k stay fixed (rotary embeddings).  Rows of v and columns of o are
+    left fixed as well: with grouped-query attention they have different lengths (one value head
+    serves several query heads), a coupling the library's equal-length groups do not express.
+    Returns (row_group, col_group, n_groups, group_segment) for sbits_reorder_coupled_all."""
+    FIXED = -2
+    row_group, col_group = [], []
+    for layer in range(layers):
+        mlp = 1 + layer
+        row_group += [FIXED, FIXED, FIXED, 0, mlp, mlp, 0]          # q k v o gate up down
+        col_group += [0, 0, 0, FIXED, 0, 0, mlp]
+    n_groups = 1 + layers
+    return row_group, col_group, n_groups, [0] * n_groups
+
+
 def tensor_id(layer: int, proj: str) -> int:
     return layer * 16 + PROJ.index(proj) * 2
 

@@ -275,3 +275,46 @@ def test_streamed_70b_shaped_model(orc):
                 check_matrix(orc, o, lshapes, lbases, idx, mats[idx][0], mats[idx][1], m, n, bits, lvl, loff)
         del mats, dm
     lplan.close(); gplan.close(); ctx.close()
+
+
+def test_coupled_reordering_four_layers(orc):
+    """Four 8B-shaped decoder layers with the Llama coupling: the residual stream couples 28
+    dimensions of 4096 channels, each MLP 3 dimensions of 14336; against the oracle's summed scores."""
+    say("coupled reordering, 4 layers of the 8B shape")
+    dev = torch.device("cuda:0")
+    L = 4
+    model = synth.LLAMA3_8B
+    shapes, mats = [], []
+    for layer in range(L):
+        for name, r, c in synth.layer_shapes(model):
+            _, s = synth.make_matrix("student_t", r, c, seed=0, tid=synth.tensor_id(layer, name), device=dev)
+            shapes.append((r, c)); mats.append(s)
+    rg, cg, ng, seg = synth.llama_coupling(model, L)
+    ctx = sb.Context(0, torch.cuda.current_stream().cuda_stream)
+    plan = sb.Plan(ctx, shapes, 128, 128, [2, 3, 4])
+    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device=dev)
+    rp = torch.empty(sum(r for r, _ in shapes), dtype=torch.int32, device=dev)
+    cp = torch.empty(sum(c for _, c in shapes), dtype=torch.int32, device=dev)
+    dm = [sb.matrix(None, s) for s in mats]
+    plan.reorder_coupled_all(dm, rg, cg, ng, seg, rp, cp, ws)
+    torch.cuda.synchronize()
+    t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+    t0.record(); plan.reorder_coupled_all(dm, rg, cg, ng, seg, rp, cp, ws); t1.record()
+    torch.cuda.synchronize()
+    say("  coupled reorder of 4 layers: %.2f ms" % t0.elapsed_time(t1))
+    rp, cp = rp.cpu().numpy(), cp.cpu().numpy()
+    scores = [orc.channel_scores(s.cpu().numpy()) for s in mats]
+    members = {}
+    for i, g in enumerate(rg):
+        if g >= 0: members.setdefault(g, []).append(scores[i][0])
+    for i, g in enumerate(cg):
+        if g >= 0: members.setdefault(g, []).append(scores[i][1])
+    assert len(members[0]) == 7 * L and all(len(members[1 + l]) == 3 for l in range(L))
+    gperm = {g: orc.coupled_perm(m) for g, m in members.items()}
+    ro = co = 0
+    for i, (r, c) in enumerate(shapes):
+        for got, g, n in ((rp[ro:ro + r], rg[i], r), (cp[co:co + c], cg[i], c)):
+            want = np.arange(n, dtype=np.int32) if g == -2 else gperm[g]
+            np.testing.assert_array_equal(got, want)
+        ro, co = ro + r, co + c
+    plan.close(); ctx.close()

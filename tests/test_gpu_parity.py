@@ -209,6 +209,75 @@ def test_cost_table_degenerate_groups(orc, ctx, dev):
     plan.close()
 
 
+# ------------------------------------------------------------------------ coupled reordering
+def test_coupled_reordering(orc, ctx, dev):
+    """A toy decoder layer: the residual stream (hidden = 256) couples the columns of q, v, up, gate
+    and the rows of o, down; the MLP activation (512) couples the rows of up, gate and the columns of
+    down; the value/output activation couples the rows of v and the columns of o inside heads of 64;
+    the rows of q stay fixed.  One independent matrix rides along."""
+    say("coupled reordering")
+    H, F, HD = 256, 512, 64
+    names = ["q", "v", "o", "up", "gate", "down", "free"]
+    shapes = [(H, H), (H, H), (H, H), (F, H), (F, H), (H, F), (128, 384)]
+    RES, MLP, ATT = 0, 1, 2
+    I, FX = sb.DIM_INDEPENDENT, sb.DIM_FIXED
+    row_group = [FX, ATT, RES, MLP, MLP, RES, I]
+    col_group = [RES, RES, ATT, RES, RES, MLP, I]
+    segment = [0, 0, HD]
+    mats = [synth.make_matrix("student_t", r, c, seed=21, tid=i) for i, (r, c) in enumerate(shapes)]
+    plan, ws = make_plan(ctx, shapes, 64, 64, [2, 3, 4], dev)
+    dS = [S.to(dev) for _, S in mats]
+    rp = torch.full((sum(r for r, _ in shapes),), -7, dtype=torch.int32, device=dev)
+    cp = torch.full((sum(c for _, c in shapes),), -7, dtype=torch.int32, device=dev)
+    plan.reorder_coupled_all([sb.matrix(None, s_) for s_ in dS], row_group, col_group, 3, segment, rp, cp, ws)
+    torch.cuda.synchronize()
+    rp, cp = rp.cpu().numpy(), cp.cpu().numpy()
+
+    scores = [orc.channel_scores(S.numpy()) for _, S in mats]       # (row scores, column scores) per matrix
+    members = {g: [] for g in (RES, MLP, ATT)}
+    for i, g in enumerate(row_group):                               # member order: all rows, then all columns
+        if g >= 0:
+            members[g].append(scores[i][0])
+    for i, g in enumerate(col_group):
+        if g >= 0:
+            members[g].append(scores[i][1])
+    gperm = {g: orc.coupled_perm(members[g], segment[g]) for g in members}
+    ro = co = 0
+    for i, (r, c) in enumerate(shapes):
+        got_r, got_c = rp[ro:ro + r], cp[co:co + c]
+        for got, g, own, n in ((got_r, row_group[i], scores[i][0], r), (got_c, col_group[i], scores[i][1], c)):
+            if g == FX:
+                want = np.arange(n, dtype=np.int32)
+            elif g == I:
+                want = orc.argsort_desc(own)
+            else:
+                want = gperm[g]
+            np.testing.assert_array_equal(got, want, err_msg="%s group %d" % (names[i], g))
+        ro, co = ro + r, co + c
+    # the attention permutation stays inside its heads
+    att = gperm[ATT]
+    assert all(att[h * HD:(h + 1) * HD].min() == h * HD and att[h * HD:(h + 1) * HD].max() == (h + 1) * HD - 1
+               for h in range(H // HD))
+    plan.close()
+
+
+def test_coupled_reordering_rejects_unequal_members(ctx, dev):
+    say("coupled reordering: unequal members")
+    shapes = [(128, 256), (256, 128)]
+    plan, ws = make_plan(ctx, shapes, 64, 64, [2, 4], dev)
+    dS = [torch.ones(r, c, dtype=torch.float32, device=dev) for r, c in shapes]
+    rp = torch.empty(384, dtype=torch.int32, device=dev)
+    cp = torch.empty(384, dtype=torch.int32, device=dev)
+    with pytest.raises(sb.SbitsError) as e:                         # rows of both: 128 vs 256
+        plan.reorder_coupled_all([sb.matrix(None, s_) for s_ in dS], [0, 0], [-1, -1], 1, None, rp, cp, ws)
+    assert e.value.status == sb.ERR_BAD_SHAPE
+    plan.reorder_coupled_all([sb.matrix(None, s_) for s_ in dS], [0, -1], [-1, 0], 1, [32], rp, cp, ws)   # 128 and 128
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(rp[:128].cpu().numpy(), cp[256:].cpu().numpy())
+    np.testing.assert_array_equal(rp[:128].cpu().numpy(), np.arange(128))   # all scores equal: ties to the lower index
+    plan.close()
+
+
 # ------------------------------------------------- reordering and cost table in one pass
 ONE_PASS_CASES = [
     # shapes, m, n, bits

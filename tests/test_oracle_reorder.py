@@ -116,3 +116,62 @@ def test_bf16_helpers_round_to_nearest_even(orc):
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5, 0.0], np.float32)
     h = orc.f32_to_bf16(x)
     np.testing.assert_array_equal(orc.bf16_to_f32(h), np.array([1.0, 1.0 + 2.0 ** -6, -2.5, 0.0], np.float32))
+
+
+# ------------------------------------------------- coupled reordering (App. "Channel Reordering")
+def test_coupled_scores_hand_example(orc):
+    """Two coupled dimensions with scores [1,5,3] and [4,0,3]: the sums are [5,5,6], so channel 2
+    comes first and the tie between channels 0 and 1 goes to the lower index."""
+    a, b = np.array([1, 5, 3], np.float32), np.array([4, 0, 3], np.float32)
+    np.testing.assert_array_equal(orc.group_scores([a, b]), np.array([5, 5, 6], np.float32))
+    np.testing.assert_array_equal(orc.coupled_perm([a, b]), [2, 0, 1])
+
+
+def test_coupled_scores_are_summed_member_after_member(orc):
+    """fp32 addition is not associative: (1e8 + 1) + (-1e8) = 0 but 1e8 + (-1e8) + 1 = 1."""
+    m = [np.array([1e8], np.float32), np.array([1.0], np.float32), np.array([-1e8], np.float32)]
+    assert orc.group_scores(m)[0] == 0.0
+    assert orc.group_scores([m[0], m[2], m[1]])[0] == 1.0
+
+
+def test_coupled_perm_of_one_member_is_the_plain_argsort(orc):
+    rng = np.random.default_rng(3)
+    s = rng.random(777).astype(np.float32)
+    np.testing.assert_array_equal(orc.coupled_perm([s]), orc.argsort_desc(s))
+
+
+def test_pieces_keep_their_channels(orc):
+    rng = np.random.default_rng(4)
+    s = rng.integers(0, 5, 96).astype(np.float32)                # many ties
+    perm = orc.argsort_desc_pieces(s, 32)
+    for p0 in range(0, 96, 32):
+        piece = perm[p0:p0 + 32]
+        assert sorted(piece) == list(range(p0, p0 + 32))          # a permutation of its own piece
+        np.testing.assert_array_equal(piece - p0, np.argsort(-s[p0:p0 + 32], kind="stable"))
+    np.testing.assert_array_equal(orc.argsort_desc_pieces(s, 0), orc.argsort_desc(s))
+
+
+def test_coupled_reordering_preserves_a_gated_mlp(orc):
+    """y = Wd (relu(Wg x) * (Wu x)): the rows of Wg, Wu and the columns of Wd carry the same
+    activation; the input side of Wg, Wu and the output side of Wd carry the residual stream.
+    Reordered with shared permutations, the block computes the same function up to the residual
+    permutation: y'[i] = y[q[i]] for x'[j] = x[q[j]].  Small integers: exact in float64."""
+    rng = np.random.default_rng(5)
+    H, F = 24, 40
+    Wg, Wu = rng.integers(-3, 4, (F, H)), rng.integers(-3, 4, (F, H))
+    Wd = rng.integers(-3, 4, (H, F))
+    Sg, Su, Sd = (rng.random((F, H)).astype(np.float32), rng.random((F, H)).astype(np.float32),
+                  rng.random((H, F)).astype(np.float32))
+    rs_g, cs_g = orc.channel_scores(Sg)
+    rs_u, cs_u = orc.channel_scores(Su)
+    rs_d, cs_d = orc.channel_scores(Sd)
+    p = orc.coupled_perm([rs_g, rs_u, cs_d])                      # the MLP's inner activation
+    q = orc.coupled_perm([rs_d, cs_g, cs_u])                      # the residual stream
+    bits = lambda M: M.astype(np.uint16)                          # gather moves 16-bit patterns
+    g2 = orc.gather(bits(Wg + 8), Sg, p, q)[0].astype(np.int64) - 8
+    u2 = orc.gather(bits(Wu + 8), Su, p, q)[0].astype(np.int64) - 8
+    d2 = orc.gather(bits(Wd + 8), Sd, q, p)[0].astype(np.int64) - 8
+    x = rng.integers(-5, 6, H)
+    y = Wd @ (np.maximum(Wg @ x, 0) * (Wu @ x))
+    y2 = d2 @ (np.maximum(g2 @ x[q], 0) * (u2 @ x[q]))
+    np.testing.assert_array_equal(y2, y[q])
