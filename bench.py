@@ -35,7 +35,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--layers", type=int, default=32, help="decoder layers (32 = the full 8B-shaped model)")
     ap.add_argument("--budget", type=float, default=2.5, help="average bits per weight")
-    ap.add_argument("--block", type=int, default=128)
+    ap.add_argument("--block", type=int, default=128, help="block rows = block columns")
+    ap.add_argument("--block-rows", type=int, default=0, help="block rows if different from --block")
     ap.add_argument("--bits", type=str, default="1,2,3,4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-route-check", action="store_true",
@@ -101,7 +102,8 @@ def main():
     dev = torch.device("cuda:0")
     sb.load()
     bits = [int(b) for b in args.bits.split(",")]
-    m = n = args.block
+    n = args.block
+    m = args.block_rows or args.block
     K = len(bits)
     model = dict(synth.LLAMA3_8B)
     shapes = []

@@ -318,3 +318,30 @@ def test_coupled_reordering_four_layers(orc):
             np.testing.assert_array_equal(got, want)
         ro, co = ro + r, co + c
     plan.close(); ctx.close()
+
+
+def test_paper_default_search_space(orc):
+    """Two 8B-shaped decoder layers in the paper's own search space (Sec. 5 "Implementation"):
+    64 x 128 blocks, group size 128, bitwidths {1,...,8}, budget 3.0."""
+    say("paper-default search space: 64x128 blocks, bits 1..8")
+    dev = torch.device("cuda:0")
+    m, n = 64, 128
+    bits, avg = [1, 2, 3, 4, 5, 6, 7, 8], 3.0
+    mats, shapes = [], []
+    for layer in range(2):
+        for name, r, c in synth.layer_shapes(synth.LLAMA3_8B):
+            w, s = synth.make_matrix("student_t", r, c, seed=0, tid=synth.tensor_id(layer, name), device=dev)
+            mats.append((w, s)); shapes.append((r, c))
+    rc, st, o, bases = run_search(dev, mats, shapes, m, n, bits, avg)
+    cost = o["cost"].cpu().numpy()
+    assert cost.shape == (2 * 26624, 8) and np.all(np.isfinite(cost)) and np.all(np.diff(cost, axis=1) < 0)
+    rc_o, level, st_o, _ = orc.allocate(cost, bits, avg)
+    assert rc == rc_o == 0 and st == st_o
+    np.testing.assert_array_equal(o["level"].cpu().numpy(), level)
+    off = orc.offsets(level, m, n, bits)
+    np.testing.assert_array_equal(o["byte_off"].cpu().numpy(), off)
+    assert st["bits_used"] <= st["bits_budget"] == int(avg * cost.shape[0])
+    assert len(np.unique(level)) >= 4                         # a real mixture of bitwidths
+    for idx in (1, 3, 13):                                    # k of layer 0, o of layer 0, down of layer 1
+        say("  matrix", idx, shapes[idx])
+        check_matrix(orc, o, shapes, bases, idx, mats[idx][0], mats[idx][1], m, n, bits, level, off)
