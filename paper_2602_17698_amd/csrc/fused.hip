@@ -60,8 +60,10 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <int LPG, int K, int CPL, int RS, int T>
-__global__ __launch_bounds__(T, (T >= 1024 ? 4 : 2))
+// Launched with T = the smallest multiple of 64 threads whose CPL chunks per lane cover a row
+// (T <= TMAX), so that rows whose chunk count is no power of two leave no lanes idle.
+template <int LPG, int K, int CPL, int RS, int TMAX>
+__global__ __launch_bounds__(TMAX, (TMAX >= 1024 ? 4 : 2))
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
@@ -76,6 +78,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     static_assert(NIT % NG == 0 && NG % NI == 0 && 8 % RS == 0, "step shape");
 
     const int tid = (int)threadIdx.x;
+    const int T = (int)blockDim.x;                   // a multiple of 64, at most TMAX
     const int lig = tid % LPG;
     const int mem = funi(find_matrix(wg_start, n_members, (int)blockIdx.x));
     const MatDesc &d = descs[funi(members[mem])];
@@ -315,8 +318,8 @@ void octet_finish_kernel(const float *__restrict__ part, int64_t NK, int K, int 
 // (written and read by lanes of one wave only) and leave as 32-bit words.
 // T threads per workgroup; launch bounds ask for 4 waves per SIMD (two workgroups of 512 or one
 // of 1024 per CU), which the kernel's ~120 registers allow.
-template <int LPG, int CPL, int RS, int T>
-__global__ __launch_bounds__(T, 4)
+template <int LPG, int CPL, int RS, int TMAX>
+__global__ __launch_bounds__(TMAX, 4)
 void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
@@ -330,6 +333,7 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     static_assert(8 % RS == 0, "step shape");
 
     const int tid = (int)threadIdx.x;
+    const int T = (int)blockDim.x;                   // a multiple of 64, at most TMAX
     const int lig = tid % LPG;
     const int mem = funi(find_matrix(wg_start, n_members, (int)blockIdx.x));
     const MatDesc &d = descs[funi(members[mem])];
@@ -504,11 +508,19 @@ struct FusedLaunch {
     int64_t cols;
 };
 
-template <int LPG, int K, int CPL, int RS, int T>
+// threads per workgroup: the chunks of a row spread over CPL per lane, rounded up to whole waves
+static int fused_threads(int64_t cols, int cpl, int tmax)
+{
+    const int64_t need = ((cols / 8 + cpl - 1) / cpl + 63) / 64 * 64;
+    return (int)(need < 64 ? 64 : (need > tmax ? tmax : need));
+}
+
+template <int LPG, int K, int CPL, int RS, int TMAX>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
+    const int T = fused_threads(a.cols, CPL, TMAX);
     static bool attr_done = false;
-    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, T>;
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX>;
     if (!attr_done) {
         SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
@@ -562,11 +574,12 @@ struct FusedPackLaunch {
     int64_t cols;
 };
 
-template <int LPG, int CPL, int RS, int T>
+template <int LPG, int CPL, int RS, int TMAX>
 static int launch_gpack_g(sbits_ctx *ctx, const FusedPackLaunch &a)
 {
+    const int T = fused_threads(a.cols, CPL, TMAX);
     static bool attr_done = false;
-    auto *fn = &gather_pack_kernel<LPG, CPL, RS, T>;
+    auto *fn = &gather_pack_kernel<LPG, CPL, RS, TMAX>;
     if (!attr_done) {
         SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
