@@ -168,6 +168,21 @@ def quant_group(w, bits):
     return q, np.float32(sc.value), np.float32(ze.value)
 
 
+def surrogates(Wp_u16, Gp, m, n, bits, level):
+    """(s_up, s_down) per block of one reordered matrix at the blocks' current levels."""
+    Wp_u16 = _u16(Wp_u16)
+    Gp = _f32(Gp)
+    R, Cc = Wp_u16.shape
+    b = np.ascontiguousarray(bits, np.int32)
+    lv = np.ascontiguousarray(level, np.uint8)
+    nb = (R // m) * (Cc // n)
+    assert lv.size == nb
+    up, dn = np.empty(nb, np.float32), np.empty(nb, np.float32)
+    lib().orc_surrogates(_p(Wp_u16), _p(Gp), C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n), _p(b), _p(lv),
+                         _p(up), _p(dn))
+    return up, dn
+
+
 def cost_table(Wp_u16, Sp, m, n, bits):
     Wp_u16 = _u16(Wp_u16)
     Sp = _f32(Sp)

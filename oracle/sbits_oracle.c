@@ -243,6 +243,63 @@ void orc_cost_table(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
     free(wrow); free(grid); free(O); free(osum);
 }
 
+/* Dynamic-sensitivity surrogates of one iteration (App. "choice of sensitivity statistics",
+ * the two displayed equations): for every block at its CURRENT bitwidth b (level[] indexes bits[]),
+ *   s_up   = sum over the block of  g * (w - what)          (signed, first order gain of one more bit)
+ *   s_down = 2^-b * sum over the block of |g * what|        (expected loss of one bit less)
+ * with what = fmaf(q, scale, min) the dequantized weight of the block's row grid and g the
+ * gradient at the quantized model (an input here).  Sums in the canonical order of the cost
+ * table; the chunk steps are a = fmaf(g, w - what, a) and a = a + |g * what|.
+ * Wp, Gp: reordered, dense; level: one entry per block of THIS matrix (row-major block grid). */
+void orc_surrogates(const uint16_t *Wp, const float *Gp, int64_t R, int64_t C, int m, int n,
+                    const int32_t *bits, const uint8_t *level, float *s_up, float *s_down)
+{
+    int64_t nbr = R / m, nbc = C / n;
+    int nj = n / 8, no = m / 8;
+    float *wrow = (float *)malloc(sizeof(float) * (size_t)n);
+    grid_t *grid = (grid_t *)malloc(sizeof(grid_t) * (size_t)m);
+    float *O = (float *)malloc(sizeof(float) * (size_t)nj);
+    float *osum = (float *)malloc(sizeof(float) * (size_t)no);
+
+    for (int64_t I = 0; I < nbr; ++I)
+    for (int64_t J = 0; J < nbc; ++J) {
+        const int b = bits[level[I * nbc + J]];
+        for (int r = 0; r < m; ++r) {
+            const uint16_t *src = Wp + (I * m + r) * C + J * n;
+            for (int e = 0; e < n; ++e) wrow[e] = bf16_to_f32(src[e]);
+            grid[r] = group_grid(wrow, n, b);
+        }
+        for (int which = 0; which < 2; ++which) {
+            for (int o = 0; o < no; ++o) {
+                for (int j = 0; j < nj; ++j) {
+                    float E[8];
+                    for (int rr = 0; rr < 8; ++rr) {
+                        int r = o * 8 + rr;
+                        const grid_t *g = &grid[r];
+                        const uint16_t *wsrc = Wp + (I * m + r) * C + J * n + j * 8;
+                        const float *gsrc = Gp + (I * m + r) * C + J * n + j * 8;
+                        float a = 0.0f;
+                        for (int e = 0; e < 8; ++e) {
+                            float w = bf16_to_f32(wsrc[e]);
+                            int q = quant_code(w - g->mn, g);
+                            float what = fmaf((float)q, g->scale, g->mn);
+                            if (which == 0) a = fmaf(gsrc[e], w - what, a);
+                            else a = a + fabsf(gsrc[e] * what);
+                        }
+                        E[rr] = a;
+                    }
+                    O[j] = pair_tree(E, 8);
+                }
+                osum[o] = pair_tree(O, nj);
+            }
+            float t = pair_tree(osum, no);
+            if (which == 0) s_up[I * nbc + J] = t;
+            else s_down[I * nbc + J] = ldexpf(t, -b);
+        }
+    }
+    free(wrow); free(grid); free(O); free(osum);
+}
+
 /* ------------------------------------------------- a6-a8: scalable greedy */
 
 static int ceil_log2_i64(int64_t v)

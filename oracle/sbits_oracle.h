@@ -87,6 +87,11 @@ void orc_quant_group(const float *w, int n, int bits,
 void orc_cost_table(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
                     int m, int n, const int32_t *bits, int K, float *cost);
 
+/* dynamic-sensitivity surrogates s_up, s_down per block at the blocks' current bitwidths
+ * (App. "choice of sensitivity statistics") */
+void orc_surrogates(const uint16_t *Wp, const float *Gp, int64_t R, int64_t C, int m, int n,
+                    const int32_t *bits, const uint8_t *level, float *s_up, float *s_down);
+
 /* ---- a6-a8: scalable greedy search (paper Algorithm 2) on a cost table ---- */
 typedef struct {
     double  gamma0, gammaT;   /* update ratios; paper Sec. 5: 0.05 and 0.02    */
