@@ -198,6 +198,22 @@ int  sbits_gather_cost_supported(const sbits_plan *plan);
 int  sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                            const int32_t *col_perm, void *w_re_bf16, float *cost, void *ws);
 
+/* ---- dynamic-sensitivity surrogates (paper App. "choice of sensitivity
+ * statistics", the two displayed equations; Algorithm 2 line 5) ------------------
+ * One pass over the ORIGINAL weights and a gradient taken at the currently
+ * quantized model (mats[i].sens holds the gradient g here: fp32, any sign, same
+ * layout rules as the sensitivity), reordered on the fly like
+ * sbits_gather_cost_all.  For every block at its CURRENT bitwidth b =
+ * bitwidths[level[i]]:
+ *   s_up[i]   = sum over the block of g * (w - what)       what = fma(q, scale, min),
+ *   s_down[i] = 2^-b * sum over the block of |g * what|    the dequantized weight
+ * (row-group grid and code q as in sbits_pack; sums in the order of the cost
+ * table).  level: DEVICE uint8[N]; s_up, s_down: DEVICE float[N].  Same shape
+ * limits as sbits_gather_cost_all, else SBITS_ERR_UNIMPLEMENTED.  Uses ws.        */
+int  sbits_surrogates_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                          const int32_t *col_perm, const uint8_t *level,
+                          float *s_up, float *s_down, void *ws);
+
 /* ---- scalable greedy search (paper Algorithm 2 with the relaxed step Eq. 5) ---
  * Runs on the device over the cost table: marginal change per bit from the
  * table, radix selection of the top-k / bottom-k sets on (value, index) keys,

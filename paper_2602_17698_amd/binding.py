@@ -24,7 +24,7 @@ EXPORTS = [
     "sbits_reorder", "sbits_reorder_all", "sbits_channel_scores", "sbits_gather", "sbits_gather_all",
     "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
-    "sbits_reorder_coupled_all",
+    "sbits_reorder_coupled_all", "sbits_surrogates_all",
     "sbits_allocate", "sbits_offsets", "sbits_pack", "sbits_search",
 ]
 
@@ -214,6 +214,12 @@ class Plan:
         arr = (Matrix * len(mats))(*mats)
         return _check(load().sbits_gather_cost_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(w_re),
                                                    _ptr(cost), _ptr(ws)), "sbits_gather_cost_all")
+
+    def surrogates_all(self, mats, row_perm, col_perm, level, s_up, s_down, ws):
+        """mats: matrix(w, g) with the gradient in the place of the sensitivity."""
+        arr = (Matrix * len(mats))(*mats)
+        return _check(load().sbits_surrogates_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(level),
+                                                  _ptr(s_up), _ptr(s_down), _ptr(ws)), "sbits_surrogates_all")
 
     def gather_pack_all(self, mats, row_perm, col_perm, level, byte_off, codes, scale, zero, ws):
         arr = (Matrix * len(mats))(*mats)

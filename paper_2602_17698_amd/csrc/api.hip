@@ -313,6 +313,19 @@ int sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int3
     return sbits_launch_gather_cost_all(plan, row_perm, col_perm, w_re_bf16, cost, ws);
 }
 
+int sbits_surrogates_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
+                         const int32_t *col_perm, const uint8_t *level, float *s_up, float *s_down, void *ws)
+{
+    int rc = check_all(plan, mats, true, true);
+    if (rc) return rc;
+    if (!row_perm || !col_perm || !level || !s_up || !s_down || !aligned16(col_perm) || !ws_ok(ws))
+        return SBITS_ERR_INVALID_ARG;
+    if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
+    if ((rc = need_device(plan))) return rc;
+    if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    return sbits_launch_surrogates_all(plan, row_perm, col_perm, level, s_up, s_down, ws);
+}
+
 int sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                           const int32_t *col_perm, const uint8_t *level, const int64_t *byte_off,
                           uint8_t *codes, float *scale, float *zero, void *ws)

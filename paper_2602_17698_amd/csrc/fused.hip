@@ -23,6 +23,7 @@
 
 #include "cost_core.hpp"
 #include "pack_core.hpp"
+#include "surrogate_core.hpp"
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
 
@@ -62,19 +63,24 @@ __device__ __forceinline__ void lds_barrier()
 
 // Launched with T = the smallest multiple of 64 threads whose CPL chunks per lane cover a row
 // (T <= TMAX), so that rows whose chunk count is no power of two leave no lanes idle.
-template <int LPG, int K, int CPL, int RS, int TMAX>
+// SUR = false: the block x bitwidth cost table (K candidates per block).
+// SUR = true : the dynamic-sensitivity surrogates (K = 2 sums per block, at the block's current
+//              level[]; the "sensitivity" input is the gradient).
+template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR>
 __global__ __launch_bounds__(TMAX, (TMAX >= 1024 ? 4 : 2))
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
-                        uint16_t *__restrict__ w_re_all, float *__restrict__ part, GridConsts gc)
+                        uint16_t *__restrict__ w_re_all, float *__restrict__ part, GridConsts gc,
+                        const uint8_t *__restrict__ level)
 {
+    static_assert(!SUR || K == 2, "two sums per block");
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int rowsrc[FU_OPU * 8];
     constexpr int NIT = RS * CPL;                    // rows x chunks scored per step
     using DP = DivPlan<LPG, K>;
     constexpr int NG = NIT > 2 ? 2 : NIT;            // of which NG are held in registers at a time
-    constexpr int NI = DP::RP < NG ? DP::RP : NG;    // and NI share a round of divisions
+    constexpr int NI = SUR ? NG : (DP::RP < NG ? DP::RP : NG);   // and NI share a round of divisions
     static_assert(NIT % NG == 0 && NG % NI == 0 && 8 % RS == 0, "step shape");
 
     const int tid = (int)threadIdx.x;
@@ -168,6 +174,8 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     float t1[CPL][K], t2[CPL][K], t3[CPL][K];
     uint16_t *const wout = w_re_all + d.elem_off;
     const int nsteps = noct * (8 / RS);
+    LevelConsts lk[SUR ? CPL : 1];                   // SUR: the current grid of each chunk's block
+    int curI = -1;
 
     prefetch(0);
     for (int st = 0; st < nsteps; ++st) {
@@ -178,6 +186,17 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         const int row = st * RS;                     // first row of the step inside the run
         const int rr0 = row & 7;
         float last[CPL][K];
+        if constexpr (SUR) {
+            const int Inow = (oct0 + (row >> 3)) / opb;          // block row of this step
+            if (Inow != curI) {
+                curI = Inow;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    const int J = min((tid + T * c) / LPG, nbc - 1);
+                    lk[c] = level_consts(gc, level[d.block_base + (int64_t)Inow * nbc + J]);
+                }
+            }
+        }
         // Items (item = rs * CPL + c) are picked out of the staged rows: all LDS reads are issued
         // here; the items are scored NG at a time, so the reads of the later ones complete under
         // the arithmetic of the earlier ones.
@@ -229,7 +248,14 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 #pragma unroll
                     for (int e = 0; e < 8; ++e) s[j][e] = gs[i0 + j][e];
                 }
-                quant_cost_round<LPG, K, NI>(wr, s, dp, out);
+                if constexpr (SUR) {
+                    LevelConsts lr[NI];
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) lr[j] = lk[(g0 + i0 + j) % CPL];
+                    surrogate_round<LPG, NI>(wr, s, lr, lig, out);
+                } else {
+                    quant_cost_round<LPG, K, NI>(wr, s, dp, out);
+                }
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
                     const int rs = (g0 + i0 + j) / CPL, c = (g0 + i0 + j) % CPL;
@@ -496,6 +522,55 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     }
 }
 
+// surrogates: s_up[b] = tree over the octets of sum 0, s_down[b] = 2^-bits * tree over those of sum 1
+__global__ __launch_bounds__(256)
+void surrogate_finish_kernel(const float *__restrict__ part, int64_t N, int opb, const uint8_t *__restrict__ level,
+                             GridConsts gc, float *__restrict__ s_up, float *__restrict__ s_down)
+{
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= 2 * N) return;
+    const int64_t b = q >> 1;
+    const int which = (int)(q & 1);
+    const float *p = part + b * opb * 2 + which;
+    float v;
+    if (opb <= 8) {
+        v = tree_upto8(p, 2, opb);
+    } else {
+        float t1 = 0.0f, t2 = 0.0f, t3 = 0.0f, t4 = 0.0f;
+        v = 0.0f;
+        const int ng = opb >> 3;
+        for (int g = 0; g < ng; ++g) {
+            v = tree_upto8(p + (int64_t)g * 16, 2, 8);
+            if (g & 1) {
+                v = t1 + v;
+                if (g & 2) {
+                    v = t2 + v;
+                    if (g & 4) {
+                        v = t3 + v;
+                        if (g & 8) v = t4 + v;
+                        else t4 = v;
+                    } else {
+                        t3 = v;
+                    }
+                } else {
+                    t2 = v;
+                }
+            } else {
+                t1 = v;
+            }
+        }
+    }
+    if (which == 0) {
+        s_up[b] = v;
+    } else {
+        int bits = gc.bits[0];
+#pragma unroll
+        for (int cc = 1; cc < 8; ++cc)
+            if (level[b] == cc) bits = gc.bits[cc];
+        s_down[b] = ldexpf(v, -bits);
+    }
+}
+
 struct FusedLaunch {
     const MatDesc *descs;
     const int *members, *wg_start;
@@ -506,6 +581,7 @@ struct FusedLaunch {
     float *part;
     GridConsts gc;
     int64_t cols;
+    const uint8_t *level;     // surrogates only
 };
 
 // threads per workgroup: the chunks of a row spread over CPL per lane, rounded up to whole waves
@@ -515,12 +591,12 @@ static int fused_threads(int64_t cols, int cpl, int tmax)
     return (int)(need < 64 ? 64 : (need > tmax ? tmax : need));
 }
 
-template <int LPG, int K, int CPL, int RS, int TMAX>
+template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int T = fused_threads(a.cols, CPL, TMAX);
     static bool attr_done = false;
-    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX>;
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, SUR>;
     if (!attr_done) {
         SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
@@ -528,7 +604,7 @@ static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
     }
     const size_t lds = (size_t)RS * a.cols * 6;
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
-                       a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc);
+                       a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc, a.level);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
@@ -537,9 +613,19 @@ template <int LPG, int K>
 static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int64_t chunks = a.cols / 8;
-    if (chunks <= 512) return launch_fused_g<LPG, K, 1, 2, 512>(ctx, a);
-    if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512>(ctx, a);
-    if (chunks <= 2048) return launch_fused_g<LPG, K, 4, 1, 512>(ctx, a);
+    if (chunks <= 512) return launch_fused_g<LPG, K, 1, 2, 512, false>(ctx, a);
+    if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, false>(ctx, a);
+    if (chunks <= 2048) return launch_fused_g<LPG, K, 4, 1, 512, false>(ctx, a);
+    return SBITS_ERR_BAD_SHAPE;
+}
+
+template <int LPG>
+static int launch_surrogates_l(sbits_ctx *ctx, const FusedLaunch &a)
+{
+    const int64_t chunks = a.cols / 8;
+    if (chunks <= 512) return launch_fused_g<LPG, 2, 1, 2, 512, true>(ctx, a);
+    if (chunks <= 1024) return launch_fused_g<LPG, 2, 2, 1, 512, true>(ctx, a);
+    if (chunks <= 2048) return launch_fused_g<LPG, 2, 4, 1, 512, true>(ctx, a);
     return SBITS_ERR_BAD_SHAPE;
 }
 
@@ -618,7 +704,8 @@ bool sbits_fused_shapes_ok(const sbits_plan *plan)
 size_t sbits_fused_ws_bytes(const sbits_plan *plan)
 {
     if (!sbits_fused_shapes_ok(plan)) return 0;
-    return sbits_align_up((size_t)plan->N * (size_t)(plan->m / 8) * (size_t)plan->K * 4, 256);
+    const size_t per_octet = (size_t)(plan->K > 2 ? plan->K : 2);     // the surrogates keep two sums per block
+    return sbits_align_up((size_t)plan->N * (size_t)(plan->m / 8) * per_octet * 4, 256);
 }
 
 // every source row must start on a 16-byte boundary (the rows are staged with 128-bit loads)
@@ -741,6 +828,44 @@ int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, cons
         if (a.total_wg == 0) continue;
         const int rc = plan->n == 64 ? launch_gpack_l<8>(ctx, a) : launch_gpack_l<16>(ctx, a);
         if (rc) return rc;
+    }
+    return SBITS_OK;
+}
+
+// dynamic-sensitivity surrogates of all matrices: the one-pass kernel in its second mode, then the
+// tree over the octets with the 2^-bits factor of s_down
+int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                                const uint8_t *level, float *s_up, float *s_down, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    if (!sbits_fused_shapes_ok(plan) || !sbits_fused_layout_ok(plan, true)) return SBITS_ERR_BAD_SHAPE;
+    int *d_mem, *d_pre;
+    int rc0 = fused_classes(plan, ws, &d_mem, &d_pre);
+    if (rc0) return rc0;
+    FusedLaunch a;
+    memset(&a, 0, sizeof a);
+    sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
+    a.descs = sbits_desc_ptr(ws);
+    a.row_perm = row_perm;
+    a.col_perm = col_perm;
+    a.m = plan->m;
+    a.w_re = nullptr;
+    a.part = static_cast<float *>(sbits_scratch(plan, ws));
+    a.level = level;
+    for (const sbits_plan::FusedClass &fc : plan->fused_classes) {
+        a.members = d_mem + fc.first;
+        a.wg_start = d_pre + fc.pre_first;
+        a.n_members = fc.n;
+        a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
+        a.cols = fc.cols;
+        if (a.total_wg == 0) continue;
+        const int rc = plan->n == 64 ? launch_surrogates_l<8>(ctx, a) : launch_surrogates_l<16>(ctx, a);
+        if (rc) return rc;
+    }
+    if (plan->N > 0) {
+        hipLaunchKernelGGL(surrogate_finish_kernel, dim3((unsigned)((2 * plan->N + 255) / 256)), dim3(256), 0,
+                           ctx->stream, a.part, plan->N, plan->m / 8, level, a.gc, s_up, s_down);
+        SBITS_HIP(ctx, hipGetLastError());
     }
     return SBITS_OK;
 }

@@ -99,6 +99,8 @@ bool sbits_fused_layout_ok(const sbits_plan *plan, bool need_s);
 size_t sbits_fused_ws_bytes(const sbits_plan *plan);
 int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                                  void *w_re, float *cost, void *ws);
+int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
+                                const uint8_t *level, float *s_up, float *s_down, void *ws);
 int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                                  const uint8_t *level, const int64_t *byte_off, uint8_t *codes, float *scale,
                                  float *zero, void *ws);

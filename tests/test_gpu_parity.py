@@ -355,6 +355,38 @@ def test_gather_pack_one_pass(orc, ctx, dev, shapes, m, n, bits):
     plan.close()
 
 
+@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES)
+def test_surrogates_one_pass(orc, ctx, dev, shapes, m, n, bits):
+    """Dynamic-sensitivity surrogates from the original weights, a signed gradient, the
+    permutations and the current levels == oracle gather + surrogates, bit for bit."""
+    say("surrogates", shapes, m, n, bits)
+    plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
+    N = plan.num_blocks()
+    mats = [synth.make_matrix("student_t", r, c, seed=13, tid=i) for i, (r, c) in enumerate(shapes)]
+    g = torch.Generator().manual_seed(23)
+    grads = [torch.randn(r, c, generator=g) * torch.exp(torch.randn(r, 1, generator=g)) for r, c in shapes]
+    rps = [torch.randperm(r, generator=g).to(torch.int32) for r, _ in shapes]
+    cps = [torch.randperm(c, generator=g).to(torch.int32) for _, c in shapes]
+    level = np.random.default_rng(N).integers(0, len(bits), size=N).astype(np.uint8)
+    dW = [W.to(dev) for W, _ in mats]
+    dG = [G.to(dev) for G in grads]
+    s_up = torch.full((N,), -7.0, dtype=torch.float32, device=dev)
+    s_dn = torch.full((N,), -7.0, dtype=torch.float32, device=dev)
+    plan.surrogates_all([sb.matrix(w, g_) for w, g_ in zip(dW, dG)], torch.cat(rps).to(dev), torch.cat(cps).to(dev),
+                        torch.from_numpy(level).to(dev), s_up, s_dn, ws)
+    torch.cuda.synchronize()
+    ups, dns, base = [], [], 0
+    for (R, C), (W, _), G, rp, cp in zip(shapes, mats, grads, rps, cps):
+        Wp, Gp = orc.gather(to_np_bf16(W), G.numpy(), rp.numpy(), cp.numpy())
+        nb = (R // m) * (C // n)
+        u, d_ = orc.surrogates(Wp, Gp, m, n, bits, level[base:base + nb])
+        ups.append(u); dns.append(d_); base += nb
+    np.testing.assert_array_equal(s_up.cpu().numpy(), np.concatenate(ups))
+    np.testing.assert_array_equal(s_dn.cpu().numpy(), np.concatenate(dns))
+    assert np.any(np.concatenate(ups) < 0) and np.all(np.concatenate(dns) >= 0)
+    plan.close()
+
+
 def test_gather_cost_one_pass_refuses_other_shapes(ctx, dev):
     say("one-pass refuses")
     plan, ws = make_plan(ctx, [(64, 256)], 32, 256, [2, 4], dev)     # 256-column blocks: two-pass route only
