@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # x 1.000 after calibration against a plain 1 GiB copy; profiles/hbm_traffic_8_layers_pmc.md)
 COST_TRAFFIC_B_PER_WEIGHT = (5114570 * 2.0 + 1664) * 1024 / 1744830464
 # the same for the one-pass stage: both gather_cost launches + octet_finish
-ONE_PASS_TRAFFIC_B_PER_WEIGHT = ((3739337 + 1380016 + 13334) * 2.0 + 20593 + 7839 + 1664) * 1024 / 1744830464
+ONE_PASS_TRAFFIC_B_PER_WEIGHT = ((3739368 + 1378226 + 13328) * 2.0 + 20405 + 7594 + 1664) * 1024 / 1744830464
 
 
 def parse():
