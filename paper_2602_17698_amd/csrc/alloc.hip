@@ -22,6 +22,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "sbits_internal.hpp"
 
 namespace sbits {
@@ -472,8 +474,8 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     if (!ctx->pinned) SBITS_HIP(ctx, hipHostMalloc(&ctx->pinned, SBITS_PINNED_BYTES, hipHostMallocDefault));
     static_assert(offsetof(AllocState, job) <= SBITS_PINNED_BYTES, "state head must fit the pinned buffer");
     AllocState *hp = static_cast<AllocState *>(ctx->pinned);   // only the head (before job[]) is valid there
-    static AllocState h;                       // host image
-    memset(&h, 0, sizeof h);
+    std::vector<unsigned char> himg(sizeof(AllocState), 0);    // host image (66 KB: not on the stack)
+    AllocState &h = *reinterpret_cast<AllocState *>(himg.data());
     h.N = N;
     h.T = (long long)floor(avg_bits * (double)N);
     h.k = (long long)floor(prm->gamma0 * (double)N);

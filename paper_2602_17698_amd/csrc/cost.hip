@@ -329,12 +329,9 @@ static float finite_threshold(float qf)
 
 static int persistent_grid(sbits_ctx *ctx, int64_t total_units)
 {
-    static int n_cu = 0;
-    if (!n_cu) {
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess) n_cu = prop.multiProcessorCount;
-        if (n_cu <= 0) n_cu = 256;
-    }
+    int n_cu = 0;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device) != hipSuccess || n_cu <= 0)
+        n_cu = 256;
     const int64_t g = (int64_t)n_cu * 2;             // two workgroups (8 waves) per CU
     return (int)(total_units < g ? total_units : g);
 }

@@ -595,13 +595,9 @@ template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int T = fused_threads(a.cols, CPL, TMAX);
-    static bool attr_done = false;
     auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, SUR>;
-    if (!attr_done) {
-        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
-        attr_done = true;
-    }
+    SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
     const size_t lds = (size_t)RS * a.cols * 6;
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc, a.level);
@@ -664,13 +660,9 @@ template <int LPG, int CPL, int RS, int TMAX>
 static int launch_gpack_g(sbits_ctx *ctx, const FusedPackLaunch &a)
 {
     const int T = fused_threads(a.cols, CPL, TMAX);
-    static bool attr_done = false;
     auto *fn = &gather_pack_kernel<LPG, CPL, RS, TMAX>;
-    if (!attr_done) {
-        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
-        attr_done = true;
-    }
+    SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
     const size_t lds = (size_t)RS * a.cols * 2 + (size_t)(CPL * T / LPG) * ((size_t)RS * LPG * a.cmax + 8);
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.level, a.byte_off, a.codes, a.scale,

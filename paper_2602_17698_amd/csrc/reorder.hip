@@ -593,14 +593,10 @@ int sbits_launch_reorder(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, i
 
 static int gather_attr(sbits_ctx *ctx)
 {
-    static bool done = false;
-    if (!done) {
-        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<float>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<uint16_t>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        done = true;
-    }
+    SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<float>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gather_kernel<uint16_t>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     return SBITS_OK;
 }
 
