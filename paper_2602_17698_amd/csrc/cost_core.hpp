@@ -140,4 +140,30 @@ __device__ __forceinline__ float octet_tree_push(float v, int rr, float &t1, flo
     return v;
 }
 
+// The same for a row index that is only known at run time (but uniform over the wave): selects
+// instead of branches.  (Sums formed with a not yet written t are discarded by the selects.)
+__device__ __forceinline__ float octet_tree_push_rt(float v, int rr, float &t1, float &t2, float &t3)
+{
+    const bool b1 = (rr & 1) != 0, s2 = (rr & 3) == 1, b2 = (rr & 3) == 3, s3 = (rr & 7) == 3, b3 = (rr & 7) == 7;
+    const float v1 = b1 ? t1 + v : v;
+    t1 = b1 ? t1 : v;
+    const float v2 = b2 ? t2 + v1 : v1;
+    t2 = s2 ? v1 : t2;
+    const float v3 = b3 ? t3 + v2 : v2;
+    t3 = s3 ? v2 : t3;
+    return v3;
+}
+
+// Two consecutive rows at once: v = (row 2p) + (row 2p + 1), the first level of the tree already
+// done; p = pair index in the octet (0..3), run-time uniform.
+__device__ __forceinline__ float octet_tree_push_pair_rt(float v, int p, float &t2, float &t3)
+{
+    const bool b2 = (p & 1) != 0, s3 = (p & 3) == 1, b3 = (p & 3) == 3;
+    const float v2 = b2 ? t2 + v : v;
+    t2 = b2 ? t2 : v;
+    const float v3 = b3 ? t3 + v2 : v2;
+    t3 = s3 ? v2 : t3;
+    return v3;
+}
+
 }  // namespace sbits

@@ -256,12 +256,19 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                 } else {
                     quant_cost_round<LPG, K, NI>(wr, s, dp, out);
                 }
-#pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    const int rs = (g0 + i0 + j) / CPL, c = (g0 + i0 + j) % CPL;
+                if constexpr (RS == 2 && CPL == 1 && NI == 2) {
+                    // the two items are rows rr0, rr0 + 1 of one chunk: their sum is the tree's first level
 #pragma unroll
                     for (int k = 0; k < K; ++k)
-                        last[c][k] = octet_tree_push(out[j][k], rr0 + rs, t1[c][k], t2[c][k], t3[c][k]);
+                        last[0][k] = octet_tree_push_pair_rt(out[0][k] + out[1][k], rr0 >> 1, t2[0][k], t3[0][k]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const int rs = (g0 + i0 + j) / CPL, c = (g0 + i0 + j) % CPL;
+#pragma unroll
+                        for (int k = 0; k < K; ++k)
+                            last[c][k] = octet_tree_push_rt(out[j][k], rr0 + rs, t1[c][k], t2[c][k], t3[c][k]);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
