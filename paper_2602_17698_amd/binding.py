@@ -116,8 +116,10 @@ def _check(rc, where, allow=()):
 def matrix(w, s) -> Matrix:
     """Descriptor of one weight matrix (bf16 tensor) and its sensitivity (fp32 tensor)."""
     rows, cols = (w.shape if w is not None else s.shape)
-    return Matrix(_ptr(w).value, _ptr(s).value, rows, cols,
-                  w.stride(0) if w is not None else cols, s.stride(0) if s is not None else cols)
+    d = Matrix(_ptr(w).value, _ptr(s).value, rows, cols,
+               w.stride(0) if w is not None else cols, s.stride(0) if s is not None else cols)
+    d._keep = (w, s)            # the descriptor holds raw addresses: keep the tensors alive as long as it lives
+    return d
 
 
 class Context:

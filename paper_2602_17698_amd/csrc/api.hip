@@ -244,6 +244,9 @@ int sbits_reorder_coupled_all(sbits_plan *plan, const sbits_matrix *mats, const 
     int rc = check_all(plan, mats, false, true);
     if (rc) return rc;
     if (!row_group || !col_group || n_groups < 0 || !row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if ((rc = sbits_coupling_tables(plan, row_group, col_group, n_groups, group_segment, nullptr, nullptr, nullptr,
+                                    nullptr)))
+        return rc;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
     return sbits_launch_reorder_coupled_all(plan, row_group, col_group, n_groups, group_segment, row_perm, col_perm,

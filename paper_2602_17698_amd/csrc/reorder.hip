@@ -648,14 +648,13 @@ int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_p
     return SBITS_OK;
 }
 
-// Coupled reordering of all matrices.  group[a] for every array a (rows of matrix a, or columns of
-// matrix a - n_mats): SBITS_DIM_INDEPENDENT, SBITS_DIM_FIXED or a group id; segment[g]: 0 or the
-// piece length for group g.  Tables go to slots 6..9 of the workspace head.
-int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group, const int32_t *col_group,
-                                     int n_groups, const int32_t *group_segment, int32_t *row_perm,
-                                     int32_t *col_perm, void *ws)
+// Host part of the coupled reordering: validates the groups and builds, per array a (rows of matrix
+// a, or columns of matrix a - n_mats), what the sort kernel does with it (mode), the piece length
+// (seg), the next member of its group (next) and, for non-leaders, the group's first member (leader).
+int sbits_coupling_tables(const sbits_plan *plan, const int32_t *row_group, const int32_t *col_group, int n_groups,
+                          const int32_t *group_segment, std::vector<int> *mode_, std::vector<int> *seg_,
+                          std::vector<int> *next_, std::vector<int> *leader_)
 {
-    sbits_ctx *ctx = plan->ctx;
     const int nm = plan->n_mats, na = 2 * nm;
     std::vector<int> mode(na), seg(na, 0), next(na, -1), leader(na, -1), last(n_groups > 0 ? n_groups : 0, -1);
     std::vector<int> first(last);
@@ -679,6 +678,22 @@ int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group,
             last[g] = a;
         }
     }
+    if (mode_) { *mode_ = mode; *seg_ = seg; *next_ = next; *leader_ = leader; }
+    return SBITS_OK;
+}
+
+// Coupled reordering of all matrices.  group[a] for every array a (rows of matrix a, or columns of
+// matrix a - n_mats): SBITS_DIM_INDEPENDENT, SBITS_DIM_FIXED or a group id; segment[g]: 0 or the
+// piece length for group g.  Tables go to slots 6..9 of the workspace head.
+int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group, const int32_t *col_group,
+                                     int n_groups, const int32_t *group_segment, int32_t *row_perm,
+                                     int32_t *col_perm, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    const int nm = plan->n_mats, na = 2 * nm;
+    std::vector<int> mode, seg, next, leader;
+    int rcv = sbits_coupling_tables(plan, row_group, col_group, n_groups, group_segment, &mode, &seg, &next, &leader);
+    if (rcv) return rcv;
     int *d_mode = sbits_prefix_ptr(plan, ws, 6), *d_seg = sbits_prefix_ptr(plan, ws, 7);
     int *d_next = sbits_prefix_ptr(plan, ws, 8), *d_leader = sbits_prefix_ptr(plan, ws, 9);
     SBITS_HIP(ctx, hipMemcpyAsync(d_mode, mode.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));

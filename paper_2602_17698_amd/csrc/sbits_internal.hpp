@@ -78,6 +78,9 @@ int sbits_launch_scores(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, in
 int sbits_launch_reorder(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, int64_t ld,
                          int32_t *row_perm, int32_t *col_perm, void *scratch);
 int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_perm, void *ws);
+int sbits_coupling_tables(const sbits_plan *plan, const int32_t *row_group, const int32_t *col_group, int n_groups,
+                          const int32_t *group_segment, std::vector<int> *mode, std::vector<int> *seg,
+                          std::vector<int> *next, std::vector<int> *leader);
 int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group, const int32_t *col_group,
                                      int n_groups, const int32_t *group_segment, int32_t *row_perm,
                                      int32_t *col_perm, void *ws);

@@ -99,3 +99,43 @@ def test_calls_validate_before_touching_the_device(ctx, lib):
     assert lib.sbits_reorder(p.h, C.c_int(0), C.byref(M), C.c_void_p(256), C.c_void_p(256), C.c_void_p(ws)) == sb.ERR_INVALID_ARG
     assert lib.sbits_num_blocks(p.h, C.c_int(5)) == sb.ERR_INVALID_ARG
     p.close()
+
+
+def test_one_pass_and_coupled_entry_points_validate_on_the_host(ctx, lib):
+    """Argument and shape errors are reported before any device work (host-only context)."""
+    ws = 256 * 1024
+    ptr = C.c_void_p(4096)                                               # aligned, never dereferenced
+    p = sb.Plan(ctx, [(256, 256), (256, 512)], 64, 128, [2, 3, 4])
+    assert lib.sbits_gather_cost_supported(p.h) == 1
+    mats = (sb.Matrix * 2)(sb.Matrix(4096, 4096, 256, 256, 256, 256), sb.Matrix(4096, 4096, 256, 512, 512, 512))
+    assert lib.sbits_gather_cost_all(p.h, mats, ptr, ptr, None, None, C.c_void_p(ws)) == sb.ERR_INVALID_ARG   # no table
+    assert lib.sbits_gather_cost_all(p.h, mats, ptr, ptr, None, ptr, C.c_void_p(ws)) == sb.ERR_HIP            # valid: needs a device
+    assert lib.sbits_gather_pack_all(p.h, mats, ptr, ptr, ptr, ptr, C.c_void_p(4100), ptr, ptr,
+                                     C.c_void_p(ws)) == sb.ERR_INVALID_ARG                                   # codes not 8-byte aligned
+    assert lib.sbits_surrogates_all(p.h, mats, ptr, ptr, None, ptr, ptr, C.c_void_p(ws)) == sb.ERR_INVALID_ARG
+    i32 = lambda *v: (C.c_int32 * len(v))(*v)
+    call = lambda rg, cg, ng, seg: lib.sbits_reorder_coupled_all(p.h, mats, rg, cg, C.c_int(ng), seg, ptr, ptr,
+                                                                 C.c_void_p(ws))
+    assert call(i32(0, 0), i32(-1, -1), 1, None) == sb.ERR_HIP           # rows 256 and 256: a valid group
+    assert call(i32(0, -1), i32(-1, 0), 1, None) == sb.ERR_BAD_SHAPE     # 256 rows with 512 columns
+    assert call(i32(1, -1), i32(-1, -1), 1, None) == sb.ERR_INVALID_ARG  # group id out of range
+    assert call(i32(0, 0), i32(-1, -1), 1, i32(96)) == sb.ERR_BAD_SHAPE  # piece length does not divide 256
+    assert call(i32(-2, -2), i32(-2, -2), 0, None) == sb.ERR_HIP         # everything fixed: valid
+    p.close()
+    q = sb.Plan(ctx, [(256, 512)], 64, 256, [2, 3, 4])                   # 256-column blocks: two-pass route only
+    assert lib.sbits_gather_cost_supported(q.h) == 0
+    m1 = (sb.Matrix * 1)(sb.Matrix(4096, 4096, 256, 512, 512, 512))
+    assert lib.sbits_gather_cost_all(q.h, m1, ptr, ptr, None, ptr, C.c_void_p(ws)) == sb.ERR_UNIMPLEMENTED
+    assert lib.sbits_gather_pack_all(q.h, m1, ptr, ptr, ptr, ptr, ptr, ptr, ptr, C.c_void_p(ws)) == sb.ERR_UNIMPLEMENTED
+    assert lib.sbits_surrogates_all(q.h, m1, ptr, ptr, ptr, ptr, ptr, C.c_void_p(ws)) == sb.ERR_UNIMPLEMENTED
+    q.close()
+
+
+def test_plan_limits(ctx):
+    """At most 32768 rows / columns per matrix and 2^24 blocks per plan."""
+    sb.Plan(ctx, [(32768, 32768)], 8, 8, [2]).close()                    # 2^24 blocks: the limit itself
+    for shapes, m, n in (([(32768 + 8, 8)], 8, 8), ([(8, 32768 + 8)], 8, 8),
+                         ([(32768, 32768), (8, 8)], 8, 8)):              # one block too many
+        with pytest.raises(sb.SbitsError) as e:
+            sb.Plan(ctx, shapes, m, n, [2])
+        assert e.value.status == sb.ERR_BAD_SHAPE

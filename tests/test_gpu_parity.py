@@ -387,6 +387,66 @@ def test_surrogates_one_pass(orc, ctx, dev, shapes, m, n, bits):
     plan.close()
 
 
+def test_one_pass_degenerate_groups(orc, ctx, dev):
+    """Constant groups, ranges so small that qmax / R overflows, signed zeros and the largest finite
+    bf16 through the one-pass cost, packing and surrogate kernels (identity and random permutations).
+    Every group's max - min stays finite in fp32: beyond that the library's results are unspecified
+    (NaN arithmetic, which the kernels are compiled not to honour)."""
+    say("one-pass degenerate groups")
+    m = n = 64
+    R, C = 128, 192
+    W, S = synth.make_matrix("gauss_outlier", R, C, seed=6)
+    Wn = to_np_bf16(W).copy()
+    Wn[0, :64] = Wn[0, 0]                                 # constant group: range 0
+    Wn[1, :64] = 0
+    Wn[1, 7] = 0x0001                                     # range = smallest subnormal: qmax / R overflows
+    Wn[2, :64] = 0x8000                                   # all -0
+    Wn[2, 3] = 0x0000                                     # +0 among -0: range 0
+    Wn[3, :64] = 0
+    Wn[3, 9] = 0x0040                                     # subnormal range whose reciprocal is finite for small qmax
+    Wn[4, 64:128] = 0x7F7F                                # largest finite bf16, constant
+    Wn[5, 128:] = 0xFEFF                                  # -1.69e38 ...
+    Wn[5, 130] = 0x7EFF                                   # ... and +1.69e38: the widest range that is finite in fp32
+    Wd = torch.from_numpy(Wn.view(np.int16)).view(torch.bfloat16).to(dev)
+    Sd = S.to(dev)
+    Gs = (S * torch.sign(torch.randn(R, C, generator=torch.Generator().manual_seed(1)))).contiguous()
+    bits = [1, 2, 3, 4, 8]
+    plan, ws = make_plan(ctx, [(R, C)], m, n, bits, dev)
+    N, K = plan.num_blocks(), len(bits)
+    g = torch.Generator().manual_seed(2)
+    for rp, cp in ((torch.arange(R), torch.arange(C)), (torch.randperm(R, generator=g), torch.randperm(C, generator=g))):
+        rp, cp = rp.to(torch.int32), cp.to(torch.int32)
+        Wp, Sp = orc.gather(Wn, S.numpy(), rp.numpy(), cp.numpy())
+        _, Gp = orc.gather(Wn, Gs.numpy(), rp.numpy(), cp.numpy())
+        cost = torch.empty(N, K, dtype=torch.float32, device=dev)
+        plan.gather_cost_all([sb.matrix(Wd, Sd)], rp.to(dev), cp.to(dev), None, cost, ws)
+        level = np.arange(N, dtype=np.uint8) % K
+        off = orc.offsets(level, m, n, bits)
+        codes_d = torch.zeros(int(off[-1]), dtype=torch.uint8, device=dev)
+        scale_d = torch.empty(N * m, dtype=torch.float32, device=dev)
+        zero_d = torch.empty(N * m, dtype=torch.float32, device=dev)
+        plan.gather_pack_all([sb.matrix(Wd, None)], rp.to(dev), cp.to(dev), torch.from_numpy(level).to(dev),
+                             torch.from_numpy(off).to(dev), codes_d, scale_d, zero_d, ws)
+        s_up = torch.empty(N, dtype=torch.float32, device=dev)
+        s_dn = torch.empty(N, dtype=torch.float32, device=dev)
+        Gd = Gs.to(dev)
+        plan.surrogates_all([sb.matrix(Wd, Gd)], rp.to(dev), cp.to(dev), torch.from_numpy(level).to(dev),
+                            s_up, s_dn, ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(cost.cpu().numpy().view(np.uint32), orc.cost_table(Wp, Sp, m, n, bits).view(np.uint32))
+        codes = np.zeros(int(off[-1]), np.uint8)
+        scale = np.zeros(N * m, np.float32)
+        zero = np.zeros(N * m, np.float32)
+        orc.pack(Wp, m, n, bits, level, off, 0, codes, scale, zero)
+        np.testing.assert_array_equal(codes_d.cpu().numpy(), codes)
+        np.testing.assert_array_equal(scale_d.cpu().numpy().view(np.uint32), scale.view(np.uint32))
+        np.testing.assert_array_equal(zero_d.cpu().numpy().view(np.uint32), zero.view(np.uint32))
+        u, d_ = orc.surrogates(Wp, Gp, m, n, bits, level)
+        np.testing.assert_array_equal(s_up.cpu().numpy().view(np.uint32), u.view(np.uint32))
+        np.testing.assert_array_equal(s_dn.cpu().numpy().view(np.uint32), d_.view(np.uint32))
+    plan.close()
+
+
 def test_gather_cost_one_pass_refuses_other_shapes(ctx, dev):
     say("one-pass refuses")
     plan, ws = make_plan(ctx, [(64, 256)], 32, 256, [2, 4], dev)     # 256-column blocks: two-pass route only
