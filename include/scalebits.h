@@ -18,7 +18,12 @@
  *     sbits_search wait for the stream because they return host results).
  *   - A weight matrix is rows x cols, row-major, rows = output channels,
  *     cols = input channels (paper App. D); weights are bfloat16, sensitivities
- *     are float32, non-negative and finite (NaN/Inf: results undefined).
+ *     are float32, non-negative and finite.  Weights are finite and max - min
+ *     over a quantization group is finite in fp32 (true whenever |w| < 1.7e38).
+ *     The kernels are compiled not to honour NaN: with NaN/Inf inputs, or a
+ *     group range that overflows, the results are undefined.  Ranges of zero
+ *     and ranges so small that qmax / range overflows are defined cases
+ *     (scale = 0: every code 0, the group dequantizes to its minimum).
  *   - A block is block_rows x block_cols (m x n) of the REORDERED matrix and is
  *     the unit of precision (paper Sec. 4.1).  The quantization group is one
  *     block row: group size = block width (paper App. E, block size).  m and n
