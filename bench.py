@@ -149,7 +149,8 @@ def main():
     def step(ev):
         ev[0].record()
         if coupling:
-            plan.reorder_coupled_all(mats, coupling[0], coupling[1], coupling[2], coupling[3], row_perm, col_perm, ws)
+            plan.reorder_coupled_all(mats, coupling[0], coupling[1], coupling[2], coupling[3], row_perm, col_perm, ws,
+                                     coupling[4], coupling[5])
         else:
             plan.reorder_all(mats, row_perm, col_perm, ws)
         ev[1].record()

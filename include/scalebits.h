@@ -146,18 +146,29 @@ int  sbits_reorder_all(sbits_plan *plan, const sbits_matrix *mats,
  * give, for the rows / columns of matrix i, SBITS_DIM_INDEPENDENT (own scores, as
  * sbits_reorder_all), SBITS_DIM_FIXED (identity: e.g. query / key rows under rotary
  * embeddings) or a group id in [0, n_groups).  All members of a group must have
- * the same length (else SBITS_ERR_BAD_SHAPE).  The group's score of channel j is
- * the fp32 sum of the members' scores of channel j, added member after member in
+ * the group's length times their repeat, see below (else SBITS_ERR_BAD_SHAPE).
+ * The group's score of channel j is the fp32 sum of the members' scores of channel j, added member after member in
  * the order: rows of matrix 0, 1, ..., then columns of matrix 0, 1, ...
  * group_segment[g] (HOST, may be NULL = all 0): 0, or a piece length dividing the
  * group's length: channels are then only permuted inside consecutive pieces of
  * that length (attention heads).  Order inside a piece: score descending, ties to
- * the lower index.  Every member receives the same permutation.  Uses ws.       */
+ * the lower index.  Every member receives the same permutation.
+ * row_repeat[i] / col_repeat[i] (HOST, n_mats each, may be NULL = all 1): with
+ * grouped-query attention one value head feeds r query heads, so the output
+ * projection's columns are r times as many as the value projection's rows.
+ * A member with repeat r > 1 (needs a segmented group) is r times the group's
+ * length; piece p of the group stands for the member's pieces r*p .. r*p + r - 1:
+ * their r scores of a channel are added one after the other (lower piece first)
+ * where a member with repeat 1 adds one, and each of those pieces receives the
+ * permutation of group piece p.  The first member of a group (in the order above)
+ * has repeat 1 (else SBITS_ERR_INVALID_ARG); independent and fixed dimensions too.
+ * Uses ws.                                                                        */
 #define SBITS_DIM_INDEPENDENT (-1)
 #define SBITS_DIM_FIXED       (-2)
 int  sbits_reorder_coupled_all(sbits_plan *plan, const sbits_matrix *mats,
                                const int32_t *row_group, const int32_t *col_group,
                                int n_groups, const int32_t *group_segment,
+                               const int32_t *row_repeat, const int32_t *col_repeat,
                                int32_t *row_perm, int32_t *col_perm, void *ws);
 /* w_out[i][j] = W[row_perm[i]][col_perm[j]], s_out likewise; outputs are dense
  * (pitch = cols) and must not alias the inputs.                                 */

@@ -147,6 +147,27 @@ def coupled_perm(member_scores, piece=0):
     return argsort_desc_pieces(group_scores(member_scores), piece)
 
 
+def fold_repeated(score, piece, repeat):
+    """A member whose dimension is `repeat` times the group's (one value head feeding several query
+    heads): group piece p stands for the member's pieces repeat*p .. repeat*p + repeat - 1.
+    Returns the `repeat` score arrays of the group's length that the member contributes to the
+    group sum, lower piece first."""
+    score = _f32(score)
+    v = score.reshape(-1, repeat, piece)             # [group piece][which of the member's pieces][channel]
+    return [np.ascontiguousarray(v[:, t, :]).reshape(-1) for t in range(repeat)]
+
+
+def expand_perm(perm, piece, repeat):
+    """The member's permutation from the group's: every one of the member's pieces takes the
+    within-piece order of the group piece it belongs to."""
+    perm = _i32(perm)
+    within = perm.reshape(-1, piece) - (np.arange(perm.size // piece, dtype=np.int32) * piece)[:, None]
+    out = np.empty(perm.size * repeat, np.int32)
+    for pc in range(perm.size // piece * repeat):
+        out[pc * piece:(pc + 1) * piece] = pc * piece + within[pc // repeat]
+    return out
+
+
 def gather(W_u16, S, rp, cp):
     W_u16 = _u16(W_u16)
     S = _f32(S)

@@ -195,14 +195,19 @@ class Plan:
         return _check(load().sbits_reorder_all(self.h, arr, _ptr(row_perm), _ptr(col_perm), _ptr(ws)),
                       "sbits_reorder_all")
 
-    def reorder_coupled_all(self, mats, row_group, col_group, n_groups, group_segment, row_perm, col_perm, ws):
-        """row_group / col_group / group_segment: host sequences of ints (see scalebits.h)."""
+    def reorder_coupled_all(self, mats, row_group, col_group, n_groups, group_segment, row_perm, col_perm, ws,
+                            row_repeat=None, col_repeat=None):
+        """row_group / col_group / group_segment / row_repeat / col_repeat: host sequences of ints
+        (see scalebits.h)."""
         arr = (Matrix * len(mats))(*mats)
         rg = (C.c_int32 * len(row_group))(*row_group)
         cg = (C.c_int32 * len(col_group))(*col_group)
         gs = (C.c_int32 * max(len(group_segment), 1))(*group_segment) if group_segment is not None else None
-        return _check(load().sbits_reorder_coupled_all(self.h, arr, rg, cg, C.c_int(n_groups), gs, _ptr(row_perm),
-                                                       _ptr(col_perm), _ptr(ws)), "sbits_reorder_coupled_all")
+        rr = (C.c_int32 * len(row_repeat))(*row_repeat) if row_repeat is not None else None
+        cr = (C.c_int32 * len(col_repeat))(*col_repeat) if col_repeat is not None else None
+        return _check(load().sbits_reorder_coupled_all(self.h, arr, rg, cg, C.c_int(n_groups), gs, rr, cr,
+                                                       _ptr(row_perm), _ptr(col_perm), _ptr(ws)),
+                      "sbits_reorder_coupled_all")
 
     def gather_all(self, mats, row_perm, col_perm, w_re, s_re, ws):
         arr = (Matrix * len(mats))(*mats)

@@ -239,18 +239,19 @@ int sbits_reorder_all(sbits_plan *plan, const sbits_matrix *mats, int32_t *row_p
 
 int sbits_reorder_coupled_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_group,
                               const int32_t *col_group, int n_groups, const int32_t *group_segment,
-                              int32_t *row_perm, int32_t *col_perm, void *ws)
+                              const int32_t *row_repeat, const int32_t *col_repeat, int32_t *row_perm,
+                              int32_t *col_perm, void *ws)
 {
     int rc = check_all(plan, mats, false, true);
     if (rc) return rc;
     if (!row_group || !col_group || n_groups < 0 || !row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
-    if ((rc = sbits_coupling_tables(plan, row_group, col_group, n_groups, group_segment, nullptr, nullptr, nullptr,
-                                    nullptr)))
+    if ((rc = sbits_coupling_tables(plan, row_group, col_group, n_groups, group_segment, row_repeat, col_repeat,
+                                    nullptr, nullptr, nullptr, nullptr, nullptr)))
         return rc;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
-    return sbits_launch_reorder_coupled_all(plan, row_group, col_group, n_groups, group_segment, row_perm, col_perm,
-                                            ws);
+    return sbits_launch_reorder_coupled_all(plan, row_group, col_group, n_groups, group_segment, row_repeat,
+                                            col_repeat, row_perm, col_perm, ws);
 }
 
 int sbits_gather_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,

@@ -382,32 +382,46 @@ void radix_argsort_kernel(const MatDesc *__restrict__ descs, MatDesc one, int n_
 // Arrays are numbered as in the sort kernel.  arr_next[a]: the next member of a's group, or -1.
 // The leader (first member) of a group accumulates, member after member in array order:
 //   s[leader][j] = (..(s[leader][j] + s[m1][j]) + s[m2][j]) + ...
+// A member with repeat r > 1 is r times as long: each piece of seg channels of the group stands
+// for r consecutive pieces of the member (one value head serving r query heads); its r scores of
+// channel j are added one after the other, lower piece first.
 __global__ __launch_bounds__(256)
 void group_sum_kernel(const MatDesc *__restrict__ descs, int n_mats, int64_t sum_rows, float *__restrict__ scores,
-                      const int *__restrict__ arr_mode, const int *__restrict__ arr_next)
+                      const int *__restrict__ arr_mode, const int *__restrict__ arr_next,
+                      const int *__restrict__ arr_seg, const int *__restrict__ arr_rep)
 {
     const int a = blockIdx.y;
     if (arr_mode[a] != ARR_SORT || arr_next[a] < 0) return;      // only leaders with other members
     const bool is_row = a < n_mats;
     const MatDesc &d = descs[is_row ? a : a - n_mats];
     const int n = (int)(is_row ? d.rows : d.cols);
+    const int sg = arr_seg[a];
     const int64_t off = is_row ? d.row_off : sum_rows + d.col_off;
     for (int j = (int)(blockIdx.x * blockDim.x + threadIdx.x); j < n; j += (int)(gridDim.x * blockDim.x)) {
         float acc = scores[off + j];
         for (int b = arr_next[a]; b >= 0; b = arr_next[b]) {
             const bool br = b < n_mats;
             const MatDesc &e = descs[br ? b : b - n_mats];
-            acc = acc + scores[(br ? e.row_off : sum_rows + e.col_off) + j];
+            const float *sb = scores + (br ? e.row_off : sum_rows + e.col_off);
+            const int r = arr_rep[b];
+            if (r == 1) {
+                acc = acc + sb[j];
+            } else {                                             // sg > 0 (checked on the host)
+                const int64_t base = (int64_t)(j / sg) * r * sg + j % sg;
+                for (int t = 0; t < r; ++t) acc = acc + sb[base + (int64_t)t * sg];
+            }
         }
         scores[off + j] = acc;
     }
 }
 
-// the members of a group take their leader's permutation
+// the members of a group take their leader's permutation; a member with repeat r applies the
+// permutation of group piece p inside each of its pieces r*p .. r*p + r - 1
 __global__ __launch_bounds__(256)
 void replicate_perm_kernel(const MatDesc *__restrict__ descs, int n_mats, int32_t *__restrict__ row_perm,
                            int32_t *__restrict__ col_perm, const int *__restrict__ arr_mode,
-                           const int *__restrict__ arr_leader)
+                           const int *__restrict__ arr_leader, const int *__restrict__ arr_seg,
+                           const int *__restrict__ arr_rep)
 {
     const int a = blockIdx.y;
     if (arr_mode[a] != ARR_SKIP) return;
@@ -416,10 +430,18 @@ void replicate_perm_kernel(const MatDesc *__restrict__ descs, int n_mats, int32_
     const MatDesc &d = descs[ar ? a : a - n_mats];
     const MatDesc &e = descs[lr ? l : l - n_mats];
     const int n = (int)(ar ? d.rows : d.cols);
+    const int r = arr_rep[a], sg = arr_seg[l];
     int32_t *dst = ar ? row_perm + d.row_off : col_perm + d.col_off;
     const int32_t *src = lr ? row_perm + e.row_off : col_perm + e.col_off;
-    for (int j = (int)(blockIdx.x * blockDim.x + threadIdx.x); j < n; j += (int)(gridDim.x * blockDim.x))
-        dst[j] = src[j];
+    for (int j = (int)(blockIdx.x * blockDim.x + threadIdx.x); j < n; j += (int)(gridDim.x * blockDim.x)) {
+        if (r == 1) {
+            dst[j] = src[j];
+        } else {
+            const int pc = j / sg, dd = j - pc * sg;             // the member's piece and the channel inside it
+            const int gbase = (pc / r) * sg;                     // first channel of the group's piece
+            dst[j] = pc * sg + (src[gbase + dd] - gbase);
+        }
+    }
 }
 
 // ================================================================ gather
@@ -652,54 +674,70 @@ int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_p
 // a, or columns of matrix a - n_mats), what the sort kernel does with it (mode), the piece length
 // (seg), the next member of its group (next) and, for non-leaders, the group's first member (leader).
 int sbits_coupling_tables(const sbits_plan *plan, const int32_t *row_group, const int32_t *col_group, int n_groups,
-                          const int32_t *group_segment, std::vector<int> *mode_, std::vector<int> *seg_,
-                          std::vector<int> *next_, std::vector<int> *leader_)
+                          const int32_t *group_segment, const int32_t *row_repeat, const int32_t *col_repeat,
+                          std::vector<int> *mode_, std::vector<int> *seg_, std::vector<int> *next_,
+                          std::vector<int> *leader_, std::vector<int> *rep_)
 {
     const int nm = plan->n_mats, na = 2 * nm;
-    std::vector<int> mode(na), seg(na, 0), next(na, -1), leader(na, -1), last(n_groups > 0 ? n_groups : 0, -1);
+    std::vector<int> mode(na), seg(na, 0), next(na, -1), leader(na, -1), rep(na, 1);
+    std::vector<int> last(n_groups > 0 ? n_groups : 0, -1);
     std::vector<int> first(last);
     auto len = [&](int a) { return a < nm ? plan->rows[a] : plan->cols[a - nm]; };
     for (int a = 0; a < na; ++a) {
         const int g = a < nm ? row_group[a] : col_group[a - nm];
-        if (g == SBITS_DIM_INDEPENDENT) { mode[a] = ARR_SORT; continue; }
-        if (g == SBITS_DIM_FIXED) { mode[a] = ARR_IDENTITY; continue; }
+        const int32_t *rp = a < nm ? row_repeat : col_repeat;
+        const int r = rp ? rp[a < nm ? a : a - nm] : 1;
+        if (r < 1) return SBITS_ERR_INVALID_ARG;
+        if (g == SBITS_DIM_INDEPENDENT || g == SBITS_DIM_FIXED) {
+            if (r != 1) return SBITS_ERR_INVALID_ARG;
+            mode[a] = g == SBITS_DIM_FIXED ? ARR_IDENTITY : ARR_SORT;
+            continue;
+        }
         if (g < 0 || g >= n_groups) return SBITS_ERR_INVALID_ARG;
         const int sg = group_segment ? group_segment[g] : 0;
-        if (sg < 0 || (sg > 0 && len(a) % sg)) return SBITS_ERR_BAD_SHAPE;
+        if (sg < 0) return SBITS_ERR_BAD_SHAPE;
+        rep[a] = r;
         if (first[g] < 0) {
+            if (r != 1) return SBITS_ERR_INVALID_ARG;              // the first member carries the group's length
+            if (sg > 0 && len(a) % sg) return SBITS_ERR_BAD_SHAPE;
             first[g] = last[g] = a;
             mode[a] = ARR_SORT;
             seg[a] = sg;
         } else {
-            if (len(a) != len(first[g])) return SBITS_ERR_BAD_SHAPE;   // coupled dimensions are the same activation
+            if (r > 1 && sg == 0) return SBITS_ERR_BAD_SHAPE;     // repeats are repeats of pieces
+            if (len(a) != (int64_t)r * len(first[g])) return SBITS_ERR_BAD_SHAPE;   // the same activation
             mode[a] = ARR_SKIP;
             leader[a] = first[g];
             next[last[g]] = a;
             last[g] = a;
         }
     }
-    if (mode_) { *mode_ = mode; *seg_ = seg; *next_ = next; *leader_ = leader; }
+    if (mode_) { *mode_ = mode; *seg_ = seg; *next_ = next; *leader_ = leader; *rep_ = rep; }
     return SBITS_OK;
 }
 
 // Coupled reordering of all matrices.  group[a] for every array a (rows of matrix a, or columns of
 // matrix a - n_mats): SBITS_DIM_INDEPENDENT, SBITS_DIM_FIXED or a group id; segment[g]: 0 or the
-// piece length for group g.  Tables go to slots 6..9 of the workspace head.
+// piece length for group g; repeat: pieces of the member per piece of the group.  Tables go to
+// slots 6..10 of the workspace head.
 int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group, const int32_t *col_group,
-                                     int n_groups, const int32_t *group_segment, int32_t *row_perm,
-                                     int32_t *col_perm, void *ws)
+                                     int n_groups, const int32_t *group_segment, const int32_t *row_repeat,
+                                     const int32_t *col_repeat, int32_t *row_perm, int32_t *col_perm, void *ws)
 {
     sbits_ctx *ctx = plan->ctx;
     const int nm = plan->n_mats, na = 2 * nm;
-    std::vector<int> mode, seg, next, leader;
-    int rcv = sbits_coupling_tables(plan, row_group, col_group, n_groups, group_segment, &mode, &seg, &next, &leader);
+    std::vector<int> mode, seg, next, leader, rep;
+    int rcv = sbits_coupling_tables(plan, row_group, col_group, n_groups, group_segment, row_repeat, col_repeat,
+                                    &mode, &seg, &next, &leader, &rep);
     if (rcv) return rcv;
     int *d_mode = sbits_prefix_ptr(plan, ws, 6), *d_seg = sbits_prefix_ptr(plan, ws, 7);
     int *d_next = sbits_prefix_ptr(plan, ws, 8), *d_leader = sbits_prefix_ptr(plan, ws, 9);
+    int *d_rep = sbits_prefix_ptr(plan, ws, 10);
     SBITS_HIP(ctx, hipMemcpyAsync(d_mode, mode.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
     SBITS_HIP(ctx, hipMemcpyAsync(d_seg, seg.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
     SBITS_HIP(ctx, hipMemcpyAsync(d_next, next.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
     SBITS_HIP(ctx, hipMemcpyAsync(d_leader, leader.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(d_rep, rep.data(), (size_t)na * 4, hipMemcpyHostToDevice, ctx->stream));
     SBITS_HIP(ctx, hipStreamSynchronize(ctx->stream));           // the host vectors go away on return
 
     ReorderWs w;
@@ -716,12 +754,12 @@ int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group,
     const int64_t maxlen = plan->max_rows > plan->max_cols ? plan->max_rows : plan->max_cols;
     const dim3 g2((unsigned)((maxlen + 255) / 256), (unsigned)na);
     hipLaunchKernelGGL(group_sum_kernel, g2, dim3(256), 0, ctx->stream, descs, nm, plan->sum_rows, w.scores,
-                       (const int *)d_mode, (const int *)d_next);
+                       (const int *)d_mode, (const int *)d_next, (const int *)d_seg, (const int *)d_rep);
     hipLaunchKernelGGL(radix_argsort_kernel, dim3((unsigned)na), dim3(RS_THREADS), 0, ctx->stream, descs, none, nm,
                        plan->sum_rows, w.scores, w.k0, w.k1, w.i0, w.i1, row_perm, col_perm, (const int *)d_mode,
                        (const int *)d_seg);
     hipLaunchKernelGGL(replicate_perm_kernel, g2, dim3(256), 0, ctx->stream, descs, nm, row_perm, col_perm,
-                       (const int *)d_mode, (const int *)d_leader);
+                       (const int *)d_mode, (const int *)d_leader, (const int *)d_seg, (const int *)d_rep);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }

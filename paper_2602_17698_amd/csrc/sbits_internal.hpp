@@ -45,7 +45,7 @@ struct sbits_plan {
 
 // The workspace head holds the per-matrix descriptor table and the small integer tables (workgroup
 // prefixes, class members, coupling tables) of the batched launches; stage scratch starts at sbits_scratch(plan, ws).
-constexpr int SBITS_N_PREFIX = 10;
+constexpr int SBITS_N_PREFIX = 11;
 static inline size_t sbits_desc_bytes(int n_mats) { return (size_t)((n_mats * sizeof(sbits::MatDesc) + 255) / 256 * 256); }
 static inline size_t sbits_prefix_bytes(int n_mats) { return (size_t)((2 * (n_mats + 1) * 4 + 255) / 256 * 256); }
 static inline sbits::MatDesc *sbits_desc_ptr(void *ws) { return static_cast<sbits::MatDesc *>(ws); }
@@ -79,11 +79,12 @@ int sbits_launch_reorder(sbits_ctx *ctx, const float *S, int64_t R, int64_t C, i
                          int32_t *row_perm, int32_t *col_perm, void *scratch);
 int sbits_launch_reorder_all(sbits_plan *plan, int32_t *row_perm, int32_t *col_perm, void *ws);
 int sbits_coupling_tables(const sbits_plan *plan, const int32_t *row_group, const int32_t *col_group, int n_groups,
-                          const int32_t *group_segment, std::vector<int> *mode, std::vector<int> *seg,
-                          std::vector<int> *next, std::vector<int> *leader);
+                          const int32_t *group_segment, const int32_t *row_repeat, const int32_t *col_repeat,
+                          std::vector<int> *mode, std::vector<int> *seg, std::vector<int> *next,
+                          std::vector<int> *leader, std::vector<int> *rep);
 int sbits_launch_reorder_coupled_all(sbits_plan *plan, const int32_t *row_group, const int32_t *col_group,
-                                     int n_groups, const int32_t *group_segment, int32_t *row_perm,
-                                     int32_t *col_perm, void *ws);
+                                     int n_groups, const int32_t *group_segment, const int32_t *row_repeat,
+                                     const int32_t *col_repeat, int32_t *row_perm, int32_t *col_perm, void *ws);
 int sbits_launch_gather_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                             void *w_re, float *s_re, void *ws);
 int sbits_launch_pack_all(sbits_plan *plan, const void *w_re, const uint8_t *level, const int64_t *byte_off,

@@ -33,22 +33,28 @@ def layer_shapes(model: dict):
             ("gate", f, h), ("up", f, h), ("down", h, f)]
 
 
-def llama_coupling(model: dict, layers: int):
+def llama_coupling(model: dict, layers: int, head_dim: int = 128):
     """Permutation groups of a Llama-shaped decoder stack, matrices in layer_shapes() order per layer
     (paper App. "Channel Reordering"): group 0 = the residual stream (columns of q, k, v, gate, up and
-    rows of o, down of every layer); one group per layer for the MLP activation (rows of gate, up,
-    columns of down).  Rows of q and k stay fixed (rotary embeddings).  Rows of v and columns of o are
-    left fixed as well: with grouped-query attention they have different lengths (one value head
-    serves several query heads), a coupling the library's equal-length groups do not express.
-    Returns (row_group, col_group, n_groups, group_segment) for sbits_reorder_coupled_all."""
+    rows of o, down of every layer); per layer one group for the MLP activation (rows of gate, up,
+    columns of down) and one for the attention values (rows of v, columns of o), reordered inside
+    each head only.  With grouped-query attention one value head serves hidden / kv query heads: the
+    columns of o are that many times the rows of v (repeat).  Rows of q and k stay fixed (rotary
+    embeddings).
+    Returns (row_group, col_group, n_groups, group_segment, row_repeat, col_repeat) for
+    sbits_reorder_coupled_all."""
     FIXED = -2
-    row_group, col_group = [], []
+    rep = model["hidden"] // model["kv"]
+    row_group, col_group, row_repeat, col_repeat = [], [], [], []
+    segment = [0]
     for layer in range(layers):
-        mlp = 1 + layer
-        row_group += [FIXED, FIXED, FIXED, 0, mlp, mlp, 0]          # q k v o gate up down
-        col_group += [0, 0, 0, FIXED, 0, 0, mlp]
-    n_groups = 1 + layers
-    return row_group, col_group, n_groups, [0] * n_groups
+        mlp, att = 1 + 2 * layer, 2 + 2 * layer
+        row_group += [FIXED, FIXED, att, 0, mlp, mlp, 0]            # q k v o gate up down
+        col_group += [0, 0, 0, att, 0, 0, mlp]
+        row_repeat += [1] * 7
+        col_repeat += [1, 1, 1, rep, 1, 1, 1]
+        segment += [0, head_dim]
+    return row_group, col_group, 1 + 2 * layers, segment, row_repeat, col_repeat
 
 
 def tensor_id(layer: int, proj: str) -> int:

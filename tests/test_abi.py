@@ -114,13 +114,20 @@ def test_one_pass_and_coupled_entry_points_validate_on_the_host(ctx, lib):
                                      C.c_void_p(ws)) == sb.ERR_INVALID_ARG                                   # codes not 8-byte aligned
     assert lib.sbits_surrogates_all(p.h, mats, ptr, ptr, None, ptr, ptr, C.c_void_p(ws)) == sb.ERR_INVALID_ARG
     i32 = lambda *v: (C.c_int32 * len(v))(*v)
-    call = lambda rg, cg, ng, seg: lib.sbits_reorder_coupled_all(p.h, mats, rg, cg, C.c_int(ng), seg, ptr, ptr,
-                                                                 C.c_void_p(ws))
+    call = lambda rg, cg, ng, seg, rr=None, cr=None: lib.sbits_reorder_coupled_all(
+        p.h, mats, rg, cg, C.c_int(ng), seg, rr, cr, ptr, ptr, C.c_void_p(ws))
     assert call(i32(0, 0), i32(-1, -1), 1, None) == sb.ERR_HIP           # rows 256 and 256: a valid group
     assert call(i32(0, -1), i32(-1, 0), 1, None) == sb.ERR_BAD_SHAPE     # 256 rows with 512 columns
     assert call(i32(1, -1), i32(-1, -1), 1, None) == sb.ERR_INVALID_ARG  # group id out of range
     assert call(i32(0, 0), i32(-1, -1), 1, i32(96)) == sb.ERR_BAD_SHAPE  # piece length does not divide 256
     assert call(i32(-2, -2), i32(-2, -2), 0, None) == sb.ERR_HIP         # everything fixed: valid
+    # rows of matrix 0 (256) lead; the 512 columns of matrix 1 are two pieces per piece of 64
+    assert call(i32(0, -1), i32(-1, 0), 1, i32(64), i32(1, 1), i32(1, 2)) == sb.ERR_HIP
+    assert call(i32(0, -1), i32(-1, 0), 1, None, i32(1, 1), i32(1, 2)) == sb.ERR_BAD_SHAPE       # repeat without pieces
+    assert call(i32(0, -1), i32(-1, 0), 1, i32(64), i32(1, 1), i32(1, 4)) == sb.ERR_BAD_SHAPE    # 4 * 256 != 512
+    assert call(i32(0, -1), i32(-1, 0), 1, i32(64), i32(1, 1), i32(1, 0)) == sb.ERR_INVALID_ARG  # repeat < 1
+    assert call(i32(0, -1), i32(-1, -1), 1, i32(64), i32(2, 1), None) == sb.ERR_INVALID_ARG      # a repeated leader
+    assert call(i32(-1, -1), i32(-1, -1), 0, None, i32(2, 1), None) == sb.ERR_INVALID_ARG        # repeat on an independent dimension
     p.close()
     q = sb.Plan(ctx, [(256, 512)], 64, 256, [2, 3, 4])                   # 256-column blocks: two-pass route only
     assert lib.sbits_gather_cost_supported(q.h) == 0

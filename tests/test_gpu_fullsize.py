@@ -279,7 +279,9 @@ def test_streamed_70b_shaped_model(orc):
 
 def test_coupled_reordering_four_layers(orc):
     """Four 8B-shaped decoder layers with the Llama coupling: the residual stream couples 28
-    dimensions of 4096 channels, each MLP 3 dimensions of 14336; against the oracle's summed scores."""
+    dimensions of 4096 channels, each MLP 3 dimensions of 14336, each attention block the 1024 value
+    rows with the 4096 output columns head by head (4 query heads per value head); against the
+    oracle's summed scores."""
     say("coupled reordering, 4 layers of the 8B shape")
     dev = torch.device("cuda:0")
     L = 4
@@ -289,32 +291,37 @@ def test_coupled_reordering_four_layers(orc):
         for name, r, c in synth.layer_shapes(model):
             _, s = synth.make_matrix("student_t", r, c, seed=0, tid=synth.tensor_id(layer, name), device=dev)
             shapes.append((r, c)); mats.append(s)
-    rg, cg, ng, seg = synth.llama_coupling(model, L)
+    rg, cg, ng, seg, rrep, crep = synth.llama_coupling(model, L)
     ctx = sb.Context(0, torch.cuda.current_stream().cuda_stream)
     plan = sb.Plan(ctx, shapes, 128, 128, [2, 3, 4])
     ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device=dev)
     rp = torch.empty(sum(r for r, _ in shapes), dtype=torch.int32, device=dev)
     cp = torch.empty(sum(c for _, c in shapes), dtype=torch.int32, device=dev)
     dm = [sb.matrix(None, s) for s in mats]
-    plan.reorder_coupled_all(dm, rg, cg, ng, seg, rp, cp, ws)
+    plan.reorder_coupled_all(dm, rg, cg, ng, seg, rp, cp, ws, rrep, crep)
     torch.cuda.synchronize()
     t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
-    t0.record(); plan.reorder_coupled_all(dm, rg, cg, ng, seg, rp, cp, ws); t1.record()
+    t0.record(); plan.reorder_coupled_all(dm, rg, cg, ng, seg, rp, cp, ws, rrep, crep); t1.record()
     torch.cuda.synchronize()
     say("  coupled reorder of 4 layers: %.2f ms" % t0.elapsed_time(t1))
     rp, cp = rp.cpu().numpy(), cp.cpu().numpy()
     scores = [orc.channel_scores(s.cpu().numpy()) for s in mats]
     members = {}
-    for i, g in enumerate(rg):
-        if g >= 0: members.setdefault(g, []).append(scores[i][0])
-    for i, g in enumerate(cg):
-        if g >= 0: members.setdefault(g, []).append(scores[i][1])
-    assert len(members[0]) == 7 * L and all(len(members[1 + l]) == 3 for l in range(L))
-    gperm = {g: orc.coupled_perm(m) for g, m in members.items()}
+    for which, groups, reps in ((0, rg, rrep), (1, cg, crep)):
+        for i, g in enumerate(groups):
+            if g < 0: continue
+            sc = scores[i][which]
+            members.setdefault(g, []).extend([sc] if reps[i] == 1 else orc.fold_repeated(sc, seg[g], reps[i]))
+    assert len(members[0]) == 7 * L
+    assert all(len(members[1 + 2 * l]) == 3 and len(members[2 + 2 * l]) == 1 + 4 for l in range(L))
+    gperm = {g: orc.coupled_perm(m, seg[g]) for g, m in members.items()}
     ro = co = 0
     for i, (r, c) in enumerate(shapes):
-        for got, g, n in ((rp[ro:ro + r], rg[i], r), (cp[co:co + c], cg[i], c)):
-            want = np.arange(n, dtype=np.int32) if g == -2 else gperm[g]
+        for got, g, n, rep in ((rp[ro:ro + r], rg[i], r, rrep[i]), (cp[co:co + c], cg[i], c, crep[i])):
+            if g == -2:
+                want = np.arange(n, dtype=np.int32)
+            else:
+                want = gperm[g] if rep == 1 else orc.expand_perm(gperm[g], seg[g], rep)
             np.testing.assert_array_equal(got, want)
         ro, co = ro + r, co + c
     plan.close(); ctx.close()

@@ -261,6 +261,38 @@ def test_coupled_reordering(orc, ctx, dev):
     plan.close()
 
 
+def test_coupled_reordering_grouped_query_heads(orc, ctx, dev):
+    """Value rows (3 heads of 64) coupled with output columns (12 heads of 64, 4 per value head)."""
+    say("coupled reordering: grouped-query heads")
+    HD, KV, REP, H = 64, 3, 4, 256
+    shapes = [(KV * HD, H), (H, KV * REP * HD)]                     # v, o
+    mats = [synth.make_matrix("student_t", r, c, seed=22, tid=i) for i, (r, c) in enumerate(shapes)]
+    plan, ws = make_plan(ctx, shapes, 64, 64, [2, 3, 4], dev)
+    dS = [S.to(dev) for _, S in mats]
+    rp = torch.full((sum(r for r, _ in shapes),), -7, dtype=torch.int32, device=dev)
+    cp = torch.full((sum(c for _, c in shapes),), -7, dtype=torch.int32, device=dev)
+    I = sb.DIM_INDEPENDENT
+    plan.reorder_coupled_all([sb.matrix(None, s_) for s_ in dS], [0, I], [I, 0], 1, [HD], rp, cp, ws,
+                             row_repeat=[1, 1], col_repeat=[1, REP])
+    torch.cuda.synchronize()
+    rp, cp = rp.cpu().numpy(), cp.cpu().numpy()
+    (rs_v, cs_v), (rs_o, cs_o) = [orc.channel_scores(S.numpy()) for _, S in mats]
+    pv = orc.coupled_perm([rs_v] + orc.fold_repeated(cs_o, HD, REP), HD)
+    np.testing.assert_array_equal(rp[:KV * HD], pv)
+    np.testing.assert_array_equal(cp[H:], orc.expand_perm(pv, HD, REP))
+    np.testing.assert_array_equal(rp[KV * HD:], orc.argsort_desc(rs_o))
+    np.testing.assert_array_equal(cp[:H], orc.argsort_desc(cs_v))
+    # a repeated member cannot lead its group, and repeats need pieces
+    for args, kw, status in ((([0, I], [I, 0]), dict(row_repeat=[REP, 1], col_repeat=[1, 1]), sb.ERR_INVALID_ARG),
+                             (([0, I], [I, 0]), dict(row_repeat=[1, 1], col_repeat=[1, 2]), sb.ERR_BAD_SHAPE)):
+        with pytest.raises(sb.SbitsError) as e:
+            plan.reorder_coupled_all([sb.matrix(None, s_) for s_ in dS], args[0], args[1], 1, [HD],
+                                     torch.empty_like(torch.from_numpy(rp)).to(dev),
+                                     torch.empty_like(torch.from_numpy(cp)).to(dev), ws, **kw)
+        assert e.value.status == status
+    plan.close()
+
+
 def test_coupled_reordering_rejects_unequal_members(ctx, dev):
     say("coupled reordering: unequal members")
     shapes = [(128, 256), (256, 128)]

@@ -175,3 +175,55 @@ def test_coupled_reordering_preserves_a_gated_mlp(orc):
     y = Wd @ (np.maximum(Wg @ x, 0) * (Wu @ x))
     y2 = d2 @ (np.maximum(g2 @ x[q], 0) * (u2 @ x[q]))
     np.testing.assert_array_equal(y2, y[q])
+
+
+def test_fold_and_expand_hand_example(orc):
+    """Group of 2 pieces x 2 channels, member with repeat 2 (8 channels): group piece 0 stands for
+    member pieces 0, 1 and group piece 1 for member pieces 2, 3."""
+    s = np.arange(8, dtype=np.float32)
+    lo, hi = orc.fold_repeated(s, 2, 2)
+    np.testing.assert_array_equal(lo, [0, 1, 4, 5])
+    np.testing.assert_array_equal(hi, [2, 3, 6, 7])
+    np.testing.assert_array_equal(orc.expand_perm([1, 0, 2, 3], 2, 2), [1, 0, 3, 2, 4, 5, 6, 7])
+
+
+def test_coupled_reordering_preserves_grouped_query_attention(orc):
+    """One token, one key position (attention weights 1): y = Wo concat_h (a_h * (Wv x)[kv(h)]) with
+    kv(h) = h // rep: query head h reads the value head it shares with rep - 1 others.  The rows of
+    Wv and the columns of Wo are reordered head by head from their summed scores (the r column
+    pieces of Wo folded onto the value head they read); the function is unchanged.  Exact integers."""
+    rng = np.random.default_rng(6)
+    HD, KV, REP, H = 8, 3, 4, 16
+    Wv = rng.integers(-3, 4, (KV * HD, H))
+    Wo = rng.integers(-3, 4, (H, KV * REP * HD))
+    Sv = rng.random(Wv.shape).astype(np.float32)
+    So = rng.random(Wo.shape).astype(np.float32)
+    a = rng.integers(1, 4, KV * REP)                              # per query head factor
+    rs_v, _ = orc.channel_scores(Sv)
+    _, cs_o = orc.channel_scores(So)
+    members = [rs_v] + orc.fold_repeated(cs_o, HD, REP)
+    assert len(members) == 1 + REP
+    pv = orc.coupled_perm(members, HD)
+    po = orc.expand_perm(pv, HD, REP)
+    assert sorted(po) == list(range(KV * REP * HD))
+    for h in range(KV * REP):                                     # every query head: its value head's order
+        np.testing.assert_array_equal(po[h * HD:(h + 1) * HD] - h * HD,
+                                      pv[(h // REP) * HD:(h // REP + 1) * HD] - (h // REP) * HD)
+    ident_v, ident_h = np.arange(KV * HD, dtype=np.int32), np.arange(H, dtype=np.int32)
+    bits = lambda M: M.astype(np.uint16)
+    v2 = orc.gather(bits(Wv + 8), Sv, pv, ident_h)[0].astype(np.int64) - 8
+    o2 = orc.gather(bits(Wo + 8), So, ident_h, po)[0].astype(np.int64) - 8
+
+    def attn(wv, wo, x):
+        v = (wv @ x).reshape(KV, HD)
+        per_head = np.concatenate([a[h] * v[h // REP] for h in range(KV * REP)])
+        return wo @ per_head
+
+    x = rng.integers(-5, 6, H)
+    np.testing.assert_array_equal(attn(v2, o2, x), attn(Wv, Wo, x))
+    # the group's score of a value channel = its own + the REP columns that read it, in that order
+    j = 5
+    want = rs_v[j]
+    for t in range(REP):
+        want = np.float32(want + cs_o[(j // HD) * REP * HD + t * HD + j % HD])
+    assert orc.group_scores(members)[j] == want
