@@ -235,6 +235,20 @@ def allocate(cost, bits, avg_bits, gamma0=0.05, gammaT=0.02, init_mode=0,
     return rc, level, st.as_dict(), trace
 
 
+def propose(s_up, s_down, level, bits, avg_bits, k):
+    """One step of Algorithm 2 on caller-supplied estimates: (kind, level_out, info);
+    kind 0 none, 1 expansion, 2 swap proposal."""
+    s_up, s_down = _f32(s_up), _f32(s_down)
+    level = np.ascontiguousarray(level, np.uint8)
+    bits = _i32(bits)
+    out = np.empty_like(level)
+    nu, nd, bb, ba = C.c_int64(0), C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    kind = lib().orc_propose(_p(s_up), _p(s_down), _p(level), C.c_int64(level.size), _p(bits), C.c_int(bits.size),
+                             C.c_double(avg_bits), C.c_int64(k), _p(out), C.byref(nu), C.byref(nd), C.byref(bb),
+                             C.byref(ba))
+    return kind, out, dict(n_up=nu.value, n_dn=nd.value, bits_before=bb.value, bits_after=ba.value)
+
+
 def cost_shift(cost) -> int:
     cost = _f32(cost)
     N, K = cost.shape

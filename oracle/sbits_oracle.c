@@ -347,6 +347,94 @@ static void msort(int64_t *idx, int64_t *tmp, int64_t n, const order_t *o)
     memcpy(idx, tmp, sizeof(int64_t) * (size_t)n);
 }
 
+/* One step of Algorithm 2 (lines 6-10) with the caller's own estimates: s_up[i] is the estimated
+ * gain of raising block i by one candidate, s_down[i] the estimated loss of lowering it by one
+ * (App. "choice of sensitivity statistics"); the values are ranked as given.  level_out receives
+ * the proposal.  Returns 1 = expansion (lines 6-7: the first min(k, eligible) blocks by
+ * (s_up descending, lower index first), cut at the first s_up <= 0 and at the budget),
+ * 2 = balanced swap to be accepted or rejected by the caller's own loss test (lines 9-12:
+ * U = first h = max(1, k/2) by s_up, D = first h by (s_down ascending, lower index first)
+ * outside U, U' = longest prefix of U that fits the slack plus the bits D frees),
+ * 0 = nothing to propose (level_out = level_in).  Negative: bad arguments.               */
+int orc_propose(const float *s_up, const float *s_down, const uint8_t *level_in, int64_t N,
+                const int32_t *bits, int K, double avg_bits, int64_t k, uint8_t *level_out,
+                int64_t *n_up, int64_t *n_dn, int64_t *bits_before, int64_t *bits_after)
+{
+    if (!s_up || !s_down || !level_in || !level_out || N <= 0 || !bits || K <= 0 || k < 1) return -3;
+    const int64_t T = (int64_t)floor(avg_bits * (double)N);
+    int64_t used = 0;
+    for (int64_t i = 0; i < N; ++i) { level_out[i] = level_in[i]; used += bits[level_in[i]]; }
+    const int64_t slack = T - used;
+    *n_up = *n_dn = 0;
+    *bits_before = *bits_after = used;
+
+    float *up = (float *)malloc(sizeof(float) * (size_t)N);
+    float *dn = (float *)malloc(sizeof(float) * (size_t)N);
+    int64_t *ordU = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);
+    int64_t *ordD = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);
+    int64_t *tmp = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);
+    uint8_t *inU = (uint8_t *)calloc((size_t)N, 1);
+    int64_t n_eu = 0, n_ed = 0;
+    for (int64_t i = 0; i < N; ++i) {
+        up[i] = s_up[i] + 0.0f;                       /* -0 ranks as +0 */
+        dn[i] = s_down[i] + 0.0f;
+        if (level_in[i] < K - 1) ordU[n_eu++] = i;
+        if (level_in[i] > 0) ordD[n_ed++] = i;
+    }
+    order_t oup = { up, 1 }, odn = { dn, 0 };
+    msort(ordU, tmp, n_eu, &oup);
+    msort(ordD, tmp, n_ed, &odn);
+
+    int kind = 0;
+    if (slack > 0) {                                  /* expansion */
+        int64_t lim = k < n_eu ? k : n_eu, cum = 0, p = 0;
+        while (p < lim) {
+            int64_t i = ordU[p];
+            int step = bits[level_in[i] + 1] - bits[level_in[i]];
+            if (!(up[i] > 0.0f) || cum + step > slack) break;
+            cum += step;
+            ++p;
+        }
+        if (p > 0) {
+            for (int64_t q = 0; q < p; ++q) level_out[ordU[q]]++;
+            *n_up = p;
+            *bits_after = used + cum;
+            kind = 1;
+        }
+    }
+    if (kind == 0) {                                  /* balanced swap */
+        int64_t h = k / 2;
+        if (h < 1) h = 1;
+        int64_t nU = h < n_eu ? h : n_eu;
+        for (int64_t q = 0; q < nU; ++q) inU[ordU[q]] = 1;
+        int64_t nD = 0, freed = 0;
+        for (int64_t q = 0; q < n_ed && nD < h; ++q) {
+            int64_t i = ordD[q];
+            if (inU[i]) continue;
+            ordD[nD++] = i;
+            freed += bits[level_in[i]] - bits[level_in[i] - 1];
+        }
+        int64_t nUp = 0, cum = 0;
+        while (nUp < nU) {
+            int64_t i = ordU[nUp];
+            int step = bits[level_in[i] + 1] - bits[level_in[i]];
+            if (cum + step > slack + freed) break;
+            cum += step;
+            ++nUp;
+        }
+        if (nUp > 0 && nD > 0) {
+            for (int64_t q = 0; q < nUp; ++q) level_out[ordU[q]]++;
+            for (int64_t q = 0; q < nD; ++q) level_out[ordD[q]]--;
+            *n_up = nUp;
+            *n_dn = nD;
+            *bits_after = used + cum - freed;
+            kind = 2;
+        }
+    }
+    free(up); free(dn); free(ordU); free(ordD); free(tmp); free(inU);
+    return kind;
+}
+
 int orc_allocate(const float *cost, int64_t N, const int32_t *bits, int K,
                  double avg_bits, const orc_params *prm, uint8_t *level,
                  orc_stats *stats, orc_trace *trace, int64_t trace_cap,

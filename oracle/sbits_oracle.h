@@ -128,6 +128,12 @@ int orc_allocate(const float *cost, int64_t N, const int32_t *bits, int K,
                  orc_stats *stats, orc_trace *trace, int64_t trace_cap,
                  int64_t *n_trace);
 
+/* One step of Algorithm 2 with caller-supplied estimates (the paper's own loop: fresh
+ * s_up / s_down every iteration, acceptance by the caller's loss): see the definition. */
+int orc_propose(const float *s_up, const float *s_down, const uint8_t *level_in, int64_t N,
+                const int32_t *bits, int K, double avg_bits, int64_t k, uint8_t *level_out,
+                int64_t *n_up, int64_t *n_dn, int64_t *bits_before, int64_t *bits_after);
+
 /* fixed-point helpers exposed for the tests */
 int32_t orc_cost_shift(const float *cost, int64_t N, int K);
 int64_t orc_fx(float v, int32_t shift);
