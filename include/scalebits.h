@@ -102,6 +102,14 @@ typedef struct {
     int64_t delta_fixed;   /* swap: fixed-point cost change of the proposal                  */
 } sbits_trace;
 
+/* Result of sbits_propose. */
+typedef struct {
+    int32_t kind;          /* 0 nothing to propose, 1 expansion, 2 balanced swap             */
+    int32_t pad_;
+    int64_t n_up, n_dn;    /* blocks raised / lowered in level_out                           */
+    int64_t bits_before, bits_after, bits_budget;   /* sum of bitwidths over blocks; floor(avg_bits * N) */
+} sbits_proposal;
+
 /* ---- context ---------------------------------------------------------------
  * device >= 0: HIP device ordinal; hip_stream: a hipStream_t (NULL = the null
  * stream).  device == -1 creates a host-only context: plans, sizes and argument
@@ -242,6 +250,29 @@ int  sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits,
                     const sbits_params *params, uint8_t *level,
                     sbits_stats *host_stats, sbits_trace *host_trace, int64_t trace_cap,
                     void *ws);
+
+/* One step of Algorithm 2 (lines 6-10) on the CALLER's estimates: the paper's own
+ * loop re-estimates s_up / s_down from a fresh gradient at every iteration (lines
+ * 4-5; sbits_surrogates_all computes them) and tests the loss of the proposal
+ * (lines 11-12), which only the caller can evaluate.  s_up[N], s_down[N]: float32,
+ * finite; ranked as given (not divided by the width of the step).  level_in[N]:
+ * the current levels; level_out[N] (may be level_in): the proposal.
+ *   slack = floor(avg_bits * N) - bits in use.
+ *   If slack > 0: expansion = the first min(k, eligible) blocks in the order
+ *     (s_up descending, lower index first), cut at the first s_up <= 0 and where
+ *     the cumulative step bits would exceed the slack; if that set is not empty it
+ *     is raised by one candidate each (kind 1; Alg. 2 applies it without a test).
+ *   Otherwise: balanced swap with h = max(1, k / 2): U = the first h by s_up,
+ *     D = the first h by (s_down ascending, lower index first) outside U, U' = the
+ *     longest prefix of U whose step bits fit slack + the bits D frees; if U' and D
+ *     are both non-empty, U' is raised and D lowered (kind 2): the caller keeps
+ *     level_out if its loss did not increase, else keeps level_in and halves k.
+ *   Else kind 0 and level_out = level_in (the caller halves k).
+ * The loop ends when k < floor(gammaT * N).  host_out (HOST, may be NULL): filled
+ * after waiting for the stream; with NULL the call does not wait.  Uses ws.       */
+int  sbits_propose(sbits_plan *plan, const float *s_up, const float *s_down,
+                   const uint8_t *level_in, double avg_bits, int64_t k,
+                   uint8_t *level_out, sbits_proposal *host_out, void *ws);
 
 /* ---- storage (paper Sec. 5.3: one bitwidth per tile) --------------------------
  * byte_off[i] = sum_{i'<i} m*n*c[level[i']]/8, byte_off[N] = total.  Uses ws.   */

@@ -25,7 +25,7 @@ EXPORTS = [
     "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
     "sbits_reorder_coupled_all", "sbits_surrogates_all",
-    "sbits_allocate", "sbits_offsets", "sbits_pack", "sbits_search",
+    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search",
 ]
 
 
@@ -53,6 +53,14 @@ class Trace(C.Structure):
     _fields_ = [("kind", C.c_int32), ("pad_", C.c_int32), ("k", C.c_int64), ("n_up", C.c_int64),
                 ("n_dn", C.c_int64), ("p_up", C.c_int64), ("p_dn", C.c_int64),
                 ("bits_before", C.c_int64), ("bits_after", C.c_int64), ("delta_fixed", C.c_int64)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_ if f != "pad_"}
+
+
+class Proposal(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("pad_", C.c_int32), ("n_up", C.c_int64), ("n_dn", C.c_int64),
+                ("bits_before", C.c_int64), ("bits_after", C.c_int64), ("bits_budget", C.c_int64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_ if f != "pad_"}
@@ -253,6 +261,15 @@ class Plan:
         _check(rc, "sbits_allocate", allow=(ERR_MAX_ITERS,))
         n = min(st.iters, trace_cap)
         return rc, st.as_dict(), [tr[i].as_dict() for i in range(n)]
+
+    def propose(self, s_up, s_down, level_in, avg_bits, k, level_out, ws, want_info=True):
+        """One step of Algorithm 2 on caller-supplied estimates; returns the proposal's dict
+        (kind 0 none, 1 expansion, 2 swap) or None without waiting when want_info is False."""
+        pr = Proposal()
+        _check(load().sbits_propose(self.h, _ptr(s_up), _ptr(s_down), _ptr(level_in), C.c_double(avg_bits),
+                                    C.c_int64(k), _ptr(level_out), C.byref(pr) if want_info else None, _ptr(ws)),
+               "sbits_propose")
+        return pr.as_dict() if want_info else None
 
     def offsets(self, level, byte_off, ws):
         return _check(load().sbits_offsets(self.h, _ptr(level), _ptr(byte_off), _ptr(ws)), "sbits_offsets")

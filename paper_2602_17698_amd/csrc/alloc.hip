@@ -58,6 +58,7 @@ struct AllocState {
     int done, status, mode;
     unsigned int maxc_bits;
     int bits[8];
+    long long prop_up, prop_dn, prop_after;   // the single step on caller-supplied estimates: its result
     SelJob job[N_JOBS];
 };
 
@@ -326,6 +327,7 @@ void apply_expand_kernel(const AllocState *st, const unsigned long long *__restr
 // after U and D are known: the raised set is the prefix of U that fits slack + freed bits
 __global__ void prep_u2_kernel(AllocState *st)
 {
+    if (st->mode == MODE_EXPAND) return;          // (single step: the swap jobs were closed by the expansion)
     const SelJob &u = st->job[JOB_U];
     const SelJob &d = st->job[JOB_D];
     long long h = st->k / 2;
@@ -406,6 +408,108 @@ void apply_swap_kernel(const AllocState *st, const unsigned long long *__restric
         const unsigned long long ku = keyU[i], kd = keyD[i];
         if (ku >= tauU2) level[i] = level[i] + 1;
         else if (kd >= tauD && !(ku >= tauU)) level[i] = level[i] - 1;
+    }
+}
+
+// ---- a single step on caller-supplied estimates (the paper's own loop: s_up / s_down are
+// re-estimated from a fresh gradient every iteration, Alg. 2 lines 4-5; the acceptance test of
+// lines 11-12 is the caller's, who owns the loss) -------------------------------------------
+// keys as in gains_kernel, the values taken as given; the bits in use are summed on the way
+__global__ __launch_bounds__(AL_THREADS)
+void step_keys_kernel(AllocState *st, const float *__restrict__ s_up, const float *__restrict__ s_down,
+                      const uint8_t *__restrict__ level, unsigned long long *__restrict__ keyU,
+                      unsigned long long *__restrict__ keyD)
+{
+    __shared__ long long su[AL_THREADS / 64];
+    const long long N = st->N;
+    const int K = st->K, IB = st->IB;
+    int bits[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) bits[c] = st->bits[c];
+    long long used = 0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x) {
+        const int l = min((int)level[i], K - 1);
+        used += bits[l];
+        const unsigned long long low = (unsigned long long)(N - 1 - i) << 8;
+        unsigned long long ku = 0, kd = 0;
+        if (l < K - 1)
+            ku = ((unsigned long long)ord_f32(s_up[i]) << (IB + 8)) | low | (unsigned)(bits[l + 1] - bits[l]);
+        if (l > 0)
+            kd = ((unsigned long long)(~ord_f32(s_down[i])) << (IB + 8)) | low | (unsigned)(bits[l] - bits[l - 1]);
+        keyU[i] = ku;
+        keyD[i] = kd;
+    }
+    for (int off = 32; off; off >>= 1) used += __shfl_xor(used, off);
+    if ((threadIdx.x & 63) == 0) su[threadIdx.x >> 6] = used;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long a = 0;
+        for (int w = 0; w < AL_THREADS / 64; ++w) a += su[w];
+        atomicAdd((unsigned long long *)&st->used, (unsigned long long)a);
+    }
+}
+
+__global__ void step_jobs_kernel(AllocState *st)
+{
+    const long long slack = st->T - st->used;
+    long long h = st->k / 2;
+    if (h < 1) h = 1;
+    const unsigned long long key_pos = (unsigned long long)0x80000001u << (st->IB + 8);  // value > +0
+    job_reset(&st->job[JOB_E], st->k, slack > 0 ? slack : 0, key_pos);
+    job_reset(&st->job[JOB_U], h, 0x7fffffffffffffffll, 1);
+    job_reset(&st->job[JOB_D], h, 0x7fffffffffffffffll, 1);
+    job_reset(&st->job[JOB_U2], h, 0, 1);
+    st->mode = MODE_NONE;
+    st->prop_up = st->prop_dn = 0;
+    st->prop_after = st->used;
+}
+
+// after the expansion's selection: an expansion closes the swap's jobs (their passes return at once)
+__global__ void step_decide_expand_kernel(AllocState *st)
+{
+    const SelJob &e = st->job[JOB_E];
+    if (st->T - st->used > 0 && e.n_sel > 0) {
+        st->mode = MODE_EXPAND;
+        st->prop_up = e.n_sel;
+        st->prop_after = st->used + e.w_sel;
+        st->job[JOB_U].resolved = st->job[JOB_D].resolved = st->job[JOB_U2].resolved = 1;
+    }
+}
+
+__global__ void step_decide_swap_kernel(AllocState *st)
+{
+    if (st->mode == MODE_EXPAND) return;
+    const SelJob &u2 = st->job[JOB_U2];
+    const SelJob &d = st->job[JOB_D];
+    if (u2.n_sel > 0 && d.n_sel > 0) {
+        st->mode = MODE_ACCEPT;                    // a proposal: the caller accepts or rejects it
+        st->prop_up = u2.n_sel;
+        st->prop_dn = d.n_sel;
+        st->prop_after = st->used + u2.w_sel - d.w_sel;
+    }
+}
+
+__global__ __launch_bounds__(AL_THREADS)
+void step_apply_kernel(const AllocState *st, const unsigned long long *__restrict__ keyU,
+                       const unsigned long long *__restrict__ keyD, const uint8_t *__restrict__ level_in,
+                       uint8_t *__restrict__ level_out)
+{
+    const int mode = st->mode;
+    const unsigned long long tauE = st->job[JOB_E].tau;
+    const unsigned long long tauU = st->job[JOB_U].tau, tauD = st->job[JOB_D].tau, tauU2 = st->job[JOB_U2].tau;
+    const long long N = st->N;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (long long)gridDim.x * blockDim.x) {
+        const unsigned long long ku = keyU[i], kd = keyD[i];
+        int l = level_in[i];
+        if (mode == MODE_EXPAND) {
+            if (ku >= tauE) ++l;
+        } else if (mode == MODE_ACCEPT) {
+            if (ku >= tauU2) ++l;
+            else if (kd >= tauD && !(ku >= tauU)) --l;
+        }
+        level_out[i] = (uint8_t)l;
     }
 }
 
@@ -568,4 +672,71 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     }
     if (h.bits_check != h.used) return SBITS_ERR_INVALID_ARG;   // internal accounting must agree
     return h.status;
+}
+
+
+// One step of Algorithm 2 on caller-supplied estimates.  Workspace as sbits_run_allocate.
+int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, const uint8_t *level_in,
+                      double avg_bits, int64_t k, uint8_t *level_out, sbits_proposal *host_out, void *ws)
+{
+    sbits_ctx *ctx = plan->ctx;
+    hipStream_t sm = ctx->stream;
+    const int64_t N = plan->N;
+    const int K = plan->K;
+
+    char *p = static_cast<char *>(ws);
+    AllocState *st = reinterpret_cast<AllocState *>(p);
+    p += sbits_align_up(sizeof(AllocState), 256);
+    unsigned long long *keyU = reinterpret_cast<unsigned long long *>(p);
+    p += sbits_align_up((size_t)N * 8, 256);
+    unsigned long long *keyD = reinterpret_cast<unsigned long long *>(p);
+
+    if (!ctx->pinned) SBITS_HIP(ctx, hipHostMalloc(&ctx->pinned, SBITS_PINNED_BYTES, hipHostMallocDefault));
+    AllocState *hp = static_cast<AllocState *>(ctx->pinned);
+    std::vector<unsigned char> himg(sizeof(AllocState), 0);
+    AllocState &h = *reinterpret_cast<AllocState *>(himg.data());
+    h.N = N;
+    h.T = (long long)floor(avg_bits * (double)N);
+    h.k = k;
+    h.K = K;
+    h.IB = ceil_log2_ll(N) > 0 ? ceil_log2_ll(N) : 1;
+    h.P = (32 + h.IB + SEL_DB - 1) / SEL_DB;
+    for (int c = 0; c < 8; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
+    SBITS_HIP(ctx, hipMemcpyAsync(st, &h, sizeof h, hipMemcpyHostToDevice, sm));
+    SBITS_HIP(ctx, hipStreamSynchronize(sm));      // the image goes away on return
+
+    const unsigned grid = (unsigned)((N + AL_THREADS - 1) / AL_THREADS < 1024 ? (N + AL_THREADS - 1) / AL_THREADS : 1024);
+    const unsigned sgrid = (unsigned)((N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) < 128 ? (N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) : 128);
+    const int P = h.P;
+    const unsigned long long *none = nullptr;
+    hipLaunchKernelGGL(step_keys_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, s_up, s_down, level_in, keyU, keyD);
+    hipLaunchKernelGGL(step_jobs_kernel, dim3(1), dim3(1), 0, sm, st);
+    for (int ps = 0; ps < P; ++ps)
+        hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_E, keyU, none, 0, ps);
+    hipLaunchKernelGGL(step_decide_expand_kernel, dim3(1), dim3(1), 0, sm, st);
+    for (int ps = 0; ps < P; ++ps)
+        hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U, keyU, none, 0, ps);
+    for (int ps = 0; ps < P; ++ps)
+        hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_D, keyD,
+                           (const unsigned long long *)keyU, (int)JOB_U, ps);
+    hipLaunchKernelGGL(prep_u2_kernel, dim3(1), dim3(1), 0, sm, st);
+    for (int ps = 0; ps < P; ++ps)
+        hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_U2, keyU, none, 0, ps);
+    hipLaunchKernelGGL(step_decide_swap_kernel, dim3(1), dim3(1), 0, sm, st);
+    hipLaunchKernelGGL(step_apply_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, (const AllocState *)st,
+                       (const unsigned long long *)keyU, (const unsigned long long *)keyD, level_in, level_out);
+    SBITS_HIP(ctx, hipGetLastError());
+    if (host_out) {
+        static_assert(offsetof(AllocState, job) <= SBITS_PINNED_BYTES, "state head must fit the pinned buffer");
+        SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+        SBITS_HIP(ctx, hipStreamSynchronize(sm));
+        host_out->kind = hp->mode == MODE_EXPAND ? 1 : hp->mode == MODE_ACCEPT ? 2 : 0;
+        host_out->pad_ = 0;
+        host_out->n_up = hp->prop_up;
+        host_out->n_dn = hp->prop_dn;
+        host_out->bits_before = hp->used;
+        host_out->bits_after = hp->prop_after;
+        host_out->bits_budget = hp->T;
+    }
+    return SBITS_OK;
 }

@@ -361,6 +361,17 @@ int sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits, const s
                               sbits_scratch(plan, ws));
 }
 
+int sbits_propose(sbits_plan *plan, const float *s_up, const float *s_down, const uint8_t *level_in,
+                  double avg_bits, int64_t k, uint8_t *level_out, sbits_proposal *host_out, void *ws)
+{
+    if (!plan || !s_up || !s_down || !level_in || !level_out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (k < 1 || !(avg_bits == avg_bits)) return SBITS_ERR_INVALID_ARG;
+    if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_run_propose(plan, s_up, s_down, level_in, avg_bits, k, level_out, host_out, sbits_scratch(plan, ws));
+}
+
 int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws)
 {
     if (!plan || !level || !byte_off || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;

@@ -108,6 +108,8 @@ int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const
 int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                                  const uint8_t *level, const int64_t *byte_off, uint8_t *codes, float *scale,
                                  float *zero, void *ws);
+int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, const uint8_t *level_in,
+                      double avg_bits, int64_t k, uint8_t *level_out, sbits_proposal *host_out, void *ws);
 int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
                        const sbits_params *prm, uint8_t *level, sbits_stats *host_stats,
                        sbits_trace *host_trace, int64_t trace_cap, void *ws);

@@ -138,6 +138,20 @@ def test_one_pass_and_coupled_entry_points_validate_on_the_host(ctx, lib):
     q.close()
 
 
+def test_propose_validates_on_the_host(ctx, lib):
+    ptr = C.c_void_p(4096)
+    p = sb.Plan(ctx, [(256, 256)], 64, 128, [2, 3, 4])
+    call = lambda su, lv, avg, k: lib.sbits_propose(p.h, su, ptr, lv, C.c_double(avg), C.c_int64(k), ptr, None,
+                                                    C.c_void_p(256 * 1024))
+    assert call(None, ptr, 3.0, 4) == sb.ERR_INVALID_ARG
+    assert call(ptr, None, 3.0, 4) == sb.ERR_INVALID_ARG
+    assert call(ptr, ptr, 3.0, 0) == sb.ERR_INVALID_ARG                 # k >= 1
+    assert call(ptr, ptr, float("nan"), 4) == sb.ERR_INVALID_ARG
+    assert call(ptr, ptr, 1.5, 4) == sb.ERR_INFEASIBLE_BUDGET           # below the smallest candidate
+    assert call(ptr, ptr, 3.0, 4) == sb.ERR_HIP                         # valid: needs a device
+    p.close()
+
+
 def test_plan_limits(ctx):
     """At most 32768 rows / columns per matrix and 2^24 blocks per plan."""
     sb.Plan(ctx, [(32768, 32768)], 8, 8, [2]).close()                    # 2^24 blocks: the limit itself

@@ -352,3 +352,70 @@ def test_paper_default_search_space(orc):
     for idx in (1, 3, 13):                                    # k of layer 0, o of layer 0, down of layer 1
         say("  matrix", idx, shapes[idx])
         check_matrix(orc, o, shapes, bases, idx, mats[idx][0], mats[idx][1], m, n, bits, level, off)
+
+
+def test_dynamic_iteration_full_model(orc):
+    """One iteration of the paper's own loop on the 8B-shaped model (Alg. 2 lines 4-10 with fresh
+    estimates): surrogates from a signed gradient at the current levels, then the proposal.  Sampled
+    matrices' surrogates against the oracle; the proposal against the oracle's step on the (GPU-made)
+    full surrogate arrays; both an expansion and a swap."""
+    say("dynamic iteration, full 8B-shaped model")
+    dev = torch.device("cuda:0")
+    m = n = 128
+    bits = [1, 2, 3, 4]
+    names, mats, shapes = [], [], []
+    for layer in range(32):
+        for name, r, c in synth.layer_shapes(synth.LLAMA3_8B):
+            w, s = synth.make_matrix("student_t", r, c, seed=0, tid=synth.tensor_id(layer, name), device=dev)
+            names.append((layer, name)); mats.append((w, s)); shapes.append((r, c))
+    ctx = sb.Context(0, torch.cuda.current_stream().cuda_stream)
+    plan = sb.Plan(ctx, shapes, m, n, bits)
+    N = plan.num_blocks()
+    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device=dev)
+    rp = torch.empty(sum(r for r, _ in shapes), dtype=torch.int32, device=dev)
+    cp = torch.empty(sum(c for _, c in shapes), dtype=torch.int32, device=dev)
+    dm = [sb.matrix(w, s) for w, s in mats]
+    plan.reorder_all(dm, rp, cp, ws)
+    torch.cuda.synchronize()
+    for _, s in mats:                                    # the "gradient": the sensitivity with a sign per element
+        r, c = s.shape
+        sign = ((torch.arange(r, device=dev)[:, None] * 7 + torch.arange(c, device=dev)[None, :] * 13) % 5 < 2)
+        s.mul_(torch.where(sign, -1.0, 1.0))
+    rng = np.random.default_rng(5)
+    level_h = rng.integers(0, 4, N).astype(np.uint8)
+    level = torch.from_numpy(level_h).to(dev)
+    s_up = torch.empty(N, dtype=torch.float32, device=dev)
+    s_dn = torch.empty(N, dtype=torch.float32, device=dev)
+    prop = torch.empty_like(level)
+    used = int(np.asarray(bits)[level_h].sum())
+    k = int(0.05 * N)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for avg, want_kind in ((used / N + 1e-9, 2), ((used + 3 * k) / N + 1e-9, 1)):
+        for rep in range(2):                             # second round timed
+            ev[0].record()
+            plan.surrogates_all(dm, rp, cp, level, s_up, s_dn, ws)
+            ev[1].record()
+            info = plan.propose(s_up, s_dn, level, avg, k, prop, ws)
+            ev[2].record()
+            torch.cuda.synchronize()
+        say("  surrogates %.2f ms, proposal %.2f ms (kind %d, %d up, %d down)" % (
+            ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), info["kind"], info["n_up"], info["n_dn"]))
+        su, sd = s_up.cpu().numpy(), s_dn.cpu().numpy()
+        assert np.all(np.isfinite(su)) and np.all(sd >= 0)
+        kind, want, winfo = orc.propose(su, sd, level_h, bits, avg, k)
+        assert kind == info["kind"] == want_kind
+        np.testing.assert_array_equal(prop.cpu().numpy(), want)
+        assert all(info[f] == winfo[f] for f in winfo)
+        assert info["bits_after"] <= max(info["bits_budget"], used)
+    rph, cph = rp.cpu().numpy(), cp.cpu().numpy()
+    for layer, name in [(0, "k"), (15, "v"), (31, "k")]:
+        idx = names.index((layer, name))
+        say("  sampled surrogates", layer, name)
+        R, C = shapes[idx]
+        ro, co = sum(r for r, _ in shapes[:idx]), sum(c for _, c in shapes[:idx])
+        Wp, Gp = orc.gather(synth.bf16_bits(mats[idx][0]), mats[idx][1].cpu().numpy(), rph[ro:ro + R], cph[co:co + C])
+        b0, nb = plan.block_base(idx), (R // m) * (C // n)
+        u, d = orc.surrogates(Wp, Gp, m, n, bits, level_h[b0:b0 + nb])
+        np.testing.assert_array_equal(su[b0:b0 + nb], u)
+        np.testing.assert_array_equal(sd[b0:b0 + nb], d)
+    plan.close(); ctx.close()

@@ -725,3 +725,94 @@ def test_search_is_deterministic(ctx, dev):
         if key == "one_pass" or (key == "s_re" and a[2]["one_pass"]):     # s_re: not written on the one-pass route
             continue
         assert torch.equal(a[2][key].view(torch.uint8), b[2][key].view(torch.uint8)), key
+
+
+# ------------------------------------------------------------------------ one step on caller-supplied estimates
+def _blocks_plan(ctx, N, bits, dev):
+    """A plan with exactly N blocks (8 x 8 blocks of one matrix, or the 8B-shaped model)."""
+    if N == 425984:
+        shapes = [(r, c) for _ in range(32) for _, r, c in synth.layer_shapes(synth.LLAMA3_8B)]
+        return make_plan(ctx, shapes, 128, 128, bits, dev)
+    if N == 50000:
+        return make_plan(ctx, [(1600, 2000)], 8, 8, bits, dev)
+    return make_plan(ctx, [(8, 8 * N)], 8, 8, bits, dev)
+
+
+@pytest.mark.parametrize("N,bits", [(1, [2, 3, 4]), (37, [1, 2, 3, 4]), (4096, [1, 2, 3, 4, 8]), (50000, [2, 4, 8]),
+                                    (425984, [1, 2, 3, 4])])
+def test_propose_matches_oracle(orc, ctx, dev, N, bits):
+    say("propose", N, bits)
+    plan, ws = _blocks_plan(ctx, N, bits, dev)
+    assert plan.num_blocks() == N
+    K = len(bits)
+    rng = np.random.default_rng(N)
+    for case in range(8):
+        level = rng.integers(0, K, N).astype(np.uint8)
+        if case == 6: level[:] = K - 1                             # nobody can be raised
+        if case == 7: level[:] = 0                                 # nobody can be lowered
+        if case % 2:                                               # many ties, some non-positive
+            s_up = rng.integers(-2, 6, N).astype(np.float32)
+            s_dn = rng.integers(0, 4, N).astype(np.float32)
+        else:
+            s_up = rng.standard_normal(N).astype(np.float32) * np.float32(3)
+            s_dn = np.abs(rng.standard_normal(N)).astype(np.float32)
+        used = int(np.asarray(bits)[level].sum())
+        slack = [0, 0, max(1, N // 50), 3 * N, -1, 1, 0, N][case]
+        avg = (used + slack) / N + 1e-9
+        if avg < bits[0]:
+            continue
+        k = [max(1, N // 20), 1, max(1, N // 20), N + 5, max(1, N // 10), 2, 4, max(1, N // 3)][case]
+        d_out = torch.full((N,), 77, dtype=torch.uint8, device=dev)
+        info = plan.propose(torch.from_numpy(s_up).to(dev), torch.from_numpy(s_dn).to(dev),
+                            torch.from_numpy(level).to(dev), avg, k, d_out, ws)
+        kind, want, winfo = orc.propose(s_up, s_dn, level, bits, avg, k)
+        assert info["kind"] == kind, (case, info, winfo)
+        np.testing.assert_array_equal(d_out.cpu().numpy(), want, err_msg="case %d" % case)
+        for f in ("n_up", "n_dn", "bits_before", "bits_after"):
+            assert info[f] == winfo[f], (case, f, info, winfo)
+        assert info["bits_budget"] == int(np.floor(avg * N))
+    # in place, and without the host read-back
+    lv = torch.from_numpy(level).to(dev)
+    plan.propose(torch.from_numpy(s_up).to(dev), torch.from_numpy(s_dn).to(dev), lv, avg, k, lv, ws, want_info=False)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(lv.cpu().numpy(), want)
+    plan.close()
+
+
+def test_propose_loop_on_exact_differences_reproduces_allocate(orc, ctx, dev):
+    """The caller-driven loop (propose, the caller's fixed-point loss test, halve k on rejection) fed with
+    the cost table's own differences ends at the allocation of sbits_allocate (contiguous bitwidths)."""
+    say("propose loop == allocate")
+    N, bits = 4096, [1, 2, 3, 4]
+    plan, ws = _blocks_plan(ctx, N, bits, dev)
+    rng = np.random.default_rng(3)
+    base = rng.lognormal(0, 1.5, N).astype(np.float32)
+    cost = (base[:, None] * np.array([1.0, 0.3, 0.1, 0.02], np.float32) *
+            rng.uniform(0.7, 1.3, (N, 4)).astype(np.float32)).astype(np.float32)
+    dcost = torch.from_numpy(cost).to(dev)
+    idx = torch.arange(N, device=dev)
+    shift = orc.cost_shift(cost)
+    for avg in (2.5, 3.0):
+        want = torch.empty(N, dtype=torch.uint8, device=dev)
+        _, st, _ = plan.allocate(dcost, avg, want, ws)
+        level = torch.full((N,), int(avg) - 1, dtype=torch.uint8, device=dev)
+        prop = torch.empty_like(level)
+        k, kmin, iters = max(1, int(0.05 * N)), max(1, int(0.02 * N)), 0
+        while k >= kmin:
+            iters += 1
+            l = level.long()
+            up = torch.where(l < 3, dcost[idx, l] - dcost[idx, (l + 1).clamp(max=3)], torch.zeros((), device=dev))
+            dn = torch.where(l > 0, dcost[idx, (l - 1).clamp(min=0)] - dcost[idx, l], torch.zeros((), device=dev))
+            info = plan.propose(up, dn, level, avg, k, prop, ws)
+            if info["kind"] == 1:
+                level, prop = prop, level
+            elif info["kind"] == 2:
+                fxs = lambda v: torch.round(v.double() * 2.0 ** shift).long().sum().item()   # exact: |v| 2^shift < 2^53
+                delta = fxs(dn[prop < level]) - fxs(up[prop > level])
+                if delta < 0: level, prop = prop, level
+                else: k //= 2
+            else:
+                k //= 2
+        np.testing.assert_array_equal(level.cpu().numpy(), want.cpu().numpy())
+        assert iters == st["iters"]
+    plan.close()
