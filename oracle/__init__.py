@@ -295,3 +295,24 @@ def pack(Wp_u16, m, n, bits, level, byte_off, block_base, codes, scale, zero):
     lib().orc_pack(_p(Wp_u16), C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n), _p(bits),
                    C.c_int(bits.size), _p(level), _p(byte_off), C.c_int64(block_base),
                    _p(codes), _p(scale), _p(zero))
+
+
+def dequant(codes, scale, zero, level, byte_off, block_base, R, Cc, m, n, bits):
+    """The stored matrix (fp32 [R, Cc]) from the packed arrays."""
+    bits = _i32(bits)
+    out = np.empty((R, Cc), np.float32)
+    lib().orc_dequant(_p(codes), _p(scale), _p(zero), _p(level), _p(byte_off), C.c_int64(block_base),
+                      C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n), _p(bits), _p(out))
+    return out
+
+
+def mp_gemm(codes, scale, zero, level, byte_off, block_base, R, Cc, m, n, bits, x_u16):
+    """y[b][i] = sum_j What[i][j] x[b][j] (float64); x_u16: bf16 patterns [batch, Cc]."""
+    bits = _i32(bits)
+    x_u16 = _u16(x_u16)
+    assert x_u16.shape[1] == Cc
+    y = np.empty((x_u16.shape[0], R), np.float64)
+    lib().orc_mp_gemm(_p(codes), _p(scale), _p(zero), _p(level), _p(byte_off), C.c_int64(block_base),
+                      C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n), _p(bits), _p(x_u16),
+                      C.c_int(x_u16.shape[0]), _p(y))
+    return y

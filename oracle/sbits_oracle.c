@@ -682,3 +682,52 @@ void orc_pack(const uint16_t *Wp, int64_t R, int64_t C, int m, int n,
     }
     free(wrow);
 }
+
+
+/* ------------------------------------------ inference: mixed-precision product (Sec. 5.3) */
+
+/* code of element e of a block stored at `blk` with c bits per code (LSB-first bit stream) */
+static unsigned stream_code(const uint8_t *blk, int64_t e, int c)
+{
+    unsigned q = 0;
+    for (int t = 0; t < c; ++t) {
+        int64_t bit = e * c + t;
+        q |= (unsigned)((blk[bit >> 3] >> (bit & 7)) & 1u) << t;
+    }
+    return q;
+}
+
+/* The stored matrix, dequantized: What[i][j] = fmaf(q, scale, zero) in fp32 (the format's
+ * definition of the stored value), from the packed arrays of one matrix of R x C in m x n blocks. */
+void orc_dequant(const uint8_t *codes, const float *scale, const float *zero, const uint8_t *level,
+                 const int64_t *byte_off, int64_t block_base, int64_t R, int64_t C, int m, int n,
+                 const int32_t *bits, float *What)
+{
+    const int64_t nbc = C / n;
+    for (int64_t i = 0; i < R; ++i)
+        for (int64_t j = 0; j < C; ++j) {
+            const int64_t blk = block_base + (i / m) * nbc + j / n;
+            const int r = (int)(i % m), cc = (int)(j % n);
+            const int c = bits[level[blk]];
+            const unsigned q = stream_code(codes + byte_off[blk], (int64_t)r * n + cc, c);
+            What[i * C + j] = fmaf((float)q, scale[blk * m + r], zero[blk * m + r]);
+        }
+}
+
+/* y[b][i] = sum_j What[i][j] * x[b][j]: the layer's product with the stored weights, x given as
+ * bf16 bit patterns [batch][C], the sum in float64 over j ascending. */
+void orc_mp_gemm(const uint8_t *codes, const float *scale, const float *zero, const uint8_t *level,
+                 const int64_t *byte_off, int64_t block_base, int64_t R, int64_t C, int m, int n,
+                 const int32_t *bits, const uint16_t *x, int batch, double *y)
+{
+    float *What = (float *)malloc(sizeof(float) * (size_t)(R * C));
+    orc_dequant(codes, scale, zero, level, byte_off, block_base, R, C, m, n, bits, What);
+    for (int b = 0; b < batch; ++b)
+        for (int64_t i = 0; i < R; ++i) {
+            double a = 0.0;
+            for (int64_t j = 0; j < C; ++j)
+                a += (double)What[i * C + j] * (double)bf16_to_f32(x[(int64_t)b * C + j]);
+            y[(int64_t)b * R + i] = a;
+        }
+    free(What);
+}

@@ -163,6 +163,17 @@ void orc_pack(const uint16_t *Wp, int64_t R, int64_t C, int m, int n,
               const int64_t *byte_off, int64_t block_base,
               uint8_t *codes, float *scale, float *zero);
 
+/* ---- inference with the stored weights (paper Sec. 5.3 "Inference Kernel") ----
+ * orc_dequant: the stored matrix What[i][j] = fmaf(q, scale, zero) (fp32).
+ * orc_mp_gemm: y[b][i] = sum_j What[i][j] * x[b][j] in float64 (x: bf16 patterns,
+ * [batch][C]; y: [batch][R]).  Arguments as orc_pack's outputs.                 */
+void orc_dequant(const uint8_t *codes, const float *scale, const float *zero, const uint8_t *level,
+                 const int64_t *byte_off, int64_t block_base, int64_t R, int64_t C, int m, int n,
+                 const int32_t *bits, float *What);
+void orc_mp_gemm(const uint8_t *codes, const float *scale, const float *zero, const uint8_t *level,
+                 const int64_t *byte_off, int64_t block_base, int64_t R, int64_t C, int m, int n,
+                 const int32_t *bits, const uint16_t *x, int batch, double *y);
+
 #ifdef __cplusplus
 }
 #endif
