@@ -320,6 +320,24 @@ int  sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits,
                   const sbits_params *params, const sbits_outputs *out,
                   sbits_stats *host_stats, void *ws);
 
+/* ---- inference with the stored weights (paper Sec. 5.3 "Inference Kernel") -----
+ * y[b][i] = sum_j What[i][j] * x[b][j] for matrix `mat` of the plan, read from the
+ * packed stream (the outputs of sbits_pack / sbits_pack_all / sbits_gather_pack_all,
+ * the GLOBAL arrays): What[i][j] = code * scale + zero of the element's block row.
+ * Dequantization is fused into the product, tile = precision block, one bitwidth
+ * per tile.  Rows and columns are the REORDERED ones: x is indexed by the matrix's
+ * permuted input channels and y by its permuted output channels (the paper stores
+ * the permuted weights and keeps connected layers consistent, App. "Channel
+ * Reordering").  x_bf16: [batch][ld_x] bfloat16, 16-byte aligned, ld_x >= cols and a
+ * multiple of 8; y: [batch][rows] float32; 1 <= batch <= 32 (larger batches: several
+ * calls).  Products are exact (integer codes times bf16) and summed in fp32 on the
+ * matrix cores; scale and zero are applied per block row in fp32.
+ * SBITS_ERR_UNIMPLEMENTED unless block_cols is 64 or 128 and block_rows a multiple
+ * of 32.  Uses ws.                                                               */
+int  sbits_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, int batch,
+                   const uint8_t *level, const int64_t *byte_off, const uint8_t *codes,
+                   const float *scale, const float *zero, float *y, void *ws);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = [
     "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
     "sbits_reorder_coupled_all", "sbits_surrogates_all",
-    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search",
+    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search", "sbits_mp_gemm",
 ]
 
 
@@ -277,6 +277,12 @@ class Plan:
     def pack(self, mat, w_re, level, byte_off, codes, scale, zero):
         return _check(load().sbits_pack(self.h, C.c_int(mat), _ptr(w_re), _ptr(level), _ptr(byte_off),
                                         _ptr(codes), _ptr(scale), _ptr(zero)), "sbits_pack")
+
+    def mp_gemm(self, mat, x, level, byte_off, codes, scale, zero, y, ws):
+        """y[b][i] = sum_j What[i][j] x[b][j] from the packed arrays; x: bf16 [batch, cols], y: fp32 [batch, rows]."""
+        return _check(load().sbits_mp_gemm(self.h, C.c_int(mat), _ptr(x), C.c_int64(x.stride(0)), C.c_int(x.shape[0]),
+                                           _ptr(level), _ptr(byte_off), _ptr(codes), _ptr(scale), _ptr(zero),
+                                           _ptr(y), _ptr(ws)), "sbits_mp_gemm")
 
     def search(self, mats, avg_bits, out: Outputs, ws, gamma0=0.05, gammaT=0.02, init_mode=0,
                max_iters=100000):

@@ -116,6 +116,8 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
     if (o > ws) ws = o;
     const size_t f = sbits_fused_ws_bytes(p);
     if (f > ws) ws = f;
+    const size_t g = sbits_mp_gemm_ws_bytes(p);
+    if (g > ws) ws = g;
     p->head_bytes = sbits_desc_bytes(n_mats) + SBITS_N_PREFIX * sbits_prefix_bytes(n_mats);
     p->ws_bytes = p->head_bytes + ws;
     *out = p;
@@ -370,6 +372,22 @@ int sbits_propose(sbits_plan *plan, const float *s_up, const float *s_down, cons
     int rc = need_device(plan);
     if (rc) return rc;
     return sbits_run_propose(plan, s_up, s_down, level_in, avg_bits, k, level_out, host_out, sbits_scratch(plan, ws));
+}
+
+int sbits_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, int batch, const uint8_t *level,
+                  const int64_t *byte_off, const uint8_t *codes, const float *scale, const float *zero, float *y,
+                  void *ws)
+{
+    if (!plan || mat < 0 || mat >= plan->n_mats || !x_bf16 || !level || !byte_off || !codes || !scale || !zero ||
+        !y || !ws_ok(ws))
+        return SBITS_ERR_INVALID_ARG;
+    if (batch < 1 || ld_x < plan->cols[mat] || (ld_x % 8) || !aligned16(x_bf16) || !aligned16(codes))
+        return SBITS_ERR_INVALID_ARG;
+    if (!sbits_mp_gemm_shapes_ok(plan) || batch > 32) return SBITS_ERR_UNIMPLEMENTED;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_launch_mp_gemm(plan, mat, x_bf16, ld_x, batch, level, byte_off, codes, scale, zero, y,
+                                sbits_scratch(plan, ws));
 }
 
 int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws)

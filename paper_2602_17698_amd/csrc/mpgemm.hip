@@ -1,0 +1,351 @@
+// Product of a small batch of activations with the stored mixed-precision weights (paper Sec. 5.3
+// "Inference Kernel": dequantization fused into the matrix product, at the granularity of the
+// precision blocks, one bitwidth per tile, no divergence inside a wave):
+//
+//     y[b][i] = sum_j What[i][j] * x[b][j],      What[i][j] = q[i][j] * scale[i][J] + zero[i][J]
+//
+// for one matrix of the plan, read straight from the packed stream of sbits_pack (blocks in global
+// order, rows of a block one after the other, LSB-first codes, scale / zero per block row).
+//
+// The sum over a block row's n columns splits as  scale * (sum_j q x) + zero * (sum_j x):
+// the matrix cores multiply the integer codes (exact in bf16) with x, a second product with
+// an all-ones operand gives sum_j x in the same register layout, and two fp32 FMAs per output and
+// block apply the row's scale and zero.  For bitwidths below 8 the codes enter as bf16 128 + q
+// (the code OR-ed into the mantissa of 128.0: no integer-to-float conversion), and the offset is
+// folded into the zero term: zero' = zero - 128 * scale.
+//
+// Mapping (v_mfma_f32_16x16x32_bf16: A = x, 16 batch rows; B = What^T, 16 output channels; K = 32):
+//   lane l supplies channel i = l % 16 and the K-quarter g = l / 16 of a block row: its n / 4 codes
+//   are n * c / 32 consecutive bytes of the stream; the wave's 16 rows x n codes are one contiguous
+//   run.  A workgroup of 16 waves covers 128 rows (4 row groups of 32 = 2 channel tiles each) x 16
+//   block columns (4 waves per row group, 4 blocks per wave); the x slice of those columns sits in
+//   LDS.  Block columns beyond the first 16 go to further workgroups (grid.y), whose partial sums a
+//   second kernel adds in a fixed order.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sbits_internal.hpp"
+
+namespace sbits {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+
+constexpr int MG_WAVES = 16, MG_THREADS = MG_WAVES * 64;
+constexpr int MG_RG = 4;                 // row groups (32 rows) per workgroup
+constexpr int MG_JL = 4;                 // waves per row group, each on its own block columns
+constexpr int MG_NBLK = 4;               // blocks per wave
+constexpr int MG_SPAN = MG_JL * MG_NBLK; // block columns per workgroup
+
+struct MpArgs {
+    const uint8_t *codes;
+    const float *scale, *zero;
+    const uint8_t *level;
+    const int64_t *byte_off;
+    const uint16_t *x;                   // bf16 [batch][ld_x]
+    float *out;                          // y [batch][R] (n_split == 1) or partials [n_split][batch][R]
+    int64_t block_base, ld_x;
+    int R, C, m, nbc, batch, n_split;
+    int bits[8];
+};
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    u32x4_t v;
+    v.x = a; v.y = b; v.z = c; v.w = d;
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// the lane's codes of one block row quarter: C dwords
+template <int C>
+__device__ __forceinline__ void load_codes(const uint8_t *p, uint32_t (&r)[8])
+{
+    const __attribute__((address_space(1))) uint32_t *q = (const __attribute__((address_space(1))) uint32_t *)p;
+#pragma unroll
+    for (int i = 0; i < C; ++i) r[i] = q[i];                 // adjacent dwords: merged into wide loads
+}
+
+// code e (0 .. 8 * words - 1) of the lane's LSB-first stream, C bits
+template <int C>
+__device__ __forceinline__ uint32_t code_at(const uint32_t (&r)[8], int e)
+{
+    const int bit = e * C, idx = bit >> 5, sh = bit & 31;
+    uint32_t v = r[idx] >> sh;
+    if (sh + C > 32) v |= r[idx + 1] << (32 - sh);
+    return v & ((1u << C) - 1u);
+}
+
+// B operand of step `st`: the lane's codes 8 * st .. 8 * st + 7 as bf16, in stream order.
+// C < 8: 128 + q (the code in the mantissa of 128.0);  C == 8: q itself (converted).
+template <int C>
+__device__ __forceinline__ bf16x8_t operand(const uint32_t (&r)[8], int st)
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t q0 = code_at<C>(r, 8 * st + 2 * p), q1 = code_at<C>(r, 8 * st + 2 * p + 1);
+        if constexpr (C < 8) {
+            w[p] = 0x43004300u | q0 | (q1 << 16);
+        } else {
+            const uint32_t f0 = __float_as_uint((float)q0), f1 = __float_as_uint((float)q1);   // <= 8 significant bits
+            w[p] = (f0 >> 16) | (f1 & 0xffff0000u);
+        }
+    }
+    return as_bf16x8(w[0], w[1], w[2], w[3]);
+}
+
+template <int N_COLS, int NB>
+struct MpWave {
+    static constexpr int KL = N_COLS / 4;          // codes per lane and block row
+    static constexpr int STEPS = KL / 8;           // MFMA steps per block
+    static constexpr int WORDS_PER_BIT = KL / 32;  // dwords per lane = c * KL / 32 (KL = 32: c; KL = 16: c / 2 -> bytes below)
+};
+
+// One block: loads were issued before (cw, sc, ze); multiply and add into acc.
+template <int C, int N_COLS, int NB>
+__device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const float (&sc)[2], const float (&ze)[2],
+                                              const bf16x8_t (&xa)[NB][N_COLS / 32], f32x4v_t (&acc)[2][NB])
+{
+    constexpr int STEPS = N_COLS / 32;
+    const bf16x8_t ones = as_bf16x8(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+    f32x4v_t d[2][NB], d1[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        d1[nb] = f32x4v_t{0.0f, 0.0f, 0.0f, 0.0f};
+        d[0][nb] = d1[nb];
+        d[1][nb] = d1[nb];
+    }
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        const bf16x8_t b0 = operand<C>(cw[0], st), b1 = operand<C>(cw[1], st);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            d[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[nb][st], b0, d[0][nb], 0, 0, 0);
+            d[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[nb][st], b1, d[1][nb], 0, 0, 0);
+            d1[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[nb][st], ones, d1[nb], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const float zz = C < 8 ? fmaf(-128.0f, sc[t], ze[t]) : ze[t];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[t][nb][r] = fmaf(sc[t], d[t][nb][r], fmaf(zz, d1[nb][r], acc[t][nb][r]));
+    }
+}
+
+template <int N_COLS, int NB>
+__global__ __launch_bounds__(MG_THREADS)
+void mp_gemm_kernel(MpArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int KL = N_COLS / 4, STEPS = N_COLS / 32;
+    constexpr int SLICE = MG_SPAN * N_COLS;                    // x columns per workgroup
+    constexpr int PITCH = SLICE * 2 + 16;                      // bytes per batch row in LDS (+16: spreads the rows over the banks)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rg = wave & (MG_RG - 1), jl = wave >> 2;
+    const int li = lane & 15, g = lane >> 4;
+    const int col0 = blockIdx.y * SLICE;                       // first x column of the slice
+    const int J0 = blockIdx.y * MG_SPAN;
+
+    // ---- x slice -> LDS (rows beyond the batch and columns beyond C read as zero)
+    for (int q = tid; q < 16 * NB * (SLICE / 8); q += MG_THREADS) {
+        const int b = q / (SLICE / 8), ch = q - b * (SLICE / 8);
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (b < a.batch && col0 + ch * 8 < a.C)
+            v = *(const __attribute__((address_space(1))) u32x4_t *)(a.x + (int64_t)b * a.ld_x + col0 + ch * 8);
+        *reinterpret_cast<u32x4_t *>(smem + (size_t)b * PITCH + ch * 16) = v;
+    }
+
+    // ---- this wave's blocks: metadata, then every load of codes / scale / zero up front
+    const int row0 = blockIdx.x * (MG_RG * 32) + rg * 32;      // first of the wave's 32 rows
+    const bool rows_ok = row0 < a.R;                           // (R is a multiple of 32)
+    const int I = rows_ok ? row0 / a.m : 0, rin = rows_ok ? row0 - I * a.m : 0;
+    int cbits[MG_NBLK];
+    uint32_t cw[MG_NBLK][2][8];
+    float sc[MG_NBLK][2], ze[MG_NBLK][2];
+    int64_t boff[MG_NBLK], blk[MG_NBLK];
+#pragma unroll
+    for (int t = 0; t < MG_NBLK; ++t) {
+        const int J = J0 + jl + MG_JL * t;
+        cbits[t] = 0;
+        if (rows_ok && J < a.nbc) {
+            blk[t] = a.block_base + (int64_t)I * a.nbc + J;
+            int lv = a.level[blk[t]];
+            lv = lv < 8 ? lv : 7;
+            cbits[t] = __builtin_amdgcn_readfirstlane(a.bits[lv]);
+            boff[t] = a.byte_off[blk[t]];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < MG_NBLK; ++t) {
+        const int c = cbits[t];
+        if (c == 0) continue;
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl) {
+            const int r = rin + 16 * tl + li;                  // row inside the block
+            const uint8_t *p = a.codes + boff[t] + ((int64_t)r * N_COLS + (int64_t)g * KL) * c / 8;
+            sc[t][tl] = a.scale[blk[t] * a.m + r];
+            ze[t][tl] = a.zero[blk[t] * a.m + r];
+            // KL * c / 8 bytes per lane: a whole number of dwords for KL = 32, of 16-bit halves for KL = 16
+            if constexpr (KL == 32) {
+                switch (c) {
+                case 1: load_codes<1>(p, cw[t][tl]); break;
+                case 2: load_codes<2>(p, cw[t][tl]); break;
+                case 3: load_codes<3>(p, cw[t][tl]); break;
+                case 4: load_codes<4>(p, cw[t][tl]); break;
+                case 5: load_codes<5>(p, cw[t][tl]); break;
+                case 6: load_codes<6>(p, cw[t][tl]); break;
+                case 7: load_codes<7>(p, cw[t][tl]); break;
+                default: load_codes<8>(p, cw[t][tl]); break;
+                }
+            } else {
+                // 2 * c bytes: read them as 16-bit halves (the stream is only 2-byte aligned here)
+                const __attribute__((address_space(1))) uint16_t *h = (const __attribute__((address_space(1))) uint16_t *)p;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (i < c) cw[t][tl][i >> 1] = (i & 1) ? (cw[t][tl][i >> 1] | ((uint32_t)h[i] << 16)) : (uint32_t)h[i];
+            }
+        }
+    }
+    __syncthreads();                                           // the x slice is in LDS
+
+    f32x4v_t acc[2][NB];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[t][nb] = f32x4v_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+#pragma unroll
+    for (int t = 0; t < MG_NBLK; ++t) {
+        const int c = cbits[t];
+        if (c == 0) continue;
+        const int Jl = jl + MG_JL * t;                         // block column inside the slice
+        bf16x8_t xa[NB][STEPS];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(
+                    smem + (size_t)(16 * nb + li) * PITCH + (size_t)(Jl * N_COLS + g * KL + 8 * st) * 2);
+                xa[nb][st] = __builtin_bit_cast(bf16x8_t, v);
+            }
+        switch (c) {
+        case 1: block_product<1, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        case 2: block_product<2, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        case 3: block_product<3, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        case 4: block_product<4, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        case 5: block_product<5, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        case 6: block_product<6, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        case 7: block_product<7, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        default: block_product<8, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        }
+    }
+
+    // ---- the four waves of a row group add up (fixed order), wave jl = 0 stores
+    __syncthreads();                                           // every wave is done with the x slice
+    float *red = reinterpret_cast<float *>(smem);              // [wave][tile][nb][r][lane]
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                red[(((wave * 2 + t) * NB + nb) * 4 + r) * 64 + lane] = acc[t][nb][r];
+    __syncthreads();
+    if (jl != 0 || !rows_ok) return;
+    float *dst = a.out + (int64_t)blockIdx.y * a.batch * a.R;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = acc[t][nb][r];
+#pragma unroll
+                for (int j = 1; j < MG_JL; ++j)
+                    v = v + red[((((rg + MG_RG * j) * 2 + t) * NB + nb) * 4 + r) * 64 + lane];
+                const int b = 16 * nb + 4 * g + r;             // D layout: row 4 * (lane / 16) + r, column lane % 16
+                if (b < a.batch) dst[(int64_t)b * a.R + row0 + 16 * t + li] = v;
+            }
+}
+
+// y = sum over the column splits of the partials, split 0 first
+__global__ __launch_bounds__(256)
+void mp_gemm_finish_kernel(const float *__restrict__ part, int64_t n, int n_split, float *__restrict__ y)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float v = part[i];
+    for (int s = 1; s < n_split; ++s) v = v + part[(int64_t)s * n + i];
+    y[i] = v;
+}
+
+}  // namespace sbits
+
+using namespace sbits;
+
+int sbits_mp_gemm_splits(int64_t cols, int n) { return (int)((cols / n + MG_SPAN - 1) / MG_SPAN); }
+
+bool sbits_mp_gemm_shapes_ok(const sbits_plan *plan)
+{
+    return (plan->n == 64 || plan->n == 128) && plan->m % 32 == 0;
+}
+
+// partial sums of the largest matrix at the largest batch (32)
+size_t sbits_mp_gemm_ws_bytes(const sbits_plan *plan)
+{
+    if (!sbits_mp_gemm_shapes_ok(plan)) return 0;
+    size_t mx = 0;
+    for (int i = 0; i < plan->n_mats; ++i) {
+        const int s = sbits_mp_gemm_splits(plan->cols[i], plan->n);
+        const size_t b = s > 1 ? (size_t)s * 32 * (size_t)plan->rows[i] * 4 : 0;
+        if (b > mx) mx = b;
+    }
+    return sbits_align_up(mx, 256);
+}
+
+template <int N_COLS, int NB>
+static int launch_mp(sbits_ctx *ctx, const MpArgs &a, dim3 grid)
+{
+    constexpr size_t x_bytes = (size_t)16 * NB * (MG_SPAN * N_COLS * 2 + 16);
+    constexpr size_t red_bytes = (size_t)MG_WAVES * 2 * NB * 4 * 64 * 4;
+    constexpr size_t lds = x_bytes > red_bytes ? x_bytes : red_bytes;
+    auto *fn = &mp_gemm_kernel<N_COLS, NB>;
+    SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds));
+    hipLaunchKernelGGL(fn, grid, dim3(MG_THREADS), lds, ctx->stream, a);
+    SBITS_HIP(ctx, hipGetLastError());
+    return SBITS_OK;
+}
+
+int sbits_launch_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, int batch,
+                         const uint8_t *level, const int64_t *byte_off, const uint8_t *codes, const float *scale,
+                         const float *zero, float *y, void *scratch)
+{
+    sbits_ctx *ctx = plan->ctx;
+    MpArgs a;
+    a.codes = codes; a.scale = scale; a.zero = zero; a.level = level; a.byte_off = byte_off;
+    a.x = static_cast<const uint16_t *>(x_bf16);
+    a.block_base = plan->base[mat]; a.ld_x = ld_x;
+    a.R = (int)plan->rows[mat]; a.C = (int)plan->cols[mat]; a.m = plan->m; a.nbc = a.C / plan->n;
+    a.batch = batch;
+    a.n_split = sbits_mp_gemm_splits(a.C, plan->n);
+    for (int c = 0; c < 8; ++c) a.bits[c] = c < plan->K ? plan->bits[c] : plan->bits[plan->K - 1];
+    a.out = a.n_split > 1 ? static_cast<float *>(scratch) : y;
+    const dim3 grid((unsigned)((a.R + MG_RG * 32 - 1) / (MG_RG * 32)), (unsigned)a.n_split);
+    const int nb = batch <= 16 ? 1 : 2;
+    int rc;
+    if (plan->n == 128) rc = nb == 1 ? launch_mp<128, 1>(ctx, a, grid) : launch_mp<128, 2>(ctx, a, grid);
+    else rc = nb == 1 ? launch_mp<64, 1>(ctx, a, grid) : launch_mp<64, 2>(ctx, a, grid);
+    if (rc) return rc;
+    if (a.n_split > 1) {
+        const int64_t n = (int64_t)batch * a.R;
+        hipLaunchKernelGGL(mp_gemm_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream,
+                           (const float *)scratch, n, a.n_split, y);
+        SBITS_HIP(ctx, hipGetLastError());
+    }
+    return SBITS_OK;
+}

@@ -108,6 +108,12 @@ int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const
 int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                                  const uint8_t *level, const int64_t *byte_off, uint8_t *codes, float *scale,
                                  float *zero, void *ws);
+// mpgemm.hip
+bool sbits_mp_gemm_shapes_ok(const sbits_plan *plan);
+size_t sbits_mp_gemm_ws_bytes(const sbits_plan *plan);
+int sbits_launch_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, int batch,
+                         const uint8_t *level, const int64_t *byte_off, const uint8_t *codes, const float *scale,
+                         const float *zero, float *y, void *scratch);
 int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, const uint8_t *level_in,
                       double avg_bits, int64_t k, uint8_t *level_out, sbits_proposal *host_out, void *ws);
 int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,

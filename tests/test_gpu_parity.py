@@ -816,3 +816,106 @@ def test_propose_loop_on_exact_differences_reproduces_allocate(orc, ctx, dev):
         np.testing.assert_array_equal(level.cpu().numpy(), want.cpu().numpy())
         assert iters == st["iters"]
     plan.close()
+
+
+# ------------------------------------------------------------------------ product with the stored weights
+def _packed_matrix(orc, R, C, m, n, bits, seed, base_blocks=3, levels=None):
+    """A random matrix packed by the oracle at random levels, its blocks starting at global id base_blocks."""
+    rng = np.random.default_rng(seed)
+    Wb = orc.f32_to_bf16(0.02 * rng.standard_t(4, size=(R, C)))
+    nb = (R // m) * (C // n)
+    N = base_blocks + nb
+    level = rng.integers(0, len(bits), size=N).astype(np.uint8) if levels is None else levels(rng, N)
+    off = orc.offsets(level, m, n, bits)
+    codes = np.zeros(int(off[-1]) , np.uint8)
+    scale = np.zeros(N * m, np.float32)
+    zero = np.zeros(N * m, np.float32)
+    orc.pack(Wb, m, n, bits, level, off, base_blocks, codes, scale, zero)
+    return level, off, codes, scale, zero
+
+
+def _mp_gemm_check(orc, y, packed, base, R, C, m, n, bits, xb):
+    level, off, codes, scale, zero = packed
+    ref = orc.mp_gemm(codes, scale, zero, level, off, base, R, C, m, n, bits, xb)
+    What = orc.dequant(codes, scale, zero, level, off, base, R, C, m, n, bits).astype(np.float64)
+    # scale of every element's block row, for the bound: the kernel sums (128 + q) * x and takes 128 * sum x out again
+    nbc = C // n
+    srow = scale.reshape(-1, m)[base:base + (R // m) * nbc].reshape(R // m, nbc, m).transpose(0, 2, 1).reshape(R, nbc)
+    xa = np.abs(orc.bf16_to_f32(xb).astype(np.float64))
+    bound = xa @ np.abs(What).T + 128.0 * (xa.reshape(xa.shape[0], nbc, n).sum(2) @ np.abs(srow.astype(np.float64)).T)
+    err = np.abs(y.astype(np.float64) - ref)
+    assert np.all(err <= bound * 2.0 ** -18 + 1e-30), float((err / (bound + 1e-300)).max())
+    assert np.sqrt((err ** 2).mean()) <= 2.0 ** -22 * np.sqrt((bound ** 2).mean())       # typical error: far below the bound
+    return ref
+
+
+@pytest.mark.parametrize("R,C,m,n,bits,batch", [
+    (64, 256, 32, 128, [1, 2, 3, 4, 5, 6, 7, 8], 16),       # every bitwidth, one workgroup
+    (160, 128 * 40, 32, 128, [2, 4, 8], 5),                 # three column splits, ragged rows and batch
+    (256, 128 * 17, 128, 128, [1, 2, 3, 4], 32),            # two batch tiles, a split with one block column
+    (128, 192, 64, 64, [1, 2, 3, 4, 5, 6, 7, 8], 17),       # group size 64
+    (192, 64 * 33, 64, 64, [2, 3, 4, 8], 1),                # group size 64, three splits, a single row of x
+])
+def test_mp_gemm(orc, ctx, dev, R, C, m, n, bits, batch):
+    say("mixed-precision product", R, C, m, n, bits, batch)
+    base = 3
+    shapes = [(m, 3 * n), (R, C)]                           # a first matrix of 3 blocks, so this one's base is 3
+    plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
+    assert plan.block_base(1) == base
+    packed = _packed_matrix(orc, R, C, m, n, bits, seed=R + C)
+    level, off, codes, scale, zero = packed
+    rng = np.random.default_rng(batch)
+    xb = orc.f32_to_bf16(rng.standard_normal((batch, C)))
+    xd = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).to(dev)
+    y = torch.full((batch, R), 7.0, dtype=torch.float32, device=dev)
+    dcodes = torch.from_numpy(codes).to(dev)
+    args = (torch.from_numpy(level).to(dev), torch.from_numpy(off).to(dev), dcodes,
+            torch.from_numpy(scale).to(dev), torch.from_numpy(zero).to(dev))
+    plan.mp_gemm(1, xd, *args, y, ws)
+    torch.cuda.synchronize()
+    _mp_gemm_check(orc, y.cpu().numpy(), packed, base, R, C, m, n, bits, xb)
+    # a strided x (ld_x > cols) gives the same bits
+    xw = torch.zeros(batch, C + 8, dtype=torch.bfloat16, device=dev)
+    xw[:, :C] = xd
+    y2 = torch.empty_like(y)
+    plan.mp_gemm(1, xw[:, :C], *args, y2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    plan.close()
+
+
+def test_mp_gemm_exact_on_integer_weights(orc, ctx, dev):
+    """Integer weights stored exactly at 8 bits and at 4 bits (0..15), integer x: the exact integer product."""
+    say("mixed-precision product: exact integers")
+    m, n, R, C = 32, 128, 64, 256
+    rng = np.random.default_rng(1)
+    plan, ws = make_plan(ctx, [(R, C)], m, n, [4, 8], dev)
+    Wi = np.empty((R, C), np.int64)
+    level = np.array([0, 1, 1, 0], np.uint8)                         # blocks (0,0) 4-bit, (0,1) 8-bit, (1,0) 8-bit, (1,1) 4-bit
+    for I in range(2):
+        for J in range(2):
+            hi = 16 if level[I * 2 + J] == 0 else 256
+            blk = rng.integers(0, hi, (m, n)); blk[:, 0] = 0; blk[:, 1] = hi - 1
+            Wi[I * m:(I + 1) * m, J * n:(J + 1) * n] = blk
+    off = orc.offsets(level, m, n, [4, 8])
+    codes = np.zeros(int(off[-1]), np.uint8); scale = np.zeros(4 * m, np.float32); zero = np.zeros(4 * m, np.float32)
+    orc.pack(orc.f32_to_bf16(Wi.astype(np.float32)), m, n, [4, 8], level, off, 0, codes, scale, zero)
+    assert np.all(scale == 1) and np.all(zero == 0)
+    xi = rng.integers(-8, 9, (16, C))
+    xd = torch.from_numpy(xi.astype(np.float32)).to(torch.bfloat16).to(dev)
+    y = torch.empty(16, R, dtype=torch.float32, device=dev)
+    plan.mp_gemm(0, xd, torch.from_numpy(level).to(dev), torch.from_numpy(off).to(dev), torch.from_numpy(codes).to(dev),
+                 torch.from_numpy(scale).to(dev), torch.from_numpy(zero).to(dev), y, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(y.cpu().numpy(), (xi @ Wi.T).astype(np.float32))
+    plan.close()
+
+
+def test_mp_gemm_refuses_other_shapes(ctx, dev):
+    plan, ws = make_plan(ctx, [(64, 512)], 16, 256, [2, 4], dev)
+    t = torch.zeros(4096, dtype=torch.uint8, device=dev)
+    x = torch.zeros(16, 512, dtype=torch.bfloat16, device=dev)
+    with pytest.raises(sb.SbitsError) as e:
+        plan.mp_gemm(0, x, t, t, t, t, t, t, ws)
+    assert e.value.status == sb.ERR_UNIMPLEMENTED
+    plan.close()
