@@ -94,19 +94,56 @@ __device__ __forceinline__ bf16x8_t operand(const uint32_t (&r)[8], int st)
     return as_bf16x8(w[0], w[1], w[2], w[3]);
 }
 
-template <int N_COLS, int NB>
-struct MpWave {
-    static constexpr int KL = N_COLS / 4;          // codes per lane and block row
-    static constexpr int STEPS = KL / 8;           // MFMA steps per block
-    static constexpr int WORDS_PER_BIT = KL / 32;  // dwords per lane = c * KL / 32 (KL = 32: c; KL = 16: c / 2 -> bytes below)
+// ---- pair order (bitwidths 1, 2, 4): a 32-bit word holds two codes 16 bits apart, so one AND-OR
+// turns  (w >> s) & mask  into the bf16 pair (128 + q_a, 128 + q_b) with b - a = 16 / C codes.
+// The operand then holds the lane's codes in the order a0, b0, a1, b1, ...; x is put into the
+// same order with byte permutes (once per block, shared by both channel tiles).
+//   C = 4: step st, pair p: codes (8 st + p,        8 st + p + 4)     word st,      shift 4 p
+//   C = 2: step st, pair p: codes (16 d + 4 h + p,  ... + 8)          word d,       shift 2 (4 h + p),  st = 2 d + h
+//   C = 1: step st, pair p: codes (4 st + p,        4 st + p + 16)    word 0,       shift 4 st + p      (32 codes per lane only)
+template <int C, int KL>
+struct PairOrder {
+    static constexpr bool value = C == 4 || C == 2 || (C == 1 && KL == 32);
 };
+
+template <int C>
+__device__ __forceinline__ bf16x8_t operand_pairs(const uint32_t (&r)[8], int st)
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        if constexpr (C == 4) w[p] = ((r[st] >> (4 * p)) & 0x000f000fu) | 0x43004300u;
+        else if constexpr (C == 2) w[p] = ((r[st >> 1] >> (2 * (4 * (st & 1) + p))) & 0x00030003u) | 0x43004300u;
+        else w[p] = ((r[0] >> (4 * st + p)) & 0x00010001u) | 0x43004300u;
+    }
+    return as_bf16x8(w[0], w[1], w[2], w[3]);
+}
+
+// x of step st in the pair order of bitwidth C; xn = the lane's x values in natural order, two per word
+template <int C, int STEPS>
+__device__ __forceinline__ bf16x8_t x_pairs(const u32x4_t (&xn)[STEPS], int st)
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        int ea, eb;                                   // element numbers (within the lane's codes) of the pair
+        if constexpr (C == 4) { ea = 8 * st + p; eb = ea + 4; }
+        else if constexpr (C == 2) { ea = 16 * (st >> 1) + 4 * (st & 1) + p; eb = ea + 8; }
+        else { ea = 4 * st + p; eb = ea + 16; }
+        const uint32_t wa = xn[ea >> 3][(ea >> 1) & 3], wb = xn[eb >> 3][(eb >> 1) & 3];
+        // both elements sit in the same half of their words (ea and eb have the same parity)
+        w[p] = __builtin_amdgcn_perm(wb, wa, (ea & 1) ? 0x07060302u : 0x05040100u);
+    }
+    return as_bf16x8(w[0], w[1], w[2], w[3]);
+}
 
 // One block: loads were issued before (cw, sc, ze); multiply and add into acc.
 template <int C, int N_COLS, int NB>
 __device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const float (&sc)[2], const float (&ze)[2],
-                                              const bf16x8_t (&xa)[NB][N_COLS / 32], f32x4v_t (&acc)[2][NB])
+                                              const u32x4_t (&xn)[NB][N_COLS / 32], f32x4v_t (&acc)[2][NB])
 {
     constexpr int STEPS = N_COLS / 32;
+    constexpr bool PAIRS = PairOrder<C, N_COLS / 4>::value;
     const bf16x8_t ones = as_bf16x8(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
     f32x4v_t d[2][NB], d1[NB];
 #pragma unroll
@@ -117,12 +154,17 @@ __device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const 
     }
 #pragma unroll
     for (int st = 0; st < STEPS; ++st) {
-        const bf16x8_t b0 = operand<C>(cw[0], st), b1 = operand<C>(cw[1], st);
+        bf16x8_t b0, b1;
+        if constexpr (PAIRS) { b0 = operand_pairs<C>(cw[0], st); b1 = operand_pairs<C>(cw[1], st); }
+        else { b0 = operand<C>(cw[0], st); b1 = operand<C>(cw[1], st); }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            d[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[nb][st], b0, d[0][nb], 0, 0, 0);
-            d[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[nb][st], b1, d[1][nb], 0, 0, 0);
-            d1[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[nb][st], ones, d1[nb], 0, 0, 0);
+            bf16x8_t xa;
+            if constexpr (PAIRS) xa = x_pairs<C, STEPS>(xn[nb], st);
+            else xa = __builtin_bit_cast(bf16x8_t, xn[nb][st]);
+            d[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, b0, d[0][nb], 0, 0, 0);
+            d[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, b1, d[1][nb], 0, 0, 0);
+            d1[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, ones, d1[nb], 0, 0, 0);
         }
     }
 #pragma unroll
@@ -144,13 +186,33 @@ void mp_gemm_kernel(MpArgs a)
     constexpr int KL = N_COLS / 4, STEPS = N_COLS / 32;
     constexpr int SLICE = MG_SPAN * N_COLS;                    // x columns per workgroup
     constexpr int PITCH = SLICE * 2 + 16;                      // bytes per batch row in LDS (+16: spreads the rows over the banks)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: the bookkeeping below stays scalar
     const int rg = wave & (MG_RG - 1), jl = wave >> 2;
     const int li = lane & 15, g = lane >> 4;
     const int col0 = blockIdx.y * SLICE;                       // first x column of the slice
     const int J0 = blockIdx.y * MG_SPAN;
 
-    // ---- x slice -> LDS (rows beyond the batch and columns beyond C read as zero)
+    // ---- this wave's blocks: all metadata loads first (they head the longest dependency chain);
+    // a block column beyond the matrix reads the last one's metadata and is skipped later
+    const int row0 = blockIdx.x * (MG_RG * 32) + rg * 32;      // first of the wave's 32 rows
+    const bool rows_ok = row0 < a.R;                           // (R is a multiple of 32)
+    const int I = rows_ok ? row0 / a.m : 0, rin = rows_ok ? row0 - I * a.m : 0;
+    int cbits[MG_NBLK];
+    uint32_t cw[MG_NBLK][2][8];
+    float sc[MG_NBLK][2], ze[MG_NBLK][2];
+    int64_t blk[MG_NBLK];
+    uint32_t lvl_v[MG_NBLK];
+    int64_t boff_v[MG_NBLK];
+#pragma unroll
+    for (int t = 0; t < MG_NBLK; ++t) {
+        const int J = J0 + jl + MG_JL * t;
+        blk[t] = a.block_base + (int64_t)I * a.nbc + (J < a.nbc ? J : a.nbc - 1);
+        lvl_v[t] = a.level[blk[t]];
+        boff_v[t] = a.byte_off[blk[t]];
+    }
+    // ---- x slice -> LDS (rows beyond the batch and columns beyond C read as zero); issued after the
+    // metadata loads, which head the longest dependency chain, and before the codes
     for (int q = tid; q < 16 * NB * (SLICE / 8); q += MG_THREADS) {
         const int b = q / (SLICE / 8), ch = q - b * (SLICE / 8);
         u32x4_t v = {0u, 0u, 0u, 0u};
@@ -159,36 +221,26 @@ void mp_gemm_kernel(MpArgs a)
         *reinterpret_cast<u32x4_t *>(smem + (size_t)b * PITCH + ch * 16) = v;
     }
 
-    // ---- this wave's blocks: metadata, then every load of codes / scale / zero up front
-    const int row0 = blockIdx.x * (MG_RG * 32) + rg * 32;      // first of the wave's 32 rows
-    const bool rows_ok = row0 < a.R;                           // (R is a multiple of 32)
-    const int I = rows_ok ? row0 / a.m : 0, rin = rows_ok ? row0 - I * a.m : 0;
-    int cbits[MG_NBLK];
-    uint32_t cw[MG_NBLK][2][8];
-    float sc[MG_NBLK][2], ze[MG_NBLK][2];
-    int64_t boff[MG_NBLK], blk[MG_NBLK];
+    const uint32_t lane_units = (uint32_t)((rin + li) * (N_COLS / 8) + g * (KL / 8));   // x c = the lane's byte offset in the block
 #pragma unroll
     for (int t = 0; t < MG_NBLK; ++t) {
         const int J = J0 + jl + MG_JL * t;
-        cbits[t] = 0;
-        if (rows_ok && J < a.nbc) {
-            blk[t] = a.block_base + (int64_t)I * a.nbc + J;
-            int lv = a.level[blk[t]];
-            lv = lv < 8 ? lv : 7;
-            cbits[t] = __builtin_amdgcn_readfirstlane(a.bits[lv]);
-            boff[t] = a.byte_off[blk[t]];
-        }
-    }
+        const int lv = __builtin_amdgcn_readfirstlane((int)lvl_v[t]);
+        int c = a.bits[0];
 #pragma unroll
-    for (int t = 0; t < MG_NBLK; ++t) {
-        const int c = cbits[t];
+        for (int k = 1; k < 8; ++k) c = lv == k ? a.bits[k] : c;
+        c = (rows_ok && J < a.nbc) ? c : 0;
+        cbits[t] = c;
         if (c == 0) continue;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)boff_v[t]);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)boff_v[t] >> 32));
+        const uint8_t *pb = a.codes + (int64_t)(((uint64_t)hi << 32) | lo);                // uniform
+        const float *ps = a.scale + blk[t] * a.m + rin, *pz = a.zero + blk[t] * a.m + rin;
 #pragma unroll
         for (int tl = 0; tl < 2; ++tl) {
-            const int r = rin + 16 * tl + li;                  // row inside the block
-            const uint8_t *p = a.codes + boff[t] + ((int64_t)r * N_COLS + (int64_t)g * KL) * c / 8;
-            sc[t][tl] = a.scale[blk[t] * a.m + r];
-            ze[t][tl] = a.zero[blk[t] * a.m + r];
+            const uint8_t *p = pb + (lane_units + (uint32_t)(tl * 16 * (N_COLS / 8))) * (uint32_t)c;
+            sc[t][tl] = ps[16 * tl + li];
+            ze[t][tl] = pz[16 * tl + li];
             // KL * c / 8 bytes per lane: a whole number of dwords for KL = 32, of 16-bit halves for KL = 16
             if constexpr (KL == 32) {
                 switch (c) {
@@ -210,7 +262,8 @@ void mp_gemm_kernel(MpArgs a)
             }
         }
     }
-    __syncthreads();                                           // the x slice is in LDS
+    // LDS-only barrier: __syncthreads() would also wait for the codes still in flight
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the x slice is in LDS
 
     f32x4v_t acc[2][NB];
 #pragma unroll
@@ -223,15 +276,13 @@ void mp_gemm_kernel(MpArgs a)
         const int c = cbits[t];
         if (c == 0) continue;
         const int Jl = jl + MG_JL * t;                         // block column inside the slice
-        bf16x8_t xa[NB][STEPS];
+        u32x4_t xa[NB][STEPS];                                 // the lane's x values of this block column, natural order
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int st = 0; st < STEPS; ++st) {
-                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(
+            for (int st = 0; st < STEPS; ++st)
+                xa[nb][st] = *reinterpret_cast<const u32x4_t *>(
                     smem + (size_t)(16 * nb + li) * PITCH + (size_t)(Jl * N_COLS + g * KL + 8 * st) * 2);
-                xa[nb][st] = __builtin_bit_cast(bf16x8_t, v);
-            }
         switch (c) {
         case 1: block_product<1, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
         case 2: block_product<2, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
