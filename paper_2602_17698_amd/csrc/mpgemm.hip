@@ -30,6 +30,8 @@ namespace sbits {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x3_t __attribute__((ext_vector_type(3)));
 
 constexpr int MG_WAVES = 16, MG_THREADS = MG_WAVES * 64;
 constexpr int MG_RG = 4;                 // row groups (32 rows) per workgroup
@@ -47,6 +49,9 @@ struct MpArgs {
     int64_t block_base, ld_x;
     int R, C, m, nbc, batch, n_split;
     int bits[8];
+#ifdef MG_EXP_TIMING
+    long long *dbg;
+#endif
 };
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
@@ -56,13 +61,25 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c
     return __builtin_bit_cast(bf16x8_t, v);
 }
 
-// the lane's codes of one block row quarter: C dwords
+// The lane's codes of one block row quarter: C dwords (C = 0: an absent block, nothing needed).
+// Always exactly two load instructions, whatever C is: the first brings min(C, 4) dwords, the second
+// the rest or, if there is no rest, dword 0 once more into r[7] (kept alive by the consumer).  With
+// the same number of loads on every path the compiler can count the loads still in flight, and a
+// block's product waits for its own codes only, not for those of the blocks behind it.
 template <int C>
 __device__ __forceinline__ void load_codes(const uint8_t *p, uint32_t (&r)[8])
 {
     const __attribute__((address_space(1))) uint32_t *q = (const __attribute__((address_space(1))) uint32_t *)p;
-#pragma unroll
-    for (int i = 0; i < C; ++i) r[i] = q[i];                 // adjacent dwords: merged into wide loads
+    constexpr int A = C == 0 ? 1 : (C < 4 ? C : 4);
+    if constexpr (A == 1) r[0] = q[0];
+    else if constexpr (A == 2) { const u32x2_t v = *(const __attribute__((address_space(1))) u32x2_t *)q; r[0] = v.x; r[1] = v.y; }
+    else if constexpr (A == 3) { const u32x3_t v = *(const __attribute__((address_space(1))) u32x3_t *)q; r[0] = v.x; r[1] = v.y; r[2] = v.z; }
+    else { const u32x4_t v = *(const __attribute__((address_space(1))) u32x4_t *)q; r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w; }
+    if constexpr (C <= 4) { r[7] = __builtin_nontemporal_load(q); }
+    else if constexpr (C == 5) r[4] = q[4];
+    else if constexpr (C == 6) { const u32x2_t v = *(const __attribute__((address_space(1))) u32x2_t *)(q + 4); r[4] = v.x; r[5] = v.y; }
+    else if constexpr (C == 7) { const u32x3_t v = *(const __attribute__((address_space(1))) u32x3_t *)(q + 4); r[4] = v.x; r[5] = v.y; r[6] = v.z; }
+    else { const u32x4_t v = *(const __attribute__((address_space(1))) u32x4_t *)(q + 4); r[4] = v.x; r[5] = v.y; r[6] = v.z; r[7] = v.w; }
 }
 
 // code e (0 .. 8 * words - 1) of the lane's LSB-first stream, C bits
@@ -144,6 +161,7 @@ __device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const 
 {
     constexpr int STEPS = N_COLS / 32;
     constexpr bool PAIRS = PairOrder<C, N_COLS / 4>::value;
+    if constexpr (C <= 4 && N_COLS == 128) asm volatile("" :: "v"(cw[0][7]), "v"(cw[1][7]));   // the second load of load_codes
     const bf16x8_t ones = as_bf16x8(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
     f32x4v_t d[2][NB], d1[NB];
 #pragma unroll
@@ -187,6 +205,13 @@ void mp_gemm_kernel(MpArgs a)
     constexpr int SLICE = MG_SPAN * N_COLS;                    // x columns per workgroup
     constexpr int PITCH = SLICE * 2 + 16;                      // bytes per batch row in LDS (+16: spreads the rows over the banks)
     const int tid = threadIdx.x, lane = tid & 63;
+#ifdef MG_EXP_TIMING
+    long long ts[8];
+#define MG_TS(i) do { __builtin_amdgcn_sched_barrier(0); ts[i] = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
+    MG_TS(0);
+#else
+#define MG_TS(i)
+#endif
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: the bookkeeping below stays scalar
     const int rg = wave & (MG_RG - 1), jl = wave >> 2;
     const int li = lane & 15, g = lane >> 4;
@@ -211,16 +236,36 @@ void mp_gemm_kernel(MpArgs a)
         lvl_v[t] = a.level[blk[t]];
         boff_v[t] = a.byte_off[blk[t]];
     }
-    // ---- x slice -> LDS (rows beyond the batch and columns beyond C read as zero); issued after the
-    // metadata loads, which head the longest dependency chain, and before the codes
-    for (int q = tid; q < 16 * NB * (SLICE / 8); q += MG_THREADS) {
+    // ---- x slice: requested together with the metadata (rows beyond the batch and columns beyond C read
+    // as zero) and in LDS by the time the metadata has arrived
+    constexpr int XCH = 16 * NB * (SLICE / 8) / MG_THREADS;    // 16-byte pieces per thread
+    static_assert(16 * NB * (SLICE / 8) % MG_THREADS == 0, "whole pieces per thread");
+    u32x4_t xs[XCH];
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) {
+        const int q = tid + i * MG_THREADS;
         const int b = q / (SLICE / 8), ch = q - b * (SLICE / 8);
-        u32x4_t v = {0u, 0u, 0u, 0u};
-        if (b < a.batch && col0 + ch * 8 < a.C)
-            v = *(const __attribute__((address_space(1))) u32x4_t *)(a.x + (int64_t)b * a.ld_x + col0 + ch * 8);
-        *reinterpret_cast<u32x4_t *>(smem + (size_t)b * PITCH + ch * 16) = v;
+        const int bc = b < a.batch ? b : a.batch - 1;                               // in bounds; zeroed below
+        const int cc = col0 + ch * 8 < a.C ? col0 + ch * 8 : 0;
+        xs[i] = *(const __attribute__((address_space(1))) u32x4_t *)(a.x + (int64_t)bc * a.ld_x + cc);
     }
 
+#ifdef MG_EXP_TIMING
+    { const int dummy = __builtin_amdgcn_readfirstlane((int)lvl_v[MG_NBLK - 1] + (int)boff_v[MG_NBLK - 1]); asm volatile("" :: "s"(dummy)); }
+#endif
+    MG_TS(1);
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) {
+        const int q = tid + i * MG_THREADS;
+        const int b = q / (SLICE / 8), ch = q - b * (SLICE / 8);
+        const bool ok = b < a.batch && col0 + ch * 8 < a.C;
+        u32x4_t v = xs[i];
+        v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+        *reinterpret_cast<u32x4_t *>(smem + (size_t)b * PITCH + ch * 16) = v;
+    }
+    // (no global load is in flight here but the metadata: the codes are requested after the barrier)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the x slice is in LDS
+    MG_TS(2);
     const uint32_t lane_units = (uint32_t)((rin + li) * (N_COLS / 8) + g * (KL / 8));   // x c = the lane's byte offset in the block
 #pragma unroll
     for (int t = 0; t < MG_NBLK; ++t) {
@@ -231,10 +276,10 @@ void mp_gemm_kernel(MpArgs a)
         for (int k = 1; k < 8; ++k) c = lv == k ? a.bits[k] : c;
         c = (rows_ok && J < a.nbc) ? c : 0;
         cbits[t] = c;
-        if (c == 0) continue;
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)boff_v[t]);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)boff_v[t] >> 32));
-        const uint8_t *pb = a.codes + (int64_t)(((uint64_t)hi << 32) | lo);                // uniform
+        // an absent block (c = 0) reads the first dword of the stream and the clamped block's scales
+        const uint8_t *pb = a.codes + (c ? (int64_t)(((uint64_t)hi << 32) | lo) : 0);      // uniform
         const float *ps = a.scale + blk[t] * a.m + rin, *pz = a.zero + blk[t] * a.m + rin;
 #pragma unroll
         for (int tl = 0; tl < 2; ++tl) {
@@ -244,6 +289,7 @@ void mp_gemm_kernel(MpArgs a)
             // KL * c / 8 bytes per lane: a whole number of dwords for KL = 32, of 16-bit halves for KL = 16
             if constexpr (KL == 32) {
                 switch (c) {
+                case 0: load_codes<0>(p, cw[t][tl]); break;
                 case 1: load_codes<1>(p, cw[t][tl]); break;
                 case 2: load_codes<2>(p, cw[t][tl]); break;
                 case 3: load_codes<3>(p, cw[t][tl]); break;
@@ -262,8 +308,6 @@ void mp_gemm_kernel(MpArgs a)
             }
         }
     }
-    // LDS-only barrier: __syncthreads() would also wait for the codes still in flight
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the x slice is in LDS
 
     f32x4v_t acc[2][NB];
 #pragma unroll
@@ -293,6 +337,10 @@ void mp_gemm_kernel(MpArgs a)
         case 7: block_product<7, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
         default: block_product<8, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
         }
+#ifdef MG_EXP_TIMING
+        { asm volatile("" :: "v"(acc[0][0][0]), "v"(acc[1][0][3])); }
+        MG_TS(3 + t);
+#endif
     }
 
     // ---- the four waves of a row group add up (fixed order), wave jl = 0 stores
@@ -306,6 +354,13 @@ void mp_gemm_kernel(MpArgs a)
             for (int r = 0; r < 4; ++r)
                 red[(((wave * 2 + t) * NB + nb) * 4 + r) * 64 + lane] = acc[t][nb][r];
     __syncthreads();
+#ifdef MG_EXP_TIMING
+    MG_TS(7);
+    if (lane == 0) {
+        long long *d = a.dbg + ((int64_t)(blockIdx.y * gridDim.x + blockIdx.x) * MG_WAVES + wave) * 8;
+        for (int i = 0; i < 8; ++i) d[i] = ts[i];
+    }
+#endif
     if (jl != 0 || !rows_ok) return;
     float *dst = a.out + (int64_t)blockIdx.y * a.batch * a.R;
 #pragma unroll
@@ -386,6 +441,9 @@ int sbits_launch_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t 
     a.n_split = sbits_mp_gemm_splits(a.C, plan->n);
     for (int c = 0; c < 8; ++c) a.bits[c] = c < plan->K ? plan->bits[c] : plan->bits[plan->K - 1];
     a.out = a.n_split > 1 ? static_cast<float *>(scratch) : y;
+#ifdef MG_EXP_TIMING
+    a.dbg = reinterpret_cast<long long *>(static_cast<char *>(scratch) + (2304 << 10));
+#endif
     const dim3 grid((unsigned)((a.R + MG_RG * 32 - 1) / (MG_RG * 32)), (unsigned)a.n_split);
     const int nb = batch <= 16 ? 1 : 2;
     int rc;
