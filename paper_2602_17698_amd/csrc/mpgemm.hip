@@ -136,28 +136,36 @@ __device__ __forceinline__ bf16x8_t operand_pairs(const uint32_t (&r)[8], int st
     return as_bf16x8(w[0], w[1], w[2], w[3]);
 }
 
-// x of step st in the pair order of bitwidth C; xn = the lane's x values in natural order, two per word
-template <int C, int STEPS>
-__device__ __forceinline__ bf16x8_t x_pairs(const u32x4_t (&xn)[STEPS], int st)
+// x operand of step st, read from the lane's 2 * KL bytes of the staged slice (natural order in LDS).
+// Stream order: the step's 16 bytes as they are.  Pair order of bitwidth C: the two elements of pair
+// p sit in the same half of two words 16 / C codes apart, fetched as two 8-byte reads and merged
+// with byte permutes.
+template <int C, bool PAIRS>
+__device__ __forceinline__ bf16x8_t x_operand(const unsigned char *xl, int st)
 {
-    uint32_t w[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        int ea, eb;                                   // element numbers (within the lane's codes) of the pair
-        if constexpr (C == 4) { ea = 8 * st + p; eb = ea + 4; }
-        else if constexpr (C == 2) { ea = 16 * (st >> 1) + 4 * (st & 1) + p; eb = ea + 8; }
-        else { ea = 4 * st + p; eb = ea + 16; }
-        const uint32_t wa = xn[ea >> 3][(ea >> 1) & 3], wb = xn[eb >> 3][(eb >> 1) & 3];
-        // both elements sit in the same half of their words (ea and eb have the same parity)
-        w[p] = __builtin_amdgcn_perm(wb, wa, (ea & 1) ? 0x07060302u : 0x05040100u);
+    if constexpr (!PAIRS) {
+        return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(xl + 16 * st));
+    } else {
+        int ea, gap;                                  // first element of pair 0; distance to its partner
+        if constexpr (C == 4) { ea = 8 * st; gap = 4; }
+        else if constexpr (C == 2) { ea = 16 * (st >> 1) + 4 * (st & 1); gap = 8; }
+        else { ea = 4 * st; gap = 16; }
+        // pairs p = 0..3 use elements ea + p and ea + p + gap: words (ea >> 1) + {0, 1} and the same + gap / 2
+        const u32x2_t wa = *reinterpret_cast<const u32x2_t *>(xl + 2 * ea);
+        const u32x2_t wb = *reinterpret_cast<const u32x2_t *>(xl + 2 * (ea + gap));
+        uint32_t w[4];
+        w[0] = __builtin_amdgcn_perm(wb.x, wa.x, 0x05040100u);
+        w[1] = __builtin_amdgcn_perm(wb.x, wa.x, 0x07060302u);
+        w[2] = __builtin_amdgcn_perm(wb.y, wa.y, 0x05040100u);
+        w[3] = __builtin_amdgcn_perm(wb.y, wa.y, 0x07060302u);
+        return as_bf16x8(w[0], w[1], w[2], w[3]);
     }
-    return as_bf16x8(w[0], w[1], w[2], w[3]);
 }
 
 // One block: loads were issued before (cw, sc, ze); multiply and add into acc.
 template <int C, int N_COLS, int NB>
 __device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const float (&sc)[2], const float (&ze)[2],
-                                              const u32x4_t (&xn)[NB][N_COLS / 32], f32x4v_t (&acc)[2][NB])
+                                              const unsigned char *const (&xl)[NB], f32x4v_t (&acc)[2][NB])
 {
     constexpr int STEPS = N_COLS / 32;
     constexpr bool PAIRS = PairOrder<C, N_COLS / 4>::value;
@@ -177,9 +185,7 @@ __device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const 
         else { b0 = operand<C>(cw[0], st); b1 = operand<C>(cw[1], st); }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            bf16x8_t xa;
-            if constexpr (PAIRS) xa = x_pairs<C, STEPS>(xn[nb], st);
-            else xa = __builtin_bit_cast(bf16x8_t, xn[nb][st]);
+            const bf16x8_t xa = x_operand<C, PAIRS>(xl[nb], st);
             d[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, b0, d[0][nb], 0, 0, 0);
             d[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, b1, d[1][nb], 0, 0, 0);
             d1[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, ones, d1[nb], 0, 0, 0);
@@ -320,13 +326,10 @@ void mp_gemm_kernel(MpArgs a)
         const int c = cbits[t];
         if (c == 0) continue;
         const int Jl = jl + MG_JL * t;                         // block column inside the slice
-        u32x4_t xa[NB][STEPS];                                 // the lane's x values of this block column, natural order
+        const unsigned char *xa[NB];                           // the lane's x values of this block column (LDS, natural order)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int st = 0; st < STEPS; ++st)
-                xa[nb][st] = *reinterpret_cast<const u32x4_t *>(
-                    smem + (size_t)(16 * nb + li) * PITCH + (size_t)(Jl * N_COLS + g * KL + 8 * st) * 2);
+            xa[nb] = smem + (size_t)(16 * nb + li) * PITCH + (size_t)(Jl * N_COLS + g * KL) * 2;
         switch (c) {
         case 1: block_product<1, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
         case 2: block_product<2, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
