@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--two-pass", action="store_true",
                     help="separate gather and cost launches instead of the fused one-pass kernel")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-mp-gemm", action="store_true",
+                    help="skip the untimed probe of the inference product on the paper's 8192 x 8192 workload")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy first (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
@@ -85,6 +87,56 @@ def cpu_baseline(torch, synth, shapes_sample, m, n, bits, avg, seed):
     return {"value": nw / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
             "sample": "decoder layers %s, all 7 projections each (%d weights), whole path incl. allocation on "
                       "the sample's own table, %.1f s" % (sorted({l for l, _, _, _ in shapes_sample}), nw, dt)}
+
+
+def mp_gemm_probe(torch, sb, synth, dev):
+    """The paper's kernel workload beside the search (outside the timed region): an 8192 x 8192
+    projection at 4 bits on average, all INT4 tiles or 40 % INT2 / 40 % INT4 / 20 % INT8, batch 16 and
+    32 (Sec. 5.3, kernel-latency table).  Latency per call over 200 back-to-back calls; bytes = the
+    packed codes plus scales and zeros."""
+    import numpy as np
+    R = C = 8192
+    m = n = 128
+    bits = [2, 4, 8]
+    ctx = sb.Context(0, torch.cuda.current_stream().cuda_stream)
+    plan = sb.Plan(ctx, [(R, C)], m, n, bits)
+    N = plan.num_blocks()
+    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device=dev)
+    W, _ = synth.make_matrix("student_t", R, C, seed=0, tid=0, device=dev)
+    res = {"workload": "8192 x 8192 projection, 128 x 128 tiles, 4 bits per weight on average", "cases": []}
+    for name, mix in (("all INT4", (0.0, 1.0, 0.0)), ("40% INT2 / 40% INT4 / 20% INT8", (0.4, 0.4, 0.2))):
+        counts = [int(round(f * N)) for f in mix]
+        counts[1] += N - sum(counts)
+        lv = np.random.default_rng(0).permutation(np.repeat(np.arange(3, dtype=np.uint8), counts))
+        level = torch.from_numpy(lv).to(dev)
+        off = torch.empty(N + 1, dtype=torch.int64, device=dev)
+        plan.offsets(level, off, ws)
+        torch.cuda.synchronize()
+        codes = torch.zeros(int(off[-1].item()), dtype=torch.uint8, device=dev)
+        scale = torch.empty(N * m, dtype=torch.float32, device=dev)
+        zero = torch.empty(N * m, dtype=torch.float32, device=dev)
+        plan.pack_all(W.reshape(-1), level, off, codes, scale, zero, ws)
+        nbytes = codes.numel() + 8 * N * m
+        for batch in (16, 32):
+            x = torch.randn(batch, C, device=dev).to(torch.bfloat16)
+            y = torch.empty(batch, R, dtype=torch.float32, device=dev)
+            for _ in range(10):
+                plan.mp_gemm(0, x, level, off, codes, scale, zero, y, ws)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 200
+            e0.record()
+            for _ in range(reps):
+                plan.mp_gemm(0, x, level, off, codes, scale, zero, y, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / reps * 1e3
+            ref = x.float() @ (W.float().t())                 # the unquantized product, for scale only
+            res["cases"].append({"tiles": name, "batch": batch, "latency_us": us, "packed_bytes": nbytes,
+                                 "GBs": nbytes / us * 1e-3, "frac_of_hbm_peak": nbytes / us * 1e-3 / HBM_PEAK_GBS,
+                                 "rel_diff_to_unquantized": float((y - ref).norm() / ref.norm())})
+    plan.close()
+    ctx.close()
+    return res
 
 
 def main():
@@ -259,6 +311,8 @@ def main():
                                  "cost_kernel_weights_per_s": nw / (t_cost * 1e-3),
                                  "tables_bit_equal": bool(torch.equal(cost.view(torch.int32), cost2.view(torch.int32)))}
         del w2, s2, cost2
+    if not args.no_mp_gemm:
+        out["mp_gemm"] = mp_gemm_probe(torch, sb, synth, dev)
     if not args.no_cpu_baseline:
         # two full decoder layers: 436 M weights, 10-20 s of single-threaded oracle time
         sample = [(l, nm_, r, c) for l in (0, 1) for nm_, r, c in synth.layer_shapes(model)]
