@@ -152,6 +152,26 @@ def test_propose_validates_on_the_host(ctx, lib):
     p.close()
 
 
+def test_mp_gemm_validates_on_the_host(ctx, lib):
+    ptr = C.c_void_p(4096)
+    ws = C.c_void_p(256 * 1024)
+    p = sb.Plan(ctx, [(256, 256)], 64, 128, [2, 3, 4])
+    call = lambda pl, mat, x, ld, batch: lib.sbits_mp_gemm(pl.h, C.c_int(mat), x, C.c_int64(ld), C.c_int(batch), ptr, ptr,
+                                                            ptr, ptr, ptr, ptr, ws)
+    assert call(p, 0, None, 256, 16) == sb.ERR_INVALID_ARG
+    assert call(p, 1, ptr, 256, 16) == sb.ERR_INVALID_ARG                # no such matrix
+    assert call(p, 0, ptr, 248, 16) == sb.ERR_INVALID_ARG                # ld_x below the column count
+    assert call(p, 0, ptr, 260, 16) == sb.ERR_INVALID_ARG                # ld_x not a multiple of 8
+    assert call(p, 0, C.c_void_p(4100), 256, 16) == sb.ERR_INVALID_ARG   # x not 16-byte aligned
+    assert call(p, 0, ptr, 256, 0) == sb.ERR_INVALID_ARG
+    assert call(p, 0, ptr, 256, 33) == sb.ERR_UNIMPLEMENTED              # more than 32 rows of x per call
+    assert call(p, 0, ptr, 256, 32) == sb.ERR_HIP                        # valid: needs a device
+    p.close()
+    q = sb.Plan(ctx, [(64, 512)], 16, 256, [2, 4])                       # 16-row blocks, 256 columns wide
+    assert call(q, 0, ptr, 512, 16) == sb.ERR_UNIMPLEMENTED
+    q.close()
+
+
 def test_plan_limits(ctx):
     """At most 32768 rows / columns per matrix and 2^24 blocks per plan."""
     sb.Plan(ctx, [(32768, 32768)], 8, 8, [2]).close()                    # 2^24 blocks: the limit itself
