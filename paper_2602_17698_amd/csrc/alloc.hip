@@ -32,6 +32,12 @@ constexpr int AL_THREADS = 256;
 constexpr int64_t TRACE_CAP = 16384;
 constexpr int SEL_DB = 11;                    // digit bits of the selection's radix descent
 constexpr int SEL_BINS = 1 << SEL_DB;
+#ifndef SEL_KPT
+#define SEL_KPT 16                            // keys per thread of a selection pass ...
+#endif
+#ifndef SEL_MAXWG
+#define SEL_MAXWG 128                         // ... and the most workgroups it uses
+#endif
 
 struct SelJob {
     unsigned long long prefix;     // decided high digits, right aligned
@@ -176,17 +182,17 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
     const unsigned long long excl_tau = excl ? st->job[excl_job].tau : 0;
     const int sh_digit = SEL_DB * (P - 1 - pass), sh_prefix = SEL_DB * (P - pass);
     const long long stride = (long long)gridDim.x * blockDim.x;
-    // four independent loads in flight per thread
-    for (long long i0 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i0 < N; i0 += 4 * stride) {
-        unsigned long long key[4], ex[4];
+    // all of a thread's keys are requested at once (SEL_KPT loads in flight: one memory latency per pass)
+    for (long long i0 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i0 < N; i0 += SEL_KPT * stride) {
+        unsigned long long key[SEL_KPT], ex[SEL_KPT];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < SEL_KPT; ++u) {
             const long long i = i0 + u * stride;
             key[u] = i < N ? keys[i] : 0ull;
             ex[u] = (excl && i < N) ? excl[i] : 0ull;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < SEL_KPT; ++u) {
             if (key[u] < key_min) continue;                      // also drops the padding (key 0)
             if (excl && ex[u] >= excl_tau) continue;
             const unsigned long long s = key[u] >> 8;
@@ -203,7 +209,10 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
             atomicAdd(&job->hist_cnt[b], hc[b]);
             atomicAdd(&job->hist_w[b], hw[b]);
         }
-    __threadfence();
+    // Everything the workgroups exchange goes through device-scope atomics, which are performed at the
+    // point of coherence: waiting for their acknowledgement (vmcnt) orders them before the ticket.  A
+    // release fence would also write the L2 back, which costs more than the rest of the pass.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned int t = atomicAdd(&job->ticket, 1u);
@@ -211,7 +220,6 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
     // the last workgroup: read the finished histogram, clear it for the next pass; thread t owns
     // the SEL_BINS/256 consecutive bins [t*G, (t+1)*G)
     constexpr int G = SEL_BINS / AL_THREADS;
@@ -614,7 +622,7 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     bool done = all_max;
     const int P = h.P;
     // the selection passes end in one global atomic per non-empty bin and workgroup: few, fat workgroups
-    const unsigned sgrid = (unsigned)((N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) < 128 ? (N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) : 128);
+    const unsigned sgrid = (unsigned)((N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) < SEL_MAXWG ? (N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) : SEL_MAXWG);
     while (!done) {
         hipLaunchKernelGGL(gains_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level, keyU, keyD);
         bool expanded = false;
@@ -706,7 +714,7 @@ int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, 
     SBITS_HIP(ctx, hipStreamSynchronize(sm));      // the image goes away on return
 
     const unsigned grid = (unsigned)((N + AL_THREADS - 1) / AL_THREADS < 1024 ? (N + AL_THREADS - 1) / AL_THREADS : 1024);
-    const unsigned sgrid = (unsigned)((N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) < 128 ? (N + AL_THREADS * 16 - 1) / (AL_THREADS * 16) : 128);
+    const unsigned sgrid = (unsigned)((N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) < SEL_MAXWG ? (N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) : SEL_MAXWG);
     const int P = h.P;
     const unsigned long long *none = nullptr;
     hipLaunchKernelGGL(step_keys_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, s_up, s_down, level_in, keyU, keyD);
