@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--two-pass", action="store_true",
                     help="separate gather and cost launches instead of the fused one-pass kernel")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--only-mp-gemm", action="store_true",
+                    help="run only the inference-product probe and print its object (for profiling that kernel)")
     ap.add_argument("--no-mp-gemm", action="store_true",
                     help="skip the untimed probe of the inference product on the paper's 8192 x 8192 workload")
     ap.add_argument("--copy-probe", action="store_true",
@@ -89,7 +91,7 @@ def cpu_baseline(torch, synth, shapes_sample, m, n, bits, avg, seed):
                       "the sample's own table, %.1f s" % (sorted({l for l, _, _, _ in shapes_sample}), nw, dt)}
 
 
-def mp_gemm_probe(torch, sb, synth, dev):
+def mp_gemm_probe(torch, sb, synth, dev, copy_probe=False):
     """The paper's kernel workload beside the search (outside the timed region): an 8192 x 8192
     projection at 4 bits on average, all INT4 tiles or 40 % INT2 / 40 % INT4 / 20 % INT8, batch 16 and
     32 (Sec. 5.3, kernel-latency table).  Latency per call over 200 back-to-back calls; bytes = the
@@ -134,6 +136,11 @@ def mp_gemm_probe(torch, sb, synth, dev):
             res["cases"].append({"tiles": name, "batch": batch, "latency_us": us, "packed_bytes": nbytes,
                                  "GBs": nbytes / us * 1e-3, "frac_of_hbm_peak": nbytes / us * 1e-3 / HBM_PEAK_GBS,
                                  "rel_diff_to_unquantized": float((y - ref).norm() / ref.norm())})
+    if copy_probe:                                   # a copy of known size, to scale the byte counters by
+        a = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
     plan.close()
     ctx.close()
     return res
@@ -153,6 +160,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     sb.load()
+    if args.only_mp_gemm:
+        print(json.dumps({"mp_gemm": mp_gemm_probe(torch, sb, synth, dev, copy_probe=args.copy_probe)}))
+        return
     bits = [int(b) for b in args.bits.split(",")]
     n = args.block
     m = args.block_rows or args.block

@@ -202,6 +202,41 @@ __device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const 
     }
 }
 
+// Codes, scales and zeros of block T of a wave -> register slot S; the same number of load
+// instructions whatever the block (c = 0: an absent block reads the first dword of the stream and the
+// clamped block's scales).  (A macro: through a function the slots end up in scratch memory.)
+#define MG_REQUEST(T, S)                                                                                          \
+    do {                                                                                                          \
+        const int c_ = cbits[T];                                                                                  \
+        const uint8_t *pb_ = a.codes + (c_ ? (int64_t)(((uint64_t)off_hi[T] << 32) | off_lo[T]) : 0);             \
+        const float *ps_ = a.scale + blk[T] * a.m + rin, *pz_ = a.zero + blk[T] * a.m + rin;                      \
+        _Pragma("unroll") for (int tl = 0; tl < 2; ++tl) {                                                        \
+            const uint8_t *p_ = pb_ + (lane_units + (uint32_t)(tl * 16 * (N_COLS / 8))) * (uint32_t)c_;           \
+            sc[S][tl] = ps_[16 * tl + li];                                                                        \
+            ze[S][tl] = pz_[16 * tl + li];                                                                        \
+            if constexpr (KL == 32) {                                                                             \
+                switch (c_) {                                                                                     \
+                case 0: load_codes<0>(p_, cw[S][tl]); break;                                                      \
+                case 1: load_codes<1>(p_, cw[S][tl]); break;                                                      \
+                case 2: load_codes<2>(p_, cw[S][tl]); break;                                                      \
+                case 3: load_codes<3>(p_, cw[S][tl]); break;                                                      \
+                case 4: load_codes<4>(p_, cw[S][tl]); break;                                                      \
+                case 5: load_codes<5>(p_, cw[S][tl]); break;                                                      \
+                case 6: load_codes<6>(p_, cw[S][tl]); break;                                                      \
+                case 7: load_codes<7>(p_, cw[S][tl]); break;                                                      \
+                default: load_codes<8>(p_, cw[S][tl]); break;                                                     \
+                }                                                                                                 \
+            } else {                                                                                              \
+                /* 2 * c bytes: 16-bit halves (the stream is only 2-byte aligned here) */                         \
+                const __attribute__((address_space(1))) uint16_t *h_ =                                            \
+                    (const __attribute__((address_space(1))) uint16_t *)p_;                                       \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                     \
+                    if (i < c_)                                                                                   \
+                        cw[S][tl][i >> 1] = (i & 1) ? (cw[S][tl][i >> 1] | ((uint32_t)h_[i] << 16)) : (uint32_t)h_[i]; \
+            }                                                                                                     \
+        }                                                                                                         \
+    } while (0)
+
 template <int N_COLS, int NB>
 __global__ __launch_bounds__(MG_THREADS)
 void mp_gemm_kernel(MpArgs a)
@@ -229,9 +264,12 @@ void mp_gemm_kernel(MpArgs a)
     const int row0 = blockIdx.x * (MG_RG * 32) + rg * 32;      // first of the wave's 32 rows
     const bool rows_ok = row0 < a.R;                           // (R is a multiple of 32)
     const int I = rows_ok ? row0 / a.m : 0, rin = rows_ok ? row0 - I * a.m : 0;
+    // PF blocks of codes are in flight at a time (a ring of PF register slots): all four when one batch
+    // tile leaves the registers for it, two otherwise
+    constexpr int PF = NB == 1 ? MG_NBLK : 2;
     int cbits[MG_NBLK];
-    uint32_t cw[MG_NBLK][2][8];
-    float sc[MG_NBLK][2], ze[MG_NBLK][2];
+    uint32_t cw[PF][2][8];
+    float sc[PF][2], ze[PF][2];
     int64_t blk[MG_NBLK];
     uint32_t lvl_v[MG_NBLK];
     int64_t boff_v[MG_NBLK];
@@ -273,6 +311,8 @@ void mp_gemm_kernel(MpArgs a)
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the x slice is in LDS
     MG_TS(2);
     const uint32_t lane_units = (uint32_t)((rin + li) * (N_COLS / 8) + g * (KL / 8));   // x c = the lane's byte offset in the block
+    // the blocks' bitwidths and stream offsets as scalars
+    uint32_t off_lo[MG_NBLK], off_hi[MG_NBLK];
 #pragma unroll
     for (int t = 0; t < MG_NBLK; ++t) {
         const int J = J0 + jl + MG_JL * t;
@@ -280,40 +320,12 @@ void mp_gemm_kernel(MpArgs a)
         int c = a.bits[0];
 #pragma unroll
         for (int k = 1; k < 8; ++k) c = lv == k ? a.bits[k] : c;
-        c = (rows_ok && J < a.nbc) ? c : 0;
-        cbits[t] = c;
-        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)boff_v[t]);
-        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)boff_v[t] >> 32));
-        // an absent block (c = 0) reads the first dword of the stream and the clamped block's scales
-        const uint8_t *pb = a.codes + (c ? (int64_t)(((uint64_t)hi << 32) | lo) : 0);      // uniform
-        const float *ps = a.scale + blk[t] * a.m + rin, *pz = a.zero + blk[t] * a.m + rin;
-#pragma unroll
-        for (int tl = 0; tl < 2; ++tl) {
-            const uint8_t *p = pb + (lane_units + (uint32_t)(tl * 16 * (N_COLS / 8))) * (uint32_t)c;
-            sc[t][tl] = ps[16 * tl + li];
-            ze[t][tl] = pz[16 * tl + li];
-            // KL * c / 8 bytes per lane: a whole number of dwords for KL = 32, of 16-bit halves for KL = 16
-            if constexpr (KL == 32) {
-                switch (c) {
-                case 0: load_codes<0>(p, cw[t][tl]); break;
-                case 1: load_codes<1>(p, cw[t][tl]); break;
-                case 2: load_codes<2>(p, cw[t][tl]); break;
-                case 3: load_codes<3>(p, cw[t][tl]); break;
-                case 4: load_codes<4>(p, cw[t][tl]); break;
-                case 5: load_codes<5>(p, cw[t][tl]); break;
-                case 6: load_codes<6>(p, cw[t][tl]); break;
-                case 7: load_codes<7>(p, cw[t][tl]); break;
-                default: load_codes<8>(p, cw[t][tl]); break;
-                }
-            } else {
-                // 2 * c bytes: read them as 16-bit halves (the stream is only 2-byte aligned here)
-                const __attribute__((address_space(1))) uint16_t *h = (const __attribute__((address_space(1))) uint16_t *)p;
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (i < c) cw[t][tl][i >> 1] = (i & 1) ? (cw[t][tl][i >> 1] | ((uint32_t)h[i] << 16)) : (uint32_t)h[i];
-            }
-        }
+        cbits[t] = (rows_ok && J < a.nbc) ? c : 0;
+        off_lo[t] = __builtin_amdgcn_readfirstlane((uint32_t)boff_v[t]);
+        off_hi[t] = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)boff_v[t] >> 32));
     }
+#pragma unroll
+    for (int t = 0; t < PF; ++t) MG_REQUEST(t, t);
 
     f32x4v_t acc[2][NB];
 #pragma unroll
@@ -324,22 +336,22 @@ void mp_gemm_kernel(MpArgs a)
 #pragma unroll
     for (int t = 0; t < MG_NBLK; ++t) {
         const int c = cbits[t];
-        if (c == 0) continue;
         const int Jl = jl + MG_JL * t;                         // block column inside the slice
         const unsigned char *xa[NB];                           // the lane's x values of this block column (LDS, natural order)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
             xa[nb] = smem + (size_t)(16 * nb + li) * PITCH + (size_t)(Jl * N_COLS + g * KL) * 2;
-        switch (c) {
-        case 1: block_product<1, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
-        case 2: block_product<2, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
-        case 3: block_product<3, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
-        case 4: block_product<4, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
-        case 5: block_product<5, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
-        case 6: block_product<6, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
-        case 7: block_product<7, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
-        default: block_product<8, N_COLS, NB>(cw[t], sc[t], ze[t], xa, acc); break;
+        if (c != 0) switch (c) {                               // (0: no such block column)
+        case 1: block_product<1, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
+        case 2: block_product<2, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
+        case 3: block_product<3, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
+        case 4: block_product<4, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
+        case 5: block_product<5, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
+        case 6: block_product<6, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
+        case 7: block_product<7, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
+        default: block_product<8, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
         }
+        if (t + PF < MG_NBLK) MG_REQUEST((t + PF) % MG_NBLK, t % PF);   // the slot is free again
 #ifdef MG_EXP_TIMING
         { asm volatile("" :: "v"(acc[0][0][0]), "v"(acc[1][0][3])); }
         MG_TS(3 + t);
