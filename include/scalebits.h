@@ -329,8 +329,8 @@ int  sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits,
  * permuted input channels and y by its permuted output channels (the paper stores
  * the permuted weights and keeps connected layers consistent, App. "Channel
  * Reordering").  x_bf16: [batch][ld_x] bfloat16, 16-byte aligned, ld_x >= cols and a
- * multiple of 8; y: [batch][rows] float32; 1 <= batch <= 32 (larger batches: several
- * calls).  Products are exact (integer codes times bf16) and summed in fp32 on the
+ * multiple of 8; y: [batch][rows] float32; batch >= 1 (32 rows of x per kernel launch:
+ * the kernel is built for the small batches of decoding).  Products are exact (integer codes times bf16) and summed in fp32 on the
  * matrix cores; scale and zero are applied per block row in fp32.
  * SBITS_ERR_UNIMPLEMENTED unless block_cols is 64 or 128 and block_rows a multiple
  * of 32.  Uses ws.                                                               */

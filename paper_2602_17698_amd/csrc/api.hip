@@ -383,11 +383,18 @@ int sbits_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, i
         return SBITS_ERR_INVALID_ARG;
     if (batch < 1 || ld_x < plan->cols[mat] || (ld_x % 8) || !aligned16(x_bf16) || !aligned16(codes))
         return SBITS_ERR_INVALID_ARG;
-    if (!sbits_mp_gemm_shapes_ok(plan) || batch > 32) return SBITS_ERR_UNIMPLEMENTED;
+    if (!sbits_mp_gemm_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
     int rc = need_device(plan);
     if (rc) return rc;
-    return sbits_launch_mp_gemm(plan, mat, x_bf16, ld_x, batch, level, byte_off, codes, scale, zero, y,
-                                sbits_scratch(plan, ws));
+    // 32 rows of x per launch (two batch tiles of the kernel); launches share the scratch in stream order
+    for (int b0 = 0; b0 < batch; b0 += 32) {
+        const int nb = batch - b0 < 32 ? batch - b0 : 32;
+        rc = sbits_launch_mp_gemm(plan, mat, static_cast<const uint16_t *>(x_bf16) + (int64_t)b0 * ld_x, ld_x, nb, level,
+                                  byte_off, codes, scale, zero, y + (int64_t)b0 * plan->rows[mat],
+                                  sbits_scratch(plan, ws));
+        if (rc) return rc;
+    }
+    return SBITS_OK;
 }
 
 int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws)

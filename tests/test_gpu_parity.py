@@ -855,6 +855,7 @@ def _mp_gemm_check(orc, y, packed, base, R, C, m, n, bits, xb):
     (256, 128 * 17, 128, 128, [1, 2, 3, 4], 32),            # two batch tiles, a split with one block column
     (128, 192, 64, 64, [1, 2, 3, 4, 5, 6, 7, 8], 17),       # group size 64
     (192, 64 * 33, 64, 64, [2, 3, 4, 8], 1),                # group size 64, three splits, a single row of x
+    (128, 128 * 18, 64, 128, [2, 4], 70),                   # more than 32 rows of x: three launches
 ])
 def test_mp_gemm(orc, ctx, dev, R, C, m, n, bits, batch):
     say("mixed-precision product", R, C, m, n, bits, batch)
