@@ -72,8 +72,10 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
                         uint16_t *__restrict__ w_re_all, float *__restrict__ part, GridConsts gc,
-                        const uint8_t *__restrict__ level)
+                        const uint8_t *__restrict__ level, int kstride, int koff)
 {
+    // kstride, koff: the K sums of an octet go to part[..][koff .. koff + K) of kstride values (a launch
+    // may cover a subset of the candidates)
     static_assert(!SUR || K == 2, "two sums per block");
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int rowsrc[FU_OPU * 8];
@@ -284,7 +286,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                 for (int k = 0; k < K; ++k) v[k] = group_allreduce<LPG>(last[c][k], OpAdd{});
                 if (lig == 0 && valid[c]) {
                     const int J = (tid + T * c) / LPG;
-                    float *dst = part + ((d.block_base + (int64_t)I * nbc + J) * opb + oib) * K;
+                    float *dst = part + ((d.block_base + (int64_t)I * nbc + J) * opb + oib) * kstride + koff;
 #pragma unroll
                     for (int k = 0; k < K; ++k) dst[k] = v[k];
                 }
@@ -589,6 +591,7 @@ struct FusedLaunch {
     GridConsts gc;
     int64_t cols;
     const uint8_t *level;     // surrogates only
+    int kstride, koff;        // where the launch's sums go among the block's (see the kernel)
 };
 
 // threads per workgroup: the chunks of a row spread over CPL per lane, rounded up to whole waves
@@ -607,7 +610,8 @@ static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
     const size_t lds = (size_t)RS * a.cols * 6;
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
-                       a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc, a.level);
+                       a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc, a.level, a.kstride,
+                       a.koff);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
@@ -787,8 +791,22 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
         a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
         a.cols = fc.cols;
         if (a.total_wg == 0) continue;
-        const int rc = plan->n == 64 ? launch_fused_l<8>(plan->K, ctx, a) : launch_fused_l<16>(plan->K, ctx, a);
-        if (rc) return rc;
+        // Four chunks per lane and seven or eight candidates do not fit the register file (three tree
+        // levels per chunk and candidate): such rows take two launches of about half the candidates
+        // each.  The grids are independent per candidate, so the table is the same bit for bit.
+        const bool split = fc.cols / 8 > 1024 && plan->K >= 7;
+        const int k0 = split ? (plan->K + 1) / 2 : plan->K;
+        for (int kb = 0; kb < plan->K; kb += k0) {
+            const int kn = plan->K - kb < k0 ? plan->K - kb : k0;
+            sbits_fill_grid_consts(plan->bits + kb, kn, &a.gc);
+            a.kstride = plan->K;
+            a.koff = kb;
+            uint16_t *const w_keep = a.w_re;
+            if (kb > 0) a.w_re = nullptr;                       // the reordered weights are written once
+            const int rc = plan->n == 64 ? launch_fused_l<8>(kn, ctx, a) : launch_fused_l<16>(kn, ctx, a);
+            a.w_re = w_keep;
+            if (rc) return rc;
+        }
     }
     const int64_t NK = plan->N * plan->K;
     if (NK > 0) {
@@ -851,6 +869,8 @@ int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const
     a.w_re = nullptr;
     a.part = static_cast<float *>(sbits_scratch(plan, ws));
     a.level = level;
+    a.kstride = 2;
+    a.koff = 0;
     for (const sbits_plan::FusedClass &fc : plan->fused_classes) {
         a.members = d_mem + fc.first;
         a.wg_start = d_pre + fc.pre_first;

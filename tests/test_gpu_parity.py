@@ -320,6 +320,8 @@ ONE_PASS_CASES = [
     ([(24, 192), (2048, 128)], 8, 64, [1, 2, 3, 4, 5, 6, 7, 8]),  # one octet per block; 16 runs
     ([(2048, 256)], 1024, 128, [3]),                              # 128 octets per block
     ([(64, 14336)], 64, 64, [1, 2, 3, 4, 8]),                     # four chunks per lane, K = 5
+    ([(64, 14336), (128, 256)], 64, 128, [1, 2, 3, 4, 5, 6, 7, 8]),  # four chunks per lane, K = 8: two launches of 4 candidates
+    ([(64, 8320)], 64, 64, [1, 2, 3, 4, 5, 6, 8]),                # K = 7: 4 + 3 candidates
 ]
 
 
