@@ -922,3 +922,35 @@ def test_mp_gemm_refuses_other_shapes(ctx, dev):
         plan.mp_gemm(0, x, t, t, t, t, t, t, ws)
     assert e.value.status == sb.ERR_UNIMPLEMENTED
     plan.close()
+
+
+def test_search_then_inference_preserves_the_layer_function(orc, ctx, dev):
+    """The whole chain on one matrix: search (reorder, allocate, pack), then the product with the
+    stored weights.  With x in the permuted input order the result is the permuted output of the layer
+    computed with the dequantized weights; against the unquantized layer it differs by the
+    quantization error only (more bits, smaller difference)."""
+    say("search -> inference")
+    R, C, m, n, bits = 256, 512, 64, 128, [2, 3, 4, 8]
+    W, S = synth.make_matrix("student_t", R, C, seed=5, tid=0)
+    rng = np.random.default_rng(8)
+    x = torch.from_numpy(rng.standard_normal((16, C)).astype(np.float32)).to(torch.bfloat16)
+    y_full = x.float().numpy().astype(np.float64) @ W.float().numpy().astype(np.float64).T      # unquantized, original order
+    errs = []
+    for avg in (2.5, 4.0, 8.0):
+        rc, st, o, _ = gpu_search(ctx, dev, [(W, S)], m, n, bits, avg)
+        assert rc == 0
+        plan, ws = make_plan(ctx, [(R, C)], m, n, bits, dev)
+        rp, cp = o["row_perm"].cpu().numpy(), o["col_perm"].cpu().numpy()
+        xp = x[:, torch.from_numpy(cp).long()].contiguous().to(dev)                               # permuted input channels
+        y = torch.empty(16, R, dtype=torch.float32, device=dev)
+        plan.mp_gemm(0, xp, o["level"], o["byte_off"], o["codes"], o["scale"], o["zero"], y, ws)
+        torch.cuda.synchronize()
+        level, off = o["level"].cpu().numpy(), o["byte_off"].cpu().numpy()
+        ref = orc.mp_gemm(o["codes"][:int(off[-1])].cpu().numpy(), o["scale"].cpu().numpy(), o["zero"].cpu().numpy(),
+                          level, off, 0, R, C, m, n, bits, to_np_bf16(xp.cpu()))
+        yh = y.cpu().numpy().astype(np.float64)
+        assert np.abs(yh - ref).max() <= 1e-4 * np.abs(ref).max()
+        errs.append(float(np.linalg.norm(yh - y_full[:, rp]) / np.linalg.norm(y_full)))           # permuted output channels
+        plan.close()
+    say("  relative difference to the unquantized layer at 2.5 / 4 / 8 bits:", errs)
+    assert errs[0] > errs[1] > errs[2] and errs[2] < 0.02
