@@ -18,9 +18,9 @@
 //   lane l supplies channel i = l % 16 and the K-quarter g = l / 16 of a block row: its n / 4 codes
 //   are n * c / 32 consecutive bytes of the stream; the wave's 16 rows x n codes are one contiguous
 //   run.  A workgroup of 16 waves covers 128 rows (4 row groups of 32 = 2 channel tiles each) x 16
-//   block columns (4 waves per row group, 4 blocks per wave); the x slice of those columns sits in
-//   LDS.  Block columns beyond the first 16 go to further workgroups (grid.y), whose partial sums a
-//   second kernel adds in a fixed order.
+//   block columns (4 waves per row group, 4 blocks per wave, two or three of them in flight in a ring
+//   of register slots); the x slice of those columns sits in LDS.  Block columns beyond the first 16
+//   go to further workgroups (grid.y), whose partial sums a second kernel adds in a fixed order.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -114,7 +114,7 @@ __device__ __forceinline__ bf16x8_t operand(const uint32_t (&r)[8], int st)
 // ---- pair order (bitwidths 1, 2, 4): a 32-bit word holds two codes 16 bits apart, so one AND-OR
 // turns  (w >> s) & mask  into the bf16 pair (128 + q_a, 128 + q_b) with b - a = 16 / C codes.
 // The operand then holds the lane's codes in the order a0, b0, a1, b1, ...; x is put into the
-// same order with byte permutes (once per block, shared by both channel tiles).
+// same order with byte permutes (x_operand; shared by both channel tiles).
 //   C = 4: step st, pair p: codes (8 st + p,        8 st + p + 4)     word st,      shift 4 p
 //   C = 2: step st, pair p: codes (16 d + 4 h + p,  ... + 8)          word d,       shift 2 (4 h + p),  st = 2 d + h
 //   C = 1: step st, pair p: codes (4 st + p,        4 st + p + 16)    word 0,       shift 4 st + p      (32 codes per lane only)
