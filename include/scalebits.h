@@ -320,6 +320,16 @@ int  sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits,
                   const sbits_params *params, const sbits_outputs *out,
                   sbits_stats *host_stats, void *ws);
 
+/* ---- the stored matrix as numbers (paper Sec. 5.3: uniform bitwidth per tile) ----
+ * out[i][j] = fmaf(code, scale, zero) of matrix `mat`, from the packed stream (GLOBAL
+ * arrays as written by the packing calls), in the REORDERED coordinates: row i and
+ * column j of the matrix the stream was packed from.  out_bf16 = 0: float32 (the
+ * format's exact value); 1: rounded to bfloat16, nearest even.  out: [rows][ld_out]
+ * elements, 16-byte aligned, ld_out >= cols and a multiple of 8.  Any block shape.  */
+int  sbits_dequant(sbits_plan *plan, int mat, const uint8_t *level, const int64_t *byte_off,
+                   const uint8_t *codes, const float *scale, const float *zero,
+                   void *out, int64_t ld_out, int out_bf16);
+
 /* ---- inference with the stored weights (paper Sec. 5.3 "Inference Kernel") -----
  * y[b][i] = sum_j What[i][j] * x[b][j] for matrix `mat` of the plan, read from the
  * packed stream (the outputs of sbits_pack / sbits_pack_all / sbits_gather_pack_all,

@@ -25,7 +25,7 @@ EXPORTS = [
     "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
     "sbits_reorder_coupled_all", "sbits_surrogates_all",
-    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search", "sbits_mp_gemm",
+    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search", "sbits_mp_gemm", "sbits_dequant",
 ]
 
 
@@ -277,6 +277,13 @@ class Plan:
     def pack(self, mat, w_re, level, byte_off, codes, scale, zero):
         return _check(load().sbits_pack(self.h, C.c_int(mat), _ptr(w_re), _ptr(level), _ptr(byte_off),
                                         _ptr(codes), _ptr(scale), _ptr(zero)), "sbits_pack")
+
+    def dequant(self, mat, level, byte_off, codes, scale, zero, out):
+        """out[i][j] = code * scale + zero of the stored (reordered) matrix; out: fp32 or bf16 [rows, cols]."""
+        import torch
+        return _check(load().sbits_dequant(self.h, C.c_int(mat), _ptr(level), _ptr(byte_off), _ptr(codes), _ptr(scale),
+                                           _ptr(zero), _ptr(out), C.c_int64(out.stride(0)),
+                                           C.c_int(1 if out.dtype == torch.bfloat16 else 0)), "sbits_dequant")
 
     def mp_gemm(self, mat, x, level, byte_off, codes, scale, zero, y, ws):
         """y[b][i] = sum_j What[i][j] x[b][j] from the packed arrays; x: bf16 [batch, cols], y: fp32 [batch, rows]."""

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscalebits.so")
-SOURCES = ["api.hip", "reorder.hip", "cost.hip", "fused.hip", "alloc.hip", "pack.hip", "mpgemm.hip"]
+SOURCES = ["api.hip", "reorder.hip", "cost.hip", "fused.hip", "alloc.hip", "pack.hip", "mpgemm.hip", "dequant.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -374,6 +374,19 @@ int sbits_propose(sbits_plan *plan, const float *s_up, const float *s_down, cons
     return sbits_run_propose(plan, s_up, s_down, level_in, avg_bits, k, level_out, host_out, sbits_scratch(plan, ws));
 }
 
+int sbits_dequant(sbits_plan *plan, int mat, const uint8_t *level, const int64_t *byte_off, const uint8_t *codes,
+                  const float *scale, const float *zero, void *out, int64_t ld_out, int out_bf16)
+{
+    if (!plan || mat < 0 || mat >= plan->n_mats || !level || !byte_off || !codes || !scale || !zero || !out)
+        return SBITS_ERR_INVALID_ARG;
+    if (ld_out < plan->cols[mat] || (ld_out % 8) || !aligned16(out) || !aligned16(codes) ||
+        (out_bf16 != 0 && out_bf16 != 1))
+        return SBITS_ERR_INVALID_ARG;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_launch_dequant(plan, mat, level, byte_off, codes, scale, zero, out, ld_out, out_bf16);
+}
+
 int sbits_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, int batch, const uint8_t *level,
                   const int64_t *byte_off, const uint8_t *codes, const float *scale, const float *zero, float *y,
                   void *ws)

@@ -482,7 +482,10 @@ void gather_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__
         T *dstl = rows + (size_t)r * C;
         if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
             for (int j = threadIdx.x * V; j < C; j += GA_THREADS * V)
-                *reinterpret_cast<uint4 *>(dstl + j) = gload_u4(src + j);
+            {
+                const u32x4_t v = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4_t *)(src + j));
+                *reinterpret_cast<uint4 *>(dstl + j) = make_uint4(v.x, v.y, v.z, v.w);
+            }
         } else {
             for (int j = threadIdx.x; j < C; j += GA_THREADS) dstl[j] = *(gtp)(src + j);
         }
@@ -502,7 +505,9 @@ void gather_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__
             T tmp[V];
 #pragma unroll
             for (int e = 0; e < V; ++e) tmp[e] = srcl[ci[e]];
-            *reinterpret_cast<uint4 *>(dst + (int64_t)r * C + j) = *reinterpret_cast<const uint4 *>(tmp);
+            // written once, not read again by this kernel: streamed past the caches
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(tmp),
+                                        (__attribute__((address_space(1))) u32x4_t *)(dst + (int64_t)r * C + j));
         }
     }
 }

@@ -108,6 +108,10 @@ int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const
 int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,
                                  const uint8_t *level, const int64_t *byte_off, uint8_t *codes, float *scale,
                                  float *zero, void *ws);
+// dequant.hip
+int sbits_launch_dequant(sbits_plan *plan, int mat, const uint8_t *level, const int64_t *byte_off,
+                         const uint8_t *codes, const float *scale, const float *zero, void *out, int64_t ld_out,
+                         int out_bf16);
 // mpgemm.hip
 bool sbits_mp_gemm_shapes_ok(const sbits_plan *plan);
 size_t sbits_mp_gemm_ws_bytes(const sbits_plan *plan);

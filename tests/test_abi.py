@@ -171,6 +171,19 @@ def test_mp_gemm_validates_on_the_host(ctx, lib):
     q.close()
 
 
+def test_dequant_validates_on_the_host(ctx, lib):
+    ptr = C.c_void_p(4096)
+    p = sb.Plan(ctx, [(256, 256)], 64, 128, [2, 3, 4])
+    call = lambda mat, out, ld, bf: lib.sbits_dequant(p.h, C.c_int(mat), ptr, ptr, ptr, ptr, ptr, out, C.c_int64(ld), C.c_int(bf))
+    assert call(0, None, 256, 0) == sb.ERR_INVALID_ARG
+    assert call(2, ptr, 256, 0) == sb.ERR_INVALID_ARG                    # no such matrix
+    assert call(0, ptr, 248, 0) == sb.ERR_INVALID_ARG                    # pitch below the column count
+    assert call(0, C.c_void_p(4100), 256, 0) == sb.ERR_INVALID_ARG       # out not 16-byte aligned
+    assert call(0, ptr, 256, 2) == sb.ERR_INVALID_ARG                    # 0 = fp32, 1 = bf16
+    assert call(0, ptr, 264, 1) == sb.ERR_HIP                            # valid: needs a device
+    p.close()
+
+
 def test_plan_limits(ctx):
     """At most 32768 rows / columns per matrix and 2^24 blocks per plan."""
     sb.Plan(ctx, [(32768, 32768)], 8, 8, [2]).close()                    # 2^24 blocks: the limit itself

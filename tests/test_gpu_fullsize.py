@@ -452,6 +452,17 @@ def test_mp_gemm_llm_scale_projection(orc, mix):
     plan.pack_all(W.reshape(-1), level, off, codes, scale, zero, ws)
     torch.cuda.synchronize()
     packed_bytes = total + 2 * 4 * N * m
+    # the stored matrix as numbers: every output of the product is checked against a dense fp32 product with it
+    What = torch.empty(R, C, dtype=torch.float32, device=dev)
+    plan.dequant(0, level, off, codes, scale, zero, What)
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for _ in range(5):
+        plan.dequant(0, level, off, codes, scale, zero, What)
+    t1.record()
+    torch.cuda.synchronize()
+    us = t0.elapsed_time(t1) / 5 * 1e3
+    say("  dequantization to fp32: %.0f us (%.2f TB/s written)" % (us, R * C * 4 / us * 1e-6))
     for batch in (16, 32):
         x = torch.randn(batch, C, device=dev).to(torch.bfloat16)
         y = torch.empty(batch, R, dtype=torch.float32, device=dev)
@@ -467,6 +478,8 @@ def test_mp_gemm_llm_scale_projection(orc, mix):
         us = t0.elapsed_time(t1) / reps * 1e3
         say("  batch %d: %.1f us per product, %.2f TB/s of packed weights (%.1f MB)" % (
             batch, us, packed_bytes / us * 1e-6, packed_bytes * 1e-6))
+        dense = x.float() @ What.t()
+        assert (y - dense).abs().max().item() <= 2e-4 * dense.abs().max().item()
         # sampled block rows through the oracle: the oracle dequantizes whole matrices, so hand it the
         # sampled block rows as a matrix of their own (their blocks are consecutive in the global order)
         yh = y.cpu().numpy()

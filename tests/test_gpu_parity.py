@@ -954,3 +954,26 @@ def test_search_then_inference_preserves_the_layer_function(orc, ctx, dev):
         plan.close()
     say("  relative difference to the unquantized layer at 2.5 / 4 / 8 bits:", errs)
     assert errs[0] > errs[1] > errs[2] and errs[2] < 0.02
+
+
+@pytest.mark.parametrize("R,C,m,n,bits", [(16, 24, 8, 8, [1, 2, 3, 4, 5, 6, 7, 8]), (128, 384, 64, 128, [1, 2, 3, 4, 8]),
+                                          (96, 1024, 32, 512, [3, 5, 7]), (2048, 2056 - 8, 1024, 8, [2, 4])])
+def test_dequant(orc, ctx, dev, R, C, m, n, bits):
+    """The stored matrix as fp32 (bit for bit the format's value) and as bf16 (nearest even)."""
+    say("dequant", R, C, m, n, bits)
+    base = 3
+    plan, ws = make_plan(ctx, [(m, 3 * n), (R, C)], m, n, bits, dev)
+    packed = _packed_matrix(orc, R, C, m, n, bits, seed=R + C)
+    level, off, codes, scale, zero = packed
+    args = (torch.from_numpy(level).to(dev), torch.from_numpy(off).to(dev), torch.from_numpy(codes).to(dev),
+            torch.from_numpy(scale).to(dev), torch.from_numpy(zero).to(dev))
+    want = orc.dequant(codes, scale, zero, level, off, base, R, C, m, n, bits)
+    out = torch.full((R, C + 8), -3.0, dtype=torch.float32, device=dev)          # a pitch wider than the matrix
+    plan.dequant(1, *args, out[:, :C])
+    ob = torch.zeros(R, C, dtype=torch.bfloat16, device=dev)
+    plan.dequant(1, *args, ob)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out[:, :C].cpu().numpy().view(np.uint32), want.view(np.uint32))
+    assert torch.all(out[:, C:] == -3.0)
+    np.testing.assert_array_equal(to_np_bf16(ob.cpu()), orc.f32_to_bf16(want))
+    plan.close()
