@@ -319,6 +319,15 @@ typedef struct {
 int  sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits,
                   const sbits_params *params, const sbits_outputs *out,
                   sbits_stats *host_stats, void *ws);
+/* The same with coupled reordering (paper Sec. 4.1, App. "Channel Reordering"): the
+ * permutations come from sbits_reorder_coupled_all with these groups (same arguments,
+ * same errors) instead of sbits_reorder_all; everything after is unchanged.        */
+int  sbits_search_coupled(sbits_plan *plan, const sbits_matrix *mats,
+                          const int32_t *row_group, const int32_t *col_group, int n_groups,
+                          const int32_t *group_segment, const int32_t *row_repeat,
+                          const int32_t *col_repeat, double avg_bits,
+                          const sbits_params *params, const sbits_outputs *out,
+                          sbits_stats *host_stats, void *ws);
 
 /* ---- the stored matrix as numbers (paper Sec. 5.3: uniform bitwidth per tile) ----
  * out[i][j] = fmaf(code, scale, zero) of matrix `mat`, from the packed stream (GLOBAL

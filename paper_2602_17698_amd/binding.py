@@ -25,7 +25,7 @@ EXPORTS = [
     "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
     "sbits_reorder_coupled_all", "sbits_surrogates_all",
-    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search", "sbits_mp_gemm", "sbits_dequant",
+    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search", "sbits_search_coupled", "sbits_mp_gemm", "sbits_dequant",
 ]
 
 
@@ -299,4 +299,18 @@ class Plan:
         rc = load().sbits_search(self.h, arr, C.c_double(avg_bits), C.byref(prm), C.byref(out),
                                  C.byref(st), _ptr(ws))
         _check(rc, "sbits_search", allow=(ERR_MAX_ITERS,))
+        return rc, st.as_dict()
+
+    def search_coupled(self, mats, coupling, avg_bits, out: Outputs, ws, gamma0=0.05, gammaT=0.02, init_mode=0,
+                       max_iters=100000):
+        """coupling = (row_group, col_group, n_groups, group_segment, row_repeat, col_repeat), host
+        sequences as for reorder_coupled_all (the last three may be None)."""
+        rg, cg, ng, seg, rrep, crep = coupling
+        i32 = lambda v: (C.c_int32 * max(len(v), 1))(*v) if v is not None else None
+        arr = (Matrix * len(mats))(*mats)
+        prm = Params(gamma0, gammaT, init_mode, max_iters)
+        st = Stats()
+        rc = load().sbits_search_coupled(self.h, arr, i32(rg), i32(cg), C.c_int(ng), i32(seg), i32(rrep), i32(crep),
+                                         C.c_double(avg_bits), C.byref(prm), C.byref(out), C.byref(st), _ptr(ws))
+        _check(rc, "sbits_search_coupled", allow=(ERR_MAX_ITERS,))
         return rc, st.as_dict()

@@ -443,8 +443,16 @@ int sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *level
     return sbits_launch_pack_all(plan, w_re_bf16, level, byte_off, codes, scale, zero, ws);
 }
 
-int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, const sbits_params *params,
-                 const sbits_outputs *out, sbits_stats *host_stats, void *ws)
+}  // extern "C"
+
+// permutation groups of a coupled search (null row_group: every dimension on its own)
+struct Coupling {
+    const int32_t *row_group, *col_group, *group_segment, *row_repeat, *col_repeat;
+    int n_groups;
+};
+
+static int search_impl(sbits_plan *plan, const sbits_matrix *mats, const Coupling &cpl, double avg_bits,
+                       const sbits_params *params, const sbits_outputs *out, sbits_stats *host_stats, void *ws)
 {
     if (!plan || !mats || !params || !out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
     if (!out->row_perm || !out->col_perm || !out->cost || !out->level ||
@@ -455,8 +463,17 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
     int rc = need_device(plan);
     if (rc) return rc;
     if ((rc = check_all(plan, mats, true, true))) return rc;
+    if (cpl.row_group &&
+        (rc = sbits_coupling_tables(plan, cpl.row_group, cpl.col_group, cpl.n_groups, cpl.group_segment, cpl.row_repeat,
+                                    cpl.col_repeat, nullptr, nullptr, nullptr, nullptr, nullptr)))
+        return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
-    if ((rc = sbits_launch_reorder_all(plan, out->row_perm, out->col_perm, ws))) return rc;
+    if (cpl.row_group)
+        rc = sbits_launch_reorder_coupled_all(plan, cpl.row_group, cpl.col_group, cpl.n_groups, cpl.group_segment,
+                                              cpl.row_repeat, cpl.col_repeat, out->row_perm, out->col_perm, ws);
+    else
+        rc = sbits_launch_reorder_all(plan, out->row_perm, out->col_perm, ws);
+    if (rc) return rc;
     const bool one_pass = sbits_fused_shapes_ok(plan) && sbits_fused_layout_ok(plan, true);
     if (one_pass) {
         if ((rc = sbits_launch_gather_cost_all(plan, out->row_perm, out->col_perm, out->w_re_bf16, out->cost, ws)))
@@ -480,6 +497,25 @@ int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, co
     if (rc) return rc;
     SBITS_HIP(plan->ctx, hipStreamSynchronize(plan->ctx->stream));
     return alloc_rc;
+}
+
+extern "C" {
+
+int sbits_search(sbits_plan *plan, const sbits_matrix *mats, double avg_bits, const sbits_params *params,
+                 const sbits_outputs *out, sbits_stats *host_stats, void *ws)
+{
+    const Coupling none = {nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    return search_impl(plan, mats, none, avg_bits, params, out, host_stats, ws);
+}
+
+int sbits_search_coupled(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_group,
+                         const int32_t *col_group, int n_groups, const int32_t *group_segment,
+                         const int32_t *row_repeat, const int32_t *col_repeat, double avg_bits,
+                         const sbits_params *params, const sbits_outputs *out, sbits_stats *host_stats, void *ws)
+{
+    if (!row_group || !col_group || n_groups < 0) return SBITS_ERR_INVALID_ARG;
+    const Coupling cpl = {row_group, col_group, group_segment, row_repeat, col_repeat, n_groups};
+    return search_impl(plan, mats, cpl, avg_bits, params, out, host_stats, ws);
 }
 
 }  // extern "C"

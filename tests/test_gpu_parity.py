@@ -977,3 +977,70 @@ def test_dequant(orc, ctx, dev, R, C, m, n, bits):
     assert torch.all(out[:, C:] == -3.0)
     np.testing.assert_array_equal(to_np_bf16(ob.cpu()), orc.f32_to_bf16(want))
     plan.close()
+
+
+def test_search_coupled_equals_the_stages(orc, ctx, dev):
+    """The one-call coupled search = coupled reordering, then the stages, each against the oracle."""
+    say("search, coupled")
+    model = dict(hidden=256, ffn=512, kv=128, layers=2)
+    mats, shapes = [], []
+    for layer in range(2):
+        for name, r, c in synth.layer_shapes(model):
+            mats.append(synth.make_matrix("student_t", r, c, seed=9, tid=synth.tensor_id(layer, name)))
+            shapes.append((r, c))
+    coupling = synth.llama_coupling(model, 2, head_dim=64)
+    rg, cg, ng, seg, rrep, crep = coupling
+    m = n = 64
+    bits, avg = [2, 3, 4], 3.0
+    plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
+    N, K = plan.num_blocks(), len(bits)
+    dW = [W.to(dev) for W, _ in mats]
+    dS = [S.to(dev) for _, S in mats]
+    o = dict(row_perm=torch.empty(sum(r for r, _ in shapes), dtype=torch.int32, device=dev),
+             col_perm=torch.empty(sum(c for _, c in shapes), dtype=torch.int32, device=dev),
+             cost=torch.empty(N, K, dtype=torch.float32, device=dev), level=torch.empty(N, dtype=torch.uint8, device=dev),
+             byte_off=torch.empty(N + 1, dtype=torch.int64, device=dev),
+             codes=torch.zeros(plan.codes_bytes_bound(avg), dtype=torch.uint8, device=dev),
+             scale=torch.empty(N * m, dtype=torch.float32, device=dev), zero=torch.empty(N * m, dtype=torch.float32, device=dev))
+    out = sb.Outputs(o["row_perm"].data_ptr(), o["col_perm"].data_ptr(), None, None, o["cost"].data_ptr(),
+                     o["level"].data_ptr(), o["byte_off"].data_ptr(), o["codes"].data_ptr(), o["codes"].numel(),
+                     o["scale"].data_ptr(), o["zero"].data_ptr())
+    assert plan.gather_cost_supported()
+    rc, st = plan.search_coupled([sb.matrix(w, s) for w, s in zip(dW, dS)], coupling, avg, out, ws)
+    torch.cuda.synchronize()
+    # oracle: group scores -> shared permutations -> per-matrix stages -> global allocation -> packing
+    scores = [orc.channel_scores(S.numpy()) for _, S in mats]
+    members = {}
+    for which, groups, reps in ((0, rg, rrep), (1, cg, crep)):
+        for i, g in enumerate(groups):
+            if g >= 0:
+                sc = scores[i][which]
+                members.setdefault(g, []).extend([sc] if reps[i] == 1 else orc.fold_repeated(sc, seg[g], reps[i]))
+    gperm = {g: orc.coupled_perm(ms, seg[g]) for g, ms in members.items()}
+    def perm_of(i, which):
+        g = (rg if which == 0 else cg)[i]
+        rep = (rrep if which == 0 else crep)[i]
+        if g == sb.DIM_FIXED:
+            return np.arange(shapes[i][which], dtype=np.int32)
+        return gperm[g] if rep == 1 else orc.expand_perm(gperm[g], seg[g], rep)
+    costs, Wps, ro, co = [], [], 0, 0
+    for i, ((W, S), (R, C)) in enumerate(zip(mats, shapes)):
+        rp, cp = perm_of(i, 0), perm_of(i, 1)
+        np.testing.assert_array_equal(o["row_perm"][ro:ro + R].cpu().numpy(), rp)
+        np.testing.assert_array_equal(o["col_perm"][co:co + C].cpu().numpy(), cp)
+        Wp, Sp = orc.gather(to_np_bf16(W), S.numpy(), rp, cp)
+        Wps.append(Wp); costs.append(orc.cost_table(Wp, Sp, m, n, bits))
+        ro, co = ro + R, co + C
+    cost = np.concatenate(costs)
+    np.testing.assert_array_equal(o["cost"].cpu().numpy(), cost)
+    rc_o, level, st_o, _ = orc.allocate(cost, bits, avg)
+    assert rc == rc_o and st == st_o
+    np.testing.assert_array_equal(o["level"].cpu().numpy(), level)
+    off = orc.offsets(level, m, n, bits)
+    codes = np.zeros(int(off[-1]), np.uint8); scale = np.zeros(N * m, np.float32); zero = np.zeros(N * m, np.float32)
+    for i, Wp in enumerate(Wps):
+        orc.pack(Wp, m, n, bits, level, off, plan.block_base(i), codes, scale, zero)
+    np.testing.assert_array_equal(o["codes"][:int(off[-1])].cpu().numpy(), codes)
+    np.testing.assert_array_equal(o["scale"].cpu().numpy(), scale)
+    np.testing.assert_array_equal(o["zero"].cpu().numpy().view(np.uint32), zero.view(np.uint32))
+    plan.close()
