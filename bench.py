@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--two-pass", action="store_true",
                     help="separate gather and cost launches instead of the fused one-pass kernel")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cost-power", type=int, default=2, choices=(1, 2),
+                    help="1: the build variant whose block cost is sum s*|d| (libscalebits_l1.so)")
     ap.add_argument("--only-mp-gemm", action="store_true",
                     help="run only the inference-product probe and print its object (for profiling that kernel)")
     ap.add_argument("--no-mp-gemm", action="store_true",
@@ -56,7 +58,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(torch, synth, shapes_sample, m, n, bits, avg, seed):
+def cpu_baseline(torch, synth, shapes_sample, m, n, bits, avg, seed, power=2):
     """The oracle as it stands, single-threaded, on a bounded sample of the same workload."""
     import numpy as np
     import oracle
@@ -72,7 +74,7 @@ def cpu_baseline(torch, synth, shapes_sample, m, n, bits, avg, seed):
         rs, cs = oracle.channel_scores(Sn)
         rp, cp = oracle.argsort_desc(rs), oracle.argsort_desc(cs)
         Wp, Sp = oracle.gather(Wn, Sn, rp, cp)
-        costs.append(oracle.cost_table(Wp, Sp, m, n, bits))
+        costs.append(oracle.cost_table(Wp, Sp, m, n, bits, power=power))
         packed.append(Wp)
     cost = np.concatenate(costs, 0)
     rc, level, st, _ = oracle.allocate(cost, bits, avg)
@@ -159,7 +161,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.cost_power == 1:
+        sb.use_library(sb.variant_path("l1"))
     sb.load()
+    assert sb.cost_power() == args.cost_power
     if args.only_mp_gemm:
         print(json.dumps({"mp_gemm": mp_gemm_probe(torch, sb, synth, dev, copy_probe=args.copy_probe)}))
         return
@@ -285,7 +290,8 @@ def main():
         "config": {"workload": "Llama-3-8B-shaped, %d layers, %d matrices, %d weights (bf16) + fp32 sensitivity, "
                                "%dx%d blocks (%d), bitwidths %s, budget %.2f%s"
                                % (args.layers, nm, nw, m, n, N, bits, args.budget,
-                                  ", coupled reordering" if args.coupled else "")},
+                                  (", coupled reordering" if args.coupled else "")
+                                  + (", cost = sum s*|d|" if args.cost_power == 1 else ""))},
         "full_search_ms": ms_per_step,
         "stage_ms": stage_ms,
         "cost_pass_weights_per_s": nw / (cost_ms * 1e-3),
@@ -326,7 +332,7 @@ def main():
     if not args.no_cpu_baseline:
         # two full decoder layers: 436 M weights, 10-20 s of single-threaded oracle time
         sample = [(l, nm_, r, c) for l in (0, 1) for nm_, r, c in synth.layer_shapes(model)]
-        out["cpu_baseline"] = cpu_baseline(torch, synth, sample, m, n, bits, args.budget, args.seed)
+        out["cpu_baseline"] = cpu_baseline(torch, synth, sample, m, n, bits, args.budget, args.seed, power=args.cost_power)
     print(json.dumps(out))
 
 

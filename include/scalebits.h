@@ -200,6 +200,12 @@ int  sbits_gather_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t 
  * the call writes this matrix's rows only.  One HBM pass over w_re and s_re.    */
 int  sbits_cost_table(sbits_plan *plan, int mat, const void *w_re_bf16, const float *s_re,
                       float *cost);
+/* The power of the change in the cost above is fixed when the library is built: 2 (the
+ * default build, libscalebits.so) or 1 (libscalebits_l1.so, built with
+ * -DSBITS_COST_POWER=1): cost = sum s * |w - what_l|, the element-wise first-order form
+ * of paper Eq. 3 when s is the absolute gradient.  Everything else (grids, summation
+ * order, the search on the table) is the same.  Returns the power of this build.     */
+int  sbits_cost_power(void);
 
 /* The same for every matrix of the plan in ONE launch.  w_re, s_re: the reordered
  * matrices concatenated in plan order, each dense (matrix i starts at element

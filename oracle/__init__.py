@@ -204,15 +204,16 @@ def surrogates(Wp_u16, Gp, m, n, bits, level):
     return up, dn
 
 
-def cost_table(Wp_u16, Sp, m, n, bits):
+def cost_table(Wp_u16, Sp, m, n, bits, power=2):
     Wp_u16 = _u16(Wp_u16)
     Sp = _f32(Sp)
     bits = _i32(bits)
     R, Cc = Wp_u16.shape
     assert R % m == 0 and Cc % n == 0
     cost = np.empty(((R // m) * (Cc // n), bits.size), np.float32)
-    lib().orc_cost_table(_p(Wp_u16), _p(Sp), C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n),
-                         _p(bits), C.c_int(bits.size), _p(cost))
+    assert power in (1, 2)
+    lib().orc_cost_table_pow(_p(Wp_u16), _p(Sp), C.c_int64(R), C.c_int64(Cc), C.c_int(m), C.c_int(n),
+                             _p(bits), C.c_int(bits.size), C.c_int(power), _p(cost))
     return cost
 
 

@@ -197,8 +197,8 @@ void orc_quant_group(const float *w, int n, int bits,
 
 /* --------------------------------------------------------- a5: cost table */
 
-void orc_cost_table(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
-                    int m, int n, const int32_t *bits, int K, float *cost)
+void orc_cost_table_pow(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
+                        int m, int n, const int32_t *bits, int K, int power, float *cost)
 {
     int64_t nbr = R / m, nbc = C / n;
     int nj = n / 8, no = m / 8;
@@ -229,7 +229,7 @@ void orc_cost_table(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
                         float x = bf16_to_f32(wsrc[e]) - g->mn;
                         int q = quant_code(x, g);
                         float d = fmaf(-(float)q, g->scale, x);   /* w - what */
-                        float e2 = d * d;
+                        float e2 = power == 1 ? fabsf(d) : d * d;
                         a = fmaf(ssrc[e], e2, a);
                     }
                     E[rr] = a;
@@ -241,6 +241,12 @@ void orc_cost_table(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
         cost[(I * nbc + J) * K + l] = pair_tree(osum, no);
     }
     free(wrow); free(grid); free(O); free(osum);
+}
+
+void orc_cost_table(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
+                    int m, int n, const int32_t *bits, int K, float *cost)
+{
+    orc_cost_table_pow(Wp, Sp, R, C, m, n, bits, K, 2, cost);
 }
 
 /* Dynamic-sensitivity surrogates of one iteration (App. "choice of sensitivity statistics",

@@ -86,6 +86,11 @@ void orc_quant_group(const float *w, int n, int bits,
  *   block cost     : adjacent-pair tree over o of the octet sums             */
 void orc_cost_table(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
                     int m, int n, const int32_t *bits, int K, float *cost);
+/* The same with the power of the change as an argument: power 2 is the table above, power 1
+ * weighs the absolute change instead, a = fmaf(S', |d|, a): the element-wise first-order
+ * form of paper Eq. 3 when S' is the absolute gradient.                                  */
+void orc_cost_table_pow(const uint16_t *Wp, const float *Sp, int64_t R, int64_t C,
+                        int m, int n, const int32_t *bits, int K, int power, float *cost);
 
 /* dynamic-sensitivity surrogates s_up, s_down per block at the blocks' current bitwidths
  * (App. "choice of sensitivity statistics") */

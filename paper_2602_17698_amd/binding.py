@@ -22,7 +22,7 @@ EXPORTS = [
     "sbits_plan_create", "sbits_plan_destroy", "sbits_num_blocks", "sbits_block_base",
     "sbits_workspace_bytes", "sbits_codes_bytes_bound",
     "sbits_reorder", "sbits_reorder_all", "sbits_channel_scores", "sbits_gather", "sbits_gather_all",
-    "sbits_cost_table", "sbits_cost_table_all", "sbits_pack_all",
+    "sbits_cost_table", "sbits_cost_table_all", "sbits_cost_power", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
     "sbits_reorder_coupled_all", "sbits_surrogates_all",
     "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search", "sbits_search_coupled", "sbits_mp_gemm", "sbits_dequant",
@@ -80,24 +80,47 @@ class SbitsError(RuntimeError):
 
 
 _lib = None
+_loaded = {}                    # path -> CDLL (a library is opened once per process)
 
 
 def load():
     """Loads libscalebits.so; raises if it has not been built."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise FileNotFoundError(
-                "%s is missing: build it with `python -m paper_2602_17698_amd.build`" % LIB_PATH)
-        lib = C.CDLL(LIB_PATH)
-        lib.sbits_strerror.restype = C.c_char_p
-        lib.sbits_num_blocks.restype = C.c_int64
-        lib.sbits_block_base.restype = C.c_int64
-        lib.sbits_workspace_bytes.restype = C.c_size_t
-        lib.sbits_codes_bytes_bound.restype = C.c_int64
-        lib.sbits_codes_bytes_bound.argtypes = [C.c_void_p, C.c_double]
-        _lib = lib
+        if LIB_PATH not in _loaded:
+            if not os.path.exists(LIB_PATH):
+                raise FileNotFoundError(
+                    "%s is missing: build it with `python -m paper_2602_17698_amd.build`" % LIB_PATH)
+            lib = C.CDLL(LIB_PATH)
+            lib.sbits_strerror.restype = C.c_char_p
+            lib.sbits_num_blocks.restype = C.c_int64
+            lib.sbits_block_base.restype = C.c_int64
+            lib.sbits_workspace_bytes.restype = C.c_size_t
+            lib.sbits_codes_bytes_bound.restype = C.c_int64
+            lib.sbits_codes_bytes_bound.argtypes = [C.c_void_p, C.c_double]
+            _loaded[LIB_PATH] = lib
+        _lib = _loaded[LIB_PATH]
     return _lib
+
+
+def variant_path(variant: str = "") -> str:
+    """In-tree path of a build variant: "" = sum s*d^2 (default), "l1" = sum s*|d|."""
+    return os.path.join(_HERE, "libscalebits%s.so" % ("_" + variant if variant else ""))
+
+
+def use_library(path: str) -> None:
+    """Routes all later calls to another build of the library (see variant_path).  Contexts and
+    plans belong to the library that created them: close them before switching, or switch back
+    before using them again."""
+    global _lib, LIB_PATH
+    LIB_PATH = path
+    _lib = None
+    load()
+
+
+def cost_power() -> int:
+    """Power of the quantization change in the block cost of the loaded build (2 or 1)."""
+    return int(load().sbits_cost_power())
 
 
 def strerror(status: int) -> str:

@@ -468,3 +468,6 @@ int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re,
     a.cost = cost;
     return launch(plan->n, plan->K, ctx, a);
 }
+
+// which cost this build computes (the arithmetic core fixes it at compile time)
+extern "C" int sbits_cost_power(void) { return SBITS_COST_POWER; }

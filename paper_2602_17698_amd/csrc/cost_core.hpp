@@ -10,6 +10,14 @@ namespace sbits {
 
 constexpr int COST_MAX_ROUND = 4;                     // rows that may share one round of divisions
 
+// Power of the quantization change in the block cost, fixed when the library is built:
+//   2 (default): cost = sum s * d^2   (the sensitivity weighs the squared change)
+//   1          : cost = sum s * |d|   (element-wise first-order form of paper Eq. 3 with s = |gradient|)
+#ifndef SBITS_COST_POWER
+#define SBITS_COST_POWER 2
+#endif
+static_assert(SBITS_COST_POWER == 1 || SBITS_COST_POWER == 2, "cost power is 1 or 2");
+
 // value held by lane j*SP + SLOT of the caller's lane group, j in [0, LPG/SP)
 template <int LPG, int SP, int SLOT>
 __device__ __forceinline__ float bcast_row(float v, int j)
@@ -57,7 +65,7 @@ struct DivPlan {
 // One round: NI rows (NI <= DivPlan::RP), each owned by the caller's lane group, the lane holding
 // 8 consecutive elements of every row: raw bf16 weights w[j] and sensitivities s[j][0..7].
 // out[j][c] = the lane's partial cost of row j at candidate c (elements left to right,
-// a = fma(s, d*d, a)).
+// a = fma(s, d*d, a); with SBITS_COST_POWER == 1: a = fma(s, |d|, a)).
 template <int LPG, int K, int NI>
 __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const float (&s)[NI][8],
                                                  const DivPlan<LPG, K> &dp, float (&out)[NI][K])
@@ -113,7 +121,7 @@ __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const 
             for (int e = 0; e < 8; ++e) {
                 const float q = rintf(x[j][e] * inv);
                 const float d = fmaf(-q, scl, x[j][e]);
-                acc = fmaf(s[j][e], d * d, acc);
+                acc = fmaf(s[j][e], SBITS_COST_POWER == 1 ? fabsf(d) : d * d, acc);
             }
             out[j][c] = acc;
         });

@@ -33,6 +33,18 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_build_variants_export_the_same_symbols_and_name_their_cost(lib):
+    from paper_2602_17698_amd import build
+    assert sb.cost_power() == 2
+    path = sb.variant_path("l1")
+    if not os.path.exists(path):
+        build.build(variant="l1")
+    l1 = C.CDLL(path)
+    for name in declared_symbols():
+        assert hasattr(l1, name), name
+    assert l1.sbits_cost_power() == 1
+
+
 def test_strerror_covers_all_codes(lib):
     for code in range(0, -10, -1):
         assert sb.strerror(code) != "unknown status"

@@ -621,7 +621,7 @@ def test_offsets_many_tiles(orc, ctx, dev):
 
 # --------------------------------------------------------------------------- end to end
 
-def oracle_search(orc, mats, m, n, bits, avg, **kw):
+def oracle_search(orc, mats, m, n, bits, avg, power=2, **kw):
     """The whole path on the CPU oracle: returns every output the library produces."""
     perms, W2, S2, costs = [], [], [], []
     for W, S in mats:
@@ -630,7 +630,7 @@ def oracle_search(orc, mats, m, n, bits, avg, **kw):
         rp, cp = orc.argsort_desc(rs), orc.argsort_desc(cs)
         Wp, Sp = orc.gather(Wn, Sn, rp, cp)
         perms.append((rp, cp)); W2.append(Wp); S2.append(Sp)
-        costs.append(orc.cost_table(Wp, Sp, m, n, bits))
+        costs.append(orc.cost_table(Wp, Sp, m, n, bits, power=power))
     cost = np.concatenate(costs, 0)
     rc, level, st, _ = orc.allocate(cost, bits, avg, **kw)
     off = orc.offsets(level, m, n, bits)
@@ -1044,3 +1044,66 @@ def test_search_coupled_equals_the_stages(orc, ctx, dev):
     np.testing.assert_array_equal(o["scale"].cpu().numpy(), scale)
     np.testing.assert_array_equal(o["zero"].cpu().numpy().view(np.uint32), zero.view(np.uint32))
     plan.close()
+
+
+# ------------------------------------------ build variant: cost = sum s * |d| (first-order form of Eq. 3)
+
+@pytest.fixture()
+def ctx_l1(dev):
+    """A context of libscalebits_l1.so; the default library is back in place afterwards."""
+    import os
+    prev = sb.LIB_PATH
+    path = sb.variant_path("l1")
+    assert os.path.exists(path), "build the variant first: python -m paper_2602_17698_amd.build"
+    sb.use_library(path)
+    try:
+        assert sb.cost_power() == 1
+        c = sb.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+        yield c
+        c.close()
+    finally:
+        sb.use_library(prev)
+        assert sb.cost_power() == 2
+
+
+def test_power_one_variant_cost_tables(orc, ctx_l1, dev):
+    say("l1 variant: cost tables, both routes")
+    shapes, m, n, bits = [(256, 384), (128, 1024), (64, 14336)], 64, 128, [1, 2, 3, 4, 8]
+    plan, ws = make_plan(ctx_l1, shapes, m, n, bits, dev)
+    N, K = plan.num_blocks(), len(bits)
+    mats = [synth.make_matrix("student_t", r, c, seed=21, tid=i) for i, (r, c) in enumerate(shapes)]
+    g = torch.Generator().manual_seed(23)
+    rps = [torch.randperm(r, generator=g).to(torch.int32) for r, _ in shapes]
+    cps = [torch.randperm(c, generator=g).to(torch.int32) for _, c in shapes]
+    dW = [W.to(dev) for W, _ in mats]
+    dS = [S.to(dev) for _, S in mats]
+    dm = [sb.matrix(w, s_) for w, s_ in zip(dW, dS)]
+    nel = sum(r * c for r, c in shapes)
+    w_re = torch.zeros(nel, dtype=torch.bfloat16, device=dev)
+    s_re = torch.zeros(nel, dtype=torch.float32, device=dev)
+    cost1 = torch.full((N, K), -1.0, dtype=torch.float32, device=dev)
+    cost2 = torch.full((N, K), -1.0, dtype=torch.float32, device=dev)
+    rp, cp = torch.cat(rps).to(dev), torch.cat(cps).to(dev)
+    plan.gather_cost_all(dm, rp, cp, None, cost1, ws)
+    plan.gather_all(dm, rp, cp, w_re, s_re, ws)
+    plan.cost_table_all(w_re, s_re, cost2, ws)
+    torch.cuda.synchronize()
+    refs = []
+    for (W, S), r_, c_ in zip(mats, rps, cps):
+        Wp, Sp = orc.gather(to_np_bf16(W), S.numpy(), r_.numpy(), c_.numpy())
+        refs.append(orc.cost_table(Wp, Sp, m, n, bits, power=1))
+    ref = np.concatenate(refs, 0)
+    np.testing.assert_array_equal(cost1.cpu().numpy(), ref)
+    np.testing.assert_array_equal(cost2.cpu().numpy(), ref)
+    plan.close()
+
+
+def test_power_one_variant_search(orc, ctx_l1, dev):
+    say("l1 variant: whole search")
+    shapes = [(512, 512), (256, 1024), (1024, 256)]
+    mats = [synth.make_matrix("student_t", r, c, seed=4, tid=i) for i, (r, c) in enumerate(shapes)]
+    ref = oracle_search(orc, mats, 64, 128, [1, 2, 3, 4, 8], 2.5, power=1)
+    rc, st, o, shp = gpu_search(ctx_l1, dev, mats, 64, 128, [1, 2, 3, 4, 8], 2.5)
+    compare_search(orc, ref, rc, st, o, shp, 64)
+    ref2 = oracle_search(orc, mats, 64, 128, [1, 2, 3, 4, 8], 2.5)
+    assert not np.array_equal(ref["level"], ref2["level"])          # the two costs do allocate differently

@@ -120,6 +120,26 @@ def test_error_is_squared_and_weighted(orc):
     assert cost[0, 0] == 23.0
 
 
+def test_power_one_weighs_the_absolute_change(orc):
+    # the same block as above under the first-order form (Eq. 3, element-wise): 5*1 + 2*3
+    W = np.zeros((8, 8), np.float32)
+    W[:, 7] = 4.0
+    W[:, 1] = 1.0
+    W[5, 7], W[5, 1] = 8.0, 3.0
+    S = np.zeros((8, 8), np.float32)
+    S[2, 1] = 5.0
+    S[5, 1] = 2.0
+    S[5, 7] = 100.0
+    assert orc.cost_table(_bf16_mat(orc, W), S, 8, 8, [1], power=1)[0, 0] == 11.0
+    # a change of 1/2: squared 1/4, absolute 1/2.  Row [0, 0.5, 0, 0, 0, 0, 0, 1] at 1 bit: 0.5 is a tie -> 0
+    W = np.zeros((8, 8), np.float32)
+    W[:, 7] = 1.0
+    W[3, 1] = 0.5
+    S = np.full((8, 8), 8.0, np.float32)
+    assert orc.cost_table(_bf16_mat(orc, W), S, 8, 8, [1], power=2)[0, 0] == 2.0
+    assert orc.cost_table(_bf16_mat(orc, W), S, 8, 8, [1], power=1)[0, 0] == 4.0
+
+
 def test_block_order_and_group_is_one_block_row(orc):
     # 16 x 24 matrix, blocks 8 x 8 -> 2 x 3 blocks, index I*3 + J.
     # Only block (1, 2) holds off-grid data; the groups are block rows of 8 columns,
@@ -175,7 +195,7 @@ def test_canonical_order_chunk_is_sequential_and_octets_pair_up(orc):
     assert cost[0, 0] == 2.0 ** 24 + 2.0
 
 
-def _cost_float64(Wf, S, m, n, bits):
+def _cost_float64(Wf, S, m, n, bits, power=2):
     """The definition written out in float64 with the textbook quantizer; the grid step is
     rounded to float32 because the stored scale, which dequantization uses, is float32."""
     R, C = Wf.shape
@@ -191,7 +211,7 @@ def _cost_float64(Wf, S, m, n, bits):
                 step = (rg.astype(np.float32) / np.float32(2 ** b - 1)).astype(np.float64)
                 step = np.where(rg > 0, step, 1.0)
                 what = np.rint((w - mn) / step) * step + mn
-                out[I * (C // n) + J, l] = (s * (w - what) ** 2).sum()
+                out[I * (C // n) + J, l] = (s * np.abs(w - what) ** power).sum()
     return out
 
 
@@ -205,6 +225,19 @@ def test_cost_table_close_to_float64_definition(orc, m, n, bits):
     ref = _cost_float64(orc.bf16_to_f32(Wb), S, m, n, bits)
     assert np.all(cost >= 0)
     np.testing.assert_allclose(cost, ref, rtol=1e-5)
+
+
+@pytest.mark.parametrize("m,n,bits", [(16, 16, [1, 2, 3, 4, 8]), (64, 128, [1, 2, 3, 4, 5, 6, 7, 8])])
+def test_power_one_table_close_to_float64_definition(orc, m, n, bits):
+    rng = np.random.default_rng(m + n + 1)
+    R, C = 2 * m, 3 * n
+    Wb = orc.f32_to_bf16(0.02 * rng.standard_t(4, size=(R, C)))
+    S = np.exp(rng.normal(size=(R, 1)) + rng.normal(size=(1, C)) + 0.5 * rng.normal(size=(R, C))).astype(np.float32)
+    cost = orc.cost_table(Wb, S, m, n, bits, power=1)
+    ref = _cost_float64(orc.bf16_to_f32(Wb), S, m, n, bits, power=1)
+    np.testing.assert_allclose(cost, ref, rtol=1e-5)
+    # and it is not the squared table
+    assert not np.allclose(cost, orc.cost_table(Wb, S, m, n, bits), rtol=1e-2)
 
 
 def test_nested_grids_give_non_increasing_block_cost(orc):
