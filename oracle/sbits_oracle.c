@@ -156,6 +156,13 @@ typedef struct {
 static grid_t group_grid(const float *w, int n, int bits)
 {
     grid_t g;
+    if (bits == 0) {                 /* Sec. 3: a component at 0 bits is pruned, what = 0 for all of it: */
+        g.mn = 0.0f;                 /* origin 0, step 0, the only code 0; nothing of the group is kept  */
+        g.inv = 0.0f;
+        g.scale = 0.0f;
+        g.qmax = 0;
+        return g;
+    }
     float mn = w[0], mx = w[0];
     for (int e = 1; e < n; ++e) {
         if (w[e] < mn) mn = w[e];

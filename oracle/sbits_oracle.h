@@ -72,6 +72,8 @@ void orc_gather_f32(const float *S, int64_t R, int64_t C, int64_t ld,
  *     mn = min, mx = max, Rg = mx - mn, qmax = 2^bits - 1
  *     inv = qmax / Rg, scale = Rg / qmax        (both 0 if inv is not finite)
  *     x = w - mn; q = clamp(rint(x * inv), 0, qmax); what = fma(q, scale, mn)
+ * bits = 0 (Sec. 3: the component is pruned): what = 0 for the whole group, stored as
+ * q = 0, scale = 0, zero = 0; its change is the weight itself, d = w.
  * q_out (n ints) may be NULL.                                                */
 void orc_quant_group(const float *w, int n, int bits,
                      int32_t *q_out, float *scale, float *zero);
