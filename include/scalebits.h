@@ -31,8 +31,13 @@
  *     cols % n == 0; rows, cols <= 32768 per matrix; at most 2^24 blocks in all.
  *   - Blocks are numbered globally: matrix after matrix in plan order, inside a
  *     matrix row-major over the block grid: id = base(mat) + I*(cols/n) + J.
- *   - Candidate bitwidths are strictly increasing integers in 1..8, at most 8
- *     of them.  A "level" is an index into that list.
+ *   - Candidate bitwidths are strictly increasing integers in 0..8 (so at most
+ *     9 of them, at least one above 0).  A "level" is an index into that list.
+ *     0 bits means the block is pruned (paper Sec. 3: b_i = 0 removes the
+ *     component): its stored value is 0 everywhere, so its cost is the sum of
+ *     s * w^2 over the block, it occupies no bytes of the code stream, its scale
+ *     and zero entries are written as 0, sbits_dequant returns zeros for it and
+ *     sbits_mp_gemm skips it; its surrogates are s_up = sum g*w and s_down = 0.
  *   - Permutations are in gather form: reordered[i] = original[perm[i]].
  *   - Return value: 0 (SBITS_OK) or a negative sbits_status; nothing throws or
  *     aborts; outputs are undefined after an error.

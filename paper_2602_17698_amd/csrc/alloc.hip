@@ -63,7 +63,7 @@ struct AllocState {
     int iters, max_iters, expansions, swaps_ok, swaps_rej;
     int done, status, mode;
     unsigned int maxc_bits;
-    int bits[8];
+    int bits[MAX_CAND];
     long long prop_up, prop_dn, prop_after;   // the single step on caller-supplied estimates: its result
     SelJob job[N_JOBS];
 };
@@ -126,9 +126,9 @@ void gains_kernel(AllocState *st, const float *__restrict__ cost, const uint8_t 
 {
     const long long N = st->N;
     const int K = st->K, IB = st->IB;
-    int bits[8];
+    int bits[MAX_CAND];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) bits[c] = st->bits[c];
+    for (int c = 0; c < MAX_CAND; ++c) bits[c] = st->bits[c];
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
          i += (long long)gridDim.x * blockDim.x) {
         const int l = level[i];
@@ -431,9 +431,9 @@ void step_keys_kernel(AllocState *st, const float *__restrict__ s_up, const floa
     __shared__ long long su[AL_THREADS / 64];
     const long long N = st->N;
     const int K = st->K, IB = st->IB;
-    int bits[8];
+    int bits[MAX_CAND];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) bits[c] = st->bits[c];
+    for (int c = 0; c < MAX_CAND; ++c) bits[c] = st->bits[c];
     long long used = 0;
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < N;
          i += (long long)gridDim.x * blockDim.x) {
@@ -598,7 +598,7 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     h.IB = ceil_log2_ll(N) > 0 ? ceil_log2_ll(N) : 1;
     h.P = (32 + h.IB + SEL_DB - 1) / SEL_DB;
     h.max_iters = prm->max_iters;
-    for (int c = 0; c < 8; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
+    for (int c = 0; c < MAX_CAND; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
 
     const bool all_max = avg_bits >= (double)plan->bits[K - 1];
     int l0 = 0;
@@ -709,7 +709,7 @@ int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, 
     h.K = K;
     h.IB = ceil_log2_ll(N) > 0 ? ceil_log2_ll(N) : 1;
     h.P = (32 + h.IB + SEL_DB - 1) / SEL_DB;
-    for (int c = 0; c < 8; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
+    for (int c = 0; c < MAX_CAND; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
     SBITS_HIP(ctx, hipMemcpyAsync(st, &h, sizeof h, hipMemcpyHostToDevice, sm));
     SBITS_HIP(ctx, hipStreamSynchronize(sm));      // the image goes away on return
 

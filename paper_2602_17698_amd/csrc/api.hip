@@ -61,11 +61,12 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
                       sbits_plan **out)
 {
     if (!ctx || !rows || !cols || n_mats <= 0 || !out || !bitwidths) return SBITS_ERR_INVALID_ARG;
-    if (n_bits <= 0 || n_bits > 8) return SBITS_ERR_BAD_BITWIDTHS;
+    if (n_bits <= 0 || n_bits > sbits::MAX_CAND) return SBITS_ERR_BAD_BITWIDTHS;
     for (int l = 0; l < n_bits; ++l) {
-        if (bitwidths[l] < 1 || bitwidths[l] > 8) return SBITS_ERR_BAD_BITWIDTHS;
+        if (bitwidths[l] < 0 || bitwidths[l] > 8) return SBITS_ERR_BAD_BITWIDTHS;
         if (l && bitwidths[l] <= bitwidths[l - 1]) return SBITS_ERR_BAD_BITWIDTHS;
     }
+    if (bitwidths[n_bits - 1] == 0) return SBITS_ERR_BAD_BITWIDTHS;      // "0 bits" alone is no search space
     if (!is_pow2(block_rows) || !is_pow2(block_cols) || block_rows < 8 || block_rows > 1024 ||
         block_cols < 8 || block_cols > 512)
         return SBITS_ERR_BAD_SHAPE;
@@ -76,7 +77,7 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
     p->m = block_rows;
     p->n = block_cols;
     p->K = n_bits;
-    for (int l = 0; l < 8; ++l) p->bits[l] = l < n_bits ? bitwidths[l] : 0;
+    for (int l = 0; l < sbits::MAX_CAND; ++l) p->bits[l] = l < n_bits ? bitwidths[l] : 0;
     p->N = 0;
     p->max_rows = p->max_cols = 0;
     p->sum_rows = p->sum_cols = p->sum_elems = 0;

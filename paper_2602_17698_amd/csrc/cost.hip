@@ -23,6 +23,7 @@
 // in flight while it computes on the current one, so HBM latency is hidden by
 // the kernel's own arithmetic rather than by occupancy (the kernel needs ~190
 // VGPRs, i.e. two waves per SIMD).
+#include <math.h>
 #include <string.h>
 
 #include <type_traits>
@@ -101,12 +102,12 @@ __device__ __forceinline__ void swizzle_s(float4 *xrow, int lane, float4 &a, flo
 
 // HALF rows of one octet: rows R_BASE .. R_BASE + HALF - 1 (R_BASE is 0 or 4).  Updates the
 // pending levels of the row tree (t1, t2, t3) and leaves the running result in cur.
-template <int LPG, int K, int R_BASE, bool SWIZZLE>
-__device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG, K> &dp,
+template <int LPG, int K, int R_BASE, bool SWIZZLE, bool Z0>
+__device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG, K - Z0> &dp,
                                              float (&t1)[K], float (&t2)[K], float (&t3)[K], float (&cur)[K],
                                              float4 *xw, int lane)
 {
-    using DP = DivPlan<LPG, K>;
+    using DP = DivPlan<LPG, K - Z0>;
     constexpr int RP = DP::RP < HALF ? DP::RP : HALF;
 #pragma unroll
     for (int r0 = 0; r0 < HALF; r0 += RP) {
@@ -120,7 +121,7 @@ __device__ __forceinline__ void compute_half(const HalfBuf &h, const DivPlan<LPG
             s[j][0] = a.x; s[j][1] = a.y; s[j][2] = a.z; s[j][3] = a.w;
             s[j][4] = b.x; s[j][5] = b.y; s[j][6] = b.z; s[j][7] = b.w;
         }
-        quant_cost_round<LPG, K, RP>(wr, s, dp, out);
+        quant_cost_round<LPG, K, RP, Z0>(wr, s, dp, out);
 #pragma unroll
         for (int j = 0; j < RP; ++j) {
             const int rr = R_BASE + r0 + j;
@@ -153,12 +154,15 @@ struct CostGeom {
     static int blocks_per_unit(int m) { const int opb = m / 8; return opb >= OS ? BX : BX * (OS / opb); }
 };
 
-template <int LPG, int K, bool STRIDED>
+// K candidates; with Z0 the first one is "0 bits" (pruned block) and gc holds the other K - 1 grids
+template <int LPG, int K, bool STRIDED, bool Z0>
 __global__ __launch_bounds__(COST_THREADS, 2)
 void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ unit_start,
                  int n_mats, int total_units, const uint16_t *__restrict__ W, const float *__restrict__ S,
-                 int m, float *__restrict__ cost, GridConsts gc)
+                 int m, float *__restrict__ cost, GridConsts gc, int kstride, int koff)
 {
+    // kstride, koff: the K sums of a block go to cost[block][koff .. koff + K) of kstride values (a launch
+    // may cover a subset of the candidates)
     using G = CostGeom<LPG>;
     constexpr int BX = G::BX, OS = G::OS;
     constexpr bool SWZ = G::OW == 1;                 // a wave walks ONE octet: 512 contiguous columns per row
@@ -177,7 +181,7 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
     const int lane = tid & 63;
     float4 *const xw = xbuf + (SWZ ? (tid >> 6) * (HALF * 128) : 0);
 
-    DivPlan<LPG, K> dp;
+    DivPlan<LPG, K - Z0> dp;
     dp.init(gc, lig);
 
     int u_begin, u_end, u_step;
@@ -209,7 +213,7 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
             d_cols = uni((int)d.cols);
             d_nbc = uni(d.nbc);
             d_elem = uni64(d.elem_off);
-            d_cbase = uni64(d.block_base * K);
+            d_cbase = uni64(d.block_base * kstride + koff);
             upr = (d_nbc + bpu - 1) / bpu;
         }
         const int ul = unit - mat_begin;
@@ -273,14 +277,14 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
         load_half<SWZ>(B, now.Wb, now.Sb, now.voff + HALF * now.wstride, now.wstride,
                        now.soA + 2u * HALF * now.wstride, now.soB + 2u * HALF * now.wstride);
         float t1[K], t2[K], t3[K], cur[K];
-        compute_half<LPG, K, 0, SWZ>(A, dp, t1, t2, t3, cur, xw, lane);
+        compute_half<LPG, K, 0, SWZ, Z0>(A, dp, t1, t2, t3, cur, xw, lane);
 
         // the next step's first half goes in flight before this step's second half is computed
         // (after the last step this re-reads the last step: harmless, keeps the loop branch-free)
         advance();
         nxt = address();
         load_half<SWZ>(A, nxt.Wb, nxt.Sb, nxt.voff, nxt.wstride, nxt.soA, nxt.soB);
-        compute_half<LPG, K, HALF, SWZ>(B, dp, t1, t2, t3, cur, xw, lane);
+        compute_half<LPG, K, HALF, SWZ, Z0>(B, dp, t1, t2, t3, cur, xw, lane);
 
         const int oct = bl * opb + o0 + pc * OS;
 #pragma unroll
@@ -304,7 +308,7 @@ void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__re
             for (int q = tid; q < bpu * K; q += COST_THREADS) {
                 const int b2 = q / K, c = q - b2 * K;
                 const int J = now.J0 + b2;
-                if (J < now.nbc) now.cbase[((int64_t)now.I * now.nbc + J) * K + c] = osum[(b2 * opb) * K + c];
+                if (J < now.nbc) now.cbase[((int64_t)now.I * now.nbc + J) * kstride + c] = osum[(b2 * opb) * K + c];
             }
             __syncthreads();
         }
@@ -347,48 +351,84 @@ struct CostLaunch {
     int m;
     float *cost;
     GridConsts gc;
+    int kstride, koff;      // row length of the table and first column this launch writes
 };
 
-template <int LPG, int K>
+template <int LPG, int K, bool Z0>
 static int launch_lk(sbits_ctx *ctx, const CostLaunch &a)
 {
     if (a.total_units > 0x7fffffff) return SBITS_ERR_BAD_SHAPE;
     const int grid = persistent_grid(ctx, a.total_units);
     if (grid == 0) return SBITS_OK;
-    hipLaunchKernelGGL((cost_kernel<LPG, K, SBITS_COST_STRIDED>), dim3((unsigned)grid), dim3(COST_THREADS), 0, ctx->stream,
-                       a.descs, a.one, a.unit_start, a.n_mats, (int)a.total_units, a.W, a.S, a.m, a.cost, a.gc);
+    hipLaunchKernelGGL((cost_kernel<LPG, K, SBITS_COST_STRIDED, Z0>), dim3((unsigned)grid), dim3(COST_THREADS), 0, ctx->stream,
+                       a.descs, a.one, a.unit_start, a.n_mats, (int)a.total_units, a.W, a.S, a.m, a.cost, a.gc,
+                       a.kstride, a.koff);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
 
+// K: all candidates; z0: the first of them is 0 bits (then 2 <= K <= 9, else 1 <= K <= 8)
 template <int LPG>
-static int launch_l(int K, sbits_ctx *ctx, const CostLaunch &a)
+static int launch_l(int K, bool z0, sbits_ctx *ctx, const CostLaunch &a)
 {
-    switch (K) {
-    case 1: return launch_lk<LPG, 1>(ctx, a);
-    case 2: return launch_lk<LPG, 2>(ctx, a);
-    case 3: return launch_lk<LPG, 3>(ctx, a);
-    case 4: return launch_lk<LPG, 4>(ctx, a);
-    case 5: return launch_lk<LPG, 5>(ctx, a);
-    case 6: return launch_lk<LPG, 6>(ctx, a);
-    case 7: return launch_lk<LPG, 7>(ctx, a);
-    case 8: return launch_lk<LPG, 8>(ctx, a);
+    if (z0) switch (K) {
+    case 2: return launch_lk<LPG, 2, true>(ctx, a);
+    case 3: return launch_lk<LPG, 3, true>(ctx, a);
+    case 4: return launch_lk<LPG, 4, true>(ctx, a);
+    case 5: return launch_lk<LPG, 5, true>(ctx, a);
+    case 6: return launch_lk<LPG, 6, true>(ctx, a);
+    case 7: return launch_lk<LPG, 7, true>(ctx, a);
+    case 8: return launch_lk<LPG, 8, true>(ctx, a);
+    case 9:
+        if constexpr (LPG != 8) return launch_lk<LPG, 9, true>(ctx, a);   // (64-column blocks: split by the caller)
+        break;
+    }
+    else switch (K) {
+    case 1: return launch_lk<LPG, 1, false>(ctx, a);
+    case 2: return launch_lk<LPG, 2, false>(ctx, a);
+    case 3: return launch_lk<LPG, 3, false>(ctx, a);
+    case 4: return launch_lk<LPG, 4, false>(ctx, a);
+    case 5: return launch_lk<LPG, 5, false>(ctx, a);
+    case 6: return launch_lk<LPG, 6, false>(ctx, a);
+    case 7: return launch_lk<LPG, 7, false>(ctx, a);
+    case 8: return launch_lk<LPG, 8, false>(ctx, a);
     }
     return SBITS_ERR_BAD_BITWIDTHS;
 }
 
-static int launch(int n, int K, sbits_ctx *ctx, const CostLaunch &a)
+static int launch_n(int n, int K, bool z0, sbits_ctx *ctx, const CostLaunch &a)
 {
     switch (n / 8) {
-    case 1:  return launch_l<1>(K, ctx, a);
-    case 2:  return launch_l<2>(K, ctx, a);
-    case 4:  return launch_l<4>(K, ctx, a);
-    case 8:  return launch_l<8>(K, ctx, a);
-    case 16: return launch_l<16>(K, ctx, a);
-    case 32: return launch_l<32>(K, ctx, a);
-    case 64: return launch_l<64>(K, ctx, a);
+    case 1:  return launch_l<1>(K, z0, ctx, a);
+    case 2:  return launch_l<2>(K, z0, ctx, a);
+    case 4:  return launch_l<4>(K, z0, ctx, a);
+    case 8:  return launch_l<8>(K, z0, ctx, a);
+    case 16: return launch_l<16>(K, z0, ctx, a);
+    case 32: return launch_l<32>(K, z0, ctx, a);
+    case 64: return launch_l<64>(K, z0, ctx, a);
     }
     return SBITS_ERR_BAD_SHAPE;
+}
+
+// All K candidates bits[0 .. K) of the table.  Nine candidates (0 .. 8 bits) on 64-column blocks would
+// need more LDS for the octet sums than a workgroup may declare: they take two launches over the
+// candidates, 0 .. 4 and 5 .. 8 (the grids are independent per candidate: the same table, bit for bit).
+static int launch(int n, const int32_t *bits, int K, sbits_ctx *ctx, CostLaunch a)
+{
+    const bool z0 = bits[0] == 0;
+    a.kstride = K;
+    if (K == 9 && n == 64) {
+        sbits_fill_grid_consts(bits + 1, 4, &a.gc);
+        a.koff = 0;
+        const int rc = launch_n(n, 5, true, ctx, a);
+        if (rc) return rc;
+        sbits_fill_grid_consts(bits + 5, 4, &a.gc);
+        a.koff = 5;
+        return launch_n(n, 4, false, ctx, a);
+    }
+    sbits_fill_grid_consts(bits + z0, K - z0, &a.gc);     // the kernels take the real grids only
+    a.koff = 0;
+    return launch_n(n, K, z0, ctx, a);
 }
 
 static int blocks_per_unit(int m, int n)
@@ -407,13 +447,15 @@ static int blocks_per_unit(int m, int n)
 
 }  // namespace sbits
 
+// Grid constants of the K candidates bits[0 .. K) (entries beyond K repeat the last one).  A 0-bit
+// candidate gets qmax 0 and an infinite threshold (see GridConsts).
 void sbits_fill_grid_consts(const int32_t *bits, int K, sbits::GridConsts *gc)
 {
-    for (int c = 0; c < 8; ++c) {
+    for (int c = 0; c < sbits::MAX_CAND; ++c) {
         const int b = c < K ? bits[c] : bits[K - 1];
         gc->bits[c] = b;
         gc->qmaxf[c] = (float)((1 << b) - 1);
-        gc->thr[c] = sbits::finite_threshold(gc->qmaxf[c]);
+        gc->thr[c] = b == 0 ? HUGE_VALF : sbits::finite_threshold(gc->qmaxf[c]);
     }
 }
 
@@ -424,7 +466,6 @@ int sbits_launch_cost(sbits_ctx *ctx, const void *Wp, const float *Sp, int64_t R
     using namespace sbits;
     CostLaunch a;
     memset(&a, 0, sizeof a);
-    sbits_fill_grid_consts(bits, K, &a.gc);
     a.one.rows = R; a.one.cols = C; a.one.nbr = (int)(R / m); a.one.nbc = (int)(C / n);
     const int bpu = blocks_per_unit(m, n);
     a.n_mats = 1;
@@ -433,7 +474,7 @@ int sbits_launch_cost(sbits_ctx *ctx, const void *Wp, const float *Sp, int64_t R
     a.S = Sp;
     a.m = m;
     a.cost = cost_rows;
-    return launch(n, K, ctx, a);
+    return launch(n, bits, K, ctx, a);
 }
 
 // all matrices of the plan in one launch; the descriptor table is already in the workspace head
@@ -443,7 +484,6 @@ int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re,
     sbits_ctx *ctx = plan->ctx;
     CostLaunch a;
     memset(&a, 0, sizeof a);
-    sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
     if (plan->cost_unit_start.empty()) {             // depends on shapes only: computed once, kept for the copies
         const int bpu = blocks_per_unit(plan->m, plan->n);
         int64_t t = 0;
@@ -466,7 +506,7 @@ int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re,
     a.S = s_re;
     a.m = plan->m;
     a.cost = cost;
-    return launch(plan->n, plan->K, ctx, a);
+    return launch(plan->n, plan->bits, plan->K, ctx, a);
 }
 
 // which cost this build computes (the arithmetic core fixes it at compile time)

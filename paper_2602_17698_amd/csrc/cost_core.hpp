@@ -66,11 +66,13 @@ struct DivPlan {
 // 8 consecutive elements of every row: raw bf16 weights w[j] and sensitivities s[j][0..7].
 // out[j][c] = the lane's partial cost of row j at candidate c (elements left to right,
 // a = fma(s, d*d, a); with SBITS_COST_POWER == 1: a = fma(s, |d|, a)).
-template <int LPG, int K, int NI>
+// K counts all candidates.  Z0: candidate 0 is "0 bits" (the block is pruned, paper Sec. 3: its
+// change is the weight itself, d = w); the division plan then holds the other K - 1 grids.
+template <int LPG, int K, int NI, bool Z0>
 __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const float (&s)[NI][8],
-                                                 const DivPlan<LPG, K> &dp, float (&out)[NI][K])
+                                                 const DivPlan<LPG, K - Z0> &dp, float (&out)[NI][K])
 {
-    using DP = DivPlan<LPG, K>;
+    using DP = DivPlan<LPG, K - Z0>;
     constexpr int SP = DP::SP, NS = DP::NS;
     static_assert(NI >= 1 && NI <= DP::RP, "too many rows for one round of divisions");
     float x[NI][8], Rg[NI];
@@ -106,7 +108,15 @@ __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const 
 
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-        static_for<0, K>([&](auto ic) {
+        if constexpr (Z0) {
+            float w[8];
+            unpack8(wraw[j], w);
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fmaf(s[j][e], SBITS_COST_POWER == 1 ? fabsf(w[e]) : w[e] * w[e], acc);
+            out[j][0] = acc;
+        }
+        static_for<0, K - Z0>([&](auto ic) {
             constexpr int c = decltype(ic)::value;
             float inv, scl;
             if constexpr (LPG >= SP) {
@@ -123,7 +133,7 @@ __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const 
                 const float d = fmaf(-q, scl, x[j][e]);
                 acc = fmaf(s[j][e], SBITS_COST_POWER == 1 ? fabsf(d) : d * d, acc);
             }
-            out[j][c] = acc;
+            out[j][Z0 + c] = acc;
         });
     }
 }

@@ -23,7 +23,7 @@ struct DequantArgs {
     void *out;
     int64_t block_base, ld_out;
     int R, C, m, n, nbc;
-    int bits[8];
+    int bits[MAX_CAND];
 };
 
 __device__ __forceinline__ uint32_t bf16_rne(float f)
@@ -45,7 +45,7 @@ void dequant_kernel(DequantArgs a)
     int lv = a.level[blk];
     int c = a.bits[0];
 #pragma unroll
-    for (int k = 1; k < 8; ++k) c = lv == k ? a.bits[k] : c;
+    for (int k = 1; k < MAX_CAND; ++k) c = lv == k ? a.bits[k] : c;
     // the run's c bytes and the aligned dwords around them (the stream ends on a multiple of 8 bytes
     // from a 16-byte aligned base, so a dword that holds one of the run's bytes lies inside it)
     const uint8_t *p = a.codes + a.byte_off[blk] + ((int64_t)r * a.n + cin) / 8 * c;
@@ -53,7 +53,7 @@ void dequant_kernel(DequantArgs a)
     const uint32_t *q = reinterpret_cast<const uint32_t *>(pa & ~(uintptr_t)3);
     const int sh = (int)(pa & 3) * 8;
     const int need = (int)(pa & 3) + c;                       // bytes from q[0] on
-    const uint32_t w0 = q[0];
+    const uint32_t w0 = c ? q[0] : 0u;                        // (a pruned block has no codes: its value is zero[] = 0)
     const uint32_t w1 = need > 4 ? q[1] : 0u;
     const uint32_t w2 = need > 8 ? q[2] : 0u;
     const unsigned long long lo64 = ((unsigned long long)w1 << 32) | w0;
@@ -91,7 +91,7 @@ int sbits_launch_dequant(sbits_plan *plan, int mat, const uint8_t *level, const 
     a.codes = codes; a.scale = scale; a.zero = zero; a.level = level; a.byte_off = byte_off;
     a.out = out; a.block_base = plan->base[mat]; a.ld_out = ld_out;
     a.R = (int)plan->rows[mat]; a.C = (int)plan->cols[mat]; a.m = plan->m; a.n = plan->n; a.nbc = a.C / plan->n;
-    for (int c = 0; c < 8; ++c) a.bits[c] = c < plan->K ? plan->bits[c] : plan->bits[plan->K - 1];
+    for (int c = 0; c < sbits::MAX_CAND; ++c) a.bits[c] = c < plan->K ? plan->bits[c] : plan->bits[plan->K - 1];
     const dim3 grid((unsigned)((a.C / 8 + 255) / 256), (unsigned)a.R);
     if (out_bf16) hipLaunchKernelGGL(dequant_kernel<true>, grid, dim3(256), 0, ctx->stream, a);
     else hipLaunchKernelGGL(dequant_kernel<false>, grid, dim3(256), 0, ctx->stream, a);

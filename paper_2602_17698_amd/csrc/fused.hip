@@ -63,10 +63,11 @@ __device__ __forceinline__ void lds_barrier()
 
 // Launched with T = the smallest multiple of 64 threads whose CPL chunks per lane cover a row
 // (T <= TMAX), so that rows whose chunk count is no power of two leave no lanes idle.
-// SUR = false: the block x bitwidth cost table (K candidates per block).
+// SUR = false: the block x bitwidth cost table (K candidates per block; with Z0 the first of them is
+//              "0 bits", the pruned block, and gc holds the other K - 1 grids).
 // SUR = true : the dynamic-sensitivity surrogates (K = 2 sums per block, at the block's current
-//              level[]; the "sensitivity" input is the gradient).
-template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR>
+//              level[]; the "sensitivity" input is the gradient; gc holds every candidate).
+template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR, bool Z0>
 __global__ __launch_bounds__(TMAX, (TMAX >= 1024 ? 4 : 2))
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
@@ -76,11 +77,11 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 {
     // kstride, koff: the K sums of an octet go to part[..][koff .. koff + K) of kstride values (a launch
     // may cover a subset of the candidates)
-    static_assert(!SUR || K == 2, "two sums per block");
+    static_assert(!SUR || (K == 2 && !Z0), "two sums per block");
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int rowsrc[FU_OPU * 8];
     constexpr int NIT = RS * CPL;                    // rows x chunks scored per step
-    using DP = DivPlan<LPG, K>;
+    using DP = DivPlan<LPG, K - Z0>;
     constexpr int NG = NIT > 2 ? 2 : NIT;            // of which NG are held in registers at a time
     constexpr int NI = SUR ? NG : (DP::RP < NG ? DP::RP : NG);   // and NI share a round of divisions
     static_assert(NIT % NG == 0 && NG % NI == 0 && 8 % RS == 0, "step shape");
@@ -256,7 +257,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                     for (int j = 0; j < NI; ++j) lr[j] = lk[(g0 + i0 + j) % CPL];
                     surrogate_round<LPG, NI>(wr, s, lr, lig, out);
                 } else {
-                    quant_cost_round<LPG, K, NI>(wr, s, dp, out);
+                    quant_cost_round<LPG, K, NI, Z0>(wr, s, dp, out);
                 }
                 if constexpr (RS == 2 && CPL == 1 && NI == 2) {
                     // the two items are rows rr0, rr0 + 1 of one chunk: their sum is the tree's first level
@@ -574,7 +575,7 @@ void surrogate_finish_kernel(const float *__restrict__ part, int64_t N, int opb,
     } else {
         int bits = gc.bits[0];
 #pragma unroll
-        for (int cc = 1; cc < 8; ++cc)
+        for (int cc = 1; cc < MAX_CAND; ++cc)
             if (level[b] == cc) bits = gc.bits[cc];
         s_down[b] = ldexpf(v, -bits);
     }
@@ -601,11 +602,11 @@ static int fused_threads(int64_t cols, int cpl, int tmax)
     return (int)(need < 64 ? 64 : (need > tmax ? tmax : need));
 }
 
-template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR>
+template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR, bool Z0>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int T = fused_threads(a.cols, CPL, TMAX);
-    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, SUR>;
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, SUR, Z0>;
     SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
     const size_t lds = (size_t)RS * a.cols * 6;
@@ -616,13 +617,13 @@ static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
     return SBITS_OK;
 }
 
-template <int LPG, int K>
+template <int LPG, int K, bool Z0>
 static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int64_t chunks = a.cols / 8;
-    if (chunks <= 512) return launch_fused_g<LPG, K, 1, 2, 512, false>(ctx, a);
-    if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, false>(ctx, a);
-    if (chunks <= 2048) return launch_fused_g<LPG, K, 4, 1, 512, false>(ctx, a);
+    if (chunks <= 512) return launch_fused_g<LPG, K, 1, 2, 512, false, Z0>(ctx, a);
+    if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, false, Z0>(ctx, a);
+    if (chunks <= 2048) return launch_fused_g<LPG, K, 4, 1, 512, false, Z0>(ctx, a);
     return SBITS_ERR_BAD_SHAPE;
 }
 
@@ -630,24 +631,35 @@ template <int LPG>
 static int launch_surrogates_l(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int64_t chunks = a.cols / 8;
-    if (chunks <= 512) return launch_fused_g<LPG, 2, 1, 2, 512, true>(ctx, a);
-    if (chunks <= 1024) return launch_fused_g<LPG, 2, 2, 1, 512, true>(ctx, a);
-    if (chunks <= 2048) return launch_fused_g<LPG, 2, 4, 1, 512, true>(ctx, a);
+    if (chunks <= 512) return launch_fused_g<LPG, 2, 1, 2, 512, true, false>(ctx, a);
+    if (chunks <= 1024) return launch_fused_g<LPG, 2, 2, 1, 512, true, false>(ctx, a);
+    if (chunks <= 2048) return launch_fused_g<LPG, 2, 4, 1, 512, true, false>(ctx, a);
     return SBITS_ERR_BAD_SHAPE;
 }
 
+// K: the candidates of this launch; z0: the first of them is 0 bits (then 2 <= K <= 9, else 1 <= K <= 8)
 template <int LPG>
-static int launch_fused_l(int K, sbits_ctx *ctx, const FusedLaunch &a)
+static int launch_fused_l(int K, bool z0, sbits_ctx *ctx, const FusedLaunch &a)
 {
-    switch (K) {
-    case 1: return launch_fused_k<LPG, 1>(ctx, a);
-    case 2: return launch_fused_k<LPG, 2>(ctx, a);
-    case 3: return launch_fused_k<LPG, 3>(ctx, a);
-    case 4: return launch_fused_k<LPG, 4>(ctx, a);
-    case 5: return launch_fused_k<LPG, 5>(ctx, a);
-    case 6: return launch_fused_k<LPG, 6>(ctx, a);
-    case 7: return launch_fused_k<LPG, 7>(ctx, a);
-    case 8: return launch_fused_k<LPG, 8>(ctx, a);
+    if (z0) switch (K) {
+    case 2: return launch_fused_k<LPG, 2, true>(ctx, a);
+    case 3: return launch_fused_k<LPG, 3, true>(ctx, a);
+    case 4: return launch_fused_k<LPG, 4, true>(ctx, a);
+    case 5: return launch_fused_k<LPG, 5, true>(ctx, a);
+    case 6: return launch_fused_k<LPG, 6, true>(ctx, a);
+    case 7: return launch_fused_k<LPG, 7, true>(ctx, a);
+    case 8: return launch_fused_k<LPG, 8, true>(ctx, a);
+    case 9: return launch_fused_k<LPG, 9, true>(ctx, a);
+    }
+    else switch (K) {
+    case 1: return launch_fused_k<LPG, 1, false>(ctx, a);
+    case 2: return launch_fused_k<LPG, 2, false>(ctx, a);
+    case 3: return launch_fused_k<LPG, 3, false>(ctx, a);
+    case 4: return launch_fused_k<LPG, 4, false>(ctx, a);
+    case 5: return launch_fused_k<LPG, 5, false>(ctx, a);
+    case 6: return launch_fused_k<LPG, 6, false>(ctx, a);
+    case 7: return launch_fused_k<LPG, 7, false>(ctx, a);
+    case 8: return launch_fused_k<LPG, 8, false>(ctx, a);
     }
     return SBITS_ERR_BAD_BITWIDTHS;
 }
@@ -777,7 +789,6 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
     if (rc0) return rc0;
     FusedLaunch a;
     memset(&a, 0, sizeof a);
-    sbits_fill_grid_consts(plan->bits, plan->K, &a.gc);
     a.descs = sbits_desc_ptr(ws);
     a.row_perm = row_perm;
     a.col_perm = col_perm;
@@ -791,19 +802,20 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
         a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
         a.cols = fc.cols;
         if (a.total_wg == 0) continue;
-        // Four chunks per lane and seven or eight candidates do not fit the register file (three tree
+        // Four chunks per lane and seven or more candidates do not fit the register file (three tree
         // levels per chunk and candidate): such rows take two launches of about half the candidates
         // each.  The grids are independent per candidate, so the table is the same bit for bit.
         const bool split = fc.cols / 8 > 1024 && plan->K >= 7;
         const int k0 = split ? (plan->K + 1) / 2 : plan->K;
         for (int kb = 0; kb < plan->K; kb += k0) {
             const int kn = plan->K - kb < k0 ? plan->K - kb : k0;
-            sbits_fill_grid_consts(plan->bits + kb, kn, &a.gc);
+            const bool z0 = plan->bits[kb] == 0;                // a 0-bit candidate (the first of the list) has no grid
+            sbits_fill_grid_consts(plan->bits + kb + z0, kn - z0, &a.gc);
             a.kstride = plan->K;
             a.koff = kb;
             uint16_t *const w_keep = a.w_re;
             if (kb > 0) a.w_re = nullptr;                       // the reordered weights are written once
-            const int rc = plan->n == 64 ? launch_fused_l<8>(kn, ctx, a) : launch_fused_l<16>(kn, ctx, a);
+            const int rc = plan->n == 64 ? launch_fused_l<8>(kn, z0, ctx, a) : launch_fused_l<16>(kn, z0, ctx, a);
             a.w_re = w_keep;
             if (rc) return rc;
         }

@@ -48,7 +48,7 @@ struct MpArgs {
     float *out;                          // y [batch][R] (n_split == 1) or partials [n_split][batch][R]
     int64_t block_base, ld_x;
     int R, C, m, nbc, batch, n_split;
-    int bits[8];
+    int bits[MAX_CAND];
 #ifdef MG_EXP_TIMING
     long long *dbg;
 #endif
@@ -203,12 +203,14 @@ __device__ __forceinline__ void block_product(const uint32_t (&cw)[2][8], const 
 }
 
 // Codes, scales and zeros of block T of a wave -> register slot S; the same number of load
-// instructions whatever the block (c = 0: an absent block reads the first dword of the stream and the
-// clamped block's scales).  (A macro: through a function the slots end up in scratch memory.)
+// instructions whatever the block.  c = 0: a block column beyond the matrix, or a pruned block (0 bits:
+// no codes, contributes nothing); its dummy loads read the first dword of the scales, which always
+// exists, and the clamped block's scales.  (A macro: through a function the slots end up in scratch memory.)
 #define MG_REQUEST(T, S)                                                                                          \
     do {                                                                                                          \
         const int c_ = cbits[T];                                                                                  \
-        const uint8_t *pb_ = a.codes + (c_ ? (int64_t)(((uint64_t)off_hi[T] << 32) | off_lo[T]) : 0);             \
+        const uint8_t *pb_ = c_ ? a.codes + (int64_t)(((uint64_t)off_hi[T] << 32) | off_lo[T])                    \
+                                : reinterpret_cast<const uint8_t *>(a.scale);                                     \
         const float *ps_ = a.scale + blk[T] * a.m + rin, *pz_ = a.zero + blk[T] * a.m + rin;                      \
         _Pragma("unroll") for (int tl = 0; tl < 2; ++tl) {                                                        \
             const uint8_t *p_ = pb_ + (lane_units + (uint32_t)(tl * 16 * (N_COLS / 8))) * (uint32_t)c_;           \
@@ -320,7 +322,7 @@ void mp_gemm_kernel(MpArgs a)
         const int lv = __builtin_amdgcn_readfirstlane((int)lvl_v[t]);
         int c = a.bits[0];
 #pragma unroll
-        for (int k = 1; k < 8; ++k) c = lv == k ? a.bits[k] : c;
+        for (int k = 1; k < MAX_CAND; ++k) c = lv == k ? a.bits[k] : c;
         cbits[t] = (rows_ok && J < a.nbc) ? c : 0;
         off_lo[t] = __builtin_amdgcn_readfirstlane((uint32_t)boff_v[t]);
         off_hi[t] = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)boff_v[t] >> 32));
@@ -342,7 +344,7 @@ void mp_gemm_kernel(MpArgs a)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
             xa[nb] = smem + (size_t)(16 * nb + li) * PITCH + (size_t)(Jl * N_COLS + g * KL) * 2;
-        if (c != 0) switch (c) {                               // (0: no such block column)
+        if (c != 0) switch (c) {                               // (0: no such block column, or a pruned block)
         case 1: block_product<1, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
         case 2: block_product<2, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
         case 3: block_product<3, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
@@ -455,7 +457,7 @@ int sbits_launch_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t 
     a.R = (int)plan->rows[mat]; a.C = (int)plan->cols[mat]; a.m = plan->m; a.nbc = a.C / plan->n;
     a.batch = batch;
     a.n_split = sbits_mp_gemm_splits(a.C, plan->n);
-    for (int c = 0; c < 8; ++c) a.bits[c] = c < plan->K ? plan->bits[c] : plan->bits[plan->K - 1];
+    for (int c = 0; c < sbits::MAX_CAND; ++c) a.bits[c] = c < plan->K ? plan->bits[c] : plan->bits[plan->K - 1];
     a.out = a.n_split > 1 ? static_cast<float *>(scratch) : y;
 #ifdef MG_EXP_TIMING
     a.dbg = reinterpret_cast<long long *>(static_cast<char *>(scratch) + (2304 << 10));

@@ -23,7 +23,9 @@ constexpr int OF_THREADS = 256;
 constexpr int OF_ITEMS = 8;
 constexpr int OF_TILE = OF_THREADS * OF_ITEMS;
 
-struct BitsTab { int bits[8]; };
+struct BitsTab { int bits[MAX_CAND]; };
+// (a level beyond the table, which no valid input holds, reads its last entry)
+__device__ __forceinline__ int tab_bits(const BitsTab &bt, int lv) { return bt.bits[lv < MAX_CAND ? lv : MAX_CAND - 1]; }
 
 __device__ __forceinline__ long long block_exclusive_scan(long long v, long long *total)
 {
@@ -53,7 +55,7 @@ void tile_sum_kernel(const uint8_t *__restrict__ level, long long N, long long M
     const long long i0 = (long long)blockIdx.x * OF_TILE + (long long)threadIdx.x * OF_ITEMS;
     long long s = 0;
     for (int e = 0; e < OF_ITEMS; ++e)
-        if (i0 + e < N) s += Mdiv8 * bt.bits[level[i0 + e] & 7];
+        if (i0 + e < N) s += Mdiv8 * tab_bits(bt, level[i0 + e]);
     long long tot;
     block_exclusive_scan(s, &tot);
     if (threadIdx.x == 0) tilesum[blockIdx.x] = tot;
@@ -81,7 +83,7 @@ void tile_scan_kernel(const uint8_t *__restrict__ level, long long N, long long 
     const long long i0 = (long long)blockIdx.x * OF_TILE + (long long)threadIdx.x * OF_ITEMS;
     long long v[OF_ITEMS], s = 0;
     for (int e = 0; e < OF_ITEMS; ++e) {
-        v[e] = (i0 + e < N) ? Mdiv8 * bt.bits[level[i0 + e] & 7] : 0;
+        v[e] = (i0 + e < N) ? Mdiv8 * tab_bits(bt, level[i0 + e]) : 0;
         s += v[e];
     }
     long long tot;
@@ -247,7 +249,7 @@ int sbits_launch_offsets(sbits_ctx *ctx, const uint8_t *level, int64_t N, int m,
                          const int32_t *bits, int K, int64_t *byte_off, void *ws)
 {
     BitsTab bt;
-    for (int c = 0; c < 8; ++c) bt.bits[c] = c < K ? bits[c] : bits[K - 1];
+    for (int c = 0; c < sbits::MAX_CAND; ++c) bt.bits[c] = c < K ? bits[c] : bits[K - 1];
     const long long Mdiv8 = (long long)m * n / 8;
     const int64_t ntiles = (N + OF_TILE - 1) / OF_TILE;
     long long *tiles = static_cast<long long *>(ws);

@@ -8,7 +8,7 @@
 
 namespace sbits {
 
-// bitwidth, qmax and the finite-quotient threshold of candidate `lv`
+// bitwidth, qmax and the finite-quotient threshold of candidate `lv` (c == 0: a pruned block)
 struct LevelConsts {
     int c;
     float qf, th;
@@ -19,7 +19,7 @@ __device__ __forceinline__ LevelConsts level_consts(const GridConsts &gc, int lv
     LevelConsts k;
     k.c = gc.bits[0]; k.qf = gc.qmaxf[0]; k.th = gc.thr[0];
 #pragma unroll
-    for (int cc = 1; cc < 8; ++cc)
+    for (int cc = 1; cc < MAX_CAND; ++cc)
         if (lv == cc) { k.c = gc.bits[cc]; k.qf = gc.qmaxf[cc]; k.th = gc.thr[cc]; }
     k.qmax = (unsigned int)k.qf;
     return k;
@@ -39,6 +39,7 @@ __device__ __forceinline__ unsigned long long quant_pack_row(const uint4 &raw, c
     mn = group_allreduce<LPG>(mn, OpMin{});
     mx = group_allreduce<LPG>(mx, OpMax{});
     const float R = mx - mn;
+    if (k.c == 0) mn = 0.0f;                         // pruned block: origin 0 (both quotients are 0 by its threshold)
     float inv;
     if (LPG >= 2) {
         float v = (odd ? R : k.qf) / (odd ? k.qf : R);
@@ -87,7 +88,7 @@ __device__ __forceinline__ void quant_pack_rows(const uint4 (&raw)[RS], const Le
                          fmaxf(fmaxf(w[rs][4], w[rs][5]), fmaxf(w[rs][6], w[rs][7])));
         lo = group_allreduce<LPG>(lo, OpMin{});
         hi = group_allreduce<LPG>(hi, OpMax{});
-        mn[rs] = lo;
+        mn[rs] = k.c == 0 ? 0.0f : lo;               // pruned block: origin 0 (both quotients are 0 by its threshold)
         R[rs] = hi - lo;
     }
     const int qi = lig & (2 * RS - 1);               // lanes beyond 2*RS repeat a quotient; nobody reads theirs

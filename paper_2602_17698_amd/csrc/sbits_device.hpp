@@ -110,10 +110,14 @@ __device__ __forceinline__ int find_matrix(const int *__restrict__ wg_start, int
 }
 
 // ---- quantization grid constants, one set per candidate ---------------------
+// Candidate bitwidths are 0 .. 8, ascending: at most MAX_CAND of them.  0 bits = the block is pruned
+// (paper Sec. 3): stored value 0, no codes; its entry has qmax 0 and an infinite threshold, which
+// makes both grid quotients 0 wherever a level's constants are used (the origin is forced to 0 there).
+constexpr int MAX_CAND = 9;
 struct GridConsts {
-    float qmaxf[8];   // 2^c - 1
-    float thr[8];     // smallest range R for which qmax / R is finite
-    int   bits[8];
+    float qmaxf[MAX_CAND];   // 2^c - 1
+    float thr[MAX_CAND];     // smallest range R for which qmax / R is finite
+    int   bits[MAX_CAND];
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }

@@ -24,7 +24,7 @@ struct sbits_plan {
     int n_mats;
     std::vector<int64_t> rows, cols, base;   // base[mat] = first global block id
     int m, n, K;
-    int32_t bits[8];
+    int32_t bits[sbits::MAX_CAND];           // ascending, within 0 .. 8; 0 = the block is pruned
     int64_t N;                               // total blocks
     int64_t max_rows, max_cols;
     int64_t sum_rows, sum_cols, sum_elems;

@@ -77,7 +77,9 @@ def test_plan_numbers_blocks_matrix_after_matrix(ctx):
     ((1024, 1024), 128, 128, [], sb.ERR_BAD_BITWIDTHS),
     ((1024, 1024), 128, 128, [2, 2, 4], sb.ERR_BAD_BITWIDTHS),   # not strictly increasing
     ((1024, 1024), 128, 128, [4, 3, 2], sb.ERR_BAD_BITWIDTHS),
-    ((1024, 1024), 128, 128, [0, 1, 2], sb.ERR_BAD_BITWIDTHS),   # 0 bits (pruning) unsupported
+    ((1024, 1024), 128, 128, [0], sb.ERR_BAD_BITWIDTHS),         # pruning alone is no search space
+    ((1024, 1024), 128, 128, [-1, 2], sb.ERR_BAD_BITWIDTHS),
+    ((1024, 1024), 128, 128, [0, 0, 2], sb.ERR_BAD_BITWIDTHS),
     ((1024, 1024), 128, 128, [2, 3, 9], sb.ERR_BAD_BITWIDTHS),
     ((1024, 1024), 128, 128, list(range(1, 9)) + [8], sb.ERR_BAD_BITWIDTHS),
 ])
@@ -85,6 +87,15 @@ def test_plan_rejects_bad_partitions(ctx, shape, m, n, bits, err):
     with pytest.raises(sb.SbitsError) as e:
         sb.Plan(ctx, [shape], m, n, bits)
     assert e.value.status == err
+
+
+def test_plan_takes_zero_bits_and_nine_candidates(ctx):
+    p = sb.Plan(ctx, [(256, 256)], 128, 128, list(range(9)))      # 0 (pruned), 1, ..., 8
+    assert p.num_blocks() == 4
+    assert p.codes_bytes_bound(0.5) == 2 * 128 * 128 // 8
+    assert p.codes_bytes_bound(0.0) == 0
+    p.close()
+    sb.Plan(ctx, [(256, 256)], 128, 128, [0, 4]).close()
 
 
 def test_calls_validate_before_touching_the_device(ctx, lib):

@@ -162,6 +162,10 @@ COST_CASES = [
     (2048, 256, 1024, 256, [2, 3, 4]),
     (128, 1024, 64, 512, [1, 2, 3, 4, 8]),
     (520, 128, 8, 128, [2, 3, 4]),                        # 65 row blocks: ragged last workgroup
+    (256, 384, 128, 128, [0, 2, 3, 4]),                   # 0 bits = the block is pruned
+    (192, 320, 64, 64, [0, 1, 2, 3, 4, 5, 6, 7, 8]),      # nine candidates on 64-column blocks: two launches
+    (24, 40, 8, 8, [0, 1, 2, 3, 4, 5, 6, 7, 8]),
+    (128, 1024, 64, 512, [0, 4]),
 ]
 
 
@@ -322,6 +326,9 @@ ONE_PASS_CASES = [
     ([(64, 14336)], 64, 64, [1, 2, 3, 4, 8]),                     # four chunks per lane, K = 5
     ([(64, 14336), (128, 256)], 64, 128, [1, 2, 3, 4, 5, 6, 7, 8]),  # four chunks per lane, K = 8: two launches of 4 candidates
     ([(64, 8320)], 64, 64, [1, 2, 3, 4, 5, 6, 8]),                # K = 7: 4 + 3 candidates
+    ([(256, 384), (128, 1024)], 128, 128, [0, 1, 2, 3, 4]),       # with the pruned candidate (0 bits)
+    ([(64, 14336), (128, 256)], 64, 128, [0, 1, 2, 3, 4, 5, 6, 7, 8]),   # nine candidates; four chunks per lane: 5 + 4
+    ([(64, 8320), (192, 320)], 64, 64, [0, 2, 4]),
 ]
 
 
@@ -520,6 +527,9 @@ ALLOC_CASES = [
     ([3], 3.0, 100, 0.05, 0.02, 0),                       # a single candidate
     ([2, 3, 4], 5.0, 100, 0.05, 0.02, 0),                 # budget above the largest candidate
     ([2, 3, 4], 3.0, 70000, 0.05, 0.02, 0),               # several workgroups and histogram flushes
+    ([0, 1, 2, 3, 4], 1.5, 5000, 0.05, 0.02, 0),          # with the pruned candidate
+    ([0, 2, 4, 8], 0.9, 3000, 0.05, 0.02, 0),             # warm start at 0 bits, uneven steps
+    ([0, 1, 2, 3, 4, 5, 6, 7, 8], 3.0, 4000, 0.05, 0.02, 0),   # nine candidates
 ]
 
 
@@ -717,6 +727,20 @@ def test_search_several_matrices(orc, ctx, dev, m, n, bits, avg, recipe):
     compare_search(orc, ref, rc, st, o, shp, m)
 
 
+def test_search_with_a_pruned_candidate(orc, ctx, dev):
+    """{0, 1, 2, 3, 4} bits at 1.5 bits per weight: blocks at 0 bits are pruned (no bytes, zero scale / zero)."""
+    say("search with 0 bits")
+    shapes = [(512, 512), (256, 1024), (1024, 256)]
+    mats = [synth.make_matrix("student_t", r, c, seed=6, tid=i) for i, (r, c) in enumerate(shapes)]
+    bits = [0, 1, 2, 3, 4]
+    ref = oracle_search(orc, mats, 64, 128, bits, 1.5)
+    rc, st, o, shp = gpu_search(ctx, dev, mats, 64, 128, bits, 1.5)
+    compare_search(orc, ref, rc, st, o, shp, 64)
+    pruned = ref["level"] == 0
+    assert pruned.any() and not pruned.all()
+    assert not ref["scale"].reshape(-1, 64)[pruned].any()
+
+
 def test_search_is_deterministic(ctx, dev):
     say("determinism")
     mats = [synth.make_matrix("student_t", 512, 1024, seed=11, tid=i) for i in range(3)]
@@ -741,7 +765,7 @@ def _blocks_plan(ctx, N, bits, dev):
 
 
 @pytest.mark.parametrize("N,bits", [(1, [2, 3, 4]), (37, [1, 2, 3, 4]), (4096, [1, 2, 3, 4, 8]), (50000, [2, 4, 8]),
-                                    (425984, [1, 2, 3, 4])])
+                                    (425984, [1, 2, 3, 4]), (4096, [0, 1, 2, 3, 4, 5, 6, 7, 8]), (1000, [0, 2, 4])])
 def test_propose_matches_oracle(orc, ctx, dev, N, bits):
     say("propose", N, bits)
     plan, ws = _blocks_plan(ctx, N, bits, dev)
@@ -858,6 +882,8 @@ def _mp_gemm_check(orc, y, packed, base, R, C, m, n, bits, xb):
     (128, 192, 64, 64, [1, 2, 3, 4, 5, 6, 7, 8], 17),       # group size 64
     (192, 64 * 33, 64, 64, [2, 3, 4, 8], 1),                # group size 64, three splits, a single row of x
     (128, 128 * 18, 64, 128, [2, 4], 70),                   # more than 32 rows of x: three launches
+    (160, 128 * 20, 32, 128, [0, 2, 4, 8], 16),             # pruned blocks among the others
+    (128, 192, 64, 64, [0, 1, 2, 3, 4, 5, 6, 7, 8], 9),     # nine candidates, group size 64
 ])
 def test_mp_gemm(orc, ctx, dev, R, C, m, n, bits, batch):
     say("mixed-precision product", R, C, m, n, bits, batch)
@@ -957,7 +983,8 @@ def test_search_then_inference_preserves_the_layer_function(orc, ctx, dev):
 
 
 @pytest.mark.parametrize("R,C,m,n,bits", [(16, 24, 8, 8, [1, 2, 3, 4, 5, 6, 7, 8]), (128, 384, 64, 128, [1, 2, 3, 4, 8]),
-                                          (96, 1024, 32, 512, [3, 5, 7]), (2048, 2056 - 8, 1024, 8, [2, 4])])
+                                          (96, 1024, 32, 512, [3, 5, 7]), (2048, 2056 - 8, 1024, 8, [2, 4]),
+                                          (128, 384, 64, 128, [0, 1, 2, 3, 4, 5, 6, 7, 8]), (64, 96, 8, 16, [0, 3])])
 def test_dequant(orc, ctx, dev, R, C, m, n, bits):
     """The stored matrix as fp32 (bit for bit the format's value) and as bf16 (nearest even)."""
     say("dequant", R, C, m, n, bits)
@@ -1068,7 +1095,7 @@ def ctx_l1(dev):
 
 def test_power_one_variant_cost_tables(orc, ctx_l1, dev):
     say("l1 variant: cost tables, both routes")
-    shapes, m, n, bits = [(256, 384), (128, 1024), (64, 14336)], 64, 128, [1, 2, 3, 4, 8]
+    shapes, m, n, bits = [(256, 384), (128, 1024), (64, 14336)], 64, 128, [0, 1, 2, 3, 4, 8]
     plan, ws = make_plan(ctx_l1, shapes, m, n, bits, dev)
     N, K = plan.num_blocks(), len(bits)
     mats = [synth.make_matrix("student_t", r, c, seed=21, tid=i) for i, (r, c) in enumerate(shapes)]
