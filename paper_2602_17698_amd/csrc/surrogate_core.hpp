@@ -30,7 +30,7 @@ __device__ __forceinline__ void surrogate_round(const uint4 (&wraw)[NI], const f
                          fmaxf(fmaxf(w[j][4], w[j][5]), fmaxf(w[j][6], w[j][7])));
         lo = group_allreduce<LPG>(lo, OpMin{});
         hi = group_allreduce<LPG>(hi, OpMax{});
-        mn[j] = k[j].c == 0 ? 0.0f : lo;             // pruned block: what = 0 (origin 0, both quotients 0)
+        mn[j] = origin_of(k[j], lo);                 // pruned block: what = 0 (origin 0, both quotients 0)
         R[j] = hi - lo;
     }
     const int qi = lig & (2 * NI - 1);               // lanes beyond 2*NI repeat a quotient; nobody reads theirs
