@@ -56,7 +56,7 @@ typedef enum {
     SBITS_OK                   =  0,
     SBITS_ERR_INVALID_ARG      = -1,  /* null pointer, index out of range, misaligned workspace */
     SBITS_ERR_BAD_SHAPE        = -2,  /* block shape not a supported power of two, or not dividing the matrix */
-    SBITS_ERR_BAD_BITWIDTHS    = -3,  /* empty, more than 8, not strictly increasing, outside 1..8 */
+    SBITS_ERR_BAD_BITWIDTHS    = -3,  /* empty, more than 9, not strictly increasing, outside 0..8, only 0 */
     SBITS_ERR_INFEASIBLE_BUDGET= -4,  /* avg_bits below the smallest candidate */
     SBITS_ERR_WORKSPACE        = -5,  /* reserved: workspace too small */
     SBITS_ERR_MAX_ITERS        = -6,  /* search stopped by max_iters; levels are valid and within budget */
