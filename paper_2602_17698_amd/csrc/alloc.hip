@@ -90,7 +90,14 @@ __global__ void max_cost_kernel(const float *__restrict__ cost, long long n, All
         if (v > 0.0f) mx = max(mx, __float_as_uint(v));
     }
     for (int off = 32; off; off >>= 1) mx = max(mx, (unsigned int)__shfl_xor((int)mx, off));
-    if ((threadIdx.x & 63) == 0 && mx) atomicMax(&st->maxc_bits, mx);
+    // one atomic per workgroup: thousands of them on one address take longer than the reads
+    __shared__ unsigned int wmx[AL_THREADS / 64];
+    if ((threadIdx.x & 63) == 0) wmx[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) mx = max(mx, wmx[w]);
+        if (mx) atomicMax(&st->maxc_bits, mx);
+    }
 }
 
 __global__ void init_state_kernel(AllocState *st, int ceil_log2_n)
