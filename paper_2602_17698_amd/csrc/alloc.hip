@@ -187,7 +187,15 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
     const int P = st->P;
     const unsigned long long prefix = job->prefix, key_min = job->key_min;
     const unsigned long long excl_tau = excl ? st->job[excl_job].tau : 0;
-    const int sh_digit = SEL_DB * (P - 1 - pass), sh_prefix = SEL_DB * (P - pass);
+    // Digits are cut from the TOP of the 32 + IB significant bits (the last one may be narrower): the
+    // first pass then already splits on 11 bits of the value instead of on the few bits that a
+    // bottom-aligned cut leaves at the top, and a selection whose boundary bucket holds one key is
+    // resolved a pass earlier.
+    const int TB = 32 + st->IB;
+    const int sh_prefix = TB - SEL_DB * pass;
+    const int sh_digit = sh_prefix > SEL_DB ? sh_prefix - SEL_DB : 0;
+    const int width = sh_prefix - sh_digit;
+    const unsigned int dmask = (1u << width) - 1u;
     const long long stride = (long long)gridDim.x * blockDim.x;
     // all of a thread's keys are requested at once (SEL_KPT loads in flight: one memory latency per pass)
     for (long long i0 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i0 < N; i0 += SEL_KPT * stride) {
@@ -205,7 +213,7 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
             const unsigned long long s = key[u] >> 8;
             const unsigned long long hi = sh_prefix >= 64 ? 0ull : (s >> sh_prefix);
             if (hi != prefix) continue;
-            const unsigned int d = (unsigned int)(s >> sh_digit) & (SEL_BINS - 1);
+            const unsigned int d = (unsigned int)(s >> sh_digit) & dmask;
             atomicAdd(&hc[d], 1u);
             atomicAdd(&hw[d], (unsigned int)(key[u] & 255u));
         }
@@ -283,7 +291,7 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
             job->tau = lo > key_min ? lo : key_min;
             job->n_sel = c; job->w_sel = w; job->resolved = 1;
         } else {
-            const unsigned long long np = (prefix << SEL_DB) | (unsigned long long)boundary;
+            const unsigned long long np = (prefix << width) | (unsigned long long)boundary;
             job->cnt_above = c; job->w_above = w;
             if (pass == P - 1 || boundary_cnt == 1) {
                 // a single key that does not fit (its remaining digits do not matter): select the
