@@ -48,8 +48,7 @@ struct SelJob {
     long long n_sel, w_sel;
     int resolved;
     unsigned int ticket;
-    unsigned int hist_cnt[SEL_BINS];
-    unsigned int hist_w[SEL_BINS];
+    unsigned long long hist[SEL_BINS];   // per bucket: (sum of step widths << 32) | number of keys
 };
 
 enum { JOB_E = 0, JOB_U = 1, JOB_D = 2, JOB_U2 = 3, N_JOBS = 4 };
@@ -178,10 +177,13 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
 {
     SelJob *job = &st->job[job_id];
     if (job->resolved) return;                                   // uniform over the grid
-    __shared__ unsigned int hc[SEL_BINS], hw[SEL_BINS];
+    // count and width sum of a bucket share one 64-bit word (count low, widths high; neither can
+    // reach 2^32: at most 2^24 keys of width <= 255): one LDS atomic per key instead of two
+    __shared__ unsigned long long h64[SEL_BINS];
+    unsigned int *const hc = reinterpret_cast<unsigned int *>(h64), *const hw = hc + SEL_BINS;   // the last workgroup's view, later
     __shared__ long long gcnt[AL_THREADS], gwgt[AL_THREADS];
     __shared__ bool is_last;
-    for (int b = threadIdx.x; b < SEL_BINS; b += AL_THREADS) { hc[b] = 0; hw[b] = 0; }
+    for (int b = threadIdx.x; b < SEL_BINS; b += AL_THREADS) h64[b] = 0ull;
     __syncthreads();
     const long long N = st->N;
     const int P = st->P;
@@ -214,16 +216,12 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
             const unsigned long long hi = sh_prefix >= 64 ? 0ull : (s >> sh_prefix);
             if (hi != prefix) continue;
             const unsigned int d = (unsigned int)(s >> sh_digit) & dmask;
-            atomicAdd(&hc[d], 1u);
-            atomicAdd(&hw[d], (unsigned int)(key[u] & 255u));
+            atomicAdd(&h64[d], ((key[u] & 255ull) << 32) | 1ull);
         }
     }
     __syncthreads();
     for (int b = threadIdx.x; b < SEL_BINS; b += AL_THREADS)
-        if (hc[b]) {
-            atomicAdd(&job->hist_cnt[b], hc[b]);
-            atomicAdd(&job->hist_w[b], hw[b]);
-        }
+        if (h64[b]) atomicAdd(&job->hist[b], h64[b]);
     // Everything the workgroups exchange goes through device-scope atomics, which are performed at the
     // point of coherence: waiting for their acknowledgement (vmcnt) orders them before the ticket.  A
     // release fence would also write the L2 back, which costs more than the rest of the pass.
@@ -239,11 +237,16 @@ void select_pass_kernel(AllocState *st, int job_id, const unsigned long long *__
     // the SEL_BINS/256 consecutive bins [t*G, (t+1)*G)
     constexpr int G = SEL_BINS / AL_THREADS;
     long long gc = 0, gw = 0;
+    unsigned long long got[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+        got[j] = __hip_atomic_exchange(&job->hist[threadIdx.x * G + j], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // (every thread read its part of h64 before the barriers above: it can be reused as hc / hw)
 #pragma unroll
     for (int j = 0; j < G; ++j) {
         const int b = threadIdx.x * G + j;
-        hc[b] = __hip_atomic_exchange(&job->hist_cnt[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        hw[b] = __hip_atomic_exchange(&job->hist_w[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        hc[b] = (unsigned int)got[j];
+        hw[b] = (unsigned int)(got[j] >> 32);
         gc += hc[b]; gw += hw[b];
     }
     // suffix sums over the groups (descending order = from the last group down): group t fits whole,
