@@ -499,3 +499,23 @@ def test_mp_gemm_llm_scale_projection(orc, mix):
             mag = np.abs(ref).max()
             assert np.abs(got - ref).max() <= 2e-4 * mag, (I, float(np.abs(got - ref).max()), float(mag))
     plan.close(); ctx.close()
+
+
+def test_sweeps_of_the_search_space_behave_as_the_ablations_say(capsys):
+    """`python -m paper_2602_17698_amd.sweep` on one decoder layer: every search meets its budget, and the
+    orderings the paper's ablations report hold for the search's own objective: mixed precision beats uniform
+    at the same budget, a wider candidate set is never worse, the update rate hardly matters on a static table."""
+    say("sweep, one layer")
+    from paper_2602_17698_amd import sweep
+    import json
+    assert sweep.main(["--layers", "1", "--json"]) == 0
+    rows = [json.loads(l) for l in capsys.readouterr().out.splitlines() if l.startswith("{")]
+    assert len(rows) >= 20 and all(r["status"] == 0 and r["bits_used"] <= r["bits_budget"] for r in rows)
+    uni = next(r for r in rows if r["sweep"] == "uniform")["objective"]
+    space = {tuple(r["bits"]): r["objective"] for r in rows if r["sweep"] == "space"}
+    full, low4 = space[tuple(range(1, 9))], space[(1, 2, 3, 4)]
+    assert full < low4 < uni                                   # capping the candidates at 4 bits costs
+    assert space[tuple(range(0, 9))] <= full * 1.001           # adding 0 bits does not
+    assert space[(3, 4, 5, 6, 7, 8)] == uni                    # nothing below 3 bits at budget 3: uniform
+    g = [r["objective"] for r in rows if r["sweep"] == "gamma0"]
+    assert max(g) <= min(g) * 1.01
