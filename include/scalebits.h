@@ -359,9 +359,12 @@ int  sbits_dequant(sbits_plan *plan, int mat, const uint8_t *level, const int64_
  * permuted input channels and y by its permuted output channels (the paper stores
  * the permuted weights and keeps connected layers consistent, App. "Channel
  * Reordering").  x_bf16: [batch][ld_x] bfloat16, 16-byte aligned, ld_x >= cols and a
- * multiple of 8; y: [batch][rows] float32; batch >= 1 (32 rows of x per kernel launch:
- * the kernel is built for the small batches of decoding).  Products are exact (integer codes times bf16) and summed in fp32 on the
- * matrix cores; scale and zero are applied per block row in fp32.
+ * multiple of 8; y: [batch][rows] float32; batch >= 1.  The kernel is built for the
+ * small batches of decoding: 32 rows of x per launch, each launch reading the whole
+ * code stream of the matrix; for large batches (prefill) take sbits_dequant to bf16
+ * once and an ordinary dense product instead.  Products are exact (integer codes
+ * times bf16) and summed in fp32 on the matrix cores; scale and zero are applied per
+ * block row in fp32.
  * SBITS_ERR_UNIMPLEMENTED unless block_cols is 64 or 128 and block_rows a multiple
  * of 32.  Uses ws.                                                               */
 int  sbits_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, int batch,
