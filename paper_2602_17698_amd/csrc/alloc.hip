@@ -571,6 +571,19 @@ static int ceil_log2_ll(long long v) { int p = 0; while ((1ll << p) < v) ++p; re
 
 using namespace sbits;
 
+// The start state on the device without waiting for the stream: the selection jobs (all zero) by a fill,
+// the head through the context's page-locked buffer.  The buffer is free here (every call that uses it
+// ends with a wait) and is next written by this call's own read-backs, which follow the upload in stream
+// order; a pageable source would need a wait before the host image may change.
+static hipError_t upload_state(sbits_ctx *ctx, AllocState *st, const AllocState &h, AllocState *pinned_head)
+{
+    constexpr size_t HEAD = offsetof(AllocState, job);
+    memcpy(pinned_head, &h, HEAD);
+    hipError_t e = hipMemsetAsync(reinterpret_cast<char *>(st) + HEAD, 0, sizeof(AllocState) - HEAD, ctx->stream);
+    if (e != hipSuccess) return e;
+    return hipMemcpyAsync(st, pinned_head, HEAD, hipMemcpyHostToDevice, ctx->stream);
+}
+
 // workspace: AllocState | keyU [N] | keyD [N] | trace [TRACE_CAP]
 size_t sbits_alloc_ws_bytes(int64_t N)
 {
@@ -629,8 +642,7 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     if (all_max) h.done = 1;
 
     const unsigned grid = (unsigned)((N + AL_THREADS - 1) / AL_THREADS < 1024 ? (N + AL_THREADS - 1) / AL_THREADS : 1024);
-    SBITS_HIP(ctx, hipMemcpyAsync(st, &h, sizeof h, hipMemcpyHostToDevice, sm));
-    SBITS_HIP(ctx, hipStreamSynchronize(sm));  // h is reused below
+    SBITS_HIP(ctx, upload_state(ctx, st, h, hp));
     hipLaunchKernelGGL(max_cost_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, cost, (long long)(N * K), st);
     hipLaunchKernelGGL(init_state_kernel, dim3(1), dim3(1), 0, sm, st, ceil_log2_ll(N));
     hipLaunchKernelGGL(fill_level_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, level, (long long)N, (uint8_t)l0);
@@ -728,6 +740,8 @@ int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, 
     h.IB = ceil_log2_ll(N) > 0 ? ceil_log2_ll(N) : 1;
     h.P = (32 + h.IB + SEL_DB - 1) / SEL_DB;
     for (int c = 0; c < MAX_CAND; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
+    // (a call without host_out returns without waiting, so the page-locked buffer may still be feeding the
+    // previous call's upload: this one goes from the pageable image and waits for it)
     SBITS_HIP(ctx, hipMemcpyAsync(st, &h, sizeof h, hipMemcpyHostToDevice, sm));
     SBITS_HIP(ctx, hipStreamSynchronize(sm));      // the image goes away on return
 
