@@ -653,19 +653,44 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     const int P = h.P;
     // the selection passes end in one global atomic per non-empty bin and workgroup: few, fat workgroups
     const unsigned sgrid = (unsigned)((N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) < SEL_MAXWG ? (N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) : SEL_MAXWG);
-    while (!done) {
+    if (!ctx->readback) SBITS_HIP(ctx, hipEventCreateWithFlags(&ctx->readback, hipEventDisableTiming));
+    constexpr size_t HEAD = offsetof(AllocState, job);
+    // A read-back ends in an event of its own: the host waits for the event, not for the stream, so the
+    // work enqueued behind the read-back keeps the device busy during the host's round trip.
+    auto read_back = [&]() -> hipError_t {
+        hipError_t e = hipMemcpyAsync(hp, st, HEAD, hipMemcpyDeviceToHost, sm);
+        return e != hipSuccess ? e : hipEventRecord(ctx->readback, sm);
+    };
+    auto wait_state = [&]() -> hipError_t {
+        hipError_t e = hipEventSynchronize(ctx->readback);
+        if (e == hipSuccess) memcpy(&h, hp, HEAD);
+        return e;
+    };
+    auto launch_gains = [&]() {
         hipLaunchKernelGGL(gains_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level, keyU, keyD);
+    };
+    // One expansion attempt: its selection, decision and application, the read-back of the state, and the
+    // keys of whatever iteration comes next (every iteration starts with them, so they are requested
+    // before the host knows the outcome: computed once too often after the last iteration, and after an
+    // attempt that raised nothing, with the same values).
+    auto enqueue_expand = [&]() -> hipError_t {
+        for (int ps = 0; ps < P; ++ps)
+            hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_E, keyU,
+                               (const unsigned long long *)nullptr, 0, ps);
+        hipLaunchKernelGGL(decide_expand_kernel, dim3(1), dim3(1), 0, sm, st, tr);
+        hipLaunchKernelGGL(apply_expand_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, level);
+        hipError_t e = hipGetLastError();
+        if (e == hipSuccess) e = read_back();
+        launch_gains();
+        return e;
+    };
+
+    if (!done) launch_gains();
+    while (!done) {
         bool expanded = false;
         if (h.T - used > 0) {
-            for (int ps = 0; ps < P; ++ps)
-                hipLaunchKernelGGL(select_pass_kernel, dim3(sgrid), dim3(AL_THREADS), 0, sm, st, (int)JOB_E, keyU,
-                                   (const unsigned long long *)nullptr, 0, ps);
-            hipLaunchKernelGGL(decide_expand_kernel, dim3(1), dim3(1), 0, sm, st, tr);
-            hipLaunchKernelGGL(apply_expand_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, level);
-            SBITS_HIP(ctx, hipGetLastError());
-            SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
-            SBITS_HIP(ctx, hipStreamSynchronize(sm));
-            memcpy(&h, hp, offsetof(AllocState, job));
+            SBITS_HIP(ctx, enqueue_expand());
+            SBITS_HIP(ctx, wait_state());
             expanded = h.mode == MODE_EXPAND;
         }
         if (!expanded) {
@@ -683,9 +708,9 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
             hipLaunchKernelGGL(decide_swap_kernel, dim3(1), dim3(1), 0, sm, st, tr);
             hipLaunchKernelGGL(apply_swap_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, keyU, keyD, level);
             SBITS_HIP(ctx, hipGetLastError());
-            SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
-            SBITS_HIP(ctx, hipStreamSynchronize(sm));
-            memcpy(&h, hp, offsetof(AllocState, job));
+            SBITS_HIP(ctx, read_back());
+            launch_gains();
+            SBITS_HIP(ctx, wait_state());
         }
         used = h.used;
         done = h.done != 0;

@@ -38,6 +38,7 @@ int sbits_create(sbits_ctx **out, int device, void *hip_stream)
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->last_hip = 0;
     c->pinned = nullptr;
+    c->readback = nullptr;
     if (device >= 0) {
         hipError_t e = hipSetDevice(device);
         if (e != hipSuccess) { c->last_hip = (int)e; delete c; return SBITS_ERR_HIP; }
@@ -50,6 +51,7 @@ int sbits_destroy(sbits_ctx *ctx)
 {
     if (!ctx) return SBITS_ERR_INVALID_ARG;
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    if (ctx->readback) (void)hipEventDestroy(ctx->readback);
     delete ctx;
     return SBITS_OK;
 }

@@ -16,6 +16,7 @@ struct sbits_ctx {
     hipStream_t stream;
     int last_hip;
     void *pinned;          // small page-locked host buffer for state read-backs (allocated on first use)
+    hipEvent_t readback;   // marks the end of a state read-back in the stream (created on first use)
 };
 constexpr size_t SBITS_PINNED_BYTES = 4096;
 
