@@ -322,7 +322,8 @@ typedef struct {
     float   *cost;         /* [N][K]                                                         */
     uint8_t *level;        /* [N]                                                            */
     int64_t *byte_off;     /* [N+1]                                                          */
-    uint8_t *codes;        /* codes_capacity bytes (>= sbits_codes_bytes_bound)              */
+    uint8_t *codes;        /* codes_capacity bytes (>= sbits_codes_bytes_bound); may be NULL */
+                           /* when that bound is 0 (a budget of 0 bits: every block pruned)  */
     int64_t  codes_capacity;
     float   *scale, *zero; /* [N*m] each                                                     */
 } sbits_outputs;

@@ -458,11 +458,12 @@ static int search_impl(sbits_plan *plan, const sbits_matrix *mats, const Couplin
                        const sbits_params *params, const sbits_outputs *out, sbits_stats *host_stats, void *ws)
 {
     if (!plan || !mats || !params || !out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
-    if (!out->row_perm || !out->col_perm || !out->cost || !out->level ||
-        !out->byte_off || !out->codes || !out->scale || !out->zero)
+    if (!out->row_perm || !out->col_perm || !out->cost || !out->level || !out->byte_off || !out->scale || !out->zero)
         return SBITS_ERR_INVALID_ARG;
     if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
     if (out->codes_capacity < sbits_codes_bytes_bound(plan, avg_bits)) return SBITS_ERR_CAPACITY;
+    // (a budget of 0 bits prunes every block: no code is ever written, so no buffer is needed)
+    if (!out->codes && sbits_codes_bytes_bound(plan, avg_bits) > 0) return SBITS_ERR_INVALID_ARG;
     int rc = need_device(plan);
     if (rc) return rc;
     if ((rc = check_all(plan, mats, true, true))) return rc;

@@ -741,6 +741,21 @@ def test_search_with_a_pruned_candidate(orc, ctx, dev):
     assert not ref["scale"].reshape(-1, 64)[pruned].any()
 
 
+@pytest.mark.parametrize("bits,avg", [([2, 4, 8], 8.0), ([0, 2, 4], 0.0), ([0, 2, 4], 0.3)])
+def test_search_at_the_ends_of_the_budget_range(orc, ctx, dev, bits, avg):
+    """Budget = the largest candidate (everything at the top level, 8-bit codes), budget 0 with a 0-bit candidate
+    (everything pruned: an empty code stream, no buffer) and a budget that keeps only a few blocks."""
+    say("search, budget", avg, "of", bits)
+    shapes = [(256, 512), (128, 1024)]
+    mats = [synth.make_matrix("student_t", r, c, seed=8, tid=i) for i, (r, c) in enumerate(shapes)]
+    ref = oracle_search(orc, mats, 64, 128, bits, avg)
+    rc, st, o, shp = gpu_search(ctx, dev, mats, 64, 128, bits, avg)
+    compare_search(orc, ref, rc, st, o, shp, 64)
+    assert st["bits_used"] <= st["bits_budget"]
+    if avg == 0.0:
+        assert o["codes"].numel() == 0 and not ref["level"].any()
+
+
 def test_search_is_deterministic(ctx, dev):
     say("determinism")
     mats = [synth.make_matrix("student_t", 512, 1024, seed=11, tid=i) for i in range(3)]
