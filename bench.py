@@ -303,6 +303,16 @@ def main():
                      "launches_per_step": launches, "avg_launch_ms": cost_ms / launches,
                      "algorithmic_bytes_per_launch": cost_bytes / launches},
     }
+    # the whole step against the same roofline: what the route has to move (S once for the scores, W and S
+    # once for the table, W once more and the packed output for the codes; two-pass: the reordered copies
+    # written and read as well) over the wall time of a step
+    packed = int(byte_off[-1].item()) + 8 * N * m
+    perms = 4 * (row_perm.numel() + col_perm.numel())
+    path_bytes = (nw * 4) + (nw * 6 + N * K * 4 + perms) + (nw * 2 + packed + perms) if one_pass else \
+                 (nw * 4) + (nw * 12 + perms) + (nw * 6 + N * K * 4) + (nw * 2 + packed)
+    out["whole_path"] = {"algorithmic_bytes_per_step": path_bytes, "GBs": path_bytes / (ms_per_step * 1e-3) / 1e9,
+                         "frac_of_hbm_peak": path_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "bytes_per_weight": path_bytes / nw}
     if one_pass and not args.no_route_check:
         # the two-pass route beside it, outside the timed region: its cost kernel alone (a5 as a
         # separate pass over reordered copies) and the bit-equality of the two tables
