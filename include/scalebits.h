@@ -13,6 +13,9 @@
  *     comment says HOST.  The library allocates no device memory; scratch is
  *     the caller's workspace `ws` of sbits_workspace_bytes() bytes, 256-byte
  *     aligned.  Calls that share a workspace must not overlap in time.
+ *   - A context and its plans keep small host-side tables that calls fill in on
+ *     first use: calls on one context (or on plans of one context) must not run
+ *     concurrently from several host threads.  Different contexts are independent.
  *   - All work is enqueued on the stream given to sbits_create() and the call
  *     returns without waiting, except where stated (sbits_allocate and
  *     sbits_search wait for the stream because they return host results).
