@@ -291,6 +291,18 @@ int  sbits_propose(sbits_plan *plan, const float *s_up, const float *s_down,
 /* ---- storage (paper Sec. 5.3: one bitwidth per tile) --------------------------
  * byte_off[i] = sum_{i'<i} m*n*c[level[i']]/8, byte_off[N] = total.  Uses ws.   */
 int  sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws);
+/* The same without a workspace, for callers that cannot allocate device memory or
+ * hand one over: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  The scan's partial sums live in a fixed array in the library's
+ * device image (32 KiB per GPU, held until the process ends), enough for plans of at
+ * most SBITS_OFFSETS_STATIC_MAX_BLOCKS blocks; larger plans get SBITS_ERR_WORKSPACE
+ * (checked on the host before anything else, also on a host-only context).  The
+ * call allocates nothing and enqueues kernels only; output identical to
+ * sbits_offsets.  Every call on one GPU shares that GPU's array: calls that overlap
+ * in time on one GPU (two streams, two contexts) race; calls in stream order do not
+ * (each call overwrites the part of the array it reads).                          */
+#define SBITS_OFFSETS_STATIC_MAX_BLOCKS 8388608
+int  sbits_offsets_static(sbits_plan *plan, const uint8_t *level, int64_t *byte_off);
 /* Re-quantizes matrix `mat` at the chosen bitwidths and writes, for each of its
  * blocks b (global id), the codes at codes[byte_off[b]...]: element e (row-major
  * in the block) occupies bits [e*c, (e+1)*c) of the block's little-endian bit

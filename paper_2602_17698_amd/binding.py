@@ -16,6 +16,7 @@ OK = 0
 ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_BAD_BITWIDTHS, ERR_INFEASIBLE_BUDGET = -1, -2, -3, -4
 DIM_INDEPENDENT, DIM_FIXED = -1, -2
 ERR_WORKSPACE, ERR_MAX_ITERS, ERR_HIP, ERR_UNIMPLEMENTED, ERR_CAPACITY = -5, -6, -7, -8, -9
+OFFSETS_STATIC_MAX_BLOCKS = 8388608          # SBITS_OFFSETS_STATIC_MAX_BLOCKS of the header
 
 EXPORTS = [
     "sbits_create", "sbits_destroy", "sbits_last_hip_error", "sbits_strerror",
@@ -25,7 +26,7 @@ EXPORTS = [
     "sbits_cost_table", "sbits_cost_table_all", "sbits_cost_power", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
     "sbits_reorder_coupled_all", "sbits_surrogates_all",
-    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_pack", "sbits_search", "sbits_search_coupled", "sbits_mp_gemm", "sbits_dequant",
+    "sbits_allocate", "sbits_propose", "sbits_offsets", "sbits_offsets_static", "sbits_pack", "sbits_search", "sbits_search_coupled", "sbits_mp_gemm", "sbits_dequant",
 ]
 
 
@@ -296,6 +297,10 @@ class Plan:
 
     def offsets(self, level, byte_off, ws):
         return _check(load().sbits_offsets(self.h, _ptr(level), _ptr(byte_off), _ptr(ws)), "sbits_offsets")
+
+    def offsets_static(self, level, byte_off):
+        """sbits_offsets on the library's fixed per-GPU scratch array: no workspace, no allocation."""
+        return _check(load().sbits_offsets_static(self.h, _ptr(level), _ptr(byte_off)), "sbits_offsets_static")
 
     def pack(self, mat, w_re, level, byte_off, codes, scale, zero):
         return _check(load().sbits_pack(self.h, C.c_int(mat), _ptr(w_re), _ptr(level), _ptr(byte_off),

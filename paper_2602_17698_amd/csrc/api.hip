@@ -42,6 +42,8 @@ int sbits_create(sbits_ctx **out, int device, void *hip_stream)
     if (device >= 0) {
         hipError_t e = hipSetDevice(device);
         if (e != hipSuccess) { c->last_hip = (int)e; delete c; return SBITS_ERR_HIP; }
+        const int rc = sbits_offsets_static_setup(c);     // this device's fixed scratch array, looked up once
+        if (rc) { delete c; return rc; }
     }
     *out = c;
     return SBITS_OK;
@@ -420,6 +422,15 @@ int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, voi
     if (rc) return rc;
     return sbits_launch_offsets(plan->ctx, level, plan->N, plan->m, plan->n, plan->bits, plan->K, byte_off,
                                 sbits_scratch(plan, ws));
+}
+
+int sbits_offsets_static(sbits_plan *plan, const uint8_t *level, int64_t *byte_off)
+{
+    if (!plan || !level || !byte_off) return SBITS_ERR_INVALID_ARG;
+    if (plan->N > SBITS_OFFSETS_STATIC_MAX_BLOCKS) return SBITS_ERR_WORKSPACE;
+    int rc = need_device(plan);
+    if (rc) return rc;
+    return sbits_launch_offsets_static(plan->ctx, level, plan->N, plan->m, plan->n, plan->bits, plan->K, byte_off);
 }
 
 int sbits_pack(sbits_plan *plan, int mat, const void *w_re_bf16, const uint8_t *level,

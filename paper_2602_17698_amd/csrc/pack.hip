@@ -10,6 +10,8 @@
 //           a row stage their bytes in LDS and the row is written out as dwords.
 #include <string.h>
 
+#include <mutex>
+
 #include "pack_core.hpp"
 #include "sbits_device.hpp"
 #include "sbits_internal.hpp"
@@ -243,6 +245,46 @@ size_t sbits_offsets_ws_bytes(int64_t N)
 {
     const int64_t ntiles = (N + OF_TILE - 1) / OF_TILE;
     return sbits_align_up((size_t)ntiles * 8, 256);
+}
+
+// ---- offsets without a caller workspace ---------------------------------------------
+// The tile sums of the scan in a fixed device array instead of the caller's workspace, for
+// callers that cannot allocate one.  Each GPU holds its own copy of the array at its own
+// address; the address is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) long long scratch[SBITS_OFFSETS_STATIC_MAX_BLOCKS / OF_TILE];
+static_assert(SBITS_OFFSETS_STATIC_MAX_BLOCKS % OF_TILE == 0, "whole tiles");
+
+constexpr int OF_MAX_DEVICES = 64;
+static std::mutex g_scratch_lock;
+static long long *g_scratch_ptr[OF_MAX_DEVICES];     // device address of scratch[], per device ordinal
+
+// Device address of this GPU's scratch array (ctx->device must be the current device).
+int sbits_offsets_static_setup(sbits_ctx *ctx)
+{
+    if (ctx->device < 0 || ctx->device >= OF_MAX_DEVICES) return SBITS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[ctx->device]) {
+        long long *ptr = nullptr;
+        SBITS_HIP(ctx, hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)));
+        if (!ptr) return SBITS_ERR_HIP;
+        g_scratch_ptr[ctx->device] = ptr;
+    }
+    return SBITS_OK;
+}
+
+int sbits_launch_offsets_static(sbits_ctx *ctx, const uint8_t *level, int64_t N, int m, int n,
+                                const int32_t *bits, int K, int64_t *byte_off)
+{
+    if (N > SBITS_OFFSETS_STATIC_MAX_BLOCKS) return SBITS_ERR_WORKSPACE;
+    if (ctx->device < 0 || ctx->device >= OF_MAX_DEVICES) return SBITS_ERR_HIP;
+    long long *ptr;
+    {
+        std::lock_guard<std::mutex> hold(g_scratch_lock);
+        ptr = g_scratch_ptr[ctx->device];
+    }
+    if (!ptr) return SBITS_ERR_HIP;                  // sbits_create resolves it; never the array's host-side name
+    // every tile sum in use is written by the first kernel before the others read it: nothing to clear
+    return sbits_launch_offsets(ctx, level, N, m, n, bits, K, byte_off, ptr);
 }
 
 int sbits_launch_offsets(sbits_ctx *ctx, const uint8_t *level, int64_t N, int m, int n,

@@ -126,6 +126,9 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
                        sbits_trace *host_trace, int64_t trace_cap, void *ws);
 int sbits_launch_offsets(sbits_ctx *ctx, const uint8_t *level, int64_t N, int m, int n,
                          const int32_t *bits, int K, int64_t *byte_off, void *ws);
+int sbits_offsets_static_setup(sbits_ctx *ctx);
+int sbits_launch_offsets_static(sbits_ctx *ctx, const uint8_t *level, int64_t N, int m, int n,
+                                const int32_t *bits, int K, int64_t *byte_off);
 int sbits_launch_pack(sbits_ctx *ctx, const void *Wp, int64_t R, int64_t C, int m, int n,
                       const int32_t *bits, int K, const uint8_t *level, const int64_t *byte_off,
                       int64_t block_base, uint8_t *codes, float *scale, float *zero);
