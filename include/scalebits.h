@@ -228,7 +228,9 @@ int  sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *
  * (reordered weights, what sbits_pack_all reads) unless it is NULL:
  * sbits_gather_pack_all does not need it.  Supported for 64- and 128-column
  * blocks, rows of at most 16384 elements, and source rows that start on 16-byte
- * boundaries (w_bf16, sens 16-byte aligned, ld_w % 8 == 0, ld_s % 4 == 0);
+ * boundaries (w_bf16, sens 16-byte aligned, ld_w % 8 == 0, ld_s % 4 == 0), on a
+ * device whose memories run with error correction (target id "sramecc+", as every
+ * MI355X reports: the kernel relies on how 16-bit register loads behave there);
  * otherwise returns SBITS_ERR_UNIMPLEMENTED and writes nothing: use the two calls
  * above.  sbits_gather_cost_supported: 1 if the plan's shapes qualify (the
  * alignment of the matrices is checked by the call itself), else 0.  Uses ws.     */

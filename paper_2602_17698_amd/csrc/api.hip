@@ -39,11 +39,16 @@ int sbits_create(sbits_ctx **out, int device, void *hip_stream)
     c->last_hip = 0;
     c->pinned = nullptr;
     c->readback = nullptr;
+    c->d16_zero_fill = true;
     if (device >= 0) {
         hipError_t e = hipSetDevice(device);
         if (e != hipSuccess) { c->last_hip = (int)e; delete c; return SBITS_ERR_HIP; }
         const int rc = sbits_offsets_static_setup(c);     // this device's fixed scratch array, looked up once
         if (rc) { delete c; return rc; }
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, device);
+        if (e != hipSuccess) { c->last_hip = (int)e; delete c; return SBITS_ERR_HIP; }
+        c->d16_zero_fill = strstr(prop.gcnArchName, "sramecc+") != nullptr;
     }
     *out = c;
     return SBITS_OK;
@@ -334,6 +339,7 @@ int sbits_surrogates_all(sbits_plan *plan, const sbits_matrix *mats, const int32
     if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
+    if (!sbits_fused_layout_ok(plan, true)) return SBITS_ERR_UNIMPLEMENTED;
     return sbits_launch_surrogates_all(plan, row_perm, col_perm, level, s_up, s_down, ws);
 }
 

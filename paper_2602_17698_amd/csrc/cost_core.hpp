@@ -62,15 +62,32 @@ struct DivPlan {
     }
 };
 
+// minimum / maximum of a lane's 8 elements as a chain (three 3-operand instructions and one 2-operand)
+__device__ __forceinline__ float min8(const float (&w)[8])
+{
+    float m = fminf(fminf(w[0], w[1]), w[2]);
+    m = fminf(fminf(m, w[3]), w[4]);
+    m = fminf(fminf(m, w[5]), w[6]);
+    return fminf(m, w[7]);
+}
+__device__ __forceinline__ float max8(const float (&w)[8])
+{
+    float m = fmaxf(fmaxf(w[0], w[1]), w[2]);
+    m = fmaxf(fmaxf(m, w[3]), w[4]);
+    m = fmaxf(fmaxf(m, w[5]), w[6]);
+    return fmaxf(m, w[7]);
+}
+
 // One round: NI rows (NI <= DivPlan::RP), each owned by the caller's lane group, the lane holding
-// 8 consecutive elements of every row: raw bf16 weights w[j] and sensitivities s[j][0..7].
+// 8 consecutive elements of every row: weights w[j][0..7] (bf16 values as floats) and sensitivities
+// s[j][0..7].
 // out[j][c] = the lane's partial cost of row j at candidate c (elements left to right,
 // a = fma(s, d*d, a); with SBITS_COST_POWER == 1: a = fma(s, |d|, a)).
 // K counts all candidates.  Z0: candidate 0 is "0 bits" (the block is pruned, paper Sec. 3: its
 // change is the weight itself, d = w); the division plan then holds the other K - 1 grids.
 template <int LPG, int K, int NI, bool Z0>
-__device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const float (&s)[NI][8],
-                                                 const DivPlan<LPG, K - Z0> &dp, float (&out)[NI][K])
+__device__ __forceinline__ void quant_cost_round_f(const float (&w)[NI][8], const float (&s)[NI][8],
+                                                   const DivPlan<LPG, K - Z0> &dp, float (&out)[NI][K])
 {
     using DP = DivPlan<LPG, K - Z0>;
     constexpr int SP = DP::SP, NS = DP::NS;
@@ -78,17 +95,11 @@ __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const 
     float x[NI][8], Rg[NI];
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-        float w[8];
-        unpack8(wraw[j], w);
-        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])),
-                         fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
-        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])),
-                         fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
-        mn = group_allreduce<LPG>(mn, OpMin{});
-        mx = group_allreduce<LPG>(mx, OpMax{});
+        const float mn = group_allreduce<LPG>(min8(w[j]), OpMin{});
+        const float mx = group_allreduce<LPG>(max8(w[j]), OpMax{});
         Rg[j] = mx - mn;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[j][e] = w[e] - mn;
+        for (int e = 0; e < 8; ++e) x[j][e] = w[j][e] - mn;
     }
 
     float val[NS];
@@ -109,11 +120,10 @@ __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const 
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         if constexpr (Z0) {
-            float w[8];
-            unpack8(wraw[j], w);
             float acc = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc = fmaf(s[j][e], SBITS_COST_POWER == 1 ? fabsf(w[e]) : w[e] * w[e], acc);
+            for (int e = 0; e < 8; ++e)
+                acc = fmaf(s[j][e], SBITS_COST_POWER == 1 ? fabsf(w[j][e]) : w[j][e] * w[j][e], acc);
             out[j][0] = acc;
         }
         static_for<0, K - Z0>([&](auto ic) {
@@ -136,6 +146,17 @@ __device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const 
             out[j][Z0 + c] = acc;
         });
     }
+}
+
+// the same from raw bf16 weights (8 consecutive elements per 128-bit word)
+template <int LPG, int K, int NI, bool Z0>
+__device__ __forceinline__ void quant_cost_round(const uint4 (&wraw)[NI], const float (&s)[NI][8],
+                                                 const DivPlan<LPG, K - Z0> &dp, float (&out)[NI][K])
+{
+    float w[NI][8];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) unpack8(wraw[j], w[j]);
+    quant_cost_round_f<LPG, K, NI, Z0>(w, s, dp, out);
 }
 
 // Adjacent-pair tree over the 8 rows of an octet, fed one row at a time: rr is the row's index

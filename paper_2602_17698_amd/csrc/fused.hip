@@ -8,15 +8,14 @@
 // round-to-nearest grids for every candidate bitwidth), with the same fixed summation order,
 // so the table equals the two-pass result bit for bit.
 //
-// Mapping.  A workgroup of 512 threads owns a run of octets (8 output rows each) of one
-// matrix, all columns.  Per step it stages RS source rows (the rows row_perm names) in LDS
-// with fully contiguous 16-byte loads, then every lane picks the 8 source columns of each of
-// its CPL output chunks (chunk = 8 consecutive output columns; LPG adjacent lanes = one
-// quantization group) out of LDS.  The next step's rows are already in flight in registers
-// while the current ones are scored.  A lane keeps the pending levels of the octet's row tree
-// per chunk; at the end of an octet the group's lanes are reduced and the octet's partial sum
-// goes to part[block][octet][candidate]; a second, tiny kernel runs the tree over the octets
-// of each block.
+// Mapping.  A workgroup owns a run of octets (8 output rows each) of one matrix, all columns.
+// Per step it has RS source rows (the rows row_perm names) brought into LDS by direct
+// global-to-LDS loads (no registers in between), then every lane picks the 8 source columns of
+// each of its CPL output chunks (chunk = 8 consecutive output columns; LPG adjacent lanes = one
+// quantization group) out of LDS and scores them while the next step's rows are on their way.
+// The levels of the octet's row tree are compile-time positions of an unrolled run of steps; at
+// the end of an octet the group's lanes are reduced and the octet's partial sum goes to
+// part[block][octet][candidate]; a second, tiny kernel runs the tree over the octets of each block.
 #include <string.h>
 
 #include <vector>
@@ -39,26 +38,69 @@ __device__ __forceinline__ int funi(int v) { return __builtin_amdgcn_readfirstla
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
 typedef __attribute__((address_space(3))) float lds_f32;
 
-// LDS address of a sensitivity from the byte offset of its weight in the staged row.  With
-// OPAQUE the compiler cannot hoist the sum out of the row loop, which would otherwise keep a
-// second address register per element alive (32 more registers at four chunks per lane).
-template <bool OPAQUE>
-__device__ __forceinline__ uint32_t s_address(uint32_t w_off, uint32_t s_base)
-{
-    if constexpr (OPAQUE) {
-        uint32_t r;
-        asm volatile("v_lshl_add_u32 %0, %1, 1, %2" : "=v"(r) : "v"(w_off), "s"(s_base));
-        return r;
-    } else {
-        return 2u * w_off + s_base;
-    }
-}
-
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
 // load in flight, which would expose the latency of the rows being prefetched into registers.
 __device__ __forceinline__ void lds_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// ---- rows into LDS without passing through registers -------------------------------------
+// A wave-wide direct load (16 bytes per lane) writes one contiguous KiB of LDS, "a piece".  The
+// RS source rows of a step are laid out piece by piece with the rows interleaved:
+//   weights        piece p (columns 512p ..) of row r at  Wb + (p * RS + r) * 1024
+//   sensitivities  piece p (columns 256p ..) of row r at  Sb + (p * RS + r) * 1024,  Sb = Wb + nW * RS * 1024
+// so one address register per element serves every row of the step (row r = offset r * 1024 of the
+// LDS instruction).  The loads carry the non-temporal hint: without it the same loop streams 12 %
+// slower.  Lanes past a row's end repeat its last 16 bytes (into the padding of the last piece).
+__device__ __forceinline__ void load_row_pieces(const char *wrow, const char *srow, int nW, int nS, uint32_t wbytes,
+                                                uint32_t sbytes, uint32_t Wb, uint32_t Sb, int RSr, int rs, int wave,
+                                                int nwv, int lane)
+{
+    const uint32_t l16 = (uint32_t)lane * 16u;
+    for (int p = wave; p < nW; p += nwv) {
+        const uint32_t off = min((uint32_t)p * 1024u + l16, wbytes - 16u);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wrow + off),
+                                         (__attribute__((address_space(3))) void *)(Wb + (uint32_t)(p * RSr + rs) * 1024u),
+                                         16, 0, 2);
+    }
+    for (int p = wave; p < nS; p += nwv) {
+        const uint32_t off = min((uint32_t)p * 1024u + l16, sbytes - 16u);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(srow + off),
+                                         (__attribute__((address_space(3))) void *)(Sb + (uint32_t)(p * RSr + rs) * 1024u),
+                                         16, 0, 2);
+    }
+}
+
+// bytes of LDS a step needs: rs rows of cols bf16 weights and (with_s) fp32 sensitivities, in whole pieces
+static inline size_t staged_step_bytes(int64_t cols, int rs, bool with_s)
+{
+    const size_t nW = (size_t)(2 * cols + 1023) / 1024, nS = with_s ? (size_t)(4 * cols + 1023) / 1024 : 0;
+    return (nW + nS) * (size_t)rs * 1024;
+}
+
+// One element out of the staged rows: the weight (bf16) is loaded into the upper half of a register
+// (d16_hi).  On a GPU whose memories run with error correction (the target id says "sramecc+"; every
+// MI355X does) such a load writes the whole register, zeros below: the register then holds the weight
+// as a float, no conversion instruction needed.  (Without error correction the lower half would keep
+// its old contents: the library refuses the one-pass route on such a device.)  The compiler does not
+// see these loads' completion: lds_gather_wait() below stands between them and the first use.
+template <int OFF>
+__device__ __forceinline__ void lds_w_hi(float &w, uint32_t addr)
+{
+    asm volatile("ds_read_u16_d16_hi %0, %1 offset:%2" : "=v"(w) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int OFF>
+__device__ __forceinline__ void lds_s(float &s, uint32_t addr)
+{
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(s) : "v"(addr), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ void lds_gather_wait(float (&w)[8], float (&s)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(w[4]), "+v"(w[5]), "+v"(w[6]), "+v"(w[7]),
+                   "+v"(s[0]), "+v"(s[1]), "+v"(s[2]), "+v"(s[3]), "+v"(s[4]), "+v"(s[5]), "+v"(s[6]), "+v"(s[7])
+                 :: "memory");
 }
 
 // Launched with T = the smallest multiple of 64 threads whose CPL chunks per lane cover a row
@@ -67,8 +109,18 @@ __device__ __forceinline__ void lds_barrier()
 //              "0 bits", the pruned block, and gc holds the other K - 1 grids).
 // SUR = true : the dynamic-sensitivity surrogates (K = 2 sums per block, at the block's current
 //              level[]; the "sensitivity" input is the gradient; gc holds every candidate).
-template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR, bool Z0>
-__global__ __launch_bounds__(TMAX, (TMAX >= 1024 ? 4 : 2))
+// Steps: RS rows each.  Per step: wait for the rows (this wave's loads, then everybody's: barrier),
+// pick the lane's elements out of LDS, barrier (the buffer is free), request the next step's rows,
+// score.  U = 8 / RS (RS = 2) or 2 (RS = 1) steps are unrolled so that the rows' positions in the
+// octet's adjacent-pair tree are compile-time constants.
+// Who talks to global memory: a wave that waits for its row loads (vmcnt 0) would also wait for any
+// store it has issued, and a store's acknowledgement under this read load takes far longer than a
+// load (the octet sums, 16 bytes per block, cost 12 % of the kernel's time that way).  So all waves
+// but the last request rows and never store; the octet sums go through a small LDS table and the
+// last wave, which requests nothing and never waits for vector memory, writes them out one step later.
+// (A workgroup of a single wave does both.)
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0>
+__global__ __launch_bounds__(TMAX, MINW)
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
@@ -78,16 +130,21 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     // kstride, koff: the K sums of an octet go to part[..][koff .. koff + K) of kstride values (a launch
     // may cover a subset of the candidates)
     static_assert(!SUR || (K == 2 && !Z0), "two sums per block");
+    static_assert(RS == 1 || RS == 2, "rows per step");
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int rowsrc[FU_OPU * 8];
     constexpr int NIT = RS * CPL;                    // rows x chunks scored per step
     using DP = DivPlan<LPG, K - Z0>;
-    constexpr int NG = NIT > 2 ? 2 : NIT;            // of which NG are held in registers at a time
-    constexpr int NI = SUR ? NG : (DP::RP < NG ? DP::RP : NG);   // and NI share a round of divisions
-    static_assert(NIT % NG == 0 && NG % NI == 0 && 8 % RS == 0, "step shape");
+    constexpr int NG = NIT > 2 ? 2 : NIT;            // items scored together
+    constexpr int NI = SUR ? NG : (DP::RP < NG ? DP::RP : NG);   // of which NI share a round of divisions
+    constexpr int U = RS == 2 ? 4 : 2;               // steps unrolled: B = U * RS rows with static tree positions
+    constexpr int B = U * RS;
+    constexpr bool SDER = RS == 1 && CPL >= 2;       // sensitivity address derived from the weight's (saves registers)
+    static_assert(NIT % NG == 0 && NG % NI == 0, "step shape");
 
     const int tid = (int)threadIdx.x;
     const int T = (int)blockDim.x;                   // a multiple of 64, at most TMAX
+    const int lane = tid & 63, wave = funi(tid >> 6), nwv = T >> 6;
     const int lig = tid % LPG;
     const int mem = funi(find_matrix(wg_start, n_members, (int)blockIdx.x));
     const MatDesc &d = descs[funi(members[mem])];
@@ -102,8 +159,13 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     const char *const Sg = reinterpret_cast<const char *>(d.s);
     const int64_t pitch_w = d.ld_w * 2, pitch_s = d.ld_s * 4;
 
-    // LDS: weights [RS][C] bf16, then sensitivities [RS][C] fp32 (32-bit LDS addresses below)
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const uint32_t wbytes = 2u * (uint32_t)C, sbytes = 4u * (uint32_t)C;
+    const int nW = (int)((wbytes + 1023u) >> 10), nS = (int)((sbytes + 1023u) >> 10);
+    const uint32_t Wb = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const uint32_t Sb = Wb + (uint32_t)(nW * RS) * 1024u;
+    float *const otab = reinterpret_cast<float *>(smem + (size_t)(nW + nS) * RS * 1024);   // [nbc][K] octet sums
+    const int nld = nwv > 1 ? nwv - 1 : 1;           // waves that request rows
+    const bool loader = wave < nld, storer = wave == nwv - 1;
 
     DP dp;
     dp.init(gc, lig);
@@ -114,10 +176,9 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         rowsrc[i] = sr < 0 ? 0 : (sr >= R ? R - 1 : sr);
     }
 
-    // source columns of this lane's chunks (fixed for the whole run), as byte offsets into a
-    // staged row of weights; twice that is the offset into a row of sensitivities
+    // LDS addresses of the source columns of this lane's chunks (fixed for the whole run), row 0 of a step
     const int nchunk = C >> 3;
-    int ci[CPL][8];
+    uint32_t aw[CPL][8], as[SDER ? 1 : CPL][SDER ? 1 : 8];
     bool valid[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
@@ -128,158 +189,153 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         const int4 b = *reinterpret_cast<const int4 *>(cp + cb + 4);
         const int t[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ci[c][e] = 2 * (t[e] < 0 ? 0 : (t[e] >= C ? C - 1 : t[e]));
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t sc = (uint32_t)(t[e] < 0 ? 0 : (t[e] >= C ? C - 1 : t[e]));
+            aw[c][e] = Wb + (((sc >> 9) * (uint32_t)RS) << 10) + ((sc & 511u) << 1);
+            if constexpr (!SDER) as[c][e] = Sb + (((sc >> 8) * (uint32_t)RS) << 10) + ((sc & 255u) << 2);
+        }
     }
+    const uint32_t sder = Sb - 2u * Wb;              // SDER: sensitivity address = 2 * weight address + sder
     __syncthreads();
 
-    // ---- the rows of a step, as contiguous 16-byte pieces (piece p of a row: bytes 16p..) ----
-    // Lanes past the row's end repeat its last piece (same bytes to the same LDS address), so no
-    // load or store sits under a lane mask.
-    uint32_t offw[CPL], offs[2 * CPL];
+    auto request = [&](int row) {                    // row = first row of the step inside the run
+        int sr[RS];                                  // (read before the first direct load is in flight)
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) offw[c] = (uint32_t)min(tid + T * c, nchunk - 1) * 16u;
+        for (int rs = 0; rs < RS; ++rs) sr[rs] = funi(rowsrc[row + rs]);
+        if (!loader) return;
 #pragma unroll
-    for (int c = 0; c < 2 * CPL; ++c) offs[c] = (uint32_t)min(tid + T * c, 2 * nchunk - 1) * 16u;
-    uint4 pw[RS][CPL];
-    float4 ps[RS][2 * CPL];
-    auto prefetch = [&](int row) {                   // row = first row of the step inside the run
-#pragma unroll
-        for (int rs = 0; rs < RS; ++rs) {
-            const int sr = funi(rowsrc[row + rs]);
-            const char *wrow = Wg + (int64_t)sr * pitch_w;
-            const char *srow = Sg + (int64_t)sr * pitch_s;
-#pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                const u32x4_t v = __builtin_nontemporal_load(
-                    (const __attribute__((address_space(1))) u32x4_t *)(wrow + offw[c]));
-                pw[rs][c] = make_uint4(v.x, v.y, v.z, v.w);
-            }
-#pragma unroll
-            for (int c = 0; c < 2 * CPL; ++c) {
-                const f32x4_t v = __builtin_nontemporal_load(
-                    (const __attribute__((address_space(1))) f32x4_t *)(srow + offs[c]));
-                ps[rs][c] = make_float4(v.x, v.y, v.z, v.w);
-            }
-        }
+        for (int rs = 0; rs < RS; ++rs)
+            load_row_pieces(Wg + (int64_t)sr[rs] * pitch_w, Sg + (int64_t)sr[rs] * pitch_s, nW, nS, wbytes, sbytes, Wb,
+                            Sb, RS, rs, wave, nld, lane);
     };
-    auto stage = [&]() {
+    // the last wave writes the octet sums of octet `og` (in otab since the previous barrier) to part[]
+    int pend_og = -1;
+    auto flush = [&]() {
+        if (pend_og < 0) return;
+        if (storer) {
+            const int I = pend_og / opb, oib = pend_og - I * opb;
+            for (int J = lane; J < nbc; J += 64) {
+                float *dst = part + ((d.block_base + (int64_t)I * nbc + J) * opb + oib) * kstride + koff;
 #pragma unroll
-        for (int rs = 0; rs < RS; ++rs) {
-#pragma unroll
-            for (int c = 0; c < CPL; ++c)
-                *reinterpret_cast<uint4 *>(smem + (size_t)rs * C * 2 + offw[c]) = pw[rs][c];
-#pragma unroll
-            for (int c = 0; c < 2 * CPL; ++c)
-                *reinterpret_cast<float4 *>(smem + (size_t)(RS * 2 + rs * 4) * C + offs[c]) = ps[rs][c];
+                for (int k = 0; k < K; ++k) dst[k] = otab[J * K + k];
+            }
         }
+        pend_og = -1;
     };
 
-    float t1[CPL][K], t2[CPL][K], t3[CPL][K];
+    float t2[CPL][K], t3[CPL][K];                    // upper levels of the octet's row tree (B < 8 only)
     uint16_t *const wout = w_re_all + d.elem_off;
-    const int nsteps = noct * (8 / RS);
+    const int nrows = noct * 8;
     LevelConsts lk[SUR ? CPL : 1];                   // SUR: the current grid of each chunk's block
     int curI = -1;
 
-    prefetch(0);
-    for (int st = 0; st < nsteps; ++st) {
-        stage();
-        lds_barrier();
-        if (st + 1 < nsteps) prefetch((st + 1) * RS);
-
-        const int row = st * RS;                     // first row of the step inside the run
-        const int rr0 = row & 7;
+    request(0);
+    for (int row0 = 0; row0 < nrows; row0 += B) {
+        float t1[CPL][K], s2[CPL][K], s3[CPL][K];    // static levels inside the unrolled rows
         float last[CPL][K];
-        if constexpr (SUR) {
-            const int Inow = (oct0 + (row >> 3)) / opb;          // block row of this step
-            if (Inow != curI) {
-                curI = Inow;
+        static_for<0, U>([&](auto iu) {
+            constexpr int u = decltype(iu)::value;
+            const int row = row0 + u * RS;           // first row of the step inside the run
+            __builtin_amdgcn_sched_barrier(0);                       // (the previous step's arithmetic stays above)
+            if (loader) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's share of the step's rows
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");    // everybody's: the rows are in LDS
+            flush();
+            if constexpr (SUR) {
+                const int Inow = (oct0 + (row >> 3)) / opb;          // block row of this step
+                if (Inow != curI) {
+                    curI = Inow;
 #pragma unroll
-                for (int c = 0; c < CPL; ++c) {
-                    const int J = min((tid + T * c) / LPG, nbc - 1);
-                    lk[c] = level_consts(gc, level[d.block_base + (int64_t)Inow * nbc + J]);
+                    for (int c = 0; c < CPL; ++c) {
+                        const int J = min((tid + T * c) / LPG, nbc - 1);
+                        lk[c] = level_consts(gc, level[d.block_base + (int64_t)Inow * nbc + J]);
+                    }
                 }
             }
-        }
-        // Items (item = rs * CPL + c) are picked out of the staged rows: all LDS reads are issued
-        // here; the items are scored NG at a time, so the reads of the later ones complete under
-        // the arithmetic of the earlier ones.
-        uint4 gwa[NIT];
-        float gsa[NIT][8];
+            // items (item = rs * CPL + c): all LDS reads of the step
+            float wv[NIT][8], gs[NIT][8];
+            static_for<0, NIT>([&](auto iit) {
+                constexpr int it = decltype(iit)::value;
+                constexpr int rs = it / CPL, c = it % CPL;
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int rs = it / CPL, c = it % CPL;
-            const uint32_t wbase = lds0 + (uint32_t)rs * (uint32_t)C * 2u;
-            const uint32_t sbase = lds0 + (uint32_t)(RS * 2 + rs * 4) * (uint32_t)C;
-            uint32_t h[8];
+                for (int e = 0; e < 8; ++e) lds_w_hi<rs * 1024>(wv[it][e], aw[c][e]);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                h[e] = *(const lds_u16 *)(wbase + (uint32_t)ci[c][e]);
-                gsa[it][e] = *(const lds_f32 *)s_address<(CPL >= 4)>((uint32_t)ci[c][e], sbase);
-            }
-            gwa[it] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-        }
-#pragma unroll
-        for (int g0 = 0; g0 < NIT; g0 += NG) {
-            // every read has completed before the last group: the rows may be overwritten from here on
-            if (g0 + NG == NIT) lds_barrier();
-            uint4 gw[NG];
-            float gs[NG][8];
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                gw[g] = gwa[g0 + g];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) gs[g][e] = gsa[g0 + g][e];
-            }
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
-                if (valid[c] && w_re_all) {
-                    const int64_t orow = (int64_t)(oct0 * 8 + row + rs);
-                    u32x4_t sv;
-                    sv.x = gw[g].x; sv.y = gw[g].y; sv.z = gw[g].z; sv.w = gw[g].w;
-                    __builtin_nontemporal_store(sv, (__attribute__((address_space(1))) u32x4_t *)(
-                                                        wout + orow * C + (int64_t)(tid + T * c) * 8));
+                for (int e = 0; e < 8; ++e) {
+                    if constexpr (SDER) {
+                        uint32_t a;
+                        asm volatile("v_lshl_add_u32 %0, %1, 1, %2" : "=v"(a) : "v"(aw[c][e]), "s"(sder));
+                        lds_s<rs * 1024>(gs[it][e], a);
+                    } else {
+                        lds_s<rs * 1024>(gs[it][e], as[c][e]);
+                    }
                 }
-            }
+            });
+            static_for<0, NIT>([&](auto iit) { lds_gather_wait(wv[decltype(iit)::value], gs[decltype(iit)::value]); });
+            asm volatile("s_barrier" ::: "memory");                  // everybody has read: the buffer is free
+            if (row + RS < nrows) request(row + RS);
+            __builtin_amdgcn_sched_barrier(0);
+
 #pragma unroll
-            for (int i0 = 0; i0 < NG; i0 += NI) {
-                uint4 wr[NI];
-                float s[NI][8], out[NI][K];
+            for (int g0 = 0; g0 < NIT; g0 += NG) {
+                if (w_re_all) {
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    wr[j] = gw[i0 + j];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) s[j][e] = gs[i0 + j][e];
+                    for (int g = 0; g < NG; ++g) {
+                        const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
+                        if (valid[c]) {
+                            const int64_t orow = (int64_t)(oct0 * 8 + row + rs);
+                            const float(&w)[8] = wv[g0 + g];
+                            u32x4_t sv;
+                            sv.x = (__float_as_uint(w[0]) >> 16) | __float_as_uint(w[1]);
+                            sv.y = (__float_as_uint(w[2]) >> 16) | __float_as_uint(w[3]);
+                            sv.z = (__float_as_uint(w[4]) >> 16) | __float_as_uint(w[5]);
+                            sv.w = (__float_as_uint(w[6]) >> 16) | __float_as_uint(w[7]);
+                            __builtin_nontemporal_store(sv, (__attribute__((address_space(1))) u32x4_t *)(
+                                                                wout + orow * C + (int64_t)(tid + T * c) * 8));
+                        }
+                    }
                 }
-                if constexpr (SUR) {
-                    LevelConsts lr[NI];
 #pragma unroll
-                    for (int j = 0; j < NI; ++j) lr[j] = lk[(g0 + i0 + j) % CPL];
-                    surrogate_round<LPG, NI>(wr, s, lr, lig, out);
-                } else {
-                    quant_cost_round<LPG, K, NI, Z0>(wr, s, dp, out);
-                }
-                if constexpr (RS == 2 && CPL == 1 && NI == 2) {
-                    // the two items are rows rr0, rr0 + 1 of one chunk: their sum is the tree's first level
+                for (int i0 = 0; i0 < NG; i0 += NI) {
+                    float w[NI][8], s[NI][8], out[NI][K];
 #pragma unroll
-                    for (int k = 0; k < K; ++k)
-                        last[0][k] = octet_tree_push_pair_rt(out[0][k] + out[1][k], rr0 >> 1, t2[0][k], t3[0][k]);
-                } else {
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) { w[j][e] = wv[g0 + i0 + j][e]; s[j][e] = gs[g0 + i0 + j][e]; }
+                    if constexpr (SUR) {
+                        LevelConsts lr[NI];
+#pragma unroll
+                        for (int j = 0; j < NI; ++j) lr[j] = lk[(g0 + i0 + j) % CPL];
+                        surrogate_round<LPG, NI>(w, s, lr, lig, out);
+                    } else {
+                        quant_cost_round_f<LPG, K, NI, Z0>(w, s, dp, out);
+                    }
+                    // The sums are used by a later step's tree addition only: without an opaque use here the
+                    // optimizer sinks the whole arithmetic below the next step's barriers and LDS reads
+                    // (and has to keep copies of every input for it).
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int k = 0; k < K; ++k) asm volatile("" : "+v"(out[j][k]));
 #pragma unroll
                     for (int j = 0; j < NI; ++j) {
                         const int rs = (g0 + i0 + j) / CPL, c = (g0 + i0 + j) % CPL;
+                        const int rr = u * RS + rs;                  // the row's place among the unrolled rows (compile time)
 #pragma unroll
-                        for (int k = 0; k < K; ++k)
-                            last[c][k] = octet_tree_push_rt(out[j][k], rr0 + rs, t1[c][k], t2[c][k], t3[c][k]);
+                        for (int k = 0; k < K; ++k) last[c][k] = octet_tree_push(out[j][k], rr, t1[c][k], s2[c][k], s3[c][k]);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
+        });
+        if constexpr (B < 8) {                       // the unrolled rows' sum enters the tree's upper levels
+            static_assert(B == 2, "pairs of rows");
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    last[c][k] = octet_tree_push_pair_rt(last[c][k], (row0 >> 1) & 3, t2[c][k], t3[c][k]);
         }
 
-        if (rr0 + RS == 8) {                         // an octet is complete: lanes of the group, then out
-            const int og = oct0 + (row >> 3);
-            const int I = og / opb, oib = og - I * opb;
+        if (((row0 + B) & 7) == 0) {                 // an octet is complete: lanes of the group, then out
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
                 float v[K];
@@ -287,13 +343,15 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                 for (int k = 0; k < K; ++k) v[k] = group_allreduce<LPG>(last[c][k], OpAdd{});
                 if (lig == 0 && valid[c]) {
                     const int J = (tid + T * c) / LPG;
-                    float *dst = part + ((d.block_base + (int64_t)I * nbc + J) * opb + oib) * kstride + koff;
 #pragma unroll
-                    for (int k = 0; k < K; ++k) dst[k] = v[k];
+                    for (int k = 0; k < K; ++k) otab[J * K + k] = v[k];
                 }
             }
+            pend_og = oct0 + (row0 >> 3);            // written out after the next barrier
         }
     }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    flush();
 }
 
 // adjacent-pair tree over n <= 8 values p[0], p[stride], ... (n a power of two)
@@ -602,14 +660,14 @@ static int fused_threads(int64_t cols, int cpl, int tmax)
     return (int)(need < 64 ? 64 : (need > tmax ? tmax : need));
 }
 
-template <int LPG, int K, int CPL, int RS, int TMAX, bool SUR, bool Z0>
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int T = fused_threads(a.cols, CPL, TMAX);
-    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, SUR, Z0>;
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, MINW, SUR, Z0>;
     SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
-    const size_t lds = (size_t)RS * a.cols * 6;
+    const size_t lds = staged_step_bytes(a.cols, RS, true) + (size_t)(a.cols / (LPG * 8)) * K * 4;   // rows + octet sums
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc, a.level, a.kstride,
                        a.koff);
@@ -617,13 +675,30 @@ static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
     return SBITS_OK;
 }
 
+// Instances by row length (chunks of 8 columns) and candidate count:
+//   up to 512 chunks : two rows per step; up to four candidates: two chunks per lane in workgroups of up
+//                      to 256 threads (three workgroups = 12 waves per CU at up to 168 registers: three
+//                      independent barrier groups hide each other's waits better than two of 8 waves);
+//                      more candidates: one chunk per lane, up to 512 threads
+//   up to 1024       : two chunks per lane, one row per step
+//   up to 2048       : the same in workgroups of up to 1024 threads (one per CU: the row takes up to
+//                      96 KB of LDS)
 template <int LPG, int K, bool Z0>
 static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int64_t chunks = a.cols / 8;
-    if (chunks <= 512) return launch_fused_g<LPG, K, 1, 2, 512, false, Z0>(ctx, a);
-    if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, false, Z0>(ctx, a);
-    if (chunks <= 2048) return launch_fused_g<LPG, K, 4, 1, 512, false, Z0>(ctx, a);
+    constexpr int MINW = K <= 4 ? 4 : 2;             // waves per SIMD the register budget is set for
+    if (chunks <= 512) {
+        // (the instances named here are the ones whose state fits 168 registers without spilling)
+        if constexpr (K <= 2 || (K <= 4 && !Z0 && LPG == 16)) return launch_fused_g<LPG, K, 2, 2, 256, 3, false, Z0>(ctx, a);
+        else return launch_fused_g<LPG, K, 1, 2, 512, MINW, false, Z0>(ctx, a);
+    }
+    if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, MINW, false, Z0>(ctx, a);
+    if (chunks <= 2048) {
+        // seven or more candidates: two chunks' state does not fit the 128 registers of a 1024-thread workgroup
+        if constexpr (K <= 6) return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0>(ctx, a);
+        else return launch_fused_g<LPG, K, 4, 1, 512, 2, false, Z0>(ctx, a);
+    }
     return SBITS_ERR_BAD_SHAPE;
 }
 
@@ -631,9 +706,9 @@ template <int LPG>
 static int launch_surrogates_l(sbits_ctx *ctx, const FusedLaunch &a)
 {
     const int64_t chunks = a.cols / 8;
-    if (chunks <= 512) return launch_fused_g<LPG, 2, 1, 2, 512, true, false>(ctx, a);
-    if (chunks <= 1024) return launch_fused_g<LPG, 2, 2, 1, 512, true, false>(ctx, a);
-    if (chunks <= 2048) return launch_fused_g<LPG, 2, 4, 1, 512, true, false>(ctx, a);
+    if (chunks <= 512) return launch_fused_g<LPG, 2, 1, 2, 512, 4, true, false>(ctx, a);
+    if (chunks <= 1024) return launch_fused_g<LPG, 2, 2, 1, 512, 4, true, false>(ctx, a);
+    if (chunks <= 2048) return launch_fused_g<LPG, 2, 2, 1, 1024, 4, true, false>(ctx, a);
     return SBITS_ERR_BAD_SHAPE;
 }
 
@@ -723,9 +798,11 @@ size_t sbits_fused_ws_bytes(const sbits_plan *plan)
     return sbits_align_up((size_t)plan->N * (size_t)(plan->m / 8) * per_octet * 4, 256);
 }
 
-// every source row must start on a 16-byte boundary (the rows are staged with 128-bit loads)
+// every source row must start on a 16-byte boundary (the rows are staged with 128-bit loads); the kernels
+// that read sensitivities also rely on 16-bit register-half loads filling the other half with zeros
 bool sbits_fused_layout_ok(const sbits_plan *plan, bool need_s)
 {
+    if (need_s && !plan->ctx->d16_zero_fill) return false;
     for (int i = 0; i < plan->n_mats; ++i) {
         const MatDesc &d = plan->descs[i];
         if ((reinterpret_cast<uintptr_t>(d.w) & 15) || (d.ld_w & 7)) return false;
@@ -802,23 +879,12 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
         a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
         a.cols = fc.cols;
         if (a.total_wg == 0) continue;
-        // Four chunks per lane and seven or more candidates do not fit the register file (three tree
-        // levels per chunk and candidate): such rows take two launches of about half the candidates
-        // each.  The grids are independent per candidate, so the table is the same bit for bit.
-        const bool split = fc.cols / 8 > 1024 && plan->K >= 7;
-        const int k0 = split ? (plan->K + 1) / 2 : plan->K;
-        for (int kb = 0; kb < plan->K; kb += k0) {
-            const int kn = plan->K - kb < k0 ? plan->K - kb : k0;
-            const bool z0 = plan->bits[kb] == 0;                // a 0-bit candidate (the first of the list) has no grid
-            sbits_fill_grid_consts(plan->bits + kb + z0, kn - z0, &a.gc);
-            a.kstride = plan->K;
-            a.koff = kb;
-            uint16_t *const w_keep = a.w_re;
-            if (kb > 0) a.w_re = nullptr;                       // the reordered weights are written once
-            const int rc = plan->n == 64 ? launch_fused_l<8>(kn, z0, ctx, a) : launch_fused_l<16>(kn, z0, ctx, a);
-            a.w_re = w_keep;
-            if (rc) return rc;
-        }
+        const bool z0 = plan->bits[0] == 0;                     // a 0-bit candidate (the first of the list) has no grid
+        sbits_fill_grid_consts(plan->bits + z0, plan->K - z0, &a.gc);
+        a.kstride = plan->K;
+        a.koff = 0;
+        const int rc = plan->n == 64 ? launch_fused_l<8>(plan->K, z0, ctx, a) : launch_fused_l<16>(plan->K, z0, ctx, a);
+        if (rc) return rc;
     }
     const int64_t NK = plan->N * plan->K;
     if (NK > 0) {

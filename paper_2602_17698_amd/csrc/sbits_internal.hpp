@@ -17,6 +17,7 @@ struct sbits_ctx {
     int last_hip;
     void *pinned;          // small page-locked host buffer for state read-backs (allocated on first use)
     hipEvent_t readback;   // marks the end of a state read-back in the stream (created on first use)
+    bool d16_zero_fill;    // 16-bit loads into a register half write zeros to the other half (target id "sramecc+")
 };
 constexpr size_t SBITS_PINNED_BYTES = 4096;
 

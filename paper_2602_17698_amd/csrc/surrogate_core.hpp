@@ -12,18 +12,17 @@
 namespace sbits {
 
 // NI rows ("items"), each owned by the caller's lane group and quantized at its own level k[j];
-// raw weights wraw[j], gradients g[j][0..7].  LPG >= 2 * NI: lane 2j of the group divides
+// weights w[j][0..7] (bf16 values as floats), gradients g[j][0..7].  LPG >= 2 * NI: lane 2j of the group divides
 // qmax_j / R_j, lane 2j + 1 divides R_j / qmax_j, so the items share one division sequence.
 // out[j][0] = the s_up partial, out[j][1] = the s_down partial (before the 2^-b factor).
 template <int LPG, int NI>
-__device__ __forceinline__ void surrogate_round(const uint4 (&wraw)[NI], const float (&g)[NI][8],
+__device__ __forceinline__ void surrogate_round(const float (&w)[NI][8], const float (&g)[NI][8],
                                                 const LevelConsts (&k)[NI], int lig, float (&out)[NI][2])
 {
     static_assert(LPG >= 2 * NI, "one lane per quotient");
-    float w[NI][8], mn[NI], R[NI];
+    float mn[NI], R[NI];
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-        unpack8(wraw[j], w[j]);
         float lo = fminf(fminf(fminf(w[j][0], w[j][1]), fminf(w[j][2], w[j][3])),
                          fminf(fminf(w[j][4], w[j][5]), fminf(w[j][6], w[j][7])));
         float hi = fmaxf(fmaxf(fmaxf(w[j][0], w[j][1]), fmaxf(w[j][2], w[j][3])),
