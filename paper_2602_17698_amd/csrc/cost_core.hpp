@@ -85,14 +85,17 @@ __device__ __forceinline__ float max8(const float (&w)[8])
 // a = fma(s, d*d, a); with SBITS_COST_POWER == 1: a = fma(s, |d|, a)).
 // K counts all candidates.  Z0: candidate 0 is "0 bits" (the block is pruned, paper Sec. 3: its
 // change is the weight itself, d = w); the division plan then holds the other K - 1 grids.
+// The round has two halves so that a caller may fetch the sensitivities while the first runs:
+// quant_cost_prep needs the weights only (row minimum and range, the shared divisions, x = w - min),
+// quant_cost_finish scores the candidates.
 template <int LPG, int K, int NI, bool Z0>
-__device__ __forceinline__ void quant_cost_round_f(const float (&w)[NI][8], const float (&s)[NI][8],
-                                                   const DivPlan<LPG, K - Z0> &dp, float (&out)[NI][K])
+__device__ __forceinline__ void quant_cost_prep(const float (&w)[NI][8], const DivPlan<LPG, K - Z0> &dp,
+                                                float (&x)[NI][8], float (&val)[DivPlan<LPG, K - Z0>::NS])
 {
     using DP = DivPlan<LPG, K - Z0>;
-    constexpr int SP = DP::SP, NS = DP::NS;
+    constexpr int NS = DP::NS;
     static_assert(NI >= 1 && NI <= DP::RP, "too many rows for one round of divisions");
-    float x[NI][8], Rg[NI];
+    float Rg[NI];
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         const float mn = group_allreduce<LPG>(min8(w[j]), OpMin{});
@@ -101,24 +104,48 @@ __device__ __forceinline__ void quant_cost_round_f(const float (&w)[NI][8], cons
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[j][e] = w[j][e] - mn;
     }
-
-    float val[NS];
-    {
-        float Rsel = Rg[0];
+    float Rsel = Rg[0];
 #pragma unroll
-        for (int j = 1; j < NI; ++j)
-            if (dp.my_row == j) Rsel = Rg[j];
+    for (int j = 1; j < NI; ++j)
+        if (dp.my_row == j) Rsel = Rg[j];
 #pragma unroll
-        for (int t = 0; t < NS; ++t) {
-            const float num = dp.is_scale[t] ? Rsel : dp.qf[t];
-            const float den = dp.is_scale[t] ? dp.qf[t] : Rsel;
-            const float v = num / den;           // IEEE correctly rounded
-            val[t] = (Rsel < dp.thr[t]) ? 0.0f : v;
-        }
+    for (int t = 0; t < NS; ++t) {
+        const float num = dp.is_scale[t] ? Rsel : dp.qf[t];
+        const float den = dp.is_scale[t] ? dp.qf[t] : Rsel;
+        const float v = num / den;           // IEEE correctly rounded
+        val[t] = (Rsel < dp.thr[t]) ? 0.0f : v;
     }
+}
 
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
+// x * (the value lane LANE of the caller's 16-lane row holds in val): the broadcast rides on the multiply
+// (v_mul_f32 with a DPP source) instead of taking a move of its own.  val must have been written at least
+// two instructions earlier (the hardware does not interlock a DPP read after a vector write): callers
+// pass it through dpp_settle() first.
+template <int LANE>
+__device__ __forceinline__ float mul_bcast16(float val, float x)
+{
+    float t;
+    asm("v_mul_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+        : "=v"(t) : "v"(val), "v"(x), "n"(LANE));
+    return t;
+}
+__device__ __forceinline__ void dpp_settle(float &val) { asm volatile("s_nop 1" : "+v"(val)); }
+
+// RIDE_OK: let the reciprocal's broadcast ride on the multiply where the group is a DPP row (see
+// mul_bcast16; a kernel that is short of registers does better without: the compiler cannot
+// reschedule around those multiplies as freely).
+template <int LPG, int K, int NI, bool Z0, bool RIDE_OK = false>
+__device__ __forceinline__ void quant_cost_finish(const float (&w)[NI][8], const float (&x)[NI][8],
+                                                  const float (&val)[DivPlan<LPG, K - Z0>::NS],
+                                                  const float (&s)[NI][8], float (&out)[NI][K])
+{
+    using DP = DivPlan<LPG, K - Z0>;
+    constexpr int SP = DP::SP;
+    constexpr bool RIDE = RIDE_OK && LPG == 16 && LPG >= SP;   // the reciprocal's broadcast rides on the multiply
+    float v0 = val[0];
+    if constexpr (RIDE) dpp_settle(v0);
+    static_for<0, NI>([&](auto ij) {
+        constexpr int j = decltype(ij)::value;
         if constexpr (Z0) {
             float acc = 0.0f;
 #pragma unroll
@@ -128,8 +155,10 @@ __device__ __forceinline__ void quant_cost_round_f(const float (&w)[NI][8], cons
         }
         static_for<0, K - Z0>([&](auto ic) {
             constexpr int c = decltype(ic)::value;
-            float inv, scl;
-            if constexpr (LPG >= SP) {
+            float inv = 0.0f, scl;
+            if constexpr (RIDE) {
+                scl = bcast_row<LPG, SP, 2 * c + 1>(v0, j);
+            } else if constexpr (LPG >= SP) {
                 inv = bcast_row<LPG, SP, 2 * c>(val[0], j);
                 scl = bcast_row<LPG, SP, 2 * c + 1>(val[0], j);
             } else {
@@ -139,13 +168,25 @@ __device__ __forceinline__ void quant_cost_round_f(const float (&w)[NI][8], cons
             float acc = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float q = rintf(x[j][e] * inv);
+                float t;
+                if constexpr (RIDE) t = mul_bcast16<((LPG / SP > 1 ? j : 0) * SP + 2 * c) % 16>(v0, x[j][e]);
+                else t = x[j][e] * inv;
+                const float q = rintf(t);
                 const float d = fmaf(-q, scl, x[j][e]);
                 acc = fmaf(s[j][e], SBITS_COST_POWER == 1 ? fabsf(d) : d * d, acc);
             }
             out[j][Z0 + c] = acc;
         });
-    }
+    });
+}
+
+template <int LPG, int K, int NI, bool Z0, bool RIDE_OK = false>
+__device__ __forceinline__ void quant_cost_round_f(const float (&w)[NI][8], const float (&s)[NI][8],
+                                                   const DivPlan<LPG, K - Z0> &dp, float (&out)[NI][K])
+{
+    float x[NI][8], val[DivPlan<LPG, K - Z0>::NS];
+    quant_cost_prep<LPG, K, NI, Z0>(w, dp, x, val);
+    quant_cost_finish<LPG, K, NI, Z0, RIDE_OK>(w, x, val, s, out);
 }
 
 // the same from raw bf16 weights (8 consecutive elements per 128-bit word)

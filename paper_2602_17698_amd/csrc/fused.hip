@@ -15,7 +15,8 @@
 // quantization group) out of LDS and scores them while the next step's rows are on their way.
 // The levels of the octet's row tree are compile-time positions of an unrolled run of steps; at
 // the end of an octet the group's lanes are reduced and the octet's partial sum goes to
-// part[block][octet][candidate]; a second, tiny kernel runs the tree over the octets of each block.
+// part[octet of the matrix][block column][candidate]; a second, tiny kernel runs the tree over the
+// octets of each block.
 #include <string.h>
 
 #include <vector>
@@ -55,16 +56,16 @@ __device__ __forceinline__ void lds_barrier()
 // slower.  Lanes past a row's end repeat its last 16 bytes (into the padding of the last piece).
 __device__ __forceinline__ void load_row_pieces(const char *wrow, const char *srow, int nW, int nS, uint32_t wbytes,
                                                 uint32_t sbytes, uint32_t Wb, uint32_t Sb, int RSr, int rs, int wave,
-                                                int nwv, int lane)
+                                                int nwv, int lane, bool do_w = true, bool do_s = true)
 {
     const uint32_t l16 = (uint32_t)lane * 16u;
-    for (int p = wave; p < nW; p += nwv) {
+    for (int p = wave; do_w && p < nW; p += nwv) {
         const uint32_t off = min((uint32_t)p * 1024u + l16, wbytes - 16u);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wrow + off),
                                          (__attribute__((address_space(3))) void *)(Wb + (uint32_t)(p * RSr + rs) * 1024u),
                                          16, 0, 2);
     }
-    for (int p = wave; p < nS; p += nwv) {
+    for (int p = wave; do_s && p < nS; p += nwv) {
         const uint32_t off = min((uint32_t)p * 1024u + l16, sbytes - 16u);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(srow + off),
                                          (__attribute__((address_space(3))) void *)(Sb + (uint32_t)(p * RSr + rs) * 1024u),
@@ -95,6 +96,12 @@ __device__ __forceinline__ void lds_s(float &s, uint32_t addr)
 {
     asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(s) : "v"(addr), "n"(OFF) : "memory");
 }
+__device__ __forceinline__ void lds_gather_wait(float (&w)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(w[4]), "+v"(w[5]), "+v"(w[6]), "+v"(w[7])
+                 :: "memory");
+}
 __device__ __forceinline__ void lds_gather_wait(float (&w)[8], float (&s)[8])
 {
     asm volatile("s_waitcnt lgkmcnt(0)"
@@ -119,7 +126,13 @@ __device__ __forceinline__ void lds_gather_wait(float (&w)[8], float (&s)[8])
 // but the last request rows and never store; the octet sums go through a small LDS table and the
 // last wave, which requests nothing and never waits for vector memory, writes them out one step later.
 // (A workgroup of a single wave does both.)
-template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0>
+// SLATE (one row per step, cost table only): the sensitivities are read out of LDS while the first half
+// of the arithmetic runs.  Order of a step: weights out of LDS, barrier, request the next row's weights;
+// sensitivities requested from LDS (ordinary loads: the compiler places the wait at their first use),
+// minimum / range / divisions / x meanwhile; barrier, request the next row's sensitivities; candidates.
+// With one workgroup per CU (rows of 8192 elements and more) nobody else would fill the time the LDS
+// needs for the gather.
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false>
 __global__ __launch_bounds__(TMAX, MINW)
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
@@ -141,6 +154,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     constexpr int B = U * RS;
     constexpr bool SDER = RS == 1 && CPL >= 2;       // sensitivity address derived from the weight's (saves registers)
     static_assert(NIT % NG == 0 && NG % NI == 0, "step shape");
+    static_assert(!SLATE || (RS == 1 && !SUR && SDER && NIT == NG), "late sensitivities: one row, one group of items");
 
     const int tid = (int)threadIdx.x;
     const int T = (int)blockDim.x;                   // a multiple of 64, at most TMAX
@@ -198,26 +212,39 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     const uint32_t sder = Sb - 2u * Wb;              // SDER: sensitivity address = 2 * weight address + sder
     __syncthreads();
 
-    auto request = [&](int row) {                    // row = first row of the step inside the run
-        int sr[RS];                                  // (read before the first direct load is in flight)
+    const int nrows = noct * 8, nrows_m1 = nrows - 1;
+    // the source rows of the step that starts at `row` (read from LDS before any direct load or gather
+    // read is in flight: the wait for them would otherwise wait for those as well)
+    struct Rows { int sr[RS]; };
+    auto source_rows = [&](int row) {
+        Rows r;
 #pragma unroll
-        for (int rs = 0; rs < RS; ++rs) sr[rs] = funi(rowsrc[row + rs]);
+        for (int rs = 0; rs < RS; ++rs) {
+            int v = rowsrc[min(row + rs, nrows_m1)];
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v));           // here, not behind the gather reads issued later
+            r.sr[rs] = funi(v);
+        }
+        return r;
+    };
+    auto request = [&](const Rows &r, bool do_w = true, bool do_s = true) {
         if (!loader) return;
 #pragma unroll
         for (int rs = 0; rs < RS; ++rs)
-            load_row_pieces(Wg + (int64_t)sr[rs] * pitch_w, Sg + (int64_t)sr[rs] * pitch_s, nW, nS, wbytes, sbytes, Wb,
-                            Sb, RS, rs, wave, nld, lane);
+            load_row_pieces(Wg + (int64_t)r.sr[rs] * pitch_w, Sg + (int64_t)r.sr[rs] * pitch_s, nW, nS, wbytes, sbytes,
+                            Wb, Sb, RS, rs, wave, nld, lane, do_w, do_s);
     };
     // the last wave writes the octet sums of octet `og` (in otab since the previous barrier) to part[]
     int pend_og = -1;
     auto flush = [&]() {
         if (pend_og < 0) return;
         if (storer) {
-            const int I = pend_og / opb, oib = pend_og - I * opb;
+            // part: per matrix [octet of the matrix][block column][candidate], so that an octet's sums are one
+            // contiguous run of whole cache lines (short writes scattered over many lines cost the read stream
+            // far more than their bytes)
+            float *row = part + ((d.block_base * opb + (int64_t)pend_og * nbc) * kstride + koff);
             for (int J = lane; J < nbc; J += 64) {
-                float *dst = part + ((d.block_base + (int64_t)I * nbc + J) * opb + oib) * kstride + koff;
 #pragma unroll
-                for (int k = 0; k < K; ++k) dst[k] = otab[J * K + k];
+                for (int k = 0; k < K; ++k) row[J * kstride + k] = otab[J * K + k];
             }
         }
         pend_og = -1;
@@ -225,11 +252,100 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 
     float t2[CPL][K], t3[CPL][K];                    // upper levels of the octet's row tree (B < 8 only)
     uint16_t *const wout = w_re_all + d.elem_off;
-    const int nrows = noct * 8;
     LevelConsts lk[SUR ? CPL : 1];                   // SUR: the current grid of each chunk's block
     int curI = -1;
 
-    request(0);
+    // a lane's 8 reordered weights of output row orow, chunk c, as bf16 (the optional W' output)
+    auto store_reordered = [&](const float (&w)[8], int orow, int c) {
+        u32x4_t sv;
+        sv.x = (__float_as_uint(w[0]) >> 16) | __float_as_uint(w[1]);
+        sv.y = (__float_as_uint(w[2]) >> 16) | __float_as_uint(w[3]);
+        sv.z = (__float_as_uint(w[4]) >> 16) | __float_as_uint(w[5]);
+        sv.w = (__float_as_uint(w[6]) >> 16) | __float_as_uint(w[7]);
+        __builtin_nontemporal_store(sv, (__attribute__((address_space(1))) u32x4_t *)(
+                                            wout + (int64_t)orow * C + (int64_t)(tid + T * c) * 8));
+    };
+
+    // SLATE: one step (one row) for a wave that owns NV chunks per lane: NIT, or 1 for the last waves of a
+    // workgroup whose second chunks lie past the row's end (they then skip that chunk's reads and arithmetic
+    // instead of running them on nothing: with rows of 1792 chunks on 16 waves every SIMD gets 7 chunk-waves)
+    constexpr bool SOLO_OK = SLATE && CPL == 2;
+    const bool solo = SOLO_OK && wave * 64 + T >= nchunk;
+    auto slate_step = [&](auto iu, auto inv, int row, const Rows &next, float (&t1)[CPL][K], float (&s2)[CPL][K],
+                          float (&s3)[CPL][K], float (&last)[CPL][K]) {
+        constexpr int u = decltype(iu)::value, NV = decltype(inv)::value;
+        constexpr int NIv = DP::RP < NV ? DP::RP : NV;               // items per round of divisions
+        float wv[NV][8], gs[NV][8];
+        static_for<0, NV>([&](auto iit) {
+            constexpr int it = decltype(iit)::value;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) lds_w_hi<0>(wv[it][e], aw[it][e]);
+        });
+        static_for<0, NV>([&](auto iit) { lds_gather_wait(wv[decltype(iit)::value]); });
+        asm volatile("s_barrier" ::: "memory");                      // everybody has its weights: that buffer is free
+#pragma unroll
+        for (int it = 0; it < NV; ++it)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint32_t a;
+                asm("v_lshl_add_u32 %0, %1, 1, %2" : "=v"(a) : "v"(aw[it][e]), "s"(sder));
+                gs[it][e] = *(const lds_f32 *)a;
+            }
+        if (row + RS < nrows) request(next, true, false);
+        __builtin_amdgcn_sched_barrier(0);
+        if (w_re_all) {
+#pragma unroll
+            for (int it = 0; it < NV; ++it)
+                if (valid[it]) store_reordered(wv[it], oct0 * 8 + row, it);
+        }
+        // first halves of all rounds, then the sensitivities' barrier
+        float xs[NV][8], vals[NV / NIv][DP::NS];
+#pragma unroll
+        for (int i0 = 0; i0 < NV; i0 += NIv) {
+            float w[NIv][8], x[NIv][8];
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[j][e] = wv[i0 + j][e];
+            quant_cost_prep<LPG, K, NIv, Z0>(w, dp, x, vals[i0 / NIv]);
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xs[i0 + j][e] = x[j][e];
+        }
+        // (the first halves' results are operands so that their arithmetic stays above the barrier)
+#pragma unroll
+        for (int r = 0; r < NV / NIv; ++r)
+#pragma unroll
+            for (int t = 0; t < DP::NS; ++t) asm volatile("" : "+v"(vals[r][t]));
+#pragma unroll
+        for (int it = 0; it < NV; ++it)
+            asm volatile("" : "+v"(xs[it][0]), "+v"(xs[it][1]), "+v"(xs[it][2]), "+v"(xs[it][3]),
+                              "+v"(xs[it][4]), "+v"(xs[it][5]), "+v"(xs[it][6]), "+v"(xs[it][7]));
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // everybody has its sensitivities
+        if (row + RS < nrows) request(next, false, true);
+#pragma unroll
+        for (int i0 = 0; i0 < NV; i0 += NIv) {
+            float w[NIv][8], x[NIv][8], sv[NIv][8], out[NIv][K];
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { w[j][e] = wv[i0 + j][e]; x[j][e] = xs[i0 + j][e]; sv[j][e] = gs[i0 + j][e]; }
+            quant_cost_finish<LPG, K, NIv, Z0, true>(w, x, vals[i0 / NIv], sv, out);
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int k = 0; k < K; ++k) asm volatile("" : "+v"(out[j][k]));     // (see the note in the other path)
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    last[i0 + j][k] = octet_tree_push(out[j][k], u, t1[i0 + j][k], s2[i0 + j][k], s3[i0 + j][k]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    request(source_rows(0));
     for (int row0 = 0; row0 < nrows; row0 += B) {
         float t1[CPL][K], s2[CPL][K], s3[CPL][K];    // static levels inside the unrolled rows
         float last[CPL][K];
@@ -240,6 +356,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
             if (loader) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's share of the step's rows
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");    // everybody's: the rows are in LDS
             flush();
+            const Rows next = source_rows(row + RS);                 // (clamped past the end; not requested then)
             if constexpr (SUR) {
                 const int Inow = (oct0 + (row >> 3)) / opb;          // block row of this step
                 if (Inow != curI) {
@@ -250,6 +367,11 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                         lk[c] = level_consts(gc, level[d.block_base + (int64_t)Inow * nbc + J]);
                     }
                 }
+            }
+            if constexpr (SLATE) {
+                if (SOLO_OK && solo) slate_step(iu, std::integral_constant<int, 1>{}, row, next, t1, s2, s3, last);
+                else slate_step(iu, std::integral_constant<int, NIT>{}, row, next, t1, s2, s3, last);
+                return;
             }
             // items (item = rs * CPL + c): all LDS reads of the step
             float wv[NIT][8], gs[NIT][8];
@@ -271,7 +393,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
             });
             static_for<0, NIT>([&](auto iit) { lds_gather_wait(wv[decltype(iit)::value], gs[decltype(iit)::value]); });
             asm volatile("s_barrier" ::: "memory");                  // everybody has read: the buffer is free
-            if (row + RS < nrows) request(row + RS);
+            if (row + RS < nrows) request(next);
             __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
@@ -280,17 +402,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 #pragma unroll
                     for (int g = 0; g < NG; ++g) {
                         const int rs = (g0 + g) / CPL, c = (g0 + g) % CPL;
-                        if (valid[c]) {
-                            const int64_t orow = (int64_t)(oct0 * 8 + row + rs);
-                            const float(&w)[8] = wv[g0 + g];
-                            u32x4_t sv;
-                            sv.x = (__float_as_uint(w[0]) >> 16) | __float_as_uint(w[1]);
-                            sv.y = (__float_as_uint(w[2]) >> 16) | __float_as_uint(w[3]);
-                            sv.z = (__float_as_uint(w[4]) >> 16) | __float_as_uint(w[5]);
-                            sv.w = (__float_as_uint(w[6]) >> 16) | __float_as_uint(w[7]);
-                            __builtin_nontemporal_store(sv, (__attribute__((address_space(1))) u32x4_t *)(
-                                                                wout + orow * C + (int64_t)(tid + T * c) * 8));
-                        }
+                        if (valid[c]) store_reordered(wv[g0 + g], oct0 * 8 + row + rs, c);
                     }
                 }
 #pragma unroll
@@ -306,7 +418,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                         for (int j = 0; j < NI; ++j) lr[j] = lk[(g0 + i0 + j) % CPL];
                         surrogate_round<LPG, NI>(w, s, lr, lig, out);
                     } else {
-                        quant_cost_round_f<LPG, K, NI, Z0>(w, s, dp, out);
+                        quant_cost_round_f<LPG, K, NI, Z0, true>(w, s, dp, out);
                     }
                     // The sums are used by a later step's tree addition only: without an opaque use here the
                     // optimizer sinks the whole arithmetic below the next step's barriers and LDS reads
@@ -329,15 +441,18 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         if constexpr (B < 8) {                       // the unrolled rows' sum enters the tree's upper levels
             static_assert(B == 2, "pairs of rows");
 #pragma unroll
-            for (int c = 0; c < CPL; ++c)
+            for (int c = 0; c < CPL; ++c) {
+                if (c > 0 && solo) continue;
 #pragma unroll
                 for (int k = 0; k < K; ++k)
                     last[c][k] = octet_tree_push_pair_rt(last[c][k], (row0 >> 1) & 3, t2[c][k], t3[c][k]);
+            }
         }
 
         if (((row0 + B) & 7) == 0) {                 // an octet is complete: lanes of the group, then out
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
+                if (c > 0 && solo) continue;
                 float v[K];
 #pragma unroll
                 for (int k = 0; k < K; ++k) v[k] = group_allreduce<LPG>(last[c][k], OpAdd{});
@@ -355,34 +470,55 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 }
 
 // adjacent-pair tree over n <= 8 values p[0], p[stride], ... (n a power of two)
-__device__ __forceinline__ float tree_upto8(const float *__restrict__ p, int stride, int n)
+__device__ __forceinline__ float tree_upto8(const float *__restrict__ p, int64_t stride, int n)
 {
     float v[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = i < n ? p[(int64_t)i * stride] : 0.0f;
+    for (int i = 0; i < 8; ++i) v[i] = i < n ? p[i * stride] : 0.0f;
     if (n == 1) return v[0];
     if (n == 2) return v[0] + v[1];
     if (n == 4) return (v[0] + v[1]) + (v[2] + v[3]);
     return ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
 }
 
+// Where the octet sums of global block b start in part[] (layout per matrix: [octet][block column][sum], ks sums
+// per entry) and the distance between consecutive octets of the block.  The matrix is found by bisection over the
+// descriptors' first block ids.
+__device__ __forceinline__ const float *block_partials(const float *__restrict__ part, const MatDesc *__restrict__ descs,
+                                                       int n_mats, int64_t b, int opb, int ks, int64_t *stride)
+{
+    int lo = 0, hi = n_mats;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (descs[mid].block_base <= b) lo = mid; else hi = mid;
+    }
+    const int64_t base = descs[lo].block_base;
+    const int nbc = descs[lo].nbc;
+    const int64_t bl = b - base;
+    const int64_t I = bl / nbc, J = bl - I * nbc;
+    *stride = (int64_t)nbc * ks;
+    return part + (base * opb + I * opb * nbc + J) * ks;
+}
+
 // cost[b][c] = adjacent-pair tree over the opb octet partials of block b (opb a power of two <= 128)
 __global__ __launch_bounds__(256)
-void octet_finish_kernel(const float *__restrict__ part, int64_t NK, int K, int opb, float *__restrict__ cost)
+void octet_finish_kernel(const float *__restrict__ part, const MatDesc *__restrict__ descs, int n_mats, int64_t NK,
+                         int K, int opb, float *__restrict__ cost)
 {
     const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (q >= NK) return;
     const int64_t b = q / K;
     const int c = (int)(q - b * K);
-    const float *p = part + b * opb * K + c;
+    int64_t so;                                      // distance between the block's consecutive octets
+    const float *p = block_partials(part, descs, n_mats, b, opb, K, &so) + c;
     if (opb <= 8) {
-        cost[q] = tree_upto8(p, K, opb);
+        cost[q] = tree_upto8(p, so, opb);
         return;
     }
     float t1 = 0.0f, t2 = 0.0f, t3 = 0.0f, t4 = 0.0f, v = 0.0f;
     const int ng = opb >> 3;                         // 2 .. 16 groups of 8 octets
     for (int g = 0; g < ng; ++g) {
-        v = tree_upto8(p + (int64_t)g * 8 * K, K, 8);
+        v = tree_upto8(p + (int64_t)g * 8 * so, so, 8);
         if (g & 1) {
             v = t1 + v;
             if (g & 2) {
@@ -592,23 +728,25 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
 
 // surrogates: s_up[b] = tree over the octets of sum 0, s_down[b] = 2^-bits * tree over those of sum 1
 __global__ __launch_bounds__(256)
-void surrogate_finish_kernel(const float *__restrict__ part, int64_t N, int opb, const uint8_t *__restrict__ level,
-                             GridConsts gc, float *__restrict__ s_up, float *__restrict__ s_down)
+void surrogate_finish_kernel(const float *__restrict__ part, const MatDesc *__restrict__ descs, int n_mats, int64_t N,
+                             int opb, const uint8_t *__restrict__ level, GridConsts gc, float *__restrict__ s_up,
+                             float *__restrict__ s_down)
 {
     const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (q >= 2 * N) return;
     const int64_t b = q >> 1;
     const int which = (int)(q & 1);
-    const float *p = part + b * opb * 2 + which;
+    int64_t so;
+    const float *p = block_partials(part, descs, n_mats, b, opb, 2, &so) + which;
     float v;
     if (opb <= 8) {
-        v = tree_upto8(p, 2, opb);
+        v = tree_upto8(p, so, opb);
     } else {
         float t1 = 0.0f, t2 = 0.0f, t3 = 0.0f, t4 = 0.0f;
         v = 0.0f;
         const int ng = opb >> 3;
         for (int g = 0; g < ng; ++g) {
-            v = tree_upto8(p + (int64_t)g * 16, 2, 8);
+            v = tree_upto8(p + (int64_t)g * 8 * so, so, 8);
             if (g & 1) {
                 v = t1 + v;
                 if (g & 2) {
@@ -660,11 +798,12 @@ static int fused_threads(int64_t cols, int cpl, int tmax)
     return (int)(need < 64 ? 64 : (need > tmax ? tmax : need));
 }
 
-template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0>
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
-    const int T = fused_threads(a.cols, CPL, TMAX);
-    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, MINW, SUR, Z0>;
+    int T = fused_threads(a.cols, CPL, TMAX);
+    if (SLATE && T > 256) T = (T + 255) / 256 * 256 <= TMAX ? (T + 255) / 256 * 256 : T;   // whole rounds of the four SIMDs
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, MINW, SUR, Z0, SLATE>;
     SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
     const size_t lds = staged_step_bytes(a.cols, RS, true) + (size_t)(a.cols / (LPG * 8)) * K * 4;   // rows + octet sums
@@ -696,7 +835,7 @@ static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
     if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, MINW, false, Z0>(ctx, a);
     if (chunks <= 2048) {
         // seven or more candidates: two chunks' state does not fit the 128 registers of a 1024-thread workgroup
-        if constexpr (K <= 6) return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0>(ctx, a);
+        if constexpr (K <= 5 || (K == 6 && !(Z0 && LPG == 8))) return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true>(ctx, a);
         else return launch_fused_g<LPG, K, 4, 1, 512, 2, false, Z0>(ctx, a);
     }
     return SBITS_ERR_BAD_SHAPE;
@@ -889,7 +1028,7 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
     const int64_t NK = plan->N * plan->K;
     if (NK > 0) {
         hipLaunchKernelGGL(octet_finish_kernel, dim3((unsigned)((NK + 255) / 256)), dim3(256), 0, ctx->stream,
-                           a.part, NK, plan->K, plan->m / 8, cost);
+                           a.part, a.descs, plan->n_mats, NK, plan->K, plan->m / 8, cost);
         SBITS_HIP(ctx, hipGetLastError());
     }
     return SBITS_OK;
@@ -961,7 +1100,7 @@ int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const
     }
     if (plan->N > 0) {
         hipLaunchKernelGGL(surrogate_finish_kernel, dim3((unsigned)((2 * plan->N + 255) / 256)), dim3(256), 0,
-                           ctx->stream, a.part, plan->N, plan->m / 8, level, a.gc, s_up, s_down);
+                           ctx->stream, a.part, a.descs, plan->n_mats, plan->N, plan->m / 8, level, a.gc, s_up, s_down);
         SBITS_HIP(ctx, hipGetLastError());
     }
     return SBITS_OK;
