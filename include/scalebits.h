@@ -27,6 +27,9 @@
  *     group range that overflows, the results are undefined.  Ranges of zero
  *     and ranges so small that qmax / range overflows are defined cases
  *     (scale = 0: every code 0, the group dequantizes to its minimum).
+ *     Every call that takes matrices requires rows that start on 16-byte
+ *     boundaries: w_bf16 and sens 16-byte aligned, ld_w a multiple of 8, ld_s a
+ *     multiple of 4, ld >= cols (else SBITS_ERR_INVALID_ARG).
  *   - A block is block_rows x block_cols (m x n) of the REORDERED matrix and is
  *     the unit of precision (paper Sec. 4.1).  The quantization group is one
  *     block row: group size = block width (paper App. E, block size).  m and n
@@ -61,11 +64,13 @@ typedef enum {
     SBITS_ERR_BAD_SHAPE        = -2,  /* block shape not a supported power of two, or not dividing the matrix */
     SBITS_ERR_BAD_BITWIDTHS    = -3,  /* empty, more than 9, not strictly increasing, outside 0..8, only 0 */
     SBITS_ERR_INFEASIBLE_BUDGET= -4,  /* avg_bits below the smallest candidate */
-    SBITS_ERR_WORKSPACE        = -5,  /* reserved: workspace too small */
+    SBITS_ERR_WORKSPACE        = -5,  /* workspace smaller than the call needs (sbits_set_workspace_size), or a
+                                         plan beyond the fixed scratch of sbits_offsets_static */
     SBITS_ERR_MAX_ITERS        = -6,  /* search stopped by max_iters; levels are valid and within budget */
     SBITS_ERR_HIP              = -7,  /* a HIP call failed; sbits_last_hip_error() has its code */
     SBITS_ERR_UNIMPLEMENTED    = -8,
-    SBITS_ERR_CAPACITY         = -9   /* an output buffer (codes) is too small */
+    SBITS_ERR_CAPACITY         = -9,  /* an output buffer (codes) is too small */
+    SBITS_ERR_INTERNAL         = -10  /* a consistency check of the library's own bookkeeping failed */
 } sbits_status;
 
 typedef struct sbits_ctx  sbits_ctx;    /* device + stream; small host state only           */
@@ -136,6 +141,13 @@ int  sbits_plan_destroy(sbits_plan *plan);
 int64_t sbits_num_blocks(const sbits_plan *plan, int mat /* -1: all matrices */);
 int64_t sbits_block_base(const sbits_plan *plan, int mat);
 size_t  sbits_workspace_bytes(const sbits_plan *plan);
+/* Declares how many bytes the workspace that later calls on this plan receive holds.  From
+ * then on every call that "uses ws" returns SBITS_ERR_WORKSPACE (on the host, before
+ * anything is enqueued) while that size is below sbits_workspace_bytes(plan); this call
+ * itself returns SBITS_ERR_WORKSPACE in that case too (the size is recorded anyway).  A
+ * plan whose workspace size was never declared is not checked: the pointer alone does not
+ * tell its extent.                                                                       */
+int  sbits_set_workspace_size(sbits_plan *plan, size_t bytes);
 /* upper bound on the packed size in bytes for a budget: floor(avg_bits*N)*m*n/8 */
 int64_t sbits_codes_bytes_bound(const sbits_plan *plan, double avg_bits);
 
@@ -227,13 +239,12 @@ int  sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *
  * or re-reading the reordered sensitivities.  cost[N][K] is written, and w_re
  * (reordered weights, what sbits_pack_all reads) unless it is NULL:
  * sbits_gather_pack_all does not need it.  Supported for 64- and 128-column
- * blocks, rows of at most 16384 elements, and source rows that start on 16-byte
- * boundaries (w_bf16, sens 16-byte aligned, ld_w % 8 == 0, ld_s % 4 == 0), on a
- * device whose memories run with error correction (target id "sramecc+", as every
- * MI355X reports: the kernel relies on how 16-bit register loads behave there);
- * otherwise returns SBITS_ERR_UNIMPLEMENTED and writes nothing: use the two calls
- * above.  sbits_gather_cost_supported: 1 if the plan's shapes qualify (the
- * alignment of the matrices is checked by the call itself), else 0.  Uses ws.     */
+ * blocks and rows of at most 16384 elements, on a device whose memories run with
+ * error correction (target id "sramecc+", as every MI355X reports: the kernel
+ * relies on how 16-bit register loads behave there); otherwise returns
+ * SBITS_ERR_UNIMPLEMENTED and writes nothing: use the two calls above.
+ * sbits_gather_cost_supported: 1 if the plan's shapes qualify (the device is
+ * checked by the call itself), else 0.  Uses ws.                                  */
 int  sbits_gather_cost_supported(const sbits_plan *plan);
 int  sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                            const int32_t *col_perm, void *w_re_bf16, float *cost, void *ws);
@@ -319,9 +330,8 @@ int  sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *leve
 
 /* The same from the ORIGINAL weights and the permutations (reordering on the fly,
  * no reordered copy needed); identical output.  mats: HOST array, only w_bf16 /
- * ld_w are read.  Same shape and alignment limits as sbits_gather_cost_all (w_bf16
- * rows on 16-byte boundaries); otherwise SBITS_ERR_UNIMPLEMENTED.  codes 8-byte,
- * scale and zero 16-byte aligned.  Uses ws.                                      */
+ * ld_w are read.  Same shape limits as sbits_gather_cost_all (any device); otherwise
+ * SBITS_ERR_UNIMPLEMENTED.  codes 8-byte, scale and zero 16-byte aligned.  Uses ws. */
 int  sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                            const int32_t *col_perm, const uint8_t *level, const int64_t *byte_off,
                            uint8_t *codes, float *scale, float *zero, void *ws);

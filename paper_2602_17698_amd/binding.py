@@ -15,13 +15,13 @@ LIB_PATH = os.environ.get("SBITS_LIB") or os.path.join(_HERE, "libscalebits.so")
 OK = 0
 ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_BAD_BITWIDTHS, ERR_INFEASIBLE_BUDGET = -1, -2, -3, -4
 DIM_INDEPENDENT, DIM_FIXED = -1, -2
-ERR_WORKSPACE, ERR_MAX_ITERS, ERR_HIP, ERR_UNIMPLEMENTED, ERR_CAPACITY = -5, -6, -7, -8, -9
+ERR_WORKSPACE, ERR_MAX_ITERS, ERR_HIP, ERR_UNIMPLEMENTED, ERR_CAPACITY, ERR_INTERNAL = -5, -6, -7, -8, -9, -10
 OFFSETS_STATIC_MAX_BLOCKS = 8388608          # SBITS_OFFSETS_STATIC_MAX_BLOCKS of the header
 
 EXPORTS = [
     "sbits_create", "sbits_destroy", "sbits_last_hip_error", "sbits_strerror",
     "sbits_plan_create", "sbits_plan_destroy", "sbits_num_blocks", "sbits_block_base",
-    "sbits_workspace_bytes", "sbits_codes_bytes_bound",
+    "sbits_workspace_bytes", "sbits_set_workspace_size", "sbits_codes_bytes_bound",
     "sbits_reorder", "sbits_reorder_all", "sbits_channel_scores", "sbits_gather", "sbits_gather_all",
     "sbits_cost_table", "sbits_cost_table_all", "sbits_cost_power", "sbits_pack_all",
     "sbits_gather_cost_supported", "sbits_gather_cost_all", "sbits_gather_pack_all",
@@ -201,6 +201,10 @@ class Plan:
 
     def workspace_bytes(self) -> int:
         return int(load().sbits_workspace_bytes(self.h))
+
+    def set_workspace_size(self, nbytes: int) -> int:
+        """Declares the size of the workspace later calls receive; calls fail with ERR_WORKSPACE while it is too small."""
+        return int(load().sbits_set_workspace_size(self.h, C.c_size_t(nbytes)))
 
     def codes_bytes_bound(self, avg_bits: float) -> int:
         return int(load().sbits_codes_bytes_bound(self.h, C.c_double(avg_bits)))

@@ -54,7 +54,7 @@ struct SelJob {
 enum { JOB_E = 0, JOB_U = 1, JOB_D = 2, JOB_U2 = 3, N_JOBS = 4 };
 enum { MODE_NONE = 0, MODE_EXPAND = 1, MODE_ACCEPT = 2, MODE_REJECT = 3 };
 
-struct AllocState {
+struct AllocHead {
     long long N, T, k, kmin, used;
     long long lossD, gainU;        // fixed-point sums of the current proposal
     long long cost_fixed, bits_check;
@@ -64,8 +64,21 @@ struct AllocState {
     unsigned int maxc_bits;
     int bits[MAX_CAND];
     long long prop_up, prop_dn, prop_after;   // the single step on caller-supplied estimates: its result
+};
+struct AllocState : AllocHead {
     SelJob job[N_JOBS];
 };
+static_assert(sizeof(AllocHead) % 8 == 0, "the jobs follow the head without padding");
+
+// The start state from a kernel argument: no host buffer has to outlive the call, so nothing waits.
+// One workgroup: thread 0 writes the head, all threads clear the selection jobs.
+__global__ __launch_bounds__(256)
+void set_state_kernel(AllocState *st, AllocHead head)
+{
+    if (threadIdx.x == 0) *static_cast<AllocHead *>(st) = head;
+    unsigned int *j = reinterpret_cast<unsigned int *>(st->job);
+    for (unsigned i = threadIdx.x; i < sizeof(st->job) / 4; i += blockDim.x) j[i] = 0u;
+}
 
 __device__ __forceinline__ unsigned int ord_f32(float f)
 {
@@ -571,19 +584,6 @@ static int ceil_log2_ll(long long v) { int p = 0; while ((1ll << p) < v) ++p; re
 
 using namespace sbits;
 
-// The start state on the device without waiting for the stream: the selection jobs (all zero) by a fill,
-// the head through the context's page-locked buffer.  The buffer is free here (every call that uses it
-// ends with a wait) and is next written by this call's own read-backs, which follow the upload in stream
-// order; a pageable source would need a wait before the host image may change.
-static hipError_t upload_state(sbits_ctx *ctx, AllocState *st, const AllocState &h, AllocState *pinned_head)
-{
-    constexpr size_t HEAD = offsetof(AllocState, job);
-    memcpy(pinned_head, &h, HEAD);
-    hipError_t e = hipMemsetAsync(reinterpret_cast<char *>(st) + HEAD, 0, sizeof(AllocState) - HEAD, ctx->stream);
-    if (e != hipSuccess) return e;
-    return hipMemcpyAsync(st, pinned_head, HEAD, hipMemcpyHostToDevice, ctx->stream);
-}
-
 // workspace: AllocState | keyU [N] | keyD [N] | trace [TRACE_CAP]
 size_t sbits_alloc_ws_bytes(int64_t N)
 {
@@ -615,10 +615,10 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     // the per-iteration read-back lands in page-locked memory: a pageable target makes every
     // copy a staged, blocking one
     if (!ctx->pinned) SBITS_HIP(ctx, hipHostMalloc(&ctx->pinned, SBITS_PINNED_BYTES, hipHostMallocDefault));
-    static_assert(offsetof(AllocState, job) <= SBITS_PINNED_BYTES, "state head must fit the pinned buffer");
-    AllocState *hp = static_cast<AllocState *>(ctx->pinned);   // only the head (before job[]) is valid there
-    std::vector<unsigned char> himg(sizeof(AllocState), 0);    // host image (66 KB: not on the stack)
-    AllocState &h = *reinterpret_cast<AllocState *>(himg.data());
+    static_assert(sizeof(AllocHead) <= SBITS_PINNED_BYTES, "state head must fit the pinned buffer");
+    AllocHead *hp = static_cast<AllocHead *>(ctx->pinned);     // the state's head as read back
+    AllocHead h;
+    memset(&h, 0, sizeof h);
     h.N = N;
     h.T = (long long)floor(avg_bits * (double)N);
     h.k = (long long)floor(prm->gamma0 * (double)N);
@@ -642,7 +642,7 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     if (all_max) h.done = 1;
 
     const unsigned grid = (unsigned)((N + AL_THREADS - 1) / AL_THREADS < 1024 ? (N + AL_THREADS - 1) / AL_THREADS : 1024);
-    SBITS_HIP(ctx, upload_state(ctx, st, h, hp));
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(256), 0, sm, st, h);
     hipLaunchKernelGGL(max_cost_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, cost, (long long)(N * K), st);
     hipLaunchKernelGGL(init_state_kernel, dim3(1), dim3(1), 0, sm, st, ceil_log2_ll(N));
     hipLaunchKernelGGL(fill_level_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, level, (long long)N, (uint8_t)l0);
@@ -654,7 +654,7 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
     // the selection passes end in one global atomic per non-empty bin and workgroup: few, fat workgroups
     const unsigned sgrid = (unsigned)((N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) < SEL_MAXWG ? (N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) : SEL_MAXWG);
     if (!ctx->readback) SBITS_HIP(ctx, hipEventCreateWithFlags(&ctx->readback, hipEventDisableTiming));
-    constexpr size_t HEAD = offsetof(AllocState, job);
+    constexpr size_t HEAD = sizeof(AllocHead);
     // A read-back ends in an event of its own: the host waits for the event, not for the stream, so the
     // work enqueued behind the read-back keeps the device busy during the host's round trip.
     auto read_back = [&]() -> hipError_t {
@@ -718,9 +718,9 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
 
     hipLaunchKernelGGL(final_stats_kernel, dim3(grid), dim3(AL_THREADS), 0, sm, st, cost, level);
     SBITS_HIP(ctx, hipGetLastError());
-    SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+    SBITS_HIP(ctx, hipMemcpyAsync(hp, st, sizeof(AllocHead), hipMemcpyDeviceToHost, sm));
     SBITS_HIP(ctx, hipStreamSynchronize(sm));
-    memcpy(&h, hp, offsetof(AllocState, job));
+    memcpy(&h, hp, sizeof(AllocHead));
     if (host_stats) {
         host_stats->iters = h.iters; host_stats->expansions = h.expansions;
         host_stats->swaps_ok = h.swaps_ok; host_stats->swaps_rej = h.swaps_rej;
@@ -733,7 +733,7 @@ int sbits_run_allocate(sbits_plan *plan, const float *cost, double avg_bits,
         SBITS_HIP(ctx, hipMemcpyAsync(host_trace, tr, (size_t)nrec * sizeof(sbits_trace), hipMemcpyDeviceToHost, sm));
         SBITS_HIP(ctx, hipStreamSynchronize(sm));
     }
-    if (h.bits_check != h.used) return SBITS_ERR_INVALID_ARG;   // internal accounting must agree
+    if (h.bits_check != h.used) return SBITS_ERR_INTERNAL;      // the loop's running total and a recount must agree
     return h.status;
 }
 
@@ -755,9 +755,9 @@ int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, 
     unsigned long long *keyD = reinterpret_cast<unsigned long long *>(p);
 
     if (!ctx->pinned) SBITS_HIP(ctx, hipHostMalloc(&ctx->pinned, SBITS_PINNED_BYTES, hipHostMallocDefault));
-    AllocState *hp = static_cast<AllocState *>(ctx->pinned);
-    std::vector<unsigned char> himg(sizeof(AllocState), 0);
-    AllocState &h = *reinterpret_cast<AllocState *>(himg.data());
+    AllocHead *hp = static_cast<AllocHead *>(ctx->pinned);
+    AllocHead h;
+    memset(&h, 0, sizeof h);
     h.N = N;
     h.T = (long long)floor(avg_bits * (double)N);
     h.k = k;
@@ -765,10 +765,8 @@ int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, 
     h.IB = ceil_log2_ll(N) > 0 ? ceil_log2_ll(N) : 1;
     h.P = (32 + h.IB + SEL_DB - 1) / SEL_DB;
     for (int c = 0; c < MAX_CAND; ++c) h.bits[c] = c < K ? plan->bits[c] : plan->bits[K - 1];
-    // (a call without host_out returns without waiting, so the page-locked buffer may still be feeding the
-    // previous call's upload: this one goes from the pageable image and waits for it)
-    SBITS_HIP(ctx, hipMemcpyAsync(st, &h, sizeof h, hipMemcpyHostToDevice, sm));
-    SBITS_HIP(ctx, hipStreamSynchronize(sm));      // the image goes away on return
+    // the start state travels as a kernel argument: nothing to keep alive, nothing to wait for
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(256), 0, sm, st, h);
 
     const unsigned grid = (unsigned)((N + AL_THREADS - 1) / AL_THREADS < 1024 ? (N + AL_THREADS - 1) / AL_THREADS : 1024);
     const unsigned sgrid = (unsigned)((N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) < SEL_MAXWG ? (N + AL_THREADS * SEL_KPT - 1) / (AL_THREADS * SEL_KPT) : SEL_MAXWG);
@@ -792,8 +790,8 @@ int sbits_run_propose(sbits_plan *plan, const float *s_up, const float *s_down, 
                        (const unsigned long long *)keyU, (const unsigned long long *)keyD, level_in, level_out);
     SBITS_HIP(ctx, hipGetLastError());
     if (host_out) {
-        static_assert(offsetof(AllocState, job) <= SBITS_PINNED_BYTES, "state head must fit the pinned buffer");
-        SBITS_HIP(ctx, hipMemcpyAsync(hp, st, offsetof(AllocState, job), hipMemcpyDeviceToHost, sm));
+        static_assert(sizeof(AllocHead) <= SBITS_PINNED_BYTES, "state head must fit the pinned buffer");
+        SBITS_HIP(ctx, hipMemcpyAsync(hp, st, sizeof(AllocHead), hipMemcpyDeviceToHost, sm));
         SBITS_HIP(ctx, hipStreamSynchronize(sm));
         host_out->kind = hp->mode == MODE_EXPAND ? 1 : hp->mode == MODE_ACCEPT ? 2 : 0;
         host_out->pad_ = 0;

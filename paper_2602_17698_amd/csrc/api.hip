@@ -20,11 +20,12 @@ const char *sbits_strerror(int status)
     case SBITS_ERR_BAD_SHAPE: return "unsupported or non-dividing block shape";
     case SBITS_ERR_BAD_BITWIDTHS: return "bad candidate bitwidth list";
     case SBITS_ERR_INFEASIBLE_BUDGET: return "budget below the smallest candidate bitwidth";
-    case SBITS_ERR_WORKSPACE: return "workspace too small";
+    case SBITS_ERR_WORKSPACE: return "workspace (or fixed scratch) too small";
     case SBITS_ERR_MAX_ITERS: return "search stopped by max_iters";
     case SBITS_ERR_HIP: return "HIP runtime error";
     case SBITS_ERR_UNIMPLEMENTED: return "not implemented";
     case SBITS_ERR_CAPACITY: return "output buffer too small";
+    case SBITS_ERR_INTERNAL: return "internal consistency check failed";
     }
     return "unknown status";
 }
@@ -130,6 +131,8 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
     if (g > ws) ws = g;
     p->head_bytes = sbits_desc_bytes(n_mats) + SBITS_N_PREFIX * sbits_prefix_bytes(n_mats);
     p->ws_bytes = p->head_bytes + ws;
+    p->ws_given = ~(size_t)0;                        // not declared: not checked
+    p->desc_pinned = nullptr;
     *out = p;
     return SBITS_OK;
 }
@@ -137,6 +140,13 @@ int sbits_plan_create(sbits_ctx *ctx, const int64_t *rows, const int64_t *cols, 
 int sbits_plan_destroy(sbits_plan *plan)
 {
     if (!plan) return SBITS_ERR_INVALID_ARG;
+    if (plan->desc_pinned) {
+        for (int i = 0; i < 2; ++i) {
+            if (plan->desc_used[i]) (void)hipEventSynchronize(plan->desc_done[i]);   // no copy may still read the buffers
+            (void)hipEventDestroy(plan->desc_done[i]);
+        }
+        (void)hipHostFree(plan->desc_pinned);
+    }
     delete plan;
     return SBITS_OK;
 }
@@ -185,8 +195,23 @@ static int need_device(const sbits_plan *plan)
 }  // extern "C"
 
 // Copies the descriptor table into the workspace head.  mats == nullptr: shapes only.
+// The image a copy reads must not change while the copy is pending: the table is built in one of two
+// page-locked buffers of the plan, taken in turns; before a buffer is rewritten the host waits for the
+// event recorded behind the copy that last read it (two uploads back: as good as always complete).
 int sbits_upload_descs(sbits_plan *plan, const sbits_matrix *mats, void *ws)
 {
+    sbits_ctx *ctx = plan->ctx;
+    const size_t bytes = (size_t)plan->n_mats * sizeof(sbits::MatDesc);
+    if (!plan->desc_pinned) {
+        SBITS_HIP(ctx, hipHostMalloc(&plan->desc_pinned, 2 * bytes, hipHostMallocDefault));
+        for (int i = 0; i < 2; ++i) SBITS_HIP(ctx, hipEventCreateWithFlags(&plan->desc_done[i], hipEventDisableTiming));
+        plan->desc_turn = 0;
+        plan->desc_used[0] = plan->desc_used[1] = false;
+    }
+    const int t = plan->desc_turn;
+    plan->desc_turn ^= 1;
+    if (plan->desc_used[t]) SBITS_HIP(ctx, hipEventSynchronize(plan->desc_done[t]));
+    sbits::MatDesc *img = reinterpret_cast<sbits::MatDesc *>(static_cast<char *>(plan->desc_pinned) + (size_t)t * bytes);
     for (int i = 0; i < plan->n_mats; ++i) {
         sbits::MatDesc &d = plan->descs[i];
         if (mats) {
@@ -197,15 +222,26 @@ int sbits_upload_descs(sbits_plan *plan, const sbits_matrix *mats, void *ws)
         } else {
             d.w = nullptr; d.s = nullptr;
         }
+        img[i] = d;
     }
-    SBITS_HIP(plan->ctx, hipMemcpyAsync(ws, plan->descs.data(), plan->n_mats * sizeof(sbits::MatDesc),
-                                        hipMemcpyHostToDevice, plan->ctx->stream));
+    SBITS_HIP(ctx, hipMemcpyAsync(ws, img, bytes, hipMemcpyHostToDevice, ctx->stream));
+    SBITS_HIP(ctx, hipEventRecord(plan->desc_done[t], ctx->stream));
+    plan->desc_used[t] = true;
     return SBITS_OK;
 }
 
 extern "C" {
 
 static bool ws_ok(const void *ws) { return ws && (reinterpret_cast<uintptr_t>(ws) & 255) == 0; }
+// the caller's workspace, if its size was declared (sbits_set_workspace_size), holds what the plan needs
+static bool ws_fits(const sbits_plan *plan) { return plan->ws_given >= plan->ws_bytes; }
+
+int sbits_set_workspace_size(sbits_plan *plan, size_t bytes)
+{
+    if (!plan) return SBITS_ERR_INVALID_ARG;
+    plan->ws_given = bytes;
+    return bytes >= plan->ws_bytes ? SBITS_OK : SBITS_ERR_WORKSPACE;
+}
 
 int sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M, float *row_score,
                          float *col_score, void *ws)
@@ -213,6 +249,7 @@ int sbits_channel_scores(sbits_plan *plan, int mat, const sbits_matrix *M, float
     int rc = check_matrix(plan, mat, M, false, true);
     if (rc) return rc;
     if (!row_score || !col_score || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if ((rc = need_device(plan))) return rc;
     return sbits_launch_scores(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, row_score, col_score,
                                sbits_scratch(plan, ws));
@@ -224,6 +261,7 @@ int sbits_reorder(sbits_plan *plan, int mat, const sbits_matrix *M, int32_t *row
     int rc = check_matrix(plan, mat, M, false, true);
     if (rc) return rc;
     if (!row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if ((rc = need_device(plan))) return rc;
     return sbits_launch_reorder(plan->ctx, M->sens, M->rows, M->cols, M->ld_s, row_perm, col_perm,
                                 sbits_scratch(plan, ws));
@@ -244,6 +282,7 @@ int sbits_reorder_all(sbits_plan *plan, const sbits_matrix *mats, int32_t *row_p
     int rc = check_all(plan, mats, false, true);
     if (rc) return rc;
     if (!row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
     return sbits_launch_reorder_all(plan, row_perm, col_perm, ws);
@@ -257,6 +296,7 @@ int sbits_reorder_coupled_all(sbits_plan *plan, const sbits_matrix *mats, const 
     int rc = check_all(plan, mats, false, true);
     if (rc) return rc;
     if (!row_group || !col_group || n_groups < 0 || !row_perm || !col_perm || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if ((rc = sbits_coupling_tables(plan, row_group, col_group, n_groups, group_segment, row_repeat, col_repeat,
                                     nullptr, nullptr, nullptr, nullptr, nullptr)))
         return rc;
@@ -274,6 +314,7 @@ int sbits_gather_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *
     if (!row_perm || !col_perm || (!w_re_bf16 && !s_re) || !aligned16(col_perm) || !aligned16(w_re_bf16) ||
         !aligned16(s_re) || !ws_ok(ws))
         return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
     return sbits_launch_gather_all(plan, row_perm, col_perm, w_re_bf16, s_re, ws);
@@ -306,6 +347,7 @@ int sbits_cost_table(sbits_plan *plan, int mat, const void *w_re_bf16, const flo
 int sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *s_re, float *cost, void *ws)
 {
     if (!plan || !w_re_bf16 || !s_re || !cost || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (!aligned16(w_re_bf16) || !aligned16(s_re)) return SBITS_ERR_INVALID_ARG;
     int rc = need_device(plan);
     if (rc) return rc;
@@ -322,6 +364,7 @@ int sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int3
     if (rc) return rc;
     if (!row_perm || !col_perm || !cost || !aligned16(col_perm) || !aligned16(w_re_bf16) || !ws_ok(ws))
         return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
@@ -336,6 +379,7 @@ int sbits_surrogates_all(sbits_plan *plan, const sbits_matrix *mats, const int32
     if (rc) return rc;
     if (!row_perm || !col_perm || !level || !s_up || !s_down || !aligned16(col_perm) || !ws_ok(ws))
         return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
@@ -352,6 +396,7 @@ int sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int3
     if (!row_perm || !col_perm || !level || !byte_off || !codes || !scale || !zero || !aligned16(col_perm) ||
         !ws_ok(ws) || (reinterpret_cast<uintptr_t>(codes) & 7) || !aligned16(scale) || !aligned16(zero))
         return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
@@ -364,6 +409,7 @@ int sbits_allocate(sbits_plan *plan, const float *cost, double avg_bits, const s
                    void *ws)
 {
     if (!plan || !cost || !params || !level || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (!(params->gamma0 >= 0) || !(params->gammaT >= 0) || params->max_iters < 1 ||
         (params->init_mode != 0 && params->init_mode != 1) || !(avg_bits == avg_bits))
         return SBITS_ERR_INVALID_ARG;
@@ -378,6 +424,7 @@ int sbits_propose(sbits_plan *plan, const float *s_up, const float *s_down, cons
                   double avg_bits, int64_t k, uint8_t *level_out, sbits_proposal *host_out, void *ws)
 {
     if (!plan || !s_up || !s_down || !level_in || !level_out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (k < 1 || !(avg_bits == avg_bits)) return SBITS_ERR_INVALID_ARG;
     if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;
     int rc = need_device(plan);
@@ -405,6 +452,7 @@ int sbits_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, i
     if (!plan || mat < 0 || mat >= plan->n_mats || !x_bf16 || !level || !byte_off || !codes || !scale || !zero ||
         !y || !ws_ok(ws))
         return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (batch < 1 || ld_x < plan->cols[mat] || (ld_x % 8) || !aligned16(x_bf16) || !aligned16(codes))
         return SBITS_ERR_INVALID_ARG;
     if (!sbits_mp_gemm_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
@@ -424,6 +472,7 @@ int sbits_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t ld_x, i
 int sbits_offsets(sbits_plan *plan, const uint8_t *level, int64_t *byte_off, void *ws)
 {
     if (!plan || !level || !byte_off || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     int rc = need_device(plan);
     if (rc) return rc;
     return sbits_launch_offsets(plan->ctx, level, plan->N, plan->m, plan->n, plan->bits, plan->K, byte_off,
@@ -456,6 +505,7 @@ int sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *level
 {
     if (!plan || !w_re_bf16 || !level || !byte_off || !codes || !scale || !zero || !ws_ok(ws))
         return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (!aligned16(w_re_bf16) || !aligned16(codes)) return SBITS_ERR_INVALID_ARG;
     int rc = need_device(plan);
     if (rc) return rc;
@@ -475,6 +525,7 @@ static int search_impl(sbits_plan *plan, const sbits_matrix *mats, const Couplin
                        const sbits_params *params, const sbits_outputs *out, sbits_stats *host_stats, void *ws)
 {
     if (!plan || !mats || !params || !out || !ws_ok(ws)) return SBITS_ERR_INVALID_ARG;
+    if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
     if (!out->row_perm || !out->col_perm || !out->cost || !out->level || !out->byte_off || !out->scale || !out->zero)
         return SBITS_ERR_INVALID_ARG;
     if (avg_bits < (double)plan->bits[0]) return SBITS_ERR_INFEASIBLE_BUDGET;

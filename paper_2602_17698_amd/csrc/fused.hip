@@ -937,17 +937,12 @@ size_t sbits_fused_ws_bytes(const sbits_plan *plan)
     return sbits_align_up((size_t)plan->N * (size_t)(plan->m / 8) * per_octet * 4, 256);
 }
 
-// every source row must start on a 16-byte boundary (the rows are staged with 128-bit loads); the kernels
-// that read sensitivities also rely on 16-bit register-half loads filling the other half with zeros
+// The kernels that read sensitivities rely on 16-bit register-half loads filling the other half with
+// zeros (the device's target id says "sramecc+").  (That every source row starts on a 16-byte boundary,
+// which the row loads need, is a rule of every entry point that takes matrices: checked there.)
 bool sbits_fused_layout_ok(const sbits_plan *plan, bool need_s)
 {
-    if (need_s && !plan->ctx->d16_zero_fill) return false;
-    for (int i = 0; i < plan->n_mats; ++i) {
-        const MatDesc &d = plan->descs[i];
-        if ((reinterpret_cast<uintptr_t>(d.w) & 15) || (d.ld_w & 7)) return false;
-        if (need_s && ((reinterpret_cast<uintptr_t>(d.s) & 15) || (d.ld_s & 3))) return false;
-    }
-    return true;
+    return !need_s || plan->ctx->d16_zero_fill;
 }
 
 // matrices grouped by column count; members and workgroup prefixes go to slots 3 and 4 of the

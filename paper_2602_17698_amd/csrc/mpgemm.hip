@@ -49,9 +49,6 @@ struct MpArgs {
     int64_t block_base, ld_x;
     int R, C, m, nbc, batch, n_split;
     int bits[MAX_CAND];
-#ifdef MG_EXP_TIMING
-    long long *dbg;
-#endif
 };
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
@@ -248,13 +245,7 @@ void mp_gemm_kernel(MpArgs a)
     constexpr int SLICE = MG_SPAN * N_COLS;                    // x columns per workgroup
     constexpr int PITCH = SLICE * 2 + 16;                      // bytes per batch row in LDS (+16: spreads the rows over the banks)
     const int tid = threadIdx.x, lane = tid & 63;
-#ifdef MG_EXP_TIMING
-    long long ts[8];
-#define MG_TS(i) do { __builtin_amdgcn_sched_barrier(0); ts[i] = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
-    MG_TS(0);
-#else
 #define MG_TS(i)
-#endif
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: the bookkeeping below stays scalar
     const int rg = wave & (MG_RG - 1), jl = wave >> 2;
     const int li = lane & 15, g = lane >> 4;
@@ -297,9 +288,6 @@ void mp_gemm_kernel(MpArgs a)
         xs[i] = *(const __attribute__((address_space(1))) u32x4_t *)(a.x + (int64_t)bc * a.ld_x + cc);
     }
 
-#ifdef MG_EXP_TIMING
-    { const int dummy = __builtin_amdgcn_readfirstlane((int)lvl_v[MG_NBLK - 1] + (int)boff_v[MG_NBLK - 1]); asm volatile("" :: "s"(dummy)); }
-#endif
     MG_TS(1);
 #pragma unroll
     for (int i = 0; i < XCH; ++i) {
@@ -355,10 +343,6 @@ void mp_gemm_kernel(MpArgs a)
         default: block_product<8, N_COLS, NB>(cw[t % PF], sc[t % PF], ze[t % PF], xa, acc); break;
         }
         if (t + PF < MG_NBLK) MG_REQUEST((t + PF) % MG_NBLK, t % PF);   // the slot is free again
-#ifdef MG_EXP_TIMING
-        { asm volatile("" :: "v"(acc[0][0][0]), "v"(acc[1][0][3])); }
-        MG_TS(3 + t);
-#endif
     }
 
     // ---- the four waves of a row group add up (fixed order), wave jl = 0 stores
@@ -372,13 +356,6 @@ void mp_gemm_kernel(MpArgs a)
             for (int r = 0; r < 4; ++r)
                 red[(((wave * 2 + t) * NB + nb) * 4 + r) * 64 + lane] = acc[t][nb][r];
     __syncthreads();
-#ifdef MG_EXP_TIMING
-    MG_TS(7);
-    if (lane == 0) {
-        long long *d = a.dbg + ((int64_t)(blockIdx.y * gridDim.x + blockIdx.x) * MG_WAVES + wave) * 8;
-        for (int i = 0; i < 8; ++i) d[i] = ts[i];
-    }
-#endif
     if (jl != 0 || !rows_ok) return;
     float *dst = a.out + (int64_t)blockIdx.y * a.batch * a.R;
 #pragma unroll
@@ -459,9 +436,6 @@ int sbits_launch_mp_gemm(sbits_plan *plan, int mat, const void *x_bf16, int64_t 
     a.n_split = sbits_mp_gemm_splits(a.C, plan->n);
     for (int c = 0; c < sbits::MAX_CAND; ++c) a.bits[c] = c < plan->K ? plan->bits[c] : plan->bits[plan->K - 1];
     a.out = a.n_split > 1 ? static_cast<float *>(scratch) : y;
-#ifdef MG_EXP_TIMING
-    a.dbg = reinterpret_cast<long long *>(static_cast<char *>(scratch) + (2304 << 10));
-#endif
     const dim3 grid((unsigned)((a.R + MG_RG * 32 - 1) / (MG_RG * 32)), (unsigned)a.n_split);
     const int nb = batch <= 16 ? 1 : 2;
     int rc;

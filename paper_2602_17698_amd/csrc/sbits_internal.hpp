@@ -43,6 +43,11 @@ struct sbits_plan {
     std::vector<sbits::MatDesc> descs;       // shape part filled at creation; pointers per call
     size_t head_bytes;                       // workspace head: descriptor table + workgroup prefixes
     size_t ws_bytes;
+    size_t ws_given;                         // size of the caller's workspace if declared, else SIZE_MAX
+    void *desc_pinned;                       // two page-locked images of the descriptor table (allocated on first upload)
+    hipEvent_t desc_done[2];                 // recorded behind the upload that read image i
+    bool desc_used[2];
+    int desc_turn;
 };
 
 // The workspace head holds the per-matrix descriptor table and the small integer tables (workgroup

@@ -46,7 +46,7 @@ def test_build_variants_export_the_same_symbols_and_name_their_cost(lib):
 
 
 def test_strerror_covers_all_codes(lib):
-    for code in range(0, -10, -1):
+    for code in range(0, -11, -1):
         assert sb.strerror(code) != "unknown status"
     assert sb.strerror(-99) == "unknown status"
 
@@ -121,6 +121,35 @@ def test_calls_validate_before_touching_the_device(ctx, lib):
     M = sb.Matrix(256, 256, 256, 256, 256, 250)                          # pitch not a multiple of 4
     assert lib.sbits_reorder(p.h, C.c_int(0), C.byref(M), C.c_void_p(256), C.c_void_p(256), C.c_void_p(ws)) == sb.ERR_INVALID_ARG
     assert lib.sbits_num_blocks(p.h, C.c_int(5)) == sb.ERR_INVALID_ARG
+    p.close()
+
+
+def test_a_declared_workspace_that_is_too_small_is_refused_on_the_host(ctx, lib):
+    """Every call that uses the workspace checks the size the caller declared for it, before any device work."""
+    p = sb.Plan(ctx, [(256, 256), (128, 512)], 128, 128, [2, 3, 4])
+    need = p.workspace_bytes()
+    ws, ptr = C.c_void_p(256 * 1024), C.c_void_p(4096)                   # aligned, never dereferenced
+    level, off = np.zeros(8, np.uint8), np.zeros(9, np.int64)
+    prm = sb.Params(0.05, 0.02, 0, 100)
+    mats = (sb.Matrix * 2)(sb.Matrix(4096, 4096, 256, 256, 256, 256), sb.Matrix(4096, 4096, 128, 512, 512, 512))
+    calls = {
+        "offsets": lambda: lib.sbits_offsets(p.h, sb._ptr(level), sb._ptr(off), ws),
+        "allocate": lambda: lib.sbits_allocate(p.h, ptr, C.c_double(3.0), C.byref(prm), sb._ptr(level), None, None,
+                                               C.c_int64(0), ws),
+        "reorder_all": lambda: lib.sbits_reorder_all(p.h, mats, ptr, ptr, ws),
+        "gather_cost_all": lambda: lib.sbits_gather_cost_all(p.h, mats, ptr, ptr, None, ptr, ws),
+        "cost_table_all": lambda: lib.sbits_cost_table_all(p.h, ptr, ptr, ptr, ws),
+        "pack_all": lambda: lib.sbits_pack_all(p.h, ptr, sb._ptr(level), sb._ptr(off), ptr, ptr, ptr, ws),
+    }
+    for name, call in calls.items():                                     # size not declared: not checked
+        assert call() == sb.ERR_HIP, name
+    assert p.set_workspace_size(need - 1) == sb.ERR_WORKSPACE
+    for name, call in calls.items():
+        assert call() == sb.ERR_WORKSPACE, name
+    assert p.set_workspace_size(need) == sb.OK
+    for name, call in calls.items():
+        assert call() == sb.ERR_HIP, name                                # past the check: host-only context has no device
+    assert lib.sbits_set_workspace_size(None, C.c_size_t(1)) == sb.ERR_INVALID_ARG
     p.close()
 
 

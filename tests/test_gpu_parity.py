@@ -82,6 +82,61 @@ def test_scores_and_permutations(orc, ctx, dev, R, C, m, n):
     plan.close()
 
 
+def test_scores_take_absolute_values_of_signed_sensitivities(orc, ctx, dev):
+    """The channel score is an l1 norm (Sec. 4.1): a sensitivity input that carries signed values (a raw
+    first-order term, a gradient) must enter by magnitude -- through the single-matrix call, the
+    batched call and the coupled call.  With the signs dropped on the device the scores of these
+    matrices would cancel and order the channels differently."""
+    say("scores of signed sensitivities")
+    shapes = [(264, 1032), (1024, 520), (264, 1032)]
+    g = torch.Generator().manual_seed(77)
+    Ss = []
+    for R, C in shapes:
+        mag = torch.exp(torch.randn(R, 1, generator=g) + torch.randn(1, C, generator=g) + 0.5 * torch.randn(R, C, generator=g))
+        sign = torch.where(torch.rand(R, C, generator=g) < 0.5, -1.0, 1.0)
+        Ss.append(mag * sign)
+    assert all((S < 0).float().mean().item() > 0.4 for S in Ss)
+    plan, ws = make_plan(ctx, shapes, 8, 8, [2, 3, 4], dev)
+    dS = [S.to(dev) for S in Ss]
+    mats = [sb.matrix(None, s_) for s_ in dS]
+    want = [orc.channel_scores(S.numpy()) for S in Ss]
+    for (rs_o, cs_o), S in zip(want, Ss):                           # the oracle's scores are those of |S| ...
+        rs_a, cs_a = orc.channel_scores(S.abs().numpy())
+        np.testing.assert_array_equal(rs_o, rs_a)
+        np.testing.assert_array_equal(cs_o, cs_a)
+        rs_sgn = S.double().sum(1).abs().numpy()                    # ... and far from those of a signed sum
+        assert np.median(rs_sgn / rs_o) < 0.2
+    for i, (R, C) in enumerate(shapes):
+        rs = torch.empty(R, dtype=torch.float32, device=dev)
+        cs = torch.empty(C, dtype=torch.float32, device=dev)
+        plan.channel_scores(i, mats[i], rs, cs, ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(rs.cpu().numpy(), want[i][0])
+        np.testing.assert_array_equal(cs.cpu().numpy(), want[i][1])
+    nr, nc = sum(r for r, _ in shapes), sum(c for _, c in shapes)
+    rp = torch.full((nr,), -7, dtype=torch.int32, device=dev)
+    cp = torch.full((nc,), -7, dtype=torch.int32, device=dev)
+    plan.reorder_all(mats, rp, cp, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(rp.cpu().numpy(), np.concatenate([orc.argsort_desc(w[0]) for w in want]))
+    np.testing.assert_array_equal(cp.cpu().numpy(), np.concatenate([orc.argsort_desc(w[1]) for w in want]))
+    # coupled: matrices 0 and 2 share both permutations (rows group 0, columns group 1), matrix 1 is on its own
+    I = sb.DIM_INDEPENDENT
+    rp.fill_(-7); cp.fill_(-7)
+    plan.reorder_coupled_all(mats, [0, I, 0], [1, I, 1], 2, [0, 0], rp, cp, ws)
+    torch.cuda.synchronize()
+    rp, cp = rp.cpu().numpy(), cp.cpu().numpy()
+    pr = orc.coupled_perm([want[0][0], want[2][0]], 0)
+    pc = orc.coupled_perm([want[0][1], want[2][1]], 0)
+    np.testing.assert_array_equal(rp[:264], pr)
+    np.testing.assert_array_equal(rp[264 + 1024:], pr)
+    np.testing.assert_array_equal(cp[:1032], pc)
+    np.testing.assert_array_equal(cp[1032 + 520:], pc)
+    np.testing.assert_array_equal(rp[264:264 + 1024], orc.argsort_desc(want[1][0]))
+    np.testing.assert_array_equal(cp[1032:1032 + 520], orc.argsort_desc(want[1][1]))
+    plan.close()
+
+
 def test_permutation_ties_go_to_the_lower_index(orc, ctx, dev):
     say("perm ties")
     R, C = 64, 128
