@@ -463,7 +463,8 @@ def main():
         ex["one_70b_shaped_layer"] = extra_run(
             torch, sb, dev, "one decoder layer of the 70B-shaped model (7 matrices, hidden 8192, ffn 28672; the model "
             "itself is streamed layer by layer), 128x128 blocks, bitwidths [2, 3, 4], budget 2.75 on the layer's "
-            "own table", s70, W7, S7, 128, 128, [2, 3, 4], 2.75)
+            "own table; the six matrices with rows of 8192 elements take the one-pass kernels, the 28672-column one "
+            "a reordered copy in the workspace for the cost stage", s70, W7, S7, 128, 128, [2, 3, 4], 2.75)
         del W7, S7
         out["extras"] = ex
     print(json.dumps(out))

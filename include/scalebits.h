@@ -239,10 +239,14 @@ int  sbits_cost_table_all(sbits_plan *plan, const void *w_re_bf16, const float *
  * or re-reading the reordered sensitivities.  cost[N][K] is written, and w_re
  * (reordered weights, what sbits_pack_all reads) unless it is NULL:
  * sbits_gather_pack_all does not need it.  Supported for 64- and 128-column
- * blocks and rows of at most 16384 elements, on a device whose memories run with
- * error correction (target id "sramecc+", as every MI355X reports: the kernel
- * relies on how 16-bit register loads behave there); otherwise returns
- * SBITS_ERR_UNIMPLEMENTED and writes nothing: use the two calls above.
+ * blocks, on a device whose memories run with error correction (target id
+ * "sramecc+", as every MI355X reports: the kernel relies on how 16-bit register
+ * loads behave there); otherwise returns SBITS_ERR_UNIMPLEMENTED and writes
+ * nothing: use the two calls above.  The route is chosen per matrix: rows of at
+ * most 16384 elements are read once (6 bytes per weight); a matrix with wider
+ * rows is reordered into a copy inside the workspace first and scored from there
+ * (18 bytes per weight; sbits_workspace_bytes covers the copy of the largest such
+ * matrix), with the same bits in the table.
  * sbits_gather_cost_supported: 1 if the plan's shapes qualify (the device is
  * checked by the call itself), else 0.  Uses ws.                                  */
 int  sbits_gather_cost_supported(const sbits_plan *plan);
@@ -259,8 +263,9 @@ int  sbits_gather_cost_all(sbits_plan *plan, const sbits_matrix *mats, const int
  *   s_up[i]   = sum over the block of g * (w - what)       what = fma(q, scale, min),
  *   s_down[i] = 2^-b * sum over the block of |g * what|    the dequantized weight
  * (row-group grid and code q as in sbits_pack; sums in the order of the cost
- * table).  level: DEVICE uint8[N]; s_up, s_down: DEVICE float[N].  Same shape
- * limits as sbits_gather_cost_all, else SBITS_ERR_UNIMPLEMENTED.  Uses ws.        */
+ * table).  level: DEVICE uint8[N]; s_up, s_down: DEVICE float[N].  64- and
+ * 128-column blocks and rows of at most 16384 elements (same device rule as
+ * sbits_gather_cost_all), else SBITS_ERR_UNIMPLEMENTED.  Uses ws.                 */
 int  sbits_surrogates_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                           const int32_t *col_perm, const uint8_t *level,
                           float *s_up, float *s_down, void *ws);
@@ -330,8 +335,9 @@ int  sbits_pack_all(sbits_plan *plan, const void *w_re_bf16, const uint8_t *leve
 
 /* The same from the ORIGINAL weights and the permutations (reordering on the fly,
  * no reordered copy needed); identical output.  mats: HOST array, only w_bf16 /
- * ld_w are read.  Same shape limits as sbits_gather_cost_all (any device); otherwise
- * SBITS_ERR_UNIMPLEMENTED.  codes 8-byte, scale and zero 16-byte aligned.  Uses ws. */
+ * ld_w are read.  64- and 128-column blocks (every row length of the plan is read
+ * once), any device; otherwise SBITS_ERR_UNIMPLEMENTED.  codes 8-byte, scale and
+ * zero 16-byte aligned.  Uses ws.                                                 */
 int  sbits_gather_pack_all(sbits_plan *plan, const sbits_matrix *mats, const int32_t *row_perm,
                            const int32_t *col_perm, const uint8_t *level, const int64_t *byte_off,
                            uint8_t *codes, float *scale, float *zero, void *ws);

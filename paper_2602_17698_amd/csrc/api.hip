@@ -380,7 +380,7 @@ int sbits_surrogates_all(sbits_plan *plan, const sbits_matrix *mats, const int32
     if (!row_perm || !col_perm || !level || !s_up || !s_down || !aligned16(col_perm) || !ws_ok(ws))
         return SBITS_ERR_INVALID_ARG;
     if (!ws_fits(plan)) return SBITS_ERR_WORKSPACE;
-    if (!sbits_fused_shapes_ok(plan)) return SBITS_ERR_UNIMPLEMENTED;
+    if (!sbits_fused_all_staged(plan)) return SBITS_ERR_UNIMPLEMENTED;
     if ((rc = need_device(plan))) return rc;
     if ((rc = sbits_upload_descs(plan, mats, ws))) return rc;
     if (!sbits_fused_layout_ok(plan, true)) return SBITS_ERR_UNIMPLEMENTED;

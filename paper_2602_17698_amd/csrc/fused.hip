@@ -31,8 +31,9 @@ void sbits_fill_grid_consts(const int32_t *bits, int K, sbits::GridConsts *gc);
 
 namespace sbits {
 
-constexpr int FU_OPU = 16;                          // octets per workgroup (128 output rows)
-constexpr int FU_MAX_COLS = 16384;                  // widest row the kernels stage (2048 chunks)
+constexpr int FU_OPU = 16;                          // octets per workgroup at most (128 output rows); fewer for small classes
+constexpr int FU_MAX_COLS = 16384;                  // widest row the cost kernel stages (2048 chunks: bf16 + fp32 row in LDS)
+constexpr int FU_PACK_MAX_COLS = 32768;             // widest row the packing kernel stages (bf16 row only)
 
 __device__ __forceinline__ int funi(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -138,7 +139,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                         const int *__restrict__ wg_start, int n_members,
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
                         uint16_t *__restrict__ w_re_all, float *__restrict__ part, GridConsts gc,
-                        const uint8_t *__restrict__ level, int kstride, int koff)
+                        const uint8_t *__restrict__ level, int kstride, int koff, int opu)
 {
     // kstride, koff: the K sums of an octet go to part[..][koff .. koff + K) of kstride values (a launch
     // may cover a subset of the candidates)
@@ -165,8 +166,8 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     const int R = funi((int)d.rows), C = funi((int)d.cols) & ~7;   // (a multiple of the block width anyway)
     const int nbc = funi(d.nbc);
     const int opb = m >> 3;
-    const int oct0 = ((int)blockIdx.x - funi(wg_start[mem])) * FU_OPU;
-    const int noct = min(FU_OPU, (R >> 3) - oct0);
+    const int oct0 = ((int)blockIdx.x - funi(wg_start[mem])) * opu;
+    const int noct = min(opu, (R >> 3) - oct0);
     const int32_t *__restrict__ rp = row_perm + d.row_off;
     const int32_t *__restrict__ cp = col_perm + d.col_off;
     const char *const Wg = reinterpret_cast<const char *>(d.w);
@@ -555,7 +556,7 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                         const int32_t *__restrict__ row_perm, const int32_t *__restrict__ col_perm, int m,
                         const uint8_t *__restrict__ level, const int64_t *__restrict__ byte_off,
                         uint8_t *__restrict__ codes, float *__restrict__ scale, float *__restrict__ zero,
-                        GridConsts gc, int cmax)
+                        GridConsts gc, int cmax, int opu)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int rowsrc[FU_OPU * 8];
@@ -570,8 +571,8 @@ void gather_pack_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     const int R = funi((int)d.rows), C = funi((int)d.cols) & ~7;
     const int nbc = funi(d.nbc);
     const int opb = m >> 3;
-    const int oct0 = ((int)blockIdx.x - funi(wg_start[mem])) * FU_OPU;
-    const int noct = min(FU_OPU, (R >> 3) - oct0);
+    const int oct0 = ((int)blockIdx.x - funi(wg_start[mem])) * opu;
+    const int noct = min(opu, (R >> 3) - oct0);
     const int32_t *__restrict__ rp = row_perm + d.row_off;
     const int32_t *__restrict__ cp = col_perm + d.col_off;
     const char *const Wg = reinterpret_cast<const char *>(d.w);
@@ -789,6 +790,7 @@ struct FusedLaunch {
     int64_t cols;
     const uint8_t *level;     // surrogates only
     int kstride, koff;        // where the launch's sums go among the block's (see the kernel)
+    int opu;                  // octets per workgroup of this class
 };
 
 // threads per workgroup: the chunks of a row spread over CPL per lane, rounded up to whole waves
@@ -809,7 +811,7 @@ static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
     const size_t lds = staged_step_bytes(a.cols, RS, true) + (size_t)(a.cols / (LPG * 8)) * K * 4;   // rows + octet sums
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc, a.level, a.kstride,
-                       a.koff);
+                       a.koff, a.opu);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
@@ -891,6 +893,7 @@ struct FusedPackLaunch {
     GridConsts gc;
     int cmax;
     int64_t cols;
+    int opu;
 };
 
 template <int LPG, int CPL, int RS, int TMAX>
@@ -903,7 +906,7 @@ static int launch_gpack_g(sbits_ctx *ctx, const FusedPackLaunch &a)
     const size_t lds = (size_t)RS * a.cols * 2 + (size_t)(CPL * T / LPG) * ((size_t)RS * LPG * a.cmax + 8);
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.level, a.byte_off, a.codes, a.scale,
-                       a.zero, a.gc, a.cmax);
+                       a.zero, a.gc, a.cmax, a.opu);
     SBITS_HIP(ctx, hipGetLastError());
     return SBITS_OK;
 }
@@ -915,6 +918,7 @@ static int launch_gpack_l(sbits_ctx *ctx, const FusedPackLaunch &a)
     if (chunks <= 512) return launch_gpack_g<LPG, 1, 4, 512>(ctx, a);
     if (chunks <= 1024) return launch_gpack_g<LPG, 2, 2, 512>(ctx, a);
     if (chunks <= 2048) return launch_gpack_g<LPG, 2, 2, 1024>(ctx, a);
+    if (chunks <= 4096) return launch_gpack_g<LPG, 4, 1, 1024>(ctx, a);
     return SBITS_ERR_BAD_SHAPE;
 }
 
@@ -923,18 +927,39 @@ static int launch_gpack_l(sbits_ctx *ctx, const FusedPackLaunch &a)
 using namespace sbits;
 
 // shapes the fused kernel takes: 64- or 128-column blocks, rows of at most FU_MAX_COLS elements
+// The route is chosen per class of matrices with equal column count.  Rows of up to FU_MAX_COLS
+// elements are staged whole (weights and sensitivities) by the one-pass cost kernel; matrices with
+// wider rows (up to the plan's limit of 32768) take, one by one, the reorder-gather into a copy in the
+// workspace and the cost kernel for reordered matrices.  The packing kernel stages weights only and
+// takes every row length.
 bool sbits_fused_shapes_ok(const sbits_plan *plan)
 {
     if (plan->n != 64 && plan->n != 128) return false;
-    return plan->max_cols <= FU_MAX_COLS;
+    return plan->max_cols <= FU_PACK_MAX_COLS;
+}
+bool sbits_fused_all_staged(const sbits_plan *plan)
+{
+    return sbits_fused_shapes_ok(plan) && plan->max_cols <= FU_MAX_COLS;
 }
 
-// octet partials: one float per (block, octet of the block, candidate)
+static size_t octet_partial_bytes(const sbits_plan *plan)
+{
+    const size_t per_octet = (size_t)(plan->K > 2 ? plan->K : 2);     // the surrogates keep two sums per block
+    return sbits_align_up((size_t)plan->N * (size_t)(plan->m / 8) * per_octet * 4, 256);
+}
+// octet partials: one float per (block, octet of the block, candidate); then room for the reordered
+// copy (bf16, then fp32) of the largest matrix whose rows are too wide to be staged
 size_t sbits_fused_ws_bytes(const sbits_plan *plan)
 {
     if (!sbits_fused_shapes_ok(plan)) return 0;
-    const size_t per_octet = (size_t)(plan->K > 2 ? plan->K : 2);     // the surrogates keep two sums per block
-    return sbits_align_up((size_t)plan->N * (size_t)(plan->m / 8) * per_octet * 4, 256);
+    size_t spill = 0;
+    for (int i = 0; i < plan->n_mats; ++i) {
+        if (plan->cols[i] <= FU_MAX_COLS) continue;
+        const size_t el = (size_t)plan->rows[i] * (size_t)plan->cols[i];
+        const size_t b = sbits_align_up(el * 2, 256) + sbits_align_up(el * 4, 256);
+        if (b > spill) spill = b;
+    }
+    return octet_partial_bytes(plan) + spill;
 }
 
 // The kernels that read sensitivities rely on 16-bit register-half loads filling the other half with
@@ -963,12 +988,23 @@ static int fused_classes(sbits_plan *plan, void *ws, int **d_mem, int **d_pre)
             fc.first = (int)plan->fused_members.size();
             fc.pre_first = (int)plan->fused_pre.size();
             fc.n = 0;
+            // octets per workgroup: FU_OPU, halved while the class would not even give every CU a few
+            // workgroups (one decoder layer of a streamed model is such a plan)
+            int opu = FU_OPU;
+            auto class_wgs = [&](int o) {
+                int64_t t = 0;
+                for (int i = 0; i < plan->n_mats; ++i)
+                    if (plan->cols[i] == c) t += (plan->rows[i] / 8 + o - 1) / o;
+                return t;
+            };
+            while (opu > 2 && class_wgs(opu) < 2048) opu >>= 1;
+            fc.opu = opu;
             int64_t t = 0;
             for (int i = 0; i < plan->n_mats; ++i) {
                 if (plan->cols[i] != c) continue;
                 plan->fused_members.push_back(i);
                 plan->fused_pre.push_back((int)t);
-                t += (plan->rows[i] / 8 + FU_OPU - 1) / FU_OPU;
+                t += (plan->rows[i] / 8 + opu - 1) / opu;
                 ++fc.n;
             }
             if (t > 0x7fffffff) {
@@ -1012,7 +1048,8 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
         a.n_members = fc.n;
         a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
         a.cols = fc.cols;
-        if (a.total_wg == 0) continue;
+        a.opu = fc.opu;
+        if (a.total_wg == 0 || fc.cols > FU_MAX_COLS) continue;
         const bool z0 = plan->bits[0] == 0;                     // a 0-bit candidate (the first of the list) has no grid
         sbits_fill_grid_consts(plan->bits + z0, plan->K - z0, &a.gc);
         a.kstride = plan->K;
@@ -1025,6 +1062,22 @@ int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, cons
         hipLaunchKernelGGL(octet_finish_kernel, dim3((unsigned)((NK + 255) / 256)), dim3(256), 0, ctx->stream,
                            a.part, a.descs, plan->n_mats, NK, plan->K, plan->m / 8, cost);
         SBITS_HIP(ctx, hipGetLastError());
+    }
+    // matrices with rows too wide to stage: reordered copy in the workspace, then the cost kernel on it; their
+    // rows of the table are written after the tree kernel above (which found nothing of theirs in part[])
+    for (int i = 0; i < plan->n_mats; ++i) {
+        if (plan->cols[i] <= FU_MAX_COLS) continue;
+        const MatDesc &d = plan->descs[i];
+        const size_t el = (size_t)plan->rows[i] * (size_t)plan->cols[i];
+        char *tmp = static_cast<char *>(sbits_scratch(plan, ws)) + octet_partial_bytes(plan);
+        void *w_tmp = w_re ? static_cast<void *>(static_cast<uint16_t *>(w_re) + d.elem_off) : static_cast<void *>(tmp);
+        float *s_tmp = reinterpret_cast<float *>(tmp + sbits_align_up(el * 2, 256));
+        int rc = sbits_launch_gather(ctx, d.w, d.s, plan->rows[i], plan->cols[i], d.ld_w, d.ld_s, row_perm + d.row_off,
+                                     col_perm + d.col_off, w_tmp, s_tmp);
+        if (rc) return rc;
+        rc = sbits_launch_cost(ctx, w_tmp, s_tmp, plan->rows[i], plan->cols[i], plan->m, plan->n, plan->bits, plan->K,
+                               cost + d.block_base * plan->K);
+        if (rc) return rc;
     }
     return SBITS_OK;
 }
@@ -1054,6 +1107,7 @@ int sbits_launch_gather_pack_all(sbits_plan *plan, const int32_t *row_perm, cons
         a.n_members = fc.n;
         a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
         a.cols = fc.cols;
+        a.opu = fc.opu;
         if (a.total_wg == 0) continue;
         const int rc = plan->n == 64 ? launch_gpack_l<8>(ctx, a) : launch_gpack_l<16>(ctx, a);
         if (rc) return rc;
@@ -1067,7 +1121,7 @@ int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const
                                 const uint8_t *level, float *s_up, float *s_down, void *ws)
 {
     sbits_ctx *ctx = plan->ctx;
-    if (!sbits_fused_shapes_ok(plan) || !sbits_fused_layout_ok(plan, true)) return SBITS_ERR_BAD_SHAPE;
+    if (!sbits_fused_all_staged(plan) || !sbits_fused_layout_ok(plan, true)) return SBITS_ERR_BAD_SHAPE;
     int *d_mem, *d_pre;
     int rc0 = fused_classes(plan, ws, &d_mem, &d_pre);
     if (rc0) return rc0;
@@ -1089,6 +1143,7 @@ int sbits_launch_surrogates_all(sbits_plan *plan, const int32_t *row_perm, const
         a.n_members = fc.n;
         a.total_wg = plan->fused_pre[fc.pre_first + fc.n];
         a.cols = fc.cols;
+        a.opu = fc.opu;
         if (a.total_wg == 0) continue;
         const int rc = plan->n == 64 ? launch_surrogates_l<8>(ctx, a) : launch_surrogates_l<16>(ctx, a);
         if (rc) return rc;

@@ -37,7 +37,7 @@ struct sbits_plan {
     struct GatherClass { int64_t cols; int first, pre_first, n, rpw_w, rpw_s; };
     std::vector<GatherClass> gather_classes; // matrices grouped by column count
     std::vector<int> gather_members, gather_pre_w, gather_pre_s;
-    struct FusedClass { int64_t cols; int first, pre_first, n; };
+    struct FusedClass { int64_t cols; int first, pre_first, n, opu; };
     std::vector<FusedClass> fused_classes;   // the same grouping for the fused gather + cost launch
     std::vector<int> fused_members, fused_pre;
     std::vector<sbits::MatDesc> descs;       // shape part filled at creation; pointers per call
@@ -106,6 +106,7 @@ int sbits_upload_descs(sbits_plan *plan, const sbits_matrix *mats, void *ws);
 int sbits_launch_cost_all(sbits_plan *plan, const void *w_re, const float *s_re, float *cost, void *ws);
 // gather fused with the cost table (reads the original matrices once; writes w_re and cost)
 bool sbits_fused_shapes_ok(const sbits_plan *plan);
+bool sbits_fused_all_staged(const sbits_plan *plan);
 bool sbits_fused_layout_ok(const sbits_plan *plan, bool need_s);
 size_t sbits_fused_ws_bytes(const sbits_plan *plan);
 int sbits_launch_gather_cost_all(sbits_plan *plan, const int32_t *row_perm, const int32_t *col_perm,

@@ -255,7 +255,8 @@ def test_streamed_70b_shaped_model(orc):
     """80-layer Llama-3-70B-shaped model (hidden 8192, ffn 28672, 8 KV heads of 128): 410 GB of inputs
     do not fit, so weights and sensitivities are regenerated per layer on the device from the seed;
     128x128 blocks, {2,3,4} bits, budget 2.75.  One per-layer plan serves the per-matrix stages of
-    every layer (pointer offsets place its outputs in the global arrays); only permutations and
+    every layer (pointer offsets place its outputs in the global arrays) through the calls the search
+    itself uses (sbits_gather_cost_all, sbits_gather_pack_all); only permutations and
     the cost table are kept, the global allocation runs on the full table, and a second streaming
     pass packs.  Layers 0, 40 and 79 are checked against the oracle."""
     say("config 4: streamed 70B-shaped model")
@@ -293,11 +294,19 @@ def test_streamed_70b_shaped_model(orc):
         rp = row_perm[layer * sum_r:(layer + 1) * sum_r]
         cp = col_perm[layer * sum_c:(layer + 1) * sum_c]
         lplan.reorder_all(dm, rp, cp, lws)
-        lplan.gather_all(dm, rp, cp, w_re, s_re, lws)
-        lplan.cost_table_all(w_re, s_re, cost[layer * NL:(layer + 1) * NL], lws)
+        lcost = cost[layer * NL:(layer + 1) * NL]
+        # the product's route: one pass over the originals for the six matrices whose rows fit in LDS,
+        # the reordered copy in the workspace for `down` (28672 columns)
+        lplan.gather_cost_all(dm, rp, cp, None, lcost, lws)
         if layer in check_layers:
+            # ... and the two-pass route beside it: the same table, and the reordered copies for the oracle check
+            cost2 = torch.empty_like(lcost)
+            lplan.gather_all(dm, rp, cp, w_re, s_re, lws)
+            lplan.cost_table_all(w_re, s_re, cost2, lws)
             torch.cuda.synchronize()
+            assert torch.equal(cost2.view(torch.int32), lcost.view(torch.int32))
             kept[layer] = dict(w_re=w_re.clone(), s_re=s_re.clone())
+            del cost2
         torch.cuda.synchronize()
         del mats, dm
         if layer % 10 == 0:
@@ -324,9 +333,8 @@ def test_streamed_70b_shaped_model(orc):
         dm = [sb.matrix(w, s) for w, s in mats]
         rp = row_perm[layer * sum_r:(layer + 1) * sum_r]
         cp = col_perm[layer * sum_c:(layer + 1) * sum_c]
-        lplan.gather_all(dm, rp, cp, w_re, None, lws)
         b0 = layer * NL
-        lplan.pack_all(w_re, level[b0:], byte_off[b0:], codes, scale[b0 * m:], zero[b0 * m:], lws)
+        lplan.gather_pack_all(dm, rp, cp, level[b0:], byte_off[b0:], codes, scale[b0 * m:], zero[b0 * m:], lws)
         torch.cuda.synchronize()
         if layer in check_layers:
             say("  checking layer", layer)

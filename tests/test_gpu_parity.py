@@ -386,8 +386,16 @@ ONE_PASS_CASES = [
     ([(64, 8320), (192, 320)], 64, 64, [0, 2, 4]),
 ]
 
+# rows wider than the cost kernel stages (16384): those matrices go through a reordered copy in the
+# workspace, the others of the same plan through the one-pass kernel; the packing kernel stages every row
+WIDE_ROW_CASES = [
+    ([(64, 28672), (128, 4096), (64, 14336)], 64, 128, [2, 3, 4]),
+    ([(128, 20480), (64, 1024)], 64, 64, [1, 2, 3, 4, 8]),
+    ([(64, 32768)], 64, 128, [0, 1, 2, 3, 4]),
+]
 
-@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES)
+
+@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES + WIDE_ROW_CASES)
 def test_gather_cost_one_pass(orc, ctx, dev, shapes, m, n, bits):
     say("one-pass gather+cost", shapes, m, n, bits)
     plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
@@ -416,7 +424,7 @@ def test_gather_cost_one_pass(orc, ctx, dev, shapes, m, n, bits):
     plan.close()
 
 
-@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES)
+@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES + WIDE_ROW_CASES)
 def test_gather_pack_one_pass(orc, ctx, dev, shapes, m, n, bits):
     """Packing straight from the original weights and the permutations == oracle gather + pack."""
     say("one-pass gather+pack", shapes, m, n, bits)
@@ -555,6 +563,24 @@ def test_gather_cost_one_pass_refuses_other_shapes(ctx, dev):
     cost = torch.zeros(plan.num_blocks(), 2, dtype=torch.float32, device=dev)
     with pytest.raises(sb.SbitsError) as e:
         plan.gather_cost_all([sb.matrix(Wd, Sd)], rp, cp, w_re, cost, ws)
+    assert e.value.status == sb.ERR_UNIMPLEMENTED
+    plan.close()
+
+
+def test_surrogates_refuse_rows_too_wide_to_stage(ctx, dev):
+    say("surrogates refuse wide rows")
+    plan, ws = make_plan(ctx, [(64, 20480)], 64, 128, [2, 4], dev)
+    assert plan.gather_cost_supported()                              # the cost table has a route for it
+    W, G = synth.make_matrix("student_t", 64, 20480, seed=1)
+    Wd, Gd = W.to(dev), G.to(dev)
+    rp = torch.arange(64, dtype=torch.int32, device=dev)
+    cp = torch.arange(20480, dtype=torch.int32, device=dev)
+    N = plan.num_blocks()
+    level = torch.zeros(N, dtype=torch.uint8, device=dev)
+    up = torch.zeros(N, dtype=torch.float32, device=dev)
+    down = torch.zeros(N, dtype=torch.float32, device=dev)
+    with pytest.raises(sb.SbitsError) as e:
+        plan.surrogates_all([sb.matrix(Wd, Gd)], rp, cp, level, up, down, ws)
     assert e.value.status == sb.ERR_UNIMPLEMENTED
     plan.close()
 
