@@ -154,9 +154,11 @@ struct CostGeom {
     static int blocks_per_unit(int m) { const int opb = m / 8; return opb >= OS ? BX : BX * (OS / opb); }
 };
 
-// K candidates; with Z0 the first one is "0 bits" (pruned block) and gc holds the other K - 1 grids
+// K candidates; with Z0 the first one is "0 bits" (pruned block) and gc holds the other K - 1 grids.
+// Up to four candidates fit the 256 registers that two waves per SIMD leave a lane; five and more need up
+// to 345, and run with one wave per SIMD rather than spill (K = 8: 12 ms for the 8B-shaped model against 21).
 template <int LPG, int K, bool STRIDED, bool Z0>
-__global__ __launch_bounds__(COST_THREADS, 2)
+__global__ __launch_bounds__(COST_THREADS, (K > 4 ? 1 : 2))
 void cost_kernel(const MatDesc *__restrict__ descs, MatDesc one, const int *__restrict__ unit_start,
                  int n_mats, int total_units, const uint16_t *__restrict__ W, const float *__restrict__ S,
                  int m, float *__restrict__ cost, GridConsts gc, int kstride, int koff)
