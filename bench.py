@@ -450,6 +450,9 @@ def main():
         ex = {}
         ex["budget_3.0"] = extra_run(torch, sb, dev, "the same model and candidates, budget 3.00 (the warm start is on "
                                      "budget: swaps only)", shapes, Ws, Ss, m, n, bits, 3.0)
+        ex["paper_default_space"] = extra_run(torch, sb, dev, "the same model, the paper's default search space: 64x128 "
+                                              "blocks (group 128), bitwidths [1 .. 8], budget 3.00", shapes, Ws, Ss,
+                                              64, 128, [1, 2, 3, 4, 5, 6, 7, 8], 3.0)
         del Ws, Ss
         torch.cuda.empty_cache()
         W5, S5 = generate(torch, synth, dev, shapes, "outlier_chan", args.seed)

@@ -838,7 +838,7 @@ static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
     if (chunks <= 2048) {
         // seven or more candidates: two chunks' state does not fit the 128 registers of a 1024-thread workgroup
         if constexpr (K <= 5 || (K == 6 && !(Z0 && LPG == 8))) return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true>(ctx, a);
-        else return launch_fused_g<LPG, K, 4, 1, 512, 2, false, Z0>(ctx, a);
+        else return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, false>(ctx, a);
     }
     return SBITS_ERR_BAD_SHAPE;
 }
