@@ -1,7 +1,7 @@
 // Reorder-gather fused with the block x bitwidth cost table: the original weights (bf16) and
-// sensitivities (fp32) are read ONCE, permuted on the fly and scored; only the reordered
-// weights (which the packing stage needs) are written back.  The reordered sensitivities
-// never reach HBM.
+// sensitivities (fp32) are read ONCE, permuted on the fly and scored; the reordered weights are
+// written back only if the caller asks for them (the packing stage reads the originals too).  The
+// reordered sensitivities never reach HBM.
 //
 // Operation: the same as gather followed by the cost table (paper Sec. 4.2 "bi-directional
 // channel reordering" applied to W and S, then Sec. 5 "Implementation": per-block-row
