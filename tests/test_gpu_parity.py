@@ -808,6 +808,18 @@ def test_search_several_matrices(orc, ctx, dev, m, n, bits, avg, recipe):
     compare_search(orc, ref, rc, st, o, shp, m)
 
 
+def test_search_with_rows_too_wide_to_stage(orc, ctx, dev):
+    """One call over a plan that mixes matrices the one-pass cost kernel stages with one it cannot (20480 columns):
+    that one is scored from a reordered copy, here written straight into the caller's w_re."""
+    say("search with a wide-row matrix")
+    shapes = [(128, 20480), (256, 1024), (128, 4096)]
+    mats = [synth.make_matrix("student_t", r, c, seed=5, tid=i) for i, (r, c) in enumerate(shapes)]
+    ref = oracle_search(orc, mats, 64, 128, [1, 2, 3, 4], 2.5)
+    rc, st, o, shp = gpu_search(ctx, dev, mats, 64, 128, [1, 2, 3, 4], 2.5)
+    assert o["one_pass"]
+    compare_search(orc, ref, rc, st, o, shp, 64)
+
+
 def test_search_with_a_pruned_candidate(orc, ctx, dev):
     """{0, 1, 2, 3, 4} bits at 1.5 bits per weight: blocks at 0 bits are pruned (no bytes, zero scale / zero)."""
     say("search with 0 bits")
