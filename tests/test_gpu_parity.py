@@ -395,7 +395,34 @@ WIDE_ROW_CASES = [
 ]
 
 
-@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES + WIDE_ROW_CASES)
+def _random_one_pass_cases(count, seed):
+    """Seeded shapes around the kernels' boundaries: block-column counts next to the chunk limits of the
+    instances (512, 1024, 2048 chunks of 8 columns), row counts that leave ragged runs of octets, every
+    number of candidates, with and without the 0-bit one."""
+    rng = np.random.default_rng(seed)
+    edge_cols = {64: [1, 3, 8, 9, 63, 64, 65, 66, 127, 128, 129, 130, 200, 255, 256],
+                 128: [1, 2, 5, 31, 32, 33, 34, 63, 64, 65, 66, 100, 127, 128]}
+    cases = []
+    for i in range(count):
+        n = int(rng.choice([64, 128]))
+        m = int(rng.choice([8, 16, 64, 128, 256]))
+        K = int(rng.integers(1, 9))
+        bits = sorted(int(b) for b in rng.choice(np.arange(1, 9), size=K, replace=False))
+        if i % 5 == 4:
+            bits = [0] + bits
+        shapes = []
+        for _ in range(int(rng.integers(1, 4))):
+            nbc = int(rng.choice(edge_cols[n]))
+            nbr = int(rng.integers(1, max(2, 320 // m)))
+            shapes.append((m * nbr, n * nbc))
+        cases.append((shapes, m, n, bits))
+    return cases
+
+
+RANDOM_ONE_PASS_CASES = _random_one_pass_cases(24, 20260217)
+
+
+@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES + WIDE_ROW_CASES + RANDOM_ONE_PASS_CASES)
 def test_gather_cost_one_pass(orc, ctx, dev, shapes, m, n, bits):
     say("one-pass gather+cost", shapes, m, n, bits)
     plan, ws = make_plan(ctx, shapes, m, n, bits, dev)
@@ -424,7 +451,7 @@ def test_gather_cost_one_pass(orc, ctx, dev, shapes, m, n, bits):
     plan.close()
 
 
-@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES + WIDE_ROW_CASES)
+@pytest.mark.parametrize("shapes,m,n,bits", ONE_PASS_CASES + WIDE_ROW_CASES + RANDOM_ONE_PASS_CASES)
 def test_gather_pack_one_pass(orc, ctx, dev, shapes, m, n, bits):
     """Packing straight from the original weights and the permutations == oracle gather + pack."""
     say("one-pass gather+pack", shapes, m, n, bits)
