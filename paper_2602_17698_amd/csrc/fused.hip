@@ -830,8 +830,12 @@ static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
     const int64_t chunks = a.cols / 8;
     constexpr int MINW = K <= 4 ? 4 : 2;             // waves per SIMD the register budget is set for
     if (chunks <= 512) {
-        // (the instances named here are the ones whose state fits 168 registers without spilling)
+        // (two chunks and two rows per lane where that fits 168 registers without spilling; else one chunk of one
+        // row, 62 to 82 registers: three workgroups per CU; measured 2 to 6 % faster than two rows per step there)
         if constexpr (K <= 2 || (K <= 4 && !Z0 && LPG == 16)) return launch_fused_g<LPG, K, 2, 2, 256, 3, false, Z0>(ctx, a);
+        // (... as long as it stays within the 80 registers that three workgroups of eight waves leave a lane)
+        else if constexpr (LPG == 16 ? (K <= 7 || (K == 8 && !Z0)) : (K <= 5 || (K == 6 && !Z0)))
+            return launch_fused_g<LPG, K, 1, 1, 512, 4, false, Z0>(ctx, a);
         else return launch_fused_g<LPG, K, 1, 2, 512, MINW, false, Z0>(ctx, a);
     }
     if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, MINW, false, Z0>(ctx, a);
