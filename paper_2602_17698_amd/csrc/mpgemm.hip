@@ -245,7 +245,6 @@ void mp_gemm_kernel(MpArgs a)
     constexpr int SLICE = MG_SPAN * N_COLS;                    // x columns per workgroup
     constexpr int PITCH = SLICE * 2 + 16;                      // bytes per batch row in LDS (+16: spreads the rows over the banks)
     const int tid = threadIdx.x, lane = tid & 63;
-#define MG_TS(i)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: the bookkeeping below stays scalar
     const int rg = wave & (MG_RG - 1), jl = wave >> 2;
     const int li = lane & 15, g = lane >> 4;
@@ -288,7 +287,6 @@ void mp_gemm_kernel(MpArgs a)
         xs[i] = *(const __attribute__((address_space(1))) u32x4_t *)(a.x + (int64_t)bc * a.ld_x + cc);
     }
 
-    MG_TS(1);
 #pragma unroll
     for (int i = 0; i < XCH; ++i) {
         const int q = tid + i * MG_THREADS;
@@ -300,7 +298,6 @@ void mp_gemm_kernel(MpArgs a)
     }
     // (no global load is in flight here but the metadata: the codes are requested after the barrier)
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the x slice is in LDS
-    MG_TS(2);
     const uint32_t lane_units = (uint32_t)((rin + li) * (N_COLS / 8) + g * (KL / 8));   // x c = the lane's byte offset in the block
     // the blocks' bitwidths and stream offsets as scalars
     uint32_t off_lo[MG_NBLK], off_hi[MG_NBLK];
