@@ -319,9 +319,9 @@ def generate(torch, synth, dev, shapes, recipe, seed):
 
 
 def extra_run(torch, sb, dev, what, shapes, Ws, Ss, m, n, bits, budget):
-    """One more workload beside the headline one, outside its timed region: 1 warm-up + 2 steps."""
+    """One more workload beside the headline one, outside its timed region: 2 warm-ups + 4 steps."""
     srch = Search(torch, sb, dev, shapes, Ws, Ss, m, n, bits, budget)
-    r = srch.run(2, 1)
+    r = srch.run(4, 2)
     out = {"workload": what, "route": "one-pass" if srch.one_pass else "two-pass", "ms_per_step": r["ms_per_step"],
            "stage_ms": r["stage_ms"], "cost_stage": srch.cost_stage(r["stage_ms"]["cost"]),
            "iterations": r["stats"]["iters"], "search_status": r["status"], "blocks": srch.N, "weights": srch.nw}

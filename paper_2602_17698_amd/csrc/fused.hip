@@ -133,7 +133,11 @@ __device__ __forceinline__ void lds_gather_wait(float (&w)[8], float (&s)[8])
 // minimum / range / divisions / x meanwhile; barrier, request the next row's sensitivities; candidates.
 // With one workgroup per CU (rows of 8192 elements and more) nobody else would fill the time the LDS
 // needs for the gather.
-template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false>
+// WPIPE (a refinement of SLATE): two buffers for the row of weights, 32 KiB apart (an immediate offset of the
+// LDS reads).  The weights of row r + 1 are in LDS a step early, and a lane picks its elements of them out of
+// LDS while it runs the second half of row r's arithmetic: no phase of a step is LDS reads alone, and a step
+// has two barriers instead of three.
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false, bool WPIPE = false>
 __global__ __launch_bounds__(TMAX, MINW)
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
@@ -156,6 +160,8 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     constexpr bool SDER = RS == 1 && CPL >= 2;       // sensitivity address derived from the weight's (saves registers)
     static_assert(NIT % NG == 0 && NG % NI == 0, "step shape");
     static_assert(!SLATE || (RS == 1 && !SUR && SDER && NIT == NG), "late sensitivities: one row, one group of items");
+    static_assert(!WPIPE || SLATE, "the weights' pipeline is a form of the slate step");
+    constexpr uint32_t WBUF = 32768u;                // WPIPE: distance of the two weight buffers (rows up to 16384 elements)
 
     const int tid = (int)threadIdx.x;
     const int T = (int)blockDim.x;                   // a multiple of 64, at most TMAX
@@ -177,8 +183,9 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     const uint32_t wbytes = 2u * (uint32_t)C, sbytes = 4u * (uint32_t)C;
     const int nW = (int)((wbytes + 1023u) >> 10), nS = (int)((sbytes + 1023u) >> 10);
     const uint32_t Wb = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    const uint32_t Sb = Wb + (uint32_t)(nW * RS) * 1024u;
-    float *const otab = reinterpret_cast<float *>(smem + (size_t)(nW + nS) * RS * 1024);   // [nbc][K] octet sums
+    const uint32_t Sb = WPIPE ? Wb + 2u * WBUF : Wb + (uint32_t)(nW * RS) * 1024u;
+    float *const otab = reinterpret_cast<float *>(smem + (WPIPE ? (size_t)2 * WBUF + (size_t)nS * 1024
+                                                                : (size_t)(nW + nS) * RS * 1024));   // [nbc][K] octet sums
     const int nld = nwv > 1 ? nwv - 1 : 1;           // waves that request rows
     const bool loader = wave < nld, storer = wave == nwv - 1;
 
@@ -227,12 +234,12 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         }
         return r;
     };
-    auto request = [&](const Rows &r, bool do_w = true, bool do_s = true) {
+    auto request = [&](const Rows &r, bool do_w = true, bool do_s = true, uint32_t wbuf = 0u) {
         if (!loader) return;
 #pragma unroll
         for (int rs = 0; rs < RS; ++rs)
             load_row_pieces(Wg + (int64_t)r.sr[rs] * pitch_w, Sg + (int64_t)r.sr[rs] * pitch_s, nW, nS, wbytes, sbytes,
-                            Wb, Sb, RS, rs, wave, nld, lane, do_w, do_s);
+                            Wb + wbuf, Sb, RS, rs, wave, nld, lane, do_w, do_s);
     };
     // the last wave writes the octet sums of octet `og` (in otab since the previous barrier) to part[]
     int pend_og = -1;
@@ -346,7 +353,96 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
         }
     };
 
+    // WPIPE: the lane's weights of the current row (parity u of the unrolled pair) and of the next one
+    float wvp[WPIPE ? 2 : 1][NIT][8];
+    auto wpipe_step = [&](auto iu, auto inv, int row, const Rows &next, const Rows &next2, float (&t1)[CPL][K],
+                          float (&s2)[CPL][K], float (&s3)[CPL][K], float (&last)[CPL][K]) {
+        constexpr int u = decltype(iu)::value, NV = decltype(inv)::value;
+        constexpr int NIv = DP::RP < NV ? DP::RP : NV;               // items per round of divisions
+        constexpr int un = WPIPE ? (u ^ 1) : 0;
+        float gs[NV][8];
+        // the row's sensitivities out of LDS while the first half of the arithmetic runs
+#pragma unroll
+        for (int it = 0; it < NV; ++it)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint32_t a;
+                asm("v_lshl_add_u32 %0, %1, 1, %2" : "=v"(a) : "v"(aw[it][e]), "s"(sder));
+                lds_s<0>(gs[it][e], a);
+            }
+        if (w_re_all) {
+#pragma unroll
+            for (int it = 0; it < NV; ++it)
+                if (valid[it]) store_reordered(wvp[u & (WPIPE ? 1 : 0)][it], oct0 * 8 + row, it);
+        }
+        float xs[NV][8], vals[NV / NIv][DP::NS];
+#pragma unroll
+        for (int i0 = 0; i0 < NV; i0 += NIv) {
+            float w[NIv][8], x[NIv][8];
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[j][e] = wvp[u & (WPIPE ? 1 : 0)][i0 + j][e];
+            quant_cost_prep<LPG, K, NIv, Z0>(w, dp, x, vals[i0 / NIv]);
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xs[i0 + j][e] = x[j][e];
+        }
+#pragma unroll
+        for (int r = 0; r < NV / NIv; ++r)
+#pragma unroll
+            for (int t = 0; t < DP::NS; ++t) asm volatile("" : "+v"(vals[r][t]));
+#pragma unroll
+        for (int it = 0; it < NV; ++it)
+            asm volatile("" : "+v"(xs[it][0]), "+v"(xs[it][1]), "+v"(xs[it][2]), "+v"(xs[it][3]),
+                              "+v"(xs[it][4]), "+v"(xs[it][5]), "+v"(xs[it][6]), "+v"(xs[it][7]));
+        static_for<0, NV>([&](auto iit) { lds_gather_wait(gs[decltype(iit)::value]); });
+        asm volatile("s_barrier" ::: "memory");                      // everybody has its sensitivities: that buffer is free
+        if (row + 2 < nrows) request(next2, true, false, (uint32_t)u * WBUF);   // weights of row r + 2 -> the buffer row r left
+        if (row + 1 < nrows) request(next, false, true);                          // sensitivities of row r + 1
+        if (row + 1 < nrows) {
+            static_for<0, NV>([&](auto iit) {
+                constexpr int it = decltype(iit)::value;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) lds_w_hi<un * WBUF>(wvp[un][it][e], aw[it][e]);
+            });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i0 = 0; i0 < NV; i0 += NIv) {
+            float w[NIv][8], x[NIv][8], sv[NIv][8], out[NIv][K];
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { w[j][e] = wvp[u & (WPIPE ? 1 : 0)][i0 + j][e]; x[j][e] = xs[i0 + j][e]; sv[j][e] = gs[i0 + j][e]; }
+            quant_cost_finish<LPG, K, NIv, Z0, true>(w, x, vals[i0 / NIv], sv, out);
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int k = 0; k < K; ++k) asm volatile("" : "+v"(out[j][k]));
+#pragma unroll
+            for (int j = 0; j < NIv; ++j)
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    last[i0 + j][k] = octet_tree_push(out[j][k], u, t1[i0 + j][k], s2[i0 + j][k], s3[i0 + j][k]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (row + 1 < nrows) static_for<0, NV>([&](auto iit) { lds_gather_wait(wvp[un][decltype(iit)::value]); });
+    };
+
     request(source_rows(0));
+    if constexpr (WPIPE) {
+        request(source_rows(1), true, false, WBUF);                  // (nrows >= 8)
+        if (loader) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        static_for<0, NIT>([&](auto iit) {
+            constexpr int it = decltype(iit)::value;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) lds_w_hi<0>(wvp[0][it][e], aw[it][e]);
+        });
+        static_for<0, NIT>([&](auto iit) { lds_gather_wait(wvp[0][decltype(iit)::value]); });
+    }
     for (int row0 = 0; row0 < nrows; row0 += B) {
         float t1[CPL][K], s2[CPL][K], s3[CPL][K];    // static levels inside the unrolled rows
         float last[CPL][K];
@@ -368,6 +464,12 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
                         lk[c] = level_consts(gc, level[d.block_base + (int64_t)Inow * nbc + J]);
                     }
                 }
+            }
+            if constexpr (WPIPE) {
+                const Rows next2 = source_rows(row + 2);
+                if (SOLO_OK && solo) wpipe_step(iu, std::integral_constant<int, 1>{}, row, next, next2, t1, s2, s3, last);
+                else wpipe_step(iu, std::integral_constant<int, NIT>{}, row, next, next2, t1, s2, s3, last);
+                return;
             }
             if constexpr (SLATE) {
                 if (SOLO_OK && solo) slate_step(iu, std::integral_constant<int, 1>{}, row, next, t1, s2, s3, last);
@@ -800,15 +902,17 @@ static int fused_threads(int64_t cols, int cpl, int tmax)
     return (int)(need < 64 ? 64 : (need > tmax ? tmax : need));
 }
 
-template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false>
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false, bool WPIPE = false>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
     int T = fused_threads(a.cols, CPL, TMAX);
     if (SLATE && T > 256) T = (T + 255) / 256 * 256 <= TMAX ? (T + 255) / 256 * 256 : T;   // whole rounds of the four SIMDs
-    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, MINW, SUR, Z0, SLATE>;
+    auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, MINW, SUR, Z0, SLATE, WPIPE>;
     SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
-    const size_t lds = staged_step_bytes(a.cols, RS, true) + (size_t)(a.cols / (LPG * 8)) * K * 4;   // rows + octet sums
+    const size_t lds = (WPIPE ? (size_t)65536 + staged_step_bytes(a.cols, RS, true) - staged_step_bytes(a.cols, RS, false)
+                              : staged_step_bytes(a.cols, RS, true)) +
+                       (size_t)(a.cols / (LPG * 8)) * K * 4;                               // rows + octet sums
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
                        a.wg_start, a.n_members, a.row_perm, a.col_perm, a.m, a.w_re, a.part, a.gc, a.level, a.kstride,
                        a.koff, a.opu);
@@ -841,7 +945,11 @@ static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
     if (chunks <= 1024) return launch_fused_g<LPG, K, 2, 1, 512, MINW, false, Z0>(ctx, a);
     if (chunks <= 2048) {
         // seven or more candidates: two chunks' state does not fit the 128 registers of a 1024-thread workgroup
-        if constexpr (K <= 5 || (K == 6 && !(Z0 && LPG == 8))) return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true>(ctx, a);
+        // the slate form; with the weights pipelined where that fits the 128 registers (or nearly: 16 bytes of
+        // scratch at five candidates still pay, 24 and more do not)
+        if constexpr (LPG == 16 ? K <= 5 : (K <= 2 || (K == 3 && !Z0)))
+            return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true, true>(ctx, a);
+        else if constexpr (K <= 5 || (K == 6 && !(Z0 && LPG == 8))) return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true>(ctx, a);
         else return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, false>(ctx, a);
     }
     return SBITS_ERR_BAD_SHAPE;
