@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # candidates) from rocprofv3 counters of that very workload: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 in KiB
 # (factors from a plain 1 GiB copy in the same runs), summed over the stage's dispatches
 # (profiles/cost_stage_8b_shaped_hbm_traffic_pmc.md).  Other workloads: null.
-ONE_PASS_TRAFFIC_KIB_32L = 41162044        # both gather_cost launches + octet_finish
-TWO_PASS_TRAFFIC_KIB_32L = 40924862        # cost_kernel
+ONE_PASS_TRAFFIC_KIB_32L = 41162492        # both gather_cost launches + octet_finish
+TWO_PASS_TRAFFIC_KIB_32L = 40924660        # cost_kernel
 
 
 def parse():
