@@ -133,11 +133,11 @@ __device__ __forceinline__ void lds_gather_wait(float (&w)[8], float (&s)[8])
 // minimum / range / divisions / x meanwhile; barrier, request the next row's sensitivities; candidates.
 // With one workgroup per CU (rows of 8192 elements and more) nobody else would fill the time the LDS
 // needs for the gather.
-// WPIPE (a refinement of SLATE): two buffers for the row of weights, 32 KiB apart (an immediate offset of the
-// LDS reads).  The weights of row r + 1 are in LDS a step early, and a lane picks its elements of them out of
+// WPIPE (a refinement of SLATE; the parameter is the distance of the buffers in bytes, 0 = off): two buffers for
+// the row of weights, a fixed distance apart (an immediate offset of the LDS reads; at least a row of weights).  The weights of row r + 1 are in LDS a step early, and a lane picks its elements of them out of
 // LDS while it runs the second half of row r's arithmetic: no phase of a step is LDS reads alone, and a step
 // has two barriers instead of three.
-template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false, bool WPIPE = false>
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false, int WPIPE = 0>
 __global__ __launch_bounds__(TMAX, MINW)
 void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict__ members,
                         const int *__restrict__ wg_start, int n_members,
@@ -161,7 +161,7 @@ void gather_cost_kernel(const MatDesc *__restrict__ descs, const int *__restrict
     static_assert(NIT % NG == 0 && NG % NI == 0, "step shape");
     static_assert(!SLATE || (RS == 1 && !SUR && SDER && NIT == NG), "late sensitivities: one row, one group of items");
     static_assert(!WPIPE || SLATE, "the weights' pipeline is a form of the slate step");
-    constexpr uint32_t WBUF = 32768u;                // WPIPE: distance of the two weight buffers (rows up to 16384 elements)
+    constexpr uint32_t WBUF = (uint32_t)WPIPE;       // distance of the two weight buffers
 
     const int tid = (int)threadIdx.x;
     const int T = (int)blockDim.x;                   // a multiple of 64, at most TMAX
@@ -902,7 +902,7 @@ static int fused_threads(int64_t cols, int cpl, int tmax)
     return (int)(need < 64 ? 64 : (need > tmax ? tmax : need));
 }
 
-template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false, bool WPIPE = false>
+template <int LPG, int K, int CPL, int RS, int TMAX, int MINW, bool SUR, bool Z0, bool SLATE = false, int WPIPE = 0>
 static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
 {
     int T = fused_threads(a.cols, CPL, TMAX);
@@ -910,7 +910,7 @@ static int launch_fused_g(sbits_ctx *ctx, const FusedLaunch &a)
     auto *fn = &gather_cost_kernel<LPG, K, CPL, RS, TMAX, MINW, SUR, Z0, SLATE, WPIPE>;
     SBITS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024));
-    const size_t lds = (WPIPE ? (size_t)65536 + staged_step_bytes(a.cols, RS, true) - staged_step_bytes(a.cols, RS, false)
+    const size_t lds = (WPIPE ? (size_t)2 * WPIPE + staged_step_bytes(a.cols, RS, true) - staged_step_bytes(a.cols, RS, false)
                               : staged_step_bytes(a.cols, RS, true)) +
                        (size_t)(a.cols / (LPG * 8)) * K * 4;                               // rows + octet sums
     hipLaunchKernelGGL(fn, dim3((unsigned)a.total_wg), dim3(T), lds, ctx->stream, a.descs, a.members,
@@ -948,7 +948,7 @@ static int launch_fused_k(sbits_ctx *ctx, const FusedLaunch &a)
         // the slate form; with the weights pipelined where that fits the 128 registers (or nearly: 16 bytes of
         // scratch at five candidates still pay, 24 and more do not)
         if constexpr (LPG == 16 ? K <= 5 : (K <= 2 || (K == 3 && !Z0)))
-            return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true, true>(ctx, a);
+            return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true, 32768>(ctx, a);
         else if constexpr (K <= 5 || (K == 6 && !(Z0 && LPG == 8))) return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, true>(ctx, a);
         else return launch_fused_g<LPG, K, 2, 1, 1024, 4, false, Z0, false>(ctx, a);
     }
